@@ -1,0 +1,181 @@
+"""CPU oracle for one worker's FCCO global-contrastive-loss step (FastCLIP v0-v3).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference that the HIP
+library is checked against.  It may be imported by tests/, by
+__graft_entry__.smoke() and by bench.py's cpu_baseline leg, and by nothing
+else; it imports nothing from the GPU package and shares no code with it.
+
+Everything is float64 numpy.  One call = Alg. 1 lines 6, 7 and 9 of the paper
+plus the gradient half of line 12, for one worker k that owns the local rows
+[off, off+b) of an already gathered global batch of B image/text embedding
+pairs, with the encoders removed: "gradient" means the gradient with respect
+to the local embedding rows themselves (the factor "nabla e" of Eqs. 2-7 is
+the identity).
+
+Notation (paper, Sec. 3 and Appendix A):
+    s_ij           dot product of image row i and text row j
+    l1(i, j, tau)  exp((s_ij - s_ii) / tau)           contrast: text j
+    l2(i, j, tau)  exp((s_ji - s_ii) / tau)           contrast: image j
+    g1_i, g2_i     mean of l1 / l2 over the batch without i   (Proc. 1)
+    u1_i, u2_i     per-sample moving-average estimators       (Eq. 1)
+    f(g)           log(eps + g)
+
+Readings taken where the paper is silent (each one is listed in the design
+notes of this repository):
+  * the inner average runs over the GLOBAL batch without the anchor and is
+    divided by M = B - 1 (Proc. 1, Eq. 1, Eqs. 2-3 all use B_{i-});
+  * similarities are plain dot products of the rows as given (inputs are
+    already L2-normalised by the caller);
+  * u^0 = 0 marks "never visited": a stored value that is exactly zero is
+    replaced by g whatever gamma is;
+  * the estimator uses u^{t+1} as a constant (no gradient through u) and the
+    temperature(s) of the current call;
+  * one worker's estimator is normalised by its local batch size b; only the
+    loss terms of the local anchors enter (Eq. 2 in full and the i-in-B_k part
+    of Eq. 3), and only gradients of local rows are produced;
+  * the scalar "loss" is the objective (GCL, RGCL, RGCL-g, or GCL without its
+    leading tau for v0) with g(S_{i-}) replaced by u^{t+1} and the dataset
+    average replaced by the local-batch average;
+  * Eq. 9's factor 1/|S| is the argument tau_grad_scale.
+
+Pins (tests/test_oracle_pins.py): gamma = 1 definition check against an
+independent scalar evaluation, central finite differences of losses written
+straight from GCL / RGCL / RGCL-g, reduction to softmax cross-entropy
+(MBCL with eps = 1/M), hand-expanded B = 2 and B = 3 cases, invariants
+(u > 0, untouched state, permutation, image/text swap, Euler identity),
+the two-visit recurrence of Eq. 1, and the closed-form values of the gamma
+schedule.  Nothing here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+V0, V1, V2, V3 = 0, 1, 2, 3
+
+
+def gamma_cosine(t: int, iters_per_epoch: int, decay_epochs: int, gamma_min: float) -> float:
+    """Inner learning rate of Sec. 4 "The Inner LR Schedule".
+
+    epoch = floor(t / iters_per_epoch); gamma = 0.5 (1 + cos(pi epoch / E)) (1 - gamma_min)
+    + gamma_min while epoch < E, and gamma_min from epoch E on.
+    """
+    epoch = t // iters_per_epoch
+    if epoch >= decay_epochs:
+        return float(gamma_min)
+    return 0.5 * (1.0 + math.cos(math.pi * epoch / decay_epochs)) * (1.0 - gamma_min) + gamma_min
+
+
+def check_indices(idx, n_state: int) -> bool:
+    """True iff every index lies in [0, n_state) and no index repeats."""
+    idx = np.asarray(idx, dtype=np.int64)
+    if idx.size == 0:
+        return True
+    if idx.min() < 0 or idx.max() >= n_state:
+        return False
+    return np.unique(idx).size == idx.size
+
+
+def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0.0,
+              tau=None, tau_img=None, tau_txt=None, tau_grad_scale=1.0):
+    """One FCCO step of worker k.  Updates u_img / u_txt IN PLACE at idx.
+
+    img, txt   [B, d] global image / text embeddings (any float dtype; used as float64)
+    off, b     local anchors are global rows off .. off+b-1
+    idx        [b] dataset index of each local anchor (distinct)
+    u_img/txt  [N] state arrays (numpy, modified in place)
+    version    V0 (GCL without leading tau, learnable global tau; Eqs. 4, 5, 8)
+               V1 (GCL, constant tau; Eqs. 2, 3)
+               V2 (RGCL, per-sample tau_img/tau_txt [N]; Eqs. 6, 7, 9)
+               V3 (RGCL-g, learnable global tau; Eqs. 2, 3, 10)
+    Returns a dict with g_img, g_txt, h_img, h_txt, u_new_img, u_new_txt, d_img,
+    d_txt ([b, d]), loss, and d_tau (v0, v3) or d_tau_img, d_tau_txt ([b], v2).
+    """
+    img = np.asarray(img, dtype=np.float64)
+    txt = np.asarray(txt, dtype=np.float64)
+    idx = np.asarray(idx, dtype=np.int64)
+    B, d = img.shape
+    assert txt.shape == (B, d) and B >= 2 and 1 <= b and 0 <= off and off + b <= B
+    assert idx.shape == (b,) and 0.0 < gamma <= 1.0 and eps >= 0.0
+    M = B - 1                                    # |B_{i-}|
+    rows = off + np.arange(b)                    # global row p of local anchor r
+    I_loc, T_loc = img[rows], txt[rows]
+
+    # temperatures entering l1 / l2 of each anchor (Proc. 1: global or individual)
+    if version == V2:
+        tau1 = np.asarray(tau_img, dtype=np.float64)[idx]
+        tau2 = np.asarray(tau_txt, dtype=np.float64)[idx]
+    else:
+        tau1 = np.full(b, float(tau))
+        tau2 = np.full(b, float(tau))
+
+    # similarities: image anchors against every text, text anchors against every image
+    S1 = I_loc @ txt.T                           # S1[r, j] = s_{p j}
+    S2 = T_loc @ img.T                           # S2[r, j] = s_{j p}
+    s_pp = np.einsum("rk,rk->r", I_loc, T_loc)   # s_ii of each anchor
+
+    # Proc. 1: l1, l2 over the batch without the anchor itself, and their means
+    X1 = S1 - s_pp[:, None]
+    X2 = S2 - s_pp[:, None]
+    E1 = np.exp(X1 / tau1[:, None])
+    E2 = np.exp(X2 / tau2[:, None])
+    E1[np.arange(b), rows] = 0.0                 # j = i is not in B_{i-}
+    E2[np.arange(b), rows] = 0.0
+    g1 = E1.sum(axis=1) / M
+    g2 = E2.sum(axis=1) / M
+    # h = mean of (s - s_ii) * l, so that d g / d tau = -h / tau^2  (nabla_3 l of Eqs. 8-10)
+    h1 = (X1 * E1).sum(axis=1) / M
+    h2 = (X2 * E2).sum(axis=1) / M
+
+    # Eq. 1: moving average at the batch positions, everything else untouched
+    def ema(u_arr, g):
+        old = np.asarray(u_arr[idx], dtype=np.float64)
+        new = np.where(old == 0.0, g, (1.0 - gamma) * old + gamma * g)
+        u_arr[idx] = new
+        return new
+    u1 = ema(u_img, g1)
+    u2 = ema(u_txt, g2)
+
+    # outer derivative f'(u) = 1/(eps+u), times the 1/|B_k| and 1/|B_{i-}| of Eqs. 2-7,
+    # times the leading factor (tau, 1, or tau_i) and the 1/tau that d l / d s brings
+    if version == V0:
+        c1 = 1.0 / (tau1 * b * M * (eps + u1))
+        c2 = 1.0 / (tau2 * b * M * (eps + u2))
+    else:                                        # leading tau (or tau_i) cancels the 1/tau
+        c1 = 1.0 / (b * M * (eps + u1))
+        c2 = 1.0 / (b * M * (eps + u2))
+
+    # Eq. 2 / 4 / 6: anchor side.  d l1(i,j)/d e_{1,i} = l1 (e_{2,j} - e_{2,i}) / tau,
+    # d l2(i,j)/d e_{1,i} = -l2 e_{2,i} / tau, and the mirror images for e_{2,i}.
+    d_img = c1[:, None] * (E1 @ txt - (M * g1)[:, None] * T_loc) - (c2 * M * g2)[:, None] * T_loc
+    d_txt = c2[:, None] * (E2 @ img - (M * g2)[:, None] * I_loc) - (c1 * M * g1)[:, None] * I_loc
+    # Eq. 3 / 5 / 7 restricted to local anchors i: local row p is a contrast of the
+    # other local anchors r'.  l2(r', p) = exp((s_{p p'} - s_{p'p'}) / tau2_{r'}) moves image
+    # row p, l1(r', p) = exp((s_{p'p} - s_{p'p'}) / tau1_{r'}) moves text row p.
+    L2 = np.exp((S1[:, rows] - s_pp[None, :]) / tau2[None, :]) * c2[None, :]
+    L1 = np.exp((S2[:, rows] - s_pp[None, :]) / tau1[None, :]) * c1[None, :]
+    np.fill_diagonal(L2, 0.0)
+    np.fill_diagonal(L1, 0.0)
+    d_img += L2 @ T_loc
+    d_txt += L1 @ I_loc
+
+    out = dict(g_img=g1, g_txt=g2, h_img=h1, h_txt=h2, u_new_img=u1, u_new_txt=u2,
+               d_img=d_img, d_txt=d_txt)
+    log1, log2 = np.log(eps + u1), np.log(eps + u2)
+    if version == V1:
+        out["loss"] = float(tau) * np.mean(log1 + log2)
+    elif version == V0:                          # Eq. 8
+        out["loss"] = np.mean(log1 + log2)
+        out["d_tau"] = -np.mean(h1 / (eps + u1) + h2 / (eps + u2)) / float(tau) ** 2
+    elif version == V3:                          # Eq. 10
+        out["loss"] = float(tau) * np.mean(log1 + log2) + 2.0 * rho * float(tau)
+        out["d_tau"] = (np.mean(log1 + log2) + 2.0 * rho
+                        - np.mean(h1 / (eps + u1) + h2 / (eps + u2)) / float(tau))
+    elif version == V2:                          # Eq. 9
+        out["loss"] = np.mean(tau1 * (log1 + rho) + tau2 * (log2 + rho))
+        out["d_tau_img"] = tau_grad_scale * (log1 + rho - h1 / (tau1 * (eps + u1)))
+        out["d_tau_txt"] = tau_grad_scale * (log2 + rho - h2 / (tau2 * (eps + u2)))
+    else:
+        raise ValueError("unknown version")
+    return out
