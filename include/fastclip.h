@@ -1,0 +1,153 @@
+/*
+ * fastclip.h - C ABI of the MI355X (gfx950) FCCO global-contrastive-loss step.
+ *
+ * One call of fastclip_step() is one worker's share of one FastCLIP iteration:
+ * Alg. 1 line 6 (the mini-batch contrastive terms g1, g2 of Proc. 1), line 7 (the
+ * moving-average update of the per-sample estimators u, Eq. 1), line 9 (the gradient
+ * estimator of Proc. 2, Eqs. 2-7, here with respect to the local embedding rows) and the
+ * gradient half of line 12 (the temperature gradients, Eqs. 8-10).
+ *
+ * Conventions
+ *   - Every pointer in fastclip_buffers and every `workspace` is DEVICE memory owned by
+ *     the caller.  The library never allocates, frees, or keeps state between calls.
+ *   - `stream` is a hipStream_t passed as void*.  All work is enqueued on it; no call
+ *     synchronises except where stated.  Outputs are valid once the stream has reached
+ *     the end of the call.
+ *   - Host-checkable errors are reported before anything is launched and leave every
+ *     buffer untouched.
+ *   - Matrices are row-major.  B = rows of the gathered global batch, b = local anchors,
+ *     which are the global rows off .. off+b-1; M = B-1.  Local anchor r is dataset sample
+ *     idx[r].  Similarities are plain dot products of the rows as given (the caller
+ *     normalises); gradients are with respect to those rows.
+ */
+#ifndef FASTCLIP_H
+#define FASTCLIP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  FASTCLIP_OK = 0,
+  FASTCLIP_ERR_NULL = 1,        /* a required pointer is NULL */
+  FASTCLIP_ERR_SHAPE = 2,       /* B<2, b<1, off<0, off+b>B, d<1, ld<d, N<1, bad struct_size */
+  FASTCLIP_ERR_VALUE = 3,       /* gamma not in (0,1], eps<0, NaN scalar, unknown version or dtype */
+  FASTCLIP_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than fastclip_workspace_bytes() */
+  FASTCLIP_ERR_UNSUPPORTED = 5, /* bf16 path: d or a row stride not a multiple of 8, or a matrix base
+                                   not 16-byte aligned; any path: B, b or d above 2^24 */
+  FASTCLIP_ERR_LAUNCH = 6,      /* the HIP runtime reported an error */
+  FASTCLIP_ERR_INDEX = 7        /* fastclip_check_indices: out-of-range or repeated index */
+} fastclip_status;
+
+/* Temperature scheme / loss (Sec. 4 "The Temperature Parameter Updates"):
+ *   V0  GCL without its leading tau, learnable global tau      (Eqs. 4, 5, 8)
+ *   V1  GCL, constant global tau                               (Eqs. 2, 3)
+ *   V2  RGCL, one learnable tau per sample and side            (Eqs. 6, 7, 9)
+ *   V3  RGCL-g, learnable global tau                           (Eqs. 2, 3, 10)          */
+typedef enum { FASTCLIP_V0 = 0, FASTCLIP_V1 = 1, FASTCLIP_V2 = 2, FASTCLIP_V3 = 3 } fastclip_version_t;
+
+/* Embedding storage type.  F32: accuracy path (fp32 rows, sums carried in fp64).
+ * BF16: MFMA path (bf16 rows, fp32 accumulation; exp values are rounded to bf16 only
+ * where they are operands of the gradient contractions). */
+typedef enum { FASTCLIP_F32 = 0, FASTCLIP_BF16 = 1 } fastclip_dtype;
+
+typedef struct {
+  uint32_t struct_size;      /* sizeof(fastclip_config) */
+  int32_t  version;          /* fastclip_version_t */
+  int32_t  emb_dtype;        /* fastclip_dtype */
+  int32_t  reserved;         /* must be 0 */
+  int64_t  B, b, off, d;     /* global rows, local anchors, first local row, embedding width */
+  int64_t  ld_img, ld_txt;   /* row strides of img_glob / txt_glob in elements, >= d */
+  int64_t  N;                /* length of the state arrays */
+  float    gamma;            /* inner learning rate of Eq. 1, in (0, 1] */
+  float    eps;              /* the small constant inside log(eps + g) */
+  float    rho;              /* RGCL / RGCL-g hyper-parameter (V2, V3) */
+  float    tau_grad_scale;   /* V2: factor in front of Eq. 9 (the paper prints 1/|S|) */
+} fastclip_config;
+
+typedef struct {
+  const void*    img_glob;   /* [B, ld_img] image embeddings of the global batch */
+  const void*    txt_glob;   /* [B, ld_txt] text embeddings of the global batch */
+  const int64_t* idx;        /* [b] dataset indices of the local anchors, in [0,N), distinct */
+  float*         u_img;      /* [N] in/out: u_1 of Eq. 1.  A stored 0.0f means "never visited":
+                                the first visit stores g whatever gamma is */
+  float*         u_txt;      /* [N] in/out: u_2 */
+  const float*   tau;        /* [1] global temperature, read on the device (V0, V1, V3) */
+  const float*   tau_img;    /* [N] per-sample temperatures tau_1 (V2); never written */
+  const float*   tau_txt;    /* [N] per-sample temperatures tau_2 (V2) */
+  float*         d_img;      /* [b, d] out: gradient w.r.t. the local image rows, fully overwritten */
+  float*         d_txt;      /* [b, d] out: gradient w.r.t. the local text rows */
+  float*         loss;       /* [1] out: local-batch objective with g replaced by u^{t+1} */
+  float*         d_tau;      /* [1] out: Eq. 8 (V0) / Eq. 10 (V3); required for V0 and V3 */
+  float*         d_tau_img;  /* [b] out, batch order: Eq. 9 first line (V2) */
+  float*         d_tau_txt;  /* [b] out: Eq. 9 second line (V2) */
+  float*         g_img;      /* [b] out, optional (NULL to skip): g_1 of Proc. 1 */
+  float*         g_txt;      /* [b] out, optional: g_2 */
+  float*         u_new_img;  /* [b] out, optional: u_1^{t+1} of the local anchors in batch order
+                                (what a multi-worker caller would All_Gather, Alg. 1 line 8) */
+  float*         u_new_txt;  /* [b] out, optional */
+} fastclip_buffers;
+
+/* Bytes of device workspace fastclip_step needs for this configuration; 0 if the
+ * configuration is invalid.  Pure host function. */
+size_t fastclip_workspace_bytes(const fastclip_config* cfg);
+
+/* Validate a configuration (and, if bufs != NULL, the pointers it requires) exactly as
+ * fastclip_step does, without launching anything.  Pure host function. */
+fastclip_status fastclip_validate(const fastclip_config* cfg, const fastclip_buffers* bufs);
+
+/* The step (Alg. 1 lines 6, 7, 9 and the gradient of line 12; Proc. 1, Eq. 1, Proc. 2,
+ * Eqs. 2-10).  Preconditions that cannot be checked without a device round trip and are
+ * therefore the caller's: idx values distinct and in range (see fastclip_check_indices),
+ * temperatures >= 0.023 for unit-norm rows so that exp((s - s_ii)/tau) stays finite in fp32.
+ * `workspace` must be 256-byte aligned.  Asynchronous on `stream`. */
+fastclip_status fastclip_step(const fastclip_config* cfg, const fastclip_buffers* bufs,
+                              void* workspace, size_t workspace_bytes, void* stream);
+
+/* Same step, but brackets every kernel with HIP events on `stream`, synchronises, and
+ * writes the duration of each phase in milliseconds to phase_ms[0 .. FASTCLIP_N_PHASES-1]
+ * (host memory; phases that a path does not run are reported as 0).  Measurement aid:
+ * it creates and destroys events and blocks the calling thread. */
+#define FASTCLIP_N_PHASES 8
+#define FASTCLIP_PHASE_PREP 0      /* s_ii and temperature gather */
+#define FASTCLIP_PHASE_STRIPS 1    /* similarity strips + exp + row sums (Proc. 1) */
+#define FASTCLIP_PHASE_STATE 2     /* Eq. 1 gather / update / scatter, coefficients, scalars */
+#define FASTCLIP_PHASE_LOCAL 3     /* local contrast block of Eqs. 3/5/7 (operand preparation) */
+#define FASTCLIP_PHASE_CONTRACT 4  /* gradient contractions of Eqs. 2-7 */
+#define FASTCLIP_PHASE_FINALIZE 5  /* split sums, scaling, diagonal terms, loss and tau gradient */
+fastclip_status fastclip_step_timed(const fastclip_config* cfg, const fastclip_buffers* bufs,
+                                    void* workspace, size_t workspace_bytes, void* stream,
+                                    float* phase_ms);
+const char* fastclip_phase_name(int phase);
+
+/* Eq. 1 alone, for n anchors whose exp-sums are already known (the state phase of
+ * fastclip_step run on its own; used to measure the gather/update/scatter kernel on many
+ * indices).  sum_img[r] / sum_txt[r] hold M * g_1 / M * g_2 of anchor r (device, [n]);
+ * u_img/u_txt [N] are updated in place at idx; u_new_img / u_new_txt [n] receive the new
+ * values in batch order.  M = the divisor |B_{i-}|.  Asynchronous on `stream`. */
+fastclip_status fastclip_state_update(const int64_t* idx, int64_t n, int64_t N, float gamma, float M,
+                                      const float* sum_img, const float* sum_txt,
+                                      float* u_img, float* u_txt,
+                                      float* u_new_img, float* u_new_txt, void* stream);
+
+/* Debug aid: checks on the device that idx[0..b) are distinct and inside [0, N).
+ * Needs fastclip_check_indices_workspace_bytes(b) bytes of workspace.  SYNCHRONISES the
+ * stream.  Returns FASTCLIP_OK or FASTCLIP_ERR_INDEX. */
+size_t fastclip_check_indices_workspace_bytes(int64_t b);
+fastclip_status fastclip_check_indices(const int64_t* idx, int64_t b, int64_t N,
+                                       void* workspace, size_t workspace_bytes, void* stream);
+
+/* Cosine schedule of the inner learning rate (Sec. 4 "The Inner LR Schedule"):
+ * epoch = t / iters_per_epoch; 0.5 (1 + cos(pi epoch / decay_epochs)) (1 - gamma_min) + gamma_min
+ * while epoch < decay_epochs, gamma_min afterwards.  Pure host function. */
+float fastclip_gamma_cosine(int64_t t, int64_t iters_per_epoch, int64_t decay_epochs, float gamma_min);
+
+const char* fastclip_status_string(fastclip_status s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FASTCLIP_H */

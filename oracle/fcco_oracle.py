@@ -77,6 +77,19 @@ def check_indices(idx, n_state: int) -> bool:
     return np.unique(idx).size == idx.size
 
 
+def ema_update(u_arr, idx, g, gamma):
+    """Eq. 1 at positions idx of the state array u_arr (modified in place); returns the new values.
+
+    A stored value of exactly zero means "never visited" and is replaced by g whatever gamma is.
+    """
+    idx = np.asarray(idx, dtype=np.int64)
+    g = np.asarray(g, dtype=np.float64)
+    old = np.asarray(u_arr[idx], dtype=np.float64)
+    new = np.where(old == 0.0, g, (1.0 - gamma) * old + gamma * g)
+    u_arr[idx] = new
+    return new
+
+
 def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0.0,
               tau=None, tau_img=None, tau_txt=None, tau_grad_scale=1.0):
     """One FCCO step of worker k.  Updates u_img / u_txt IN PLACE at idx.
@@ -129,13 +142,8 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
     h2 = (X2 * E2).sum(axis=1) / M
 
     # Eq. 1: moving average at the batch positions, everything else untouched
-    def ema(u_arr, g):
-        old = np.asarray(u_arr[idx], dtype=np.float64)
-        new = np.where(old == 0.0, g, (1.0 - gamma) * old + gamma * g)
-        u_arr[idx] = new
-        return new
-    u1 = ema(u_img, g1)
-    u2 = ema(u_txt, g2)
+    u1 = ema_update(u_img, idx, g1, gamma)
+    u2 = ema_update(u_txt, idx, g2, gamma)
 
     # outer derivative f'(u) = 1/(eps+u), times the 1/|B_k| and 1/|B_{i-}| of Eqs. 2-7,
     # times the leading factor (tau, 1, or tau_i) and the 1/tau that d l / d s brings

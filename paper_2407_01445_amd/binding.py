@@ -1,0 +1,170 @@
+"""ctypes binding of libfastclip.so: the same names as include/fastclip.h, argument marshalling only.
+
+PyTorch is used for nothing but device memory (`tensor.data_ptr()`) and the current
+stream handle; every step of the path runs in the library's HIP kernels.  There is no
+CPU or PyTorch fallback: if the library cannot be loaded, calls raise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libfastclip.so")
+
+OK, ERR_NULL, ERR_SHAPE, ERR_VALUE, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_INDEX = range(8)
+V0, V1, V2, V3 = 0, 1, 2, 3
+F32, BF16 = 0, 1
+N_PHASES = 8
+
+
+class fastclip_config(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("version", C.c_int32), ("emb_dtype", C.c_int32),
+                ("reserved", C.c_int32),
+                ("B", C.c_int64), ("b", C.c_int64), ("off", C.c_int64), ("d", C.c_int64),
+                ("ld_img", C.c_int64), ("ld_txt", C.c_int64), ("N", C.c_int64),
+                ("gamma", C.c_float), ("eps", C.c_float), ("rho", C.c_float), ("tau_grad_scale", C.c_float)]
+
+
+_BUF_FIELDS = ["img_glob", "txt_glob", "idx", "u_img", "u_txt", "tau", "tau_img", "tau_txt", "d_img", "d_txt",
+               "loss", "d_tau", "d_tau_img", "d_tau_txt", "g_img", "g_txt", "u_new_img", "u_new_txt"]
+
+
+class fastclip_buffers(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _BUF_FIELDS]
+
+
+_lib = None
+
+
+def load(build_if_missing: bool = True):
+    """Load libfastclip.so (building it first only if it does not exist)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise RuntimeError("libfastclip.so is not built: run __graft_entry__.build()")
+        from .build import build
+        build()
+    lib = C.CDLL(LIB_PATH)
+    cfgp, bufp = C.POINTER(fastclip_config), C.POINTER(fastclip_buffers)
+    lib.fastclip_workspace_bytes.restype = C.c_size_t
+    lib.fastclip_workspace_bytes.argtypes = [cfgp]
+    lib.fastclip_validate.restype = C.c_int
+    lib.fastclip_validate.argtypes = [cfgp, bufp]
+    lib.fastclip_step.restype = C.c_int
+    lib.fastclip_step.argtypes = [cfgp, bufp, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fastclip_step_timed.restype = C.c_int
+    lib.fastclip_step_timed.argtypes = [cfgp, bufp, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
+    lib.fastclip_phase_name.restype = C.c_char_p
+    lib.fastclip_phase_name.argtypes = [C.c_int]
+    lib.fastclip_state_update.restype = C.c_int
+    lib.fastclip_state_update.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_float, C.c_float] + [C.c_void_p] * 7
+    lib.fastclip_check_indices_workspace_bytes.restype = C.c_size_t
+    lib.fastclip_check_indices_workspace_bytes.argtypes = [C.c_int64]
+    lib.fastclip_check_indices.restype = C.c_int
+    lib.fastclip_check_indices.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fastclip_gamma_cosine.restype = C.c_float
+    lib.fastclip_gamma_cosine.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_float]
+    lib.fastclip_status_string.restype = C.c_char_p
+    lib.fastclip_status_string.argtypes = [C.c_int]
+    _lib = lib
+    return lib
+
+
+class FastclipError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__("fastclip: %s (status %d)" % (fastclip_status_string(status), status))
+
+
+def make_config(*, version, emb_dtype, B, b, off, d, N, gamma, eps, rho=0.0, tau_grad_scale=1.0,
+                ld_img=None, ld_txt=None) -> fastclip_config:
+    return fastclip_config(C.sizeof(fastclip_config), int(version), int(emb_dtype), 0, int(B), int(b), int(off),
+                           int(d), int(d if ld_img is None else ld_img), int(d if ld_txt is None else ld_txt),
+                           int(N), float(gamma), float(eps), float(rho), float(tau_grad_scale))
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if not t.is_cuda:
+        raise TypeError("fastclip buffers must be device tensors")
+    return t.data_ptr()
+
+
+def make_buffers(**tensors) -> fastclip_buffers:
+    """Field name -> CUDA tensor (or raw device address, or None)."""
+    unknown = set(tensors) - set(_BUF_FIELDS)
+    if unknown:
+        raise TypeError("unknown buffer(s): %s" % sorted(unknown))
+    return fastclip_buffers(*[_ptr(tensors.get(n)) for n in _BUF_FIELDS])
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def fastclip_workspace_bytes(cfg: fastclip_config) -> int:
+    return int(load().fastclip_workspace_bytes(C.byref(cfg)))
+
+
+def fastclip_validate(cfg, bufs=None) -> int:
+    return int(load().fastclip_validate(C.byref(cfg) if cfg is not None else None,
+                                        C.byref(bufs) if bufs is not None else None))
+
+
+def fastclip_step(cfg, bufs, workspace, workspace_bytes=None, stream=None, check=True) -> int:
+    """workspace: CUDA uint8 tensor (or raw address with workspace_bytes given)."""
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    st = int(load().fastclip_step(C.byref(cfg), C.byref(bufs), _ptr(workspace), nbytes, _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+def fastclip_step_timed(cfg, bufs, workspace, workspace_bytes=None, stream=None):
+    """Returns {phase name: milliseconds}.  Synchronises."""
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    ms = (C.c_float * N_PHASES)()
+    st = int(load().fastclip_step_timed(C.byref(cfg), C.byref(bufs), _ptr(workspace), nbytes, _stream(stream), ms))
+    if st != OK:
+        raise FastclipError(st)
+    return {fastclip_phase_name(i): float(ms[i]) for i in range(N_PHASES) if fastclip_phase_name(i) != "unused"}
+
+
+def fastclip_phase_name(phase: int) -> str:
+    return load().fastclip_phase_name(phase).decode()
+
+
+def fastclip_state_update(idx, n, N, gamma, M, sum_img, sum_txt, u_img, u_txt, u_new_img, u_new_txt,
+                          stream=None, check=True) -> int:
+    st = int(load().fastclip_state_update(_ptr(idx), int(n), int(N), float(gamma), float(M), _ptr(sum_img),
+                                          _ptr(sum_txt), _ptr(u_img), _ptr(u_txt), _ptr(u_new_img),
+                                          _ptr(u_new_txt), _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+def fastclip_check_indices_workspace_bytes(b: int) -> int:
+    return int(load().fastclip_check_indices_workspace_bytes(int(b)))
+
+
+def fastclip_check_indices(idx, b, N, workspace, workspace_bytes=None, stream=None) -> int:
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    return int(load().fastclip_check_indices(_ptr(idx), int(b), int(N), _ptr(workspace), nbytes, _stream(stream)))
+
+
+def fastclip_gamma_cosine(t, iters_per_epoch, decay_epochs, gamma_min) -> float:
+    return float(load().fastclip_gamma_cosine(int(t), int(iters_per_epoch), int(decay_epochs), float(gamma_min)))
+
+
+def fastclip_status_string(status: int) -> str:
+    return load().fastclip_status_string(int(status)).decode()

@@ -1,0 +1,245 @@
+// C ABI of libfastclip: argument validation, workspace carving, launch sequences.
+// The arithmetic lives in the kernel translation units; nothing here runs on the CPU
+// except checks, address arithmetic and the gamma schedule.
+#include <math.h>
+#include <string.h>
+
+#include "fc_internal.hpp"
+
+namespace fc {
+
+static bool bad_float(float x) { return !(x == x) || isinf(x); }
+
+fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
+  if (!cfg) return FASTCLIP_ERR_NULL;
+  if (cfg->struct_size != sizeof(fastclip_config) || cfg->reserved != 0) return FASTCLIP_ERR_SHAPE;
+  if (cfg->B < 2 || cfg->b < 1 || cfg->off < 0 || cfg->off + cfg->b > cfg->B || cfg->d < 1 ||
+      cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1)
+    return FASTCLIP_ERR_SHAPE;
+  if (cfg->version < FASTCLIP_V0 || cfg->version > FASTCLIP_V3) return FASTCLIP_ERR_VALUE;
+  if (cfg->emb_dtype != FASTCLIP_F32 && cfg->emb_dtype != FASTCLIP_BF16) return FASTCLIP_ERR_VALUE;
+  if (bad_float(cfg->gamma) || bad_float(cfg->eps) || bad_float(cfg->rho) || bad_float(cfg->tau_grad_scale))
+    return FASTCLIP_ERR_VALUE;
+  if (!(cfg->gamma > 0.0f && cfg->gamma <= 1.0f) || cfg->eps < 0.0f) return FASTCLIP_ERR_VALUE;
+  const int64_t lim = (int64_t)1 << 24;
+  if (cfg->B > lim || cfg->b > lim || cfg->d > lim || cfg->ld_img > ((int64_t)1 << 30) ||
+      cfg->ld_txt > ((int64_t)1 << 30))
+    return FASTCLIP_ERR_UNSUPPORTED;
+  if (cfg->emb_dtype == FASTCLIP_BF16 && (cfg->d % 8 || cfg->ld_img % 8 || cfg->ld_txt % 8))
+    return FASTCLIP_ERR_UNSUPPORTED;
+  if (bufs) {
+    if (!bufs->img_glob || !bufs->txt_glob || !bufs->idx || !bufs->u_img || !bufs->u_txt ||
+        !bufs->d_img || !bufs->d_txt || !bufs->loss)
+      return FASTCLIP_ERR_NULL;
+    if (cfg->version == FASTCLIP_V2) {
+      if (!bufs->tau_img || !bufs->tau_txt || !bufs->d_tau_img || !bufs->d_tau_txt) return FASTCLIP_ERR_NULL;
+    } else {
+      if (!bufs->tau) return FASTCLIP_ERR_NULL;
+      if ((cfg->version == FASTCLIP_V0 || cfg->version == FASTCLIP_V3) && !bufs->d_tau) return FASTCLIP_ERR_NULL;
+    }
+    if (cfg->emb_dtype == FASTCLIP_BF16 &&
+        (((uintptr_t)bufs->img_glob & 15) || ((uintptr_t)bufs->txt_glob & 15)))
+      return FASTCLIP_ERR_UNSUPPORTED;
+    if (((uintptr_t)bufs->d_img & 15) || ((uintptr_t)bufs->d_txt & 15)) return FASTCLIP_ERR_UNSUPPORTED;
+  }
+  return FASTCLIP_OK;
+}
+
+void make_layout(const fastclip_config& cfg, Layout* L) {
+  memset(L, 0, sizeof(*L));
+  L->B = cfg.B; L->b = cfg.b; L->off = cfg.off; L->d = cfg.d; L->N = cfg.N;
+  L->bf16 = cfg.emb_dtype == FASTCLIP_BF16;
+  L->bstride = (int64_t)round_up((size_t)cfg.b, 64);
+  size_t at = 0;
+  auto take = [&](size_t bytes) { size_t o = at; at += round_up(bytes, 256); return o; };
+  const size_t fb = sizeof(float) * (size_t)L->bstride;
+  if (L->bf16) {
+    L->nparts = (int)((cfg.B + kTileContrasts - 1) / kTileContrasts);
+    L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
+    L->ldW = (int64_t)round_up((size_t)cfg.b, 64);
+    // split the contraction over contrasts so that the two strips give about one workgroup per CU
+    const int64_t tiles = ((cfg.b + 255) / 256) * ((cfg.d + 255) / 256) * 2;
+    int64_t want = (256 + tiles - 1) / tiles;
+    if (want > kMaxSplit) want = kMaxSplit;
+    if (want < 1) want = 1;
+    int64_t ks = (cfg.B + want - 1) / want;
+    ks = (int64_t)round_up((size_t)ks, kTileK);
+    if (ks < 4 * kTileK) ks = 4 * kTileK;
+    L->kslice = ks;
+    L->nsplit = (int)((cfg.B + ks - 1) / ks);
+  } else {
+    L->nparts = 1;
+    L->ldE = cfg.B;
+    L->ldW = 0;
+    L->nsplit = 0;
+    L->kslice = 0;
+  }
+  L->nstate_blocks = (int)((cfg.b + 31) / 32);
+  L->diag = take(fb); L->tau1 = take(fb); L->tau2 = take(fb); L->k1 = take(fb); L->k2 = take(fb);
+  L->sums = take(fb * 4 * (size_t)L->nparts);
+  L->c1 = take(fb); L->c2 = take(fb); L->dcoef = take(fb);
+  L->red = take(sizeof(float) * 2 * (size_t)L->nstate_blocks);
+  const size_t esz = L->bf16 ? sizeof(bf16_t) : sizeof(float);
+  for (int s = 0; s < 2; ++s) L->E[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
+  if (L->bf16) {
+    for (int s = 0; s < 2; ++s) L->WT[s] = take(sizeof(bf16_t) * (size_t)cfg.b * (size_t)L->ldW);
+    for (int s = 0; s < 2; ++s)
+      L->Opart[s] = take(sizeof(float) * (size_t)L->nsplit * (size_t)cfg.b * (size_t)cfg.d);
+    for (int s = 0; s < 2; ++s) L->A6[s] = take(sizeof(float) * (size_t)cfg.b * (size_t)cfg.d);
+  }
+  L->total = at;
+}
+
+static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffers* bufs, void* workspace,
+                                size_t workspace_bytes, void* stream, float* phase_ms) {
+  fastclip_status st = validate(cfg, bufs);
+  if (st != FASTCLIP_OK) return st;
+  if (!bufs) return FASTCLIP_ERR_NULL;
+  StepCtx c;
+  c.cfg = *cfg;
+  c.buf = *bufs;
+  make_layout(*cfg, &c.L);
+  if (!workspace) return FASTCLIP_ERR_NULL;
+  if (workspace_bytes < c.L.total || ((uintptr_t)workspace & 255)) return FASTCLIP_ERR_WORKSPACE;
+  c.ws = (char*)workspace;
+  c.s = (hipStream_t)stream;
+  (void)hipGetLastError();
+
+  hipEvent_t ev[FASTCLIP_N_PHASES + 1];
+  int nev = 0;
+  int phase_of[FASTCLIP_N_PHASES];
+  auto mark = [&](int phase) {
+    if (!phase_ms) return;
+    if (nev == 0) { (void)hipEventCreate(&ev[0]); (void)hipEventRecord(ev[0], c.s); nev = 1; }
+    if (phase >= 0) { (void)hipEventCreate(&ev[nev]); (void)hipEventRecord(ev[nev], c.s); phase_of[nev - 1] = phase; ++nev; }
+  };
+  mark(-1);
+  launch_prep(c);                         mark(FASTCLIP_PHASE_PREP);
+  if (c.L.bf16) {
+    launch_strips_bf16(c);                mark(FASTCLIP_PHASE_STRIPS);
+    launch_state(c);                      mark(FASTCLIP_PHASE_STATE);
+    launch_local_bf16(c);                 mark(FASTCLIP_PHASE_LOCAL);
+    launch_contract_bf16(c);              mark(FASTCLIP_PHASE_CONTRACT);
+    launch_finalize_bf16(c);              mark(FASTCLIP_PHASE_FINALIZE);
+  } else {
+    launch_strips_f32(c);                 mark(FASTCLIP_PHASE_STRIPS);
+    launch_state(c);                      mark(FASTCLIP_PHASE_STATE);
+    launch_grad_f32(c);                   mark(FASTCLIP_PHASE_FINALIZE);
+  }
+  fastclip_status rc = hipGetLastError() == hipSuccess ? FASTCLIP_OK : FASTCLIP_ERR_LAUNCH;
+  if (phase_ms) {
+    for (int i = 0; i < FASTCLIP_N_PHASES; ++i) phase_ms[i] = 0.0f;
+    if (hipStreamSynchronize(c.s) != hipSuccess) rc = FASTCLIP_ERR_LAUNCH;
+    for (int i = 0; i + 1 < nev; ++i) {
+      float ms = 0.0f;
+      if (rc == FASTCLIP_OK && hipEventElapsedTime(&ms, ev[i], ev[i + 1]) == hipSuccess) phase_ms[phase_of[i]] += ms;
+    }
+    for (int i = 0; i < nev; ++i) (void)hipEventDestroy(ev[i]);
+  }
+  return rc;
+}
+
+}  // namespace fc
+
+extern "C" {
+
+size_t fastclip_workspace_bytes(const fastclip_config* cfg) {
+  if (fc::validate(cfg, nullptr) != FASTCLIP_OK) return 0;
+  fc::Layout L;
+  fc::make_layout(*cfg, &L);
+  return L.total;
+}
+
+fastclip_status fastclip_validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
+  return fc::validate(cfg, bufs);
+}
+
+fastclip_status fastclip_step(const fastclip_config* cfg, const fastclip_buffers* bufs, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  return fc::run_step(cfg, bufs, workspace, workspace_bytes, stream, nullptr);
+}
+
+fastclip_status fastclip_step_timed(const fastclip_config* cfg, const fastclip_buffers* bufs, void* workspace,
+                                    size_t workspace_bytes, void* stream, float* phase_ms) {
+  if (!phase_ms) return FASTCLIP_ERR_NULL;
+  return fc::run_step(cfg, bufs, workspace, workspace_bytes, stream, phase_ms);
+}
+
+const char* fastclip_phase_name(int phase) {
+  switch (phase) {
+    case FASTCLIP_PHASE_PREP: return "prep";
+    case FASTCLIP_PHASE_STRIPS: return "strips";
+    case FASTCLIP_PHASE_STATE: return "state";
+    case FASTCLIP_PHASE_LOCAL: return "local";
+    case FASTCLIP_PHASE_CONTRACT: return "contract";
+    case FASTCLIP_PHASE_FINALIZE: return "finalize";
+    default: return "unused";
+  }
+}
+
+fastclip_status fastclip_state_update(const int64_t* idx, int64_t n, int64_t N, float gamma, float M,
+                                      const float* sum_img, const float* sum_txt, float* u_img, float* u_txt,
+                                      float* u_new_img, float* u_new_txt, void* stream) {
+  if (!idx || !sum_img || !sum_txt || !u_img || !u_txt || !u_new_img || !u_new_txt) return FASTCLIP_ERR_NULL;
+  if (n < 0 || N < 1 || n > ((int64_t)1 << 31) - 1024) return FASTCLIP_ERR_SHAPE;
+  if (fc::bad_float(gamma) || fc::bad_float(M) || !(gamma > 0.0f && gamma <= 1.0f) || !(M > 0.0f))
+    return FASTCLIP_ERR_VALUE;
+  if (n == 0) return FASTCLIP_OK;
+  (void)hipGetLastError();
+  fc::launch_state_flat(idx, n, N, gamma, M, sum_img, sum_txt, u_img, u_txt, u_new_img, u_new_txt,
+                        (hipStream_t)stream);
+  return hipGetLastError() == hipSuccess ? FASTCLIP_OK : FASTCLIP_ERR_LAUNCH;
+}
+
+static size_t table_slots(int64_t b) {
+  size_t s = 64;
+  while (s < (size_t)b * 2) s <<= 1;
+  return s;
+}
+
+size_t fastclip_check_indices_workspace_bytes(int64_t b) {
+  if (b < 0 || b > ((int64_t)1 << 28)) return 0;
+  return 256 + table_slots(b) * sizeof(int64_t);
+}
+
+fastclip_status fastclip_check_indices(const int64_t* idx, int64_t b, int64_t N, void* workspace,
+                                       size_t workspace_bytes, void* stream) {
+  if (!idx || !workspace) return FASTCLIP_ERR_NULL;
+  if (b < 0 || N < 1 || b > ((int64_t)1 << 28)) return FASTCLIP_ERR_SHAPE;
+  if (workspace_bytes < fastclip_check_indices_workspace_bytes(b) || ((uintptr_t)workspace & 255))
+    return FASTCLIP_ERR_WORKSPACE;
+  if (b == 0) return FASTCLIP_OK;
+  hipStream_t s = (hipStream_t)stream;
+  (void)hipGetLastError();
+  fc::launch_check_indices(idx, b, N, workspace, s);
+  int flag = 0;
+  if (hipGetLastError() != hipSuccess) return FASTCLIP_ERR_LAUNCH;
+  if (hipMemcpyAsync(&flag, workspace, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return FASTCLIP_ERR_LAUNCH;
+  if (hipStreamSynchronize(s) != hipSuccess) return FASTCLIP_ERR_LAUNCH;
+  return flag ? FASTCLIP_ERR_INDEX : FASTCLIP_OK;
+}
+
+float fastclip_gamma_cosine(int64_t t, int64_t iters_per_epoch, int64_t decay_epochs, float gamma_min) {
+  if (iters_per_epoch < 1) iters_per_epoch = 1;
+  if (t < 0) t = 0;
+  const int64_t epoch = t / iters_per_epoch;
+  if (decay_epochs < 1 || epoch >= decay_epochs) return gamma_min;
+  const double c = cos(M_PI * (double)epoch / (double)decay_epochs);
+  return (float)(0.5 * (1.0 + c) * (1.0 - (double)gamma_min) + (double)gamma_min);
+}
+
+const char* fastclip_status_string(fastclip_status s) {
+  switch (s) {
+    case FASTCLIP_OK: return "ok";
+    case FASTCLIP_ERR_NULL: return "a required pointer is NULL";
+    case FASTCLIP_ERR_SHAPE: return "invalid shape or struct_size";
+    case FASTCLIP_ERR_VALUE: return "invalid scalar, version or dtype";
+    case FASTCLIP_ERR_WORKSPACE: return "workspace too small or misaligned";
+    case FASTCLIP_ERR_UNSUPPORTED: return "unsupported size or alignment";
+    case FASTCLIP_ERR_LAUNCH: return "HIP runtime error";
+    case FASTCLIP_ERR_INDEX: return "index out of range or repeated";
+    default: return "unknown status";
+  }
+}
+
+}  // extern "C"

@@ -1,0 +1,69 @@
+// Internal declarations shared by the translation units of libfastclip (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "fastclip.h"
+
+namespace fc {
+
+typedef uint16_t bf16_t;  // raw bf16 bits in memory
+
+constexpr int kTileAnchors = 256;    // anchor rows per workgroup tile of the strip kernel
+constexpr int kTileContrasts = 256;  // contrast rows per workgroup tile of the strip kernel
+constexpr int kTileK = 64;           // contraction depth per LDS stage (bf16 elements)
+constexpr int kMaxSplit = 64;
+
+static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
+
+// Where everything lives inside the caller's workspace (byte offsets, 256-byte aligned).
+struct Layout {
+  int64_t B, b, off, d, N;
+  int bf16;          // 1: MFMA path, 0: fp32 accuracy path
+  int nparts;        // partial row sums per anchor and quantity written by the strip phase
+  int64_t bstride;   // anchors padded to a multiple of 64 (stride of the per-anchor arrays)
+  int64_t ldE;       // row stride of the stored exp strips (elements)
+  int64_t ldW;       // row stride of the transposed, scaled local blocks (elements)
+  int nsplit;        // split of the contraction over contrasts
+  int64_t kslice;    // contrasts per split
+  int nstate_blocks; // blocks of the state kernel (one scalar partial each)
+  size_t diag, tau1, tau2, k1, k2;   // float[bstride]
+  size_t sums;                       // float[4][nparts][bstride]: sum e1, sum x1 e1, sum e2, sum x2 e2
+  size_t c1, c2, dcoef;              // float[bstride]
+  size_t red;                        // float[nstate_blocks][2]
+  size_t E[2];                       // bf16 or float [b][ldE]
+  size_t WT[2];                      // bf16 [b][ldW]          (MFMA path)
+  size_t Opart[2];                   // float [nsplit][b][d]   (MFMA path)
+  size_t A6[2];                      // float [b][d]           (MFMA path)
+  size_t total;
+};
+
+fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* bufs);
+void make_layout(const fastclip_config& cfg, Layout* L);
+
+// ---- kernel launchers (each enqueues on `s` and returns; errors are read by the caller
+//      through hipGetLastError) -----------------------------------------------------------
+struct StepCtx {
+  fastclip_config cfg;
+  fastclip_buffers buf;
+  Layout L;
+  char* ws;
+  hipStream_t s;
+};
+
+void launch_prep(const StepCtx& c);            // s_ii, temperature gather / broadcast
+void launch_strips_f32(const StepCtx& c);      // accuracy path: exp strips + row sums
+void launch_strips_bf16(const StepCtx& c);     // MFMA path: exp strips + row sums
+void launch_state(const StepCtx& c);           // Eq. 1, coefficients, scalar partials
+void launch_grad_f32(const StepCtx& c);        // accuracy path: gradients + scalars
+void launch_local_bf16(const StepCtx& c);      // MFMA path: scaled, transposed local blocks
+void launch_contract_bf16(const StepCtx& c);   // MFMA path: E x X contractions
+void launch_finalize_bf16(const StepCtx& c);   // MFMA path: combine + scalars
+
+void launch_state_flat(const int64_t* idx, int64_t n, int64_t N, float gamma, float M,
+                       const float* sum_img, const float* sum_txt, float* u_img, float* u_txt,
+                       float* u_new_img, float* u_new_txt, hipStream_t s);
+void launch_check_indices(const int64_t* idx, int64_t b, int64_t N, void* ws, hipStream_t s);
+
+}  // namespace fc

@@ -1,0 +1,422 @@
+// Small kernels of the FCCO step: s_ii and temperature gather, the state update of Eq. 1 with
+// the per-anchor coefficients, the fp32-storage accuracy path (strips and gradients in
+// plain loops with fp64 accumulation), the scalar outputs, and the index checker.
+#include "fc_internal.hpp"
+
+namespace fc {
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+__device__ inline double wave_sum(double v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+__device__ inline float load_elem(const float* p) { return *p; }
+__device__ inline float load_elem(const bf16_t* p) { return __uint_as_float((uint32_t)(*p) << 16); }
+
+// ------------------------------------------------------------------------------------------
+// prep: one wavefront per local anchor r.  s_pp = <img_p, txt_p> (the s_ii of Sec. 3), the
+// temperatures that enter l1 / l2 of this anchor (Proc. 1: global tau, or tau_1[idx], tau_2[idx]),
+// and k = log2(e) / tau for the exp2-based evaluation in the MFMA path.
+template <typename T>
+__global__ void __launch_bounds__(256) k_prep(const T* __restrict__ img, const T* __restrict__ txt, int64_t ld_img,
+                                              int64_t ld_txt, int64_t off, int64_t b, int64_t d,
+                                              const int64_t* __restrict__ idx, const float* __restrict__ tau,
+                                              const float* __restrict__ tau_img, const float* __restrict__ tau_txt,
+                                              int version, float* __restrict__ diag, float* __restrict__ tau1,
+                                              float* __restrict__ tau2, float* __restrict__ k1, float* __restrict__ k2) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= b) return;
+  const T* pi = img + (off + r) * ld_img;
+  const T* pt = txt + (off + r) * ld_txt;
+  double acc = 0.0;
+  for (int64_t k = lane; k < d; k += 64) acc += (double)load_elem(pi + k) * (double)load_elem(pt + k);
+  acc = wave_sum(acc);
+  if (lane == 0) {
+    float t1, t2;
+    if (version == FASTCLIP_V2) {
+      const int64_t n = idx[r];
+      t1 = tau_img[n];
+      t2 = tau_txt[n];
+    } else {
+      t1 = t2 = tau[0];
+    }
+    diag[r] = (float)acc;
+    tau1[r] = t1;
+    tau2[r] = t2;
+    k1[r] = kLog2e / t1;
+    k2[r] = kLog2e / t2;
+  }
+}
+
+void launch_prep(const StepCtx& c) {
+  const Layout& L = c.L;
+  float* diag = (float*)(c.ws + L.diag);
+  float* tau1 = (float*)(c.ws + L.tau1);
+  float* tau2 = (float*)(c.ws + L.tau2);
+  float* k1 = (float*)(c.ws + L.k1);
+  float* k2 = (float*)(c.ws + L.k2);
+  dim3 grid((unsigned)((L.b + 3) / 4)), block(256);
+  if (L.bf16)
+    hipLaunchKernelGGL(k_prep<bf16_t>, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
+                       c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, c.buf.idx, c.buf.tau, c.buf.tau_img,
+                       c.buf.tau_txt, c.cfg.version, diag, tau1, tau2, k1, k2);
+  else
+    hipLaunchKernelGGL(k_prep<float>, grid, block, 0, c.s, (const float*)c.buf.img_glob, (const float*)c.buf.txt_glob,
+                       c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, c.buf.idx, c.buf.tau, c.buf.tau_img,
+                       c.buf.tau_txt, c.cfg.version, diag, tau1, tau2, k1, k2);
+}
+
+// ------------------------------------------------------------------------------------------
+// Accuracy path, strips (Proc. 1).  Block (r, side): anchor r against every contrast row j != p;
+// side 0: image anchor vs texts (l1), side 1: text anchor vs images (l2).  One wavefront per
+// contrast row, fp64 accumulation; stores l as fp32 and the two row sums.
+__global__ void __launch_bounds__(256) k_strips_f32(const float* __restrict__ img, const float* __restrict__ txt,
+                                                    int64_t ld_img, int64_t ld_txt, int64_t off, int64_t b, int64_t B,
+                                                    int64_t d, const float* __restrict__ diag,
+                                                    const float* __restrict__ tau1, const float* __restrict__ tau2,
+                                                    float* __restrict__ E1, float* __restrict__ E2, int64_t ldE,
+                                                    float* __restrict__ sums, int64_t bstride) {
+  const int64_t r = blockIdx.x;
+  const int side = blockIdx.y;
+  const int64_t p = off + r;
+  const float* anchor = side == 0 ? img + p * ld_img : txt + p * ld_txt;
+  const float* X = side == 0 ? txt : img;
+  const int64_t ldx = side == 0 ? ld_txt : ld_img;
+  float* E = (side == 0 ? E1 : E2) + r * ldE;
+  const double s_pp = (double)diag[r];
+  const double tau = (double)(side == 0 ? tau1[r] : tau2[r]);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  double sg = 0.0, sh = 0.0;
+  for (int64_t j = wave; j < B; j += 4) {
+    const float* x = X + j * ldx;
+    double acc = 0.0;
+    for (int64_t k = lane; k < d; k += 64) acc += (double)anchor[k] * (double)x[k];
+    acc = wave_sum(acc);
+    const double xs = acc - s_pp;
+    const double e = j == p ? 0.0 : exp(xs / tau);
+    if (lane == 0) E[j] = (float)e;
+    sg += e;
+    sh += xs * e;
+  }
+  __shared__ double red[2][4];
+  if (lane == 0) { red[0][wave] = sg; red[1][wave] = sh; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    // quantities 0,1 belong to side 0 (sum e1, sum x1 e1), 2,3 to side 1; nparts == 1 on this path
+    sums[(size_t)(2 * side + 0) * bstride + r] = (float)(red[0][0] + red[0][1] + red[0][2] + red[0][3]);
+    sums[(size_t)(2 * side + 1) * bstride + r] = (float)(red[1][0] + red[1][1] + red[1][2] + red[1][3]);
+  }
+}
+
+void launch_strips_f32(const StepCtx& c) {
+  const Layout& L = c.L;
+  dim3 grid((unsigned)L.b, 2), block(256);
+  hipLaunchKernelGGL(k_strips_f32, grid, block, 0, c.s, (const float*)c.buf.img_glob, (const float*)c.buf.txt_glob,
+                     c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.B, L.d, (const float*)(c.ws + L.diag),
+                     (const float*)(c.ws + L.tau1), (const float*)(c.ws + L.tau2), (float*)(c.ws + L.E[0]),
+                     (float*)(c.ws + L.E[1]), L.ldE, (float*)(c.ws + L.sums), L.bstride);
+}
+
+// ------------------------------------------------------------------------------------------
+// State phase.  Eq. 1 at the batch positions (first visit: stored 0 -> g), the coefficient
+// 1/(|B_k| |B_i-| (eps+u)) of Eqs. 2-7 (with the extra 1/tau of Eqs. 4-5 for V0), Eq. 9 per anchor,
+// and per-block partial sums of the two scalars that Eqs. 8 and 10 and the loss need.
+struct StateArgs {
+  const int64_t* idx;
+  float *u_img, *u_txt;
+  const float *tau1, *tau2;
+  const float* sums;   // [4][nparts][bstride]
+  int nparts;
+  int64_t bstride, b;
+  float M, gamma, eps, rho, tau_scale;
+  int version;
+  float *c1, *c2, *dcoef, *red;
+  float *d_tau_img, *d_tau_txt, *g_img, *g_txt, *u_new_img, *u_new_txt;
+};
+
+__device__ inline float ema_update(float u_old, float g, float gamma) {
+  return u_old == 0.0f ? g : fmaf(gamma, g, (1.0f - gamma) * u_old);
+}
+
+// 256 threads = 32 anchors x 8 groups over the partial sums.
+__global__ void __launch_bounds__(256) k_state(StateArgs a) {
+  __shared__ float part[4][8][32];
+  __shared__ float scal[2][32];
+  const int al = threadIdx.x & 31, grp = threadIdx.x >> 5;
+  const int64_t r = (int64_t)blockIdx.x * 32 + al;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  if (r < a.b) {
+    for (int pt = grp; pt < a.nparts; pt += 8) {
+#pragma unroll
+      for (int q = 0; q < 4; ++q) acc[q] += a.sums[((size_t)q * a.nparts + pt) * a.bstride + r];
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) part[q][grp][al] = acc[q];
+  __syncthreads();
+  if (threadIdx.x < 32) {
+    float lsum = 0.f, hsum = 0.f;
+    if (r < a.b) {
+      float s[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        float t = 0.f;
+#pragma unroll
+        for (int g = 0; g < 8; ++g) t += part[q][g][al];
+        s[q] = t;
+      }
+      const float invM = 1.0f / a.M;
+      const float g1 = s[0] * invM, h1 = s[1] * invM, g2 = s[2] * invM, h2 = s[3] * invM;
+      const int64_t n = a.idx[r];
+      const float u1 = ema_update(a.u_img[n], g1, a.gamma);
+      const float u2 = ema_update(a.u_txt[n], g2, a.gamma);
+      a.u_img[n] = u1;
+      a.u_txt[n] = u2;
+      const float t1 = a.tau1[r], t2 = a.tau2[r];
+      const float e1 = a.eps + u1, e2 = a.eps + u2;
+      const float bm = (float)a.b * a.M;
+      float c1 = 1.0f / (bm * e1), c2 = 1.0f / (bm * e2);
+      if (a.version == FASTCLIP_V0) { c1 /= t1; c2 /= t2; }
+      a.c1[r] = c1;
+      a.c2[r] = c2;
+      a.dcoef[r] = c1 * s[0] + c2 * s[2];          // c1 M g1 + c2 M g2
+      const float l1 = logf(e1), l2 = logf(e2);
+      if (a.version == FASTCLIP_V2) {
+        a.d_tau_img[r] = a.tau_scale * (l1 + a.rho - h1 / (t1 * e1));
+        a.d_tau_txt[r] = a.tau_scale * (l2 + a.rho - h2 / (t2 * e2));
+        lsum = t1 * (l1 + a.rho) + t2 * (l2 + a.rho);
+      } else {
+        lsum = l1 + l2;
+      }
+      hsum = h1 / e1 + h2 / e2;
+      if (a.g_img) a.g_img[r] = g1;
+      if (a.g_txt) a.g_txt[r] = g2;
+      if (a.u_new_img) a.u_new_img[r] = u1;
+      if (a.u_new_txt) a.u_new_txt[r] = u2;
+    }
+    scal[0][al] = lsum;
+    scal[1][al] = hsum;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double x = 0.0, y = 0.0;
+    for (int i = 0; i < 32; ++i) { x += (double)scal[0][i]; y += (double)scal[1][i]; }
+    a.red[2 * blockIdx.x + 0] = (float)x;
+    a.red[2 * blockIdx.x + 1] = (float)y;
+  }
+}
+
+void launch_state(const StepCtx& c) {
+  const Layout& L = c.L;
+  StateArgs a;
+  a.idx = c.buf.idx; a.u_img = c.buf.u_img; a.u_txt = c.buf.u_txt;
+  a.tau1 = (const float*)(c.ws + L.tau1); a.tau2 = (const float*)(c.ws + L.tau2);
+  a.sums = (const float*)(c.ws + L.sums); a.nparts = L.nparts; a.bstride = L.bstride; a.b = L.b;
+  a.M = (float)(L.B - 1); a.gamma = c.cfg.gamma; a.eps = c.cfg.eps; a.rho = c.cfg.rho;
+  a.tau_scale = c.cfg.tau_grad_scale; a.version = c.cfg.version;
+  a.c1 = (float*)(c.ws + L.c1); a.c2 = (float*)(c.ws + L.c2); a.dcoef = (float*)(c.ws + L.dcoef);
+  a.red = (float*)(c.ws + L.red);
+  a.d_tau_img = c.buf.d_tau_img; a.d_tau_txt = c.buf.d_tau_txt; a.g_img = c.buf.g_img; a.g_txt = c.buf.g_txt;
+  a.u_new_img = c.buf.u_new_img; a.u_new_txt = c.buf.u_new_txt;
+  hipLaunchKernelGGL(k_state, dim3((unsigned)L.nstate_blocks), dim3(256), 0, c.s, a);
+}
+
+// Eq. 1 alone, one thread per anchor (the same update as in k_state).
+__global__ void __launch_bounds__(256) k_state_flat(const int64_t* __restrict__ idx, int64_t n, float gamma, float invM,
+                                                    const float* __restrict__ s1, const float* __restrict__ s2,
+                                                    float* __restrict__ u_img, float* __restrict__ u_txt,
+                                                    float* __restrict__ o1, float* __restrict__ o2) {
+  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (r >= n) return;
+  const int64_t i = idx[r];
+  const float u1 = ema_update(u_img[i], s1[r] * invM, gamma);
+  const float u2 = ema_update(u_txt[i], s2[r] * invM, gamma);
+  u_img[i] = u1;
+  u_txt[i] = u2;
+  o1[r] = u1;
+  o2[r] = u2;
+}
+
+void launch_state_flat(const int64_t* idx, int64_t n, int64_t N, float gamma, float M, const float* sum_img,
+                       const float* sum_txt, float* u_img, float* u_txt, float* u_new_img, float* u_new_txt,
+                       hipStream_t s) {
+  (void)N;
+  hipLaunchKernelGGL(k_state_flat, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, idx, n, gamma, 1.0f / M, sum_img,
+                     sum_txt, u_img, u_txt, u_new_img, u_new_txt);
+}
+
+// ------------------------------------------------------------------------------------------
+// Scalars (one thread): loss of the local batch with g replaced by u^{t+1}; Eq. 8 (V0), Eq. 10 (V3).
+__device__ void write_scalars(const float* red, int nblocks, int64_t b, int version, const float* tau, float rho,
+                              float* loss, float* d_tau) {
+  double A = 0.0, H = 0.0;
+  for (int i = 0; i < nblocks; ++i) { A += (double)red[2 * i]; H += (double)red[2 * i + 1]; }
+  A /= (double)b;
+  H /= (double)b;
+  if (version == FASTCLIP_V2) { *loss = (float)A; return; }
+  const double t = (double)tau[0];
+  if (version == FASTCLIP_V1) { *loss = (float)(t * A); return; }
+  if (version == FASTCLIP_V0) { *loss = (float)A; *d_tau = (float)(-H / (t * t)); return; }
+  *loss = (float)(t * A + 2.0 * (double)rho * t);
+  *d_tau = (float)(A + 2.0 * (double)rho - H / t);
+}
+
+// ------------------------------------------------------------------------------------------
+// Accuracy path, gradients (Eqs. 2-7 for the local rows).  Block (r, side) writes one output row:
+//   side 0: d_img[r] = c1_r * sum_j l1(r,j) txt_j - (c1_r M g1_r + c2_r M g2_r) txt_p
+//                      + sum_{r' != r} c2_{r'} l2(r', p) txt_{p'}
+//   side 1: the mirror image.  The stored strips hold l with the anchor's own column zeroed.
+__global__ void __launch_bounds__(256) k_grad_f32(const float* __restrict__ img, const float* __restrict__ txt,
+                                                  int64_t ld_img, int64_t ld_txt, int64_t off, int64_t b, int64_t B,
+                                                  int64_t d, const float* __restrict__ E1, const float* __restrict__ E2,
+                                                  int64_t ldE, const float* __restrict__ c1, const float* __restrict__ c2,
+                                                  const float* __restrict__ dcoef, float* __restrict__ d_img,
+                                                  float* __restrict__ d_txt, const float* __restrict__ red, int nblocks,
+                                                  int version, const float* __restrict__ tau, float rho,
+                                                  float* __restrict__ loss, float* __restrict__ d_tau) {
+  const int64_t r = blockIdx.x;
+  const int side = blockIdx.y;
+  const int64_t p = off + r;
+  const float* X = side == 0 ? txt : img;       // rows that the exp weights multiply
+  const int64_t ldx = side == 0 ? ld_txt : ld_img;
+  const float* Eown = (side == 0 ? E1 : E2) + r * ldE;       // l of this anchor over all contrasts
+  const float* Eoth = side == 0 ? E2 : E1;                   // l of the other local anchors at column p
+  const float* cown = side == 0 ? c1 : c2;
+  const float* coth = side == 0 ? c2 : c1;
+  float* out = (side == 0 ? d_img : d_txt) + r * d;
+  int cw = 32;
+  while (cw < 256 && cw < d) cw <<= 1;
+  const int groups = 256 / cw;
+  const int cl = threadIdx.x % cw, grp = threadIdx.x / cw;
+  __shared__ double red2[256];
+  for (int64_t c0 = 0; c0 < d; c0 += cw) {
+    const int64_t col = c0 + cl;
+    double acc = 0.0, acc6 = 0.0;
+    if (col < d) {
+      for (int64_t j = grp; j < B; j += groups) acc += (double)Eown[j] * (double)X[j * ldx + col];
+      for (int64_t q = grp; q < b; q += groups)
+        acc6 += (double)coth[q] * (double)Eoth[q * ldE + p] * (double)X[(off + q) * ldx + col];
+    }
+    red2[threadIdx.x] = (double)cown[r] * acc + acc6;
+    __syncthreads();
+    if (grp == 0 && col < d) {
+      double t = 0.0;
+      for (int g = 0; g < groups; ++g) t += red2[g * cw + cl];
+      out[col] = (float)(t - (double)dcoef[r] * (double)X[p * ldx + col]);
+    }
+    __syncthreads();
+  }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
+}
+
+void launch_grad_f32(const StepCtx& c) {
+  const Layout& L = c.L;
+  dim3 grid((unsigned)L.b, 2), block(256);
+  hipLaunchKernelGGL(k_grad_f32, grid, block, 0, c.s, (const float*)c.buf.img_glob, (const float*)c.buf.txt_glob,
+                     c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.B, L.d, (const float*)(c.ws + L.E[0]),
+                     (const float*)(c.ws + L.E[1]), L.ldE, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
+                     (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
+                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau);
+}
+
+// ------------------------------------------------------------------------------------------
+// MFMA path, last phase.  d_img[r] = c1_r * (sum over splits of E1 x txt)[r] + A6_img[r] - dcoef_r txt_p,
+// and the mirror image; block (0,0) also writes the scalars.
+__global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict__ img, const bf16_t* __restrict__ txt,
+                                                       int64_t ld_img, int64_t ld_txt, int64_t off, int64_t b, int64_t d,
+                                                       const float* __restrict__ O1, const float* __restrict__ O2,
+                                                       int nsplit, const float* __restrict__ A6_1,
+                                                       const float* __restrict__ A6_2, const float* __restrict__ c1,
+                                                       const float* __restrict__ c2, const float* __restrict__ dcoef,
+                                                       float* __restrict__ d_img, float* __restrict__ d_txt,
+                                                       const float* __restrict__ red, int nblocks, int version,
+                                                       const float* __restrict__ tau, float rho, float* __restrict__ loss,
+                                                       float* __restrict__ d_tau) {
+  const int64_t r = blockIdx.x;
+  const int side = blockIdx.y;
+  const int64_t p = off + r;
+  const bf16_t* xp = side == 0 ? txt + p * ld_txt : img + p * ld_img;
+  const float* O = (side == 0 ? O1 : O2) + r * d;
+  const float* A6 = (side == 0 ? A6_1 : A6_2) + r * d;
+  const float cown = side == 0 ? c1[r] : c2[r];
+  const float dc = dcoef[r];
+  float* out = (side == 0 ? d_img : d_txt) + r * d;
+  const size_t split_stride = (size_t)b * (size_t)d;
+  for (int64_t c0 = (int64_t)threadIdx.x * 4; c0 < d; c0 += 1024) {   // d % 8 == 0 on this path
+    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int s = 0; s < nsplit; ++s) {
+      const float4 v = *(const float4*)(O + (size_t)s * split_stride + c0);
+      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
+    }
+    const float4 a6 = *(const float4*)(A6 + c0);
+    const uint2 xr = *(const uint2*)(xp + c0);
+    const float x0 = __uint_as_float(xr.x << 16), x1 = __uint_as_float(xr.x & 0xffff0000u);
+    const float x2 = __uint_as_float(xr.y << 16), x3 = __uint_as_float(xr.y & 0xffff0000u);
+    float4 o;
+    o.x = fmaf(cown, acc.x, a6.x) - dc * x0;
+    o.y = fmaf(cown, acc.y, a6.y) - dc * x1;
+    o.z = fmaf(cown, acc.z, a6.z) - dc * x2;
+    o.w = fmaf(cown, acc.w, a6.w) - dc * x3;
+    *(float4*)(out + c0) = o;
+  }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+    write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
+}
+
+void launch_finalize_bf16(const StepCtx& c) {
+  const Layout& L = c.L;
+  dim3 grid((unsigned)L.b, 2), block(256);
+  hipLaunchKernelGGL(k_finalize_bf16, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
+                     c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, (const float*)(c.ws + L.Opart[0]),
+                     (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.A6[0]),
+                     (const float*)(c.ws + L.A6[1]), (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
+                     (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
+                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau);
+}
+
+// ------------------------------------------------------------------------------------------
+// Index checker: open-addressing hash set of the b indices; flag word at ws[0].
+__global__ void __launch_bounds__(256) k_idx_fill(int* flag, long long* table, size_t slots) {
+  const size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (i == 0) *flag = 0;
+  if (i < slots) table[i] = -1;
+}
+
+__global__ void __launch_bounds__(256) k_idx_insert(const int64_t* __restrict__ idx, int64_t b, int64_t N, int* flag,
+                                                    unsigned long long* table, size_t slots, int shift) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= b) return;
+  const int64_t v = idx[i];
+  if (v < 0 || v >= N) { *flag = 1; return; }
+  size_t h = (size_t)(((unsigned long long)v * 11400714819323198485ull) >> shift);
+  for (size_t probe = 0; probe < slots; ++probe) {     // bounded: the table has at least 2b slots
+    const unsigned long long old = atomicCAS(&table[h], ~0ull, (unsigned long long)v);
+    if (old == ~0ull) return;
+    if (old == (unsigned long long)v) { *flag = 1; return; }
+    h = (h + 1) & (slots - 1);
+  }
+  *flag = 1;
+}
+
+void launch_check_indices(const int64_t* idx, int64_t b, int64_t N, void* ws, hipStream_t s) {
+  size_t slots = 64;
+  int log2s = 6;
+  while (slots < (size_t)b * 2) { slots <<= 1; ++log2s; }
+  int* flag = (int*)ws;
+  long long* table = (long long*)((char*)ws + 256);
+  hipLaunchKernelGGL(k_idx_fill, dim3((unsigned)((slots + 255) / 256)), dim3(256), 0, s, flag, table, slots);
+  hipLaunchKernelGGL(k_idx_insert, dim3((unsigned)((b + 255) / 256)), dim3(256), 0, s, idx, b, N, flag,
+                     (unsigned long long*)table, slots, 64 - log2s);
+}
+
+}  // namespace fc

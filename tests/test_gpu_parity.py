@@ -1,0 +1,262 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle on identical seeded inputs.
+
+Tolerances (relative): 1e-5 on the fp32 accuracy path, 2e-2 on the bf16 MFMA path, for loss, u, g,
+gradients and temperature gradients; scatter positions, untouched state entries and repeated runs are
+compared bit for bit.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import V0, V1, V2, V3, ema_update, fcco_step, gamma_cosine
+from paper_2407_01445_amd import binding as fc
+from paper_2407_01445_amd.workloads import WORKLOADS, draw_indices, make_embeddings, step_seed
+
+from gpu_harness import DEV, GpuStep, compare, rel_each
+
+pytestmark = pytest.mark.gpu
+
+TOL_F32 = 1e-5
+TOL_BF16 = 2e-2
+
+
+def oracle_step(g: GpuStep, img32, txt32, idx, u_img, u_txt, gamma, tau=0.07, tau_img=None, tau_txt=None):
+    return fcco_step(img32.astype(np.float64), txt32.astype(np.float64), g.off, g.b, idx, u_img, u_txt,
+                     version=g.version, gamma=gamma, eps=g.eps, rho=g.rho, tau=tau, tau_img=tau_img,
+                     tau_txt=tau_txt, tau_grad_scale=g.scale)
+
+
+def check_state(g: GpuStep, u_img_before, u_txt_before, idx, want_u_img, want_u_txt, tol):
+    """Positions outside idx: bit-identical.  Positions in idx: equal to the dense u_new outputs bit for bit
+    (the scatter wrote exactly what was reported) and within tol of the oracle."""
+    ui, ut = g.u_img.cpu().numpy(), g.u_txt.cpu().numpy()
+    mask = np.ones(g.N, bool)
+    mask[idx] = False
+    assert np.array_equal(ui[mask].view(np.uint32), u_img_before[mask].view(np.uint32))
+    assert np.array_equal(ut[mask].view(np.uint32), u_txt_before[mask].view(np.uint32))
+    assert np.array_equal(ui[idx], g.u_new_img.cpu().numpy())
+    assert np.array_equal(ut[idx], g.u_new_txt.cpu().numpy())
+    assert (ui[idx] > 0).all() and (ut[idx] > 0).all()
+    assert rel_each(ui[idx], want_u_img[idx]) <= tol and rel_each(ut[idx], want_u_txt[idx]) <= tol
+
+
+# ------------------------------------------------------------------------------- fp32 accuracy path
+@pytest.mark.parametrize("version", [V1, V0, V3, V2])
+def test_cfg0_ten_steps_f32(version):
+    w = WORKLOADS["cfg0"]
+    rho = {V1: 0.0, V0: 0.0, V3: 6.5, V2: 7.0}[version]
+    g = GpuStep(B=w["B"], b=w["b"], off=0, d=w["d"], N=w["N"], dtype="f32", version=version, eps=w["eps"], rho=rho,
+                tau=w["tau"], tau_grad_scale=1.0 / w["N"])
+    u_img = np.zeros(w["N"])
+    u_txt = np.zeros(w["N"])
+    tau_arr = np.full(w["N"], np.float32(w["tau"]), np.float64)
+    for step in range(w["steps"]):
+        seed = step_seed("cfg0", step)
+        img, txt = make_embeddings(seed, w["B"], w["d"], w["noise"], "f32")
+        idx = draw_indices(seed + 500, w["b"], w["N"])
+        before = (g.u_img.cpu().numpy(), g.u_txt.cpu().numpy())
+        g.set_inputs(img, txt, idx)
+        g.step(w["gamma"])
+        want = oracle_step(g, img, txt, idx, u_img, u_txt, w["gamma"], tau=float(np.float32(w["tau"])),
+                           tau_img=tau_arr, tau_txt=tau_arr)
+        compare(g.outputs(), want, version, TOL_F32, "cfg0 v%d step %d" % (version, step))
+        check_state(g, before[0], before[1], idx, u_img, u_txt, TOL_F32)
+
+
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_f32_ragged_strided_local_share(version):
+    B, b, off, d, N = 37, 11, 13, 19, 200
+    rng = np.random.default_rng(40 + version)
+    img, txt = make_embeddings(91, B, d, 0.5, "f32")
+    idx = draw_indices(92, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="f32", version=version, eps=1e-3, rho=5.0, tau=0.07,
+                tau_grad_scale=0.25, ld_img=24, ld_txt=19, u_img0=u0i, u_txt0=u0t, tau_img0=t_img, tau_txt0=t_txt)
+    g.set_inputs(img, txt, idx)
+    g.step(0.35)
+    u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+    want = oracle_step(g, img, txt, idx, u_img, u_txt, 0.35, tau=float(np.float32(0.07)),
+                       tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64))
+    compare(g.outputs(), want, version, TOL_F32, "f32 ragged v%d" % version)
+    check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_F32)
+
+
+def test_f32_two_anchor_batch_and_gamma_one():
+    """Smallest legal batch (B = 2) and gamma = 1: u must equal g exactly as reported."""
+    img, txt = make_embeddings(5, 2, 8, 0.5, "f32")
+    g = GpuStep(B=2, b=2, off=0, d=8, N=4, dtype="f32", version=V3, eps=1e-14, rho=6.5, tau=0.07,
+                u_img0=np.array([0.5, 0, 0.25, 0], np.float32), u_txt0=np.array([0.5, 0, 0.25, 0], np.float32))
+    idx = np.array([2, 1])
+    g.set_inputs(img, txt, idx)
+    g.step(1.0)
+    u_img = np.array([0.5, 0, 0.25, 0])
+    u_txt = u_img.copy()
+    want = oracle_step(g, img, txt, idx, u_img, u_txt, 1.0, tau=float(np.float32(0.07)))
+    compare(g.outputs(), want, V3, TOL_F32, "B=2")
+    assert np.array_equal(g.u_new_img.cpu().numpy(), g.g_img.cpu().numpy())
+    assert np.array_equal(g.u_new_txt.cpu().numpy(), g.g_txt.cpu().numpy())
+
+
+# ------------------------------------------------------------------------------- bf16 MFMA path, small shapes
+BF16_SMALL = [
+    # B, b, off, d: several 256-tiles with ragged tails in anchors, contrasts and width; local share and full batch
+    (700, 300, 133, 72),
+    (520, 520, 0, 64),
+    (1000, 64, 936, 136),
+    (257, 257, 0, 8),
+]
+
+
+@pytest.mark.parametrize("B,b,off,d", BF16_SMALL)
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_bf16_small_shapes(B, b, off, d, version):
+    N = 5000
+    rng = np.random.default_rng(B + version)
+    img, txt = make_embeddings(B + d, B, d, 0.5, "bf16")
+    idx = draw_indices(B + 1, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=version, eps=1e-6, rho=6.5, tau=0.07,
+                tau_grad_scale=1.0 / N, ld_img=d + 8, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img, tau_txt0=t_txt)
+    g.set_inputs(img, txt, idx)
+    g.step(0.6)
+    u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+    want = oracle_step(g, img, txt, idx, u_img, u_txt, 0.6, tau=float(np.float32(0.07)),
+                       tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64))
+    compare(g.outputs(), want, version, TOL_BF16, "bf16 %s v%d" % ((B, b, off, d), version))
+    check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
+
+
+def test_bf16_repeatable_bit_for_bit():
+    B, b, off, d, N = 700, 300, 133, 72, 5000
+    img, txt = make_embeddings(3, B, d, 0.5, "bf16")
+    idx = draw_indices(4, b, N)
+    res = []
+    for _ in range(2):
+        g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=V3, eps=1e-14, rho=6.5)
+        g.set_inputs(img, txt, idx)
+        g.step(0.7)
+        res.append((g.d_img.cpu(), g.d_txt.cpu(), g.u_img.cpu(), g.loss.cpu(), g.d_tau.cpu()))
+    for x, y in zip(*res):
+        assert torch.equal(x, y)
+
+
+# ------------------------------------------------------------------------------- full-size workloads
+def run_workload(name, steps_checked, n_steps):
+    w = WORKLOADS[name]
+    B, b, off, d, N, version = w["B"], w["b"], w["off"], w["d"], w["N"], w["version"]
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=w["dtype"], version=version, eps=w["eps"], rho=w["rho"],
+                tau=w["tau"], tau_grad_scale=1.0 / N)
+    tau32 = float(np.float32(w["tau"]))
+    for step in range(n_steps):
+        gamma = w["gamma"] if not isinstance(w["gamma"], tuple) else gamma_cosine(step, 1, w["gamma"][1], w["gamma"][2])
+        seed = step_seed(name, step)
+        if step in steps_checked or step == 0:
+            img, txt = make_embeddings(seed, B, d, w["noise"], w["dtype"])
+        idx = draw_indices(seed + 500, b, N)
+        g.set_inputs(img, txt, idx)
+        if step not in steps_checked:
+            g.step(gamma)
+            continue
+        # the oracle sees the state as the GPU holds it before the step, on a compact copy indexed 0..b-1
+        idx_t = torch.from_numpy(idx).to(DEV)
+        u_img_c = g.u_img[idx_t].cpu().numpy().astype(np.float64)
+        u_txt_c = g.u_txt[idx_t].cpu().numpy().astype(np.float64)
+        keep_img, keep_txt = g.u_img.clone(), g.u_txt.clone()
+        print("[%s] step %d gamma %.4f" % (name, step, gamma), flush=True)
+        g.step(gamma)
+        tau_c = np.full(b, tau32)
+        want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, np.arange(b), u_img_c, u_txt_c,
+                         version=version, gamma=gamma, eps=w["eps"], rho=w["rho"], tau=tau32, tau_img=tau_c,
+                         tau_txt=tau_c, tau_grad_scale=1.0 / N)
+        compare(g.outputs(), want, version, TOL_BF16, "%s step %d" % (name, step))
+        # state: scattered values are the reported ones, everything else is bit-identical
+        assert torch.equal(g.u_img[idx_t], g.u_new_img) and torch.equal(g.u_txt[idx_t], g.u_new_txt)
+        keep_img[idx_t] = g.u_new_img
+        keep_txt[idx_t] = g.u_new_txt
+        assert torch.equal(keep_img.view(torch.int32), g.u_img.view(torch.int32))
+        assert torch.equal(keep_txt.view(torch.int32), g.u_txt.view(torch.int32))
+        assert rel_each(g.u_new_img.cpu().numpy(), u_img_c) <= TOL_BF16
+        del keep_img, keep_txt
+    return g
+
+
+def test_cfg1_full_size():
+    run_workload("cfg1", {0, 1, 5}, 6)
+
+
+def test_cfg2_full_size():
+    run_workload("cfg2", {0, 2}, 3)
+
+
+def test_cfg3_full_size():
+    run_workload("cfg3", {0, 1}, 2)
+
+
+def test_cfg4_full_size():
+    run_workload("cfg4", {0, 1}, 2)
+
+
+# ------------------------------------------------------------------------------- auxiliary entry points
+def test_check_indices_on_device():
+    N = 1_000_000
+    for b in (1, 64, 1000, 100_000):
+        idx = draw_indices(b, b, N)
+        ws = torch.empty(fc.fastclip_check_indices_workspace_bytes(b), dtype=torch.uint8, device=DEV)
+        t = torch.from_numpy(idx).to(DEV)
+        assert fc.fastclip_check_indices(t, b, N, ws) == fc.OK
+        if b > 1:
+            dup = idx.copy()
+            dup[b // 2] = dup[0]
+            assert fc.fastclip_check_indices(torch.from_numpy(dup).to(DEV), b, N, ws) == fc.ERR_INDEX
+        for bad in (-1, N):
+            oob = idx.copy()
+            oob[-1] = bad
+            assert fc.fastclip_check_indices(torch.from_numpy(oob).to(DEV), b, N, ws) == fc.ERR_INDEX
+
+
+@pytest.mark.parametrize("n", [1, 1000, 1 << 18])
+def test_state_update_alone(n):
+    N = 3_000_000
+    rng = np.random.default_rng(n)
+    idx = draw_indices(n + 7, n, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    s1 = rng.uniform(1.0, 900.0, n).astype(np.float32)
+    s2 = rng.uniform(1.0, 900.0, n).astype(np.float32)
+    M, gamma = 1023.0, 0.4
+    dev = lambda a: torch.from_numpy(a).to(DEV)
+    ui, ut, o1, o2 = dev(u0i), dev(u0t), torch.empty(n, device=DEV), torch.empty(n, device=DEV)
+    fc.fastclip_state_update(dev(idx), n, N, gamma, M, dev(s1), dev(s2), ui, ut, o1, o2)
+    torch.cuda.synchronize()
+    wi, wt = u0i.astype(np.float64), u0t.astype(np.float64)
+    n1 = ema_update(wi, idx, s1.astype(np.float64) / M, gamma)
+    n2 = ema_update(wt, idx, s2.astype(np.float64) / M, gamma)
+    assert rel_each(o1.cpu().numpy(), n1) <= 1e-6 and rel_each(o2.cpu().numpy(), n2) <= 1e-6
+    got_i, got_t = ui.cpu().numpy(), ut.cpu().numpy()
+    assert np.array_equal(got_i[idx], o1.cpu().numpy()) and np.array_equal(got_t[idx], o2.cpu().numpy())
+    mask = np.ones(N, bool)
+    mask[idx] = False
+    assert np.array_equal(got_i[mask].view(np.uint32), u0i[mask].view(np.uint32))
+    assert np.array_equal(got_t[mask].view(np.uint32), u0t[mask].view(np.uint32))
+
+
+def test_step_timed_reports_phases_and_same_result():
+    B, b, off, d, N = 700, 300, 133, 72, 5000
+    img, txt = make_embeddings(3, B, d, 0.5, "bf16")
+    idx = draw_indices(4, b, N)
+    outs = []
+    for timed in (False, True):
+        g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=V0, eps=1e-14)
+        g.set_inputs(img, txt, idx)
+        ms = g.step(0.7, timed=timed)
+        outs.append((g.d_img.cpu(), g.u_img.cpu(), g.d_tau.cpu()))
+    assert set(ms) == {"prep", "strips", "state", "local", "contract", "finalize"}
+    assert all(v > 0 for v in ms.values())
+    for x, y in zip(*outs):
+        assert torch.equal(x, y)
