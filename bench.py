@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Benchmark of the FCCO loss step (fwd + bwd) on one MI355X.
+
+A "step" is one fastclip_step call: similarity strips, exp sums, state update of u by dataset index,
+gradient contractions, temperature gradient, over one batch of synthetic embeddings that already sit
+in HBM.  Prints ONE JSON line: anchors/s for the whole step, the roofline of the dominant kernel
+(per-kernel durations from HIP events recorded by the library on its launch stream), the per-phase
+times, the state-update kernel on 2^24 indices against the HBM roofline, and the CPU oracle timed on
+the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_FLOPS = 2.5e15     # MI355X dense bf16 MFMA
+PEAK_HBM_BYTES = 8.0e12      # MI355X HBM3E
+
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# (profiles/), keyed by (workload, phase); absent = not measured.
+MEASURED_TRAFFIC = {}
+
+
+def algorithmic_flops(B, b, d):
+    """Flop the method needs per step and phase (recomputation and padding not counted): one
+    'unit' = 2 b B d.  Full batch (b == B): similarity once, then W T and W^T I.  Local share:
+    two strips, two anchor-side contractions, and the local contrast-side block (4 b^2 d)."""
+    unit = 2.0 * b * B * d
+    if b == B:
+        return {"strips": unit, "contract": 2 * unit}
+    return {"strips": 2 * unit, "contract": 2 * unit + 4.0 * b * b * d}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg4", help="cfg1..cfg4 (bf16 workloads of BASELINE.json)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-state-bench", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_2407_01445_amd import binding as fc
+    from paper_2407_01445_amd.workloads import WORKLOADS, draw_indices, make_embeddings, step_seed
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    fc.load()
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    name = args.workload
+    w = WORKLOADS[name]
+    B, b, off, d, N, version = w["B"], w["b"], w["off"], w["d"], w["N"], w["version"]
+    K, W = args.steps, args.warmup
+
+    # ---- inputs, resident in HBM before anything is timed
+    img32, txt32 = make_embeddings(step_seed(name, 0), B, d, w["noise"], w["dtype"])
+    tdt = torch.bfloat16 if w["dtype"] == "bf16" else torch.float32
+    img, txt = torch.from_numpy(img32).to(tdt).to(dev), torch.from_numpy(txt32).to(tdt).to(dev)
+    f32 = dict(dtype=torch.float32, device=dev)
+    u_img, u_txt = torch.zeros(N, **f32), torch.zeros(N, **f32)
+    tau = torch.full((1,), w["tau"], **f32)
+    tau_img = torch.full((N,), w["tau"], **f32) if version == fc.V2 else None
+    tau_txt = torch.full((N,), w["tau"], **f32) if version == fc.V2 else None
+    d_img, d_txt = torch.empty(b, d, **f32), torch.empty(b, d, **f32)
+    loss, d_tau = torch.empty(1, **f32), torch.empty(1, **f32)
+    d_tau_img, d_tau_txt = torch.empty(b, **f32), torch.empty(b, **f32)
+    n_sets = W + 2 * K
+    idx_sets = [torch.from_numpy(draw_indices(step_seed(name, t) + 500, b, N)).to(dev) for t in range(n_sets)]
+
+    def gamma_at(t):
+        g = w["gamma"]
+        return fc.fastclip_gamma_cosine(t, 1, g[1], g[2]) if isinstance(g, tuple) else g
+
+    def cfg_at(t):
+        return fc.make_config(version=version, emb_dtype=fc.BF16 if w["dtype"] == "bf16" else fc.F32, B=B, b=b,
+                              off=off, d=d, N=N, gamma=gamma_at(t), eps=w["eps"], rho=w["rho"], tau_grad_scale=1.0 / N)
+
+    def bufs_at(t):
+        return fc.make_buffers(img_glob=img, txt_glob=txt, idx=idx_sets[t], u_img=u_img, u_txt=u_txt, tau=tau,
+                               tau_img=tau_img, tau_txt=tau_txt, d_img=d_img, d_txt=d_txt, loss=loss, d_tau=d_tau,
+                               d_tau_img=d_tau_img, d_tau_txt=d_tau_txt)
+
+    ws = torch.empty(fc.fastclip_workspace_bytes(cfg_at(0)), dtype=torch.uint8, device=dev)
+    cfgs = [cfg_at(t) for t in range(n_sets)]
+    bufs = [bufs_at(t) for t in range(n_sets)]
+
+    # ---- warm-up, then exactly K timed steps bracketed by synchronisation
+    for t in range(W):
+        fc.fastclip_step(cfgs[t], bufs[t], ws)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for t in range(W, W + K):
+        fc.fastclip_step(cfgs[t], bufs[t], ws)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / K
+    anchors_per_s = b * K / (t1 - t0)
+    assert torch.isfinite(loss).all() and torch.isfinite(d_img).all()
+
+    # ---- per-kernel durations: the library records HIP events around every kernel on its launch stream
+    phase_ms = {}
+    for t in range(W + K, W + 2 * K):
+        for k, v in fc.fastclip_step_timed(cfgs[t], bufs[t], ws).items():
+            phase_ms[k] = phase_ms.get(k, 0.0) + v / K
+    alg = algorithmic_flops(B, b, d)
+    dom = max(("strips", "contract"), key=lambda k: phase_ms.get(k, 0.0))
+    achieved = alg[dom] / (phase_ms[dom] * 1e-3) / 1e12
+    roofline = {"kernel": {"strips": "k_strips_bf16", "contract": "k_gemm_nn_bf16"}[dom], "bound": "mfma",
+                "achieved": round(achieved, 2), "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
+                "frac": round(achieved * 1e12 / PEAK_BF16_FLOPS, 4),
+                "traffic": MEASURED_TRAFFIC.get((name, dom)),
+                "algorithmic_flop_per_launch": alg[dom], "avg_launch_ms": round(phase_ms[dom], 5),
+                "timing": "HIP events around each kernel on the launch stream, %d extra steps" % K}
+    gemm_ms = phase_ms["strips"] + phase_ms["contract"]
+    gemm_phases = {"algorithmic_tflops": round((alg["strips"] + alg["contract"]) / (gemm_ms * 1e-3) / 1e12, 2),
+                   "frac_of_bf16_peak": round((alg["strips"] + alg["contract"]) / (gemm_ms * 1e-3) / PEAK_BF16_FLOPS, 4),
+                   "strips_tflops": round(alg["strips"] / (phase_ms["strips"] * 1e-3) / 1e12, 2),
+                   "contract_tflops": round(alg["contract"] / (phase_ms["contract"] * 1e-3) / 1e12, 2)}
+
+    out = {"metric": "FCCO loss fwd+bwd anchors/sec", "value": round(anchors_per_s, 1), "unit": "anchors/s",
+           "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+           "scaling": "weak", "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
+           "config": {"workload": "%s: b=%d local anchors x B=%d global pairs, d=%d %s, N=%d state entries, "
+                                  "FastCLIP-v%d" % (name, b, B, d, w["dtype"], N, version),
+                      "B": B, "b": b, "off": off, "d": d, "N": N, "version": version},
+           "roofline": roofline, "gemm_phases": gemm_phases,
+           "phase_ms": {k: round(v, 5) for k, v in phase_ms.items()}}
+
+    # ---- the state-update kernel alone on many indices: the HBM-bound part of the method
+    if not args.no_state_bench:
+        n_idx = 1 << 24
+        big_idx = torch.randperm(N, device=dev)[:n_idx].contiguous()
+        s1 = torch.rand(n_idx, **f32) * 100 + 1
+        s2 = torch.rand(n_idx, **f32) * 100 + 1
+        o1, o2 = torch.empty(n_idx, **f32), torch.empty(n_idx, **f32)
+        for _ in range(2):
+            fc.fastclip_state_update(big_idx, n_idx, N, 0.5, float(B - 1), s1, s2, u_img, u_txt, o1, o2)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            fc.fastclip_state_update(big_idx, n_idx, N, 0.5, float(B - 1), s1, s2, u_img, u_txt, o1, o2)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        alg_bytes = 40.0 * n_idx     # idx 8 + u read 2x4 + u write 2x4 + sums 2x4 + u_new 2x4
+        out["state_update"] = {"kernel": "k_state_flat", "n_idx": n_idx, "N": N, "ms": round(ms, 4),
+                               "bound": "hbm", "achieved": round(alg_bytes / (ms * 1e-3) / 1e9, 1),
+                               "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s",
+                               "frac": round(alg_bytes / (ms * 1e-3) / PEAK_HBM_BYTES, 4),
+                               "algorithmic_bytes_per_index": 40}
+        del big_idx, s1, s2, o1, o2
+
+    # ---- the CPU oracle on the same workload (one full step), host cores
+    if not args.no_cpu_baseline:
+        from threadpoolctl import threadpool_info
+
+        from oracle import fcco_step
+        img64, txt64 = img32.astype(np.float64), txt32.astype(np.float64)
+        u1, u2 = np.zeros(b), np.zeros(b)
+        tau_c = np.full(b, float(np.float32(w["tau"])))
+        reps = 0
+        c0 = time.perf_counter()
+        while True:
+            fcco_step(img64, txt64, off, b, np.arange(b), u1, u2, version=version, gamma=gamma_at(0), eps=w["eps"],
+                      rho=w["rho"], tau=tau_c[0], tau_img=tau_c, tau_txt=tau_c, tau_grad_scale=1.0 / N)
+            reps += 1
+            if time.perf_counter() - c0 > 10.0 or reps >= 20:
+                break
+        cpu_s = (time.perf_counter() - c0) / reps
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        out["cpu_baseline"] = {"value": round(b / cpu_s, 1), "unit": "anchors/s", "cores": int(threads),
+                               "kind": "oracle", "sample": "%d full step(s) of %s (all %d anchors), fp64 numpy, "
+                               "%.2f s per step" % (reps, name, b, cpu_s)}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

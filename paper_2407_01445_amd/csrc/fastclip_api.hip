@@ -57,16 +57,16 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
     L->nparts = (int)((cfg.B + kTileContrasts - 1) / kTileContrasts);
     L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
     L->ldW = (int64_t)round_up((size_t)cfg.b, 64);
-    // split the contraction over contrasts so that the two strips give about one workgroup per CU
+    // split the contraction over its (extended) column range so that the two strips give about one workgroup per CU
+    const int64_t stages = (L->ldE + L->ldW) / 32;
     const int64_t tiles = ((cfg.b + 255) / 256) * ((cfg.d + 255) / 256) * 2;
     int64_t want = (256 + tiles - 1) / tiles;
     if (want > kMaxSplit) want = kMaxSplit;
     if (want < 1) want = 1;
-    int64_t ks = (cfg.B + want - 1) / want;
-    ks = (int64_t)round_up((size_t)ks, kTileK);
-    if (ks < 4 * kTileK) ks = 4 * kTileK;
-    L->kslice = ks;
-    L->nsplit = (int)((cfg.B + ks - 1) / ks);
+    int64_t slice = (stages + want - 1) / want;
+    if (slice < 8) slice = 8;
+    L->kslice = slice;
+    L->nsplit = (int)((stages + slice - 1) / slice);
   } else {
     L->nparts = 1;
     L->ldE = cfg.B;
@@ -80,12 +80,14 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   L->c1 = take(fb); L->c2 = take(fb); L->dcoef = take(fb);
   L->red = take(sizeof(float) * 2 * (size_t)L->nstate_blocks);
   const size_t esz = L->bf16 ? sizeof(bf16_t) : sizeof(float);
-  for (int s = 0; s < 2; ++s) L->E[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
   if (L->bf16) {
-    for (int s = 0; s < 2; ++s) L->WT[s] = take(sizeof(bf16_t) * (size_t)cfg.b * (size_t)L->ldW);
+    // fragment-ordered strips: anchors padded to whole 256-row tiles, columns = contrasts + local anchors
+    const size_t rows = round_up((size_t)cfg.b, 256);
+    for (int s = 0; s < 2; ++s) L->E[s] = take(esz * rows * (size_t)(L->ldE + L->ldW));
     for (int s = 0; s < 2; ++s)
       L->Opart[s] = take(sizeof(float) * (size_t)L->nsplit * (size_t)cfg.b * (size_t)cfg.d);
-    for (int s = 0; s < 2; ++s) L->A6[s] = take(sizeof(float) * (size_t)cfg.b * (size_t)cfg.d);
+  } else {
+    for (int s = 0; s < 2; ++s) L->E[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
   }
   L->total = at;
 }

@@ -10,9 +10,7 @@ namespace fc {
 
 typedef uint16_t bf16_t;  // raw bf16 bits in memory
 
-constexpr int kTileAnchors = 256;    // anchor rows per workgroup tile of the strip kernel
 constexpr int kTileContrasts = 256;  // contrast rows per workgroup tile of the strip kernel
-constexpr int kTileK = 64;           // contraction depth per LDS stage (bf16 elements)
 constexpr int kMaxSplit = 64;
 
 static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
@@ -23,19 +21,17 @@ struct Layout {
   int bf16;          // 1: MFMA path, 0: fp32 accuracy path
   int nparts;        // partial row sums per anchor and quantity written by the strip phase
   int64_t bstride;   // anchors padded to a multiple of 64 (stride of the per-anchor arrays)
-  int64_t ldE;       // row stride of the stored exp strips (elements)
-  int64_t ldW;       // row stride of the transposed, scaled local blocks (elements)
-  int nsplit;        // split of the contraction over contrasts
-  int64_t kslice;    // contrasts per split
+  int64_t ldE;       // contrast columns of the stored exp strips (MFMA path: multiple of 64; fp32 path: B)
+  int64_t ldW;       // local-anchor columns appended to the strips (MFMA path, multiple of 64)
+  int nsplit;        // split of the contraction over its column range
+  int64_t kslice;    // 32-deep stages per split
   int nstate_blocks; // blocks of the state kernel (one scalar partial each)
   size_t diag, tau1, tau2, k1, k2;   // float[bstride]
   size_t sums;                       // float[4][nparts][bstride]: sum e1, sum x1 e1, sum e2, sum x2 e2
   size_t c1, c2, dcoef;              // float[bstride]
   size_t red;                        // float[nstate_blocks][2]
-  size_t E[2];                       // bf16 or float [b][ldE]
-  size_t WT[2];                      // bf16 [b][ldW]          (MFMA path)
+  size_t E[2];                       // fp32 path: float [b][ldE]; MFMA path: fragment-ordered bf16 strips
   size_t Opart[2];                   // float [nsplit][b][d]   (MFMA path)
-  size_t A6[2];                      // float [b][d]           (MFMA path)
   size_t total;
 };
 
@@ -57,8 +53,8 @@ void launch_strips_f32(const StepCtx& c);      // accuracy path: exp strips + ro
 void launch_strips_bf16(const StepCtx& c);     // MFMA path: exp strips + row sums
 void launch_state(const StepCtx& c);           // Eq. 1, coefficients, scalar partials
 void launch_grad_f32(const StepCtx& c);        // accuracy path: gradients + scalars
-void launch_local_bf16(const StepCtx& c);      // MFMA path: scaled, transposed local blocks
-void launch_contract_bf16(const StepCtx& c);   // MFMA path: E x X contractions
+void launch_local_bf16(const StepCtx& c);      // MFMA path: local contrast-side operand columns
+void launch_contract_bf16(const StepCtx& c);   // MFMA path: strips x X contractions
 void launch_finalize_bf16(const StepCtx& c);   // MFMA path: combine + scalars
 
 void launch_state_flat(const int64_t* idx, int64_t n, int64_t N, float gamma, float M,

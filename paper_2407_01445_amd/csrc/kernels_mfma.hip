@@ -1,21 +1,29 @@
 // bf16 MFMA kernels of the FCCO step for gfx950 (wave64, v_mfma_f32_32x32x16_bf16).
 //
-//  k_strips_bf16   S = anchors x contrasts^T tile by tile from LDS-staged operands, then in registers
-//                  l = exp((s - s_ii)/tau) (Sec. 3), row sums of l and of (s - s_ii) l (Proc. 1 and the
-//                  nabla_3 l sums of Eqs. 8-10), and l rounded to bf16 stored as the operand of the
-//                  gradient contraction.  The similarity matrix itself never reaches memory.
-//  k_local_bf16    the local b x b block of the other side's strip, scaled by that side's coefficients
-//                  and transposed: the operand of the contrast-side term of Eqs. 3 / 5 / 7.
-//  k_gemm_nn_bf16  C = A x Bm with A [M][K] and Bm [K][N] both row-major (the contraction runs over the
-//                  ROW index of Bm, so Bm tiles are transposed in registers on their way to LDS), split
-//                  over K into per-slice fp32 partial results.  Used for sum_j l(r,j) x_j (Eqs. 2/4/6) and
-//                  for the local contrast-side term.
+//  k_strips_bf16    S^T tile = contrasts x anchors^T from LDS-staged operands (256 x 256 per workgroup), then in
+//                   registers l = exp((s - s_ii)/tau) (Sec. 3), per-anchor sums of l and of (s - s_ii) l (Proc. 1
+//                   and the nabla_3 l sums of Eqs. 8-10), and l rounded to bf16 stored as the operand of the
+//                   gradient contraction.  The similarity matrix itself never reaches memory.  Anchors run along
+//                   lanes, so the sums are lane-local and every store is a contiguous 1 KiB per wavefront.
+//  k_local_bf16     the local contrast-side operand of Eqs. 3 / 5 / 7: c_other[q] l_other(q, p_r) / c_own[r], written
+//                   behind the strip as extra contraction columns, so that one contraction yields
+//                   sum_j l(r,j) x_j + (1/c_r) sum_q c_q l(q,p_r) x_q.
+//  k_contract_bf16  C[r][n] = sum_c Efrag[r][c] Xext[c][n] over the extended column range, split over c into fp32
+//                   partial results (Eqs. 2/4/6 plus the local part of Eqs. 3/5/7).
 //
-// Workgroup = 256 threads = 2 x 2 wavefronts, each owning a 128 x 128 accumulator block (4 x 4 MFMA tiles,
-// 256 fp32 accumulators per lane); workgroup tile 256 x 256, contraction depth 64 per LDS stage, two stages.
-// MFMA operand layout used throughout (32x32x16, wave64): lane l supplies row (l & 31) of its operand and the
-// 8 consecutive k values starting at 8 * (l >> 5); accumulator register v of lane l is
-// D[8 * (v >> 2) + 4 * (l >> 5) + (v & 3)][l & 31].
+// Stored exp strips ("Efrag"): for anchor block ab = r / 32 and column block cb = c / 16 one 1 KiB fragment, laid out
+// exactly as the A operand of the 32x32x16 MFMA: lane L = (r % 32) + 32 h holds 8 bf16, slot e <-> column
+// 16 cb + 8 (e / 4) + 4 h + (e % 4).  The same slot order is used for the rows of X in the contraction, so the
+// permutation cancels.  Columns [0, ldE) are contrasts (global rows, zero beyond B), columns [ldE, ldE + ldW) are the
+// local anchors q of k_local_bf16 (zero beyond b).
+//
+// MFMA layout facts used (32x32x16, wave64): lane l supplies row/column (l & 31) of its operand and 8 contraction
+// slots selected by (l >> 5); accumulator register v of lane l is D[8 (v >> 2) + 4 (l >> 5) + (v & 3)][l & 31].
+//
+// Main loop (interior tiles): a ring of four 32 KiB LDS slots, each one 32-deep stage of both operands, filled by
+// global_load_lds_dwordx4 (no VGPR staging) three stages ahead; one barrier per stage; LDS operand reads of the next
+// 16-deep step are issued between the MFMAs of the current one.  Tiles that touch a ragged edge use guarded
+// register loads into the same LDS images, one stage at a time.
 #include "fc_internal.hpp"
 
 namespace fc {
@@ -23,252 +31,418 @@ namespace fc {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
+typedef short v4s __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) v4s lds_v4s;
 
-constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int kTileElems = 256 * TK;      // one operand tile in LDS: 256 rows x 64 k (bf16) = 32 KiB
+constexpr int BK = 32;                       // contraction depth of one LDS stage
+constexpr int kOpBytes = 256 * BK * 2;       // one operand tile of a stage: 16 KiB
+constexpr int kStageBytes = 2 * kOpBytes;    // 32 KiB
+constexpr int kRingBytes = 4 * kStageBytes;  // 128 KiB
 
-// 16-byte chunk c (0..7) of row `row` lives at chunk position c ^ swz(row): conflict-free both for
-// row-wise stores (8 lanes per row), for the transposed stores of k_gemm_nn_bf16 (lanes 8 rows apart) and
-// for MFMA operand reads (32 consecutive rows, one chunk).
-__device__ __forceinline__ int swz(int row) { return (row ^ (row >> 3)) & 7; }
-__device__ __forceinline__ int lds_off(int row, int chunk) { return row * TK + ((chunk ^ swz(row)) << 3); }
+#define FC_PIN() __builtin_amdgcn_sched_barrier(0)
+#define FC_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0f70)
+#define FC_WAIT_VMCNT8() __builtin_amdgcn_s_waitcnt(0x0f78)
 
-__device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
+__device__ __forceinline__ uint32_t lds_addr(const void* p) {
+  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
+}
+// 16 bytes per lane from global memory straight into LDS at lds_byte_addr + 16 * lane (wave-uniform address).
+// Completion is tracked by vmcnt; the compiler does not see the LDS write, so every use below is fenced by an
+// explicit s_waitcnt vmcnt + barrier.  M0 (the LDS base of the transfer) is written here and used by nothing else
+// in these kernels.
+__device__ __forceinline__ void dma16(const void* g, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+               :
+               : "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_byte_addr))
+               : "memory");
+}
 __device__ __forceinline__ float bf2f(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
+__device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
 
-// Global -> registers for a K-contiguous operand tile (256 rows x 64 k): thread t fetches chunk (t & 7)
-// of rows (t >> 3) + 32 i.  Rows >= rows_valid and k >= k_valid read as zero.
-__device__ __forceinline__ void gload_rows(u32x4 (&reg)[8], const bf16_t* __restrict__ base, int64_t ld,
-                                           int64_t row0, int64_t rows_valid, int64_t k0, int64_t k_valid, int tid) {
-  const int64_t k = k0 + ((tid & 7) << 3);
-  const bool kok = k < k_valid;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int64_t row = row0 + (tid >> 3) + 32 * i;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (kok && row < rows_valid) v = *(const u32x4*)(base + row * ld + k);
-    reg[i] = v;
-  }
-}
-__device__ __forceinline__ void lds_store_rows(bf16_t* tile, const u32x4 (&reg)[8], int tid) {
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int row = (tid >> 3) + 32 * i;
-    *(u32x4*)(tile + lds_off(row, tid & 7)) = reg[i];
-  }
-}
+// LDS image of a K-contiguous operand tile (256 rows x 32 k, 64 bytes per row): 16-byte chunk c of row r sits at
+// chunk position c ^ ((r >> 1) & 3), which makes both the row-wise fills and the MFMA operand reads conflict-free.
+__device__ __forceinline__ int rt_off(int row, int chunk) { return row * 64 + (((chunk ^ (row >> 1)) & 3) << 4); }
+// LDS image of a [32 k][256 n] tile of a row-major matrix (512 bytes per k row): 16-byte piece p of row k sits at
+// piece position p ^ ((k & 3) << 1), so that the four rows of a transposing read hit different banks.
+__device__ __forceinline__ int nt_off(int k, int piece) { return k * 512 + ((piece ^ ((k & 3) << 1)) << 4); }
 
-// Global -> registers for a tile of a [K][N] row-major matrix (64 k rows x 256 n columns): thread t fetches,
-// for k rows 8 (t >> 5) + i, the 8 columns starting at 8 (t & 31).  Then an 8 x 8 transpose in registers and
-// a store so that LDS holds the tile as [n][k], k contiguous, exactly like a K-contiguous operand.
-__device__ __forceinline__ void gload_cols(u32x4 (&reg)[8], const bf16_t* __restrict__ base, int64_t ld,
-                                           int64_t k0, int64_t k_valid, int64_t n0, int64_t n_valid, int tid) {
-  const int64_t n = n0 + ((tid & 31) << 3);
-  const bool nok = n < n_valid;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const int64_t k = k0 + ((tid >> 5) << 3) + i;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (nok && k < k_valid) v = *(const u32x4*)(base + k * ld + n);
-    reg[i] = v;
-  }
-}
-__device__ __forceinline__ void lds_store_cols_transposed(bf16_t* tile, const u32x4 (&reg)[8], int tid) {
-  const int kchunk = tid >> 5;
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {          // column n = 8 (t & 31) + j of the tile
-    u32x4 o;
-#pragma unroll
-    for (int w = 0; w < 4; ++w) {        // output word w holds k = 2w (low half) and 2w + 1 (high half)
-      const uint32_t lo = reg[2 * w][j >> 1], hi = reg[2 * w + 1][j >> 1];
-      o[w] = (j & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
-    }
-    const int row = ((tid & 31) << 3) + j;
-    *(u32x4*)(tile + lds_off(row, kchunk)) = o;
-  }
-}
-
-// One LDS stage: acc[ti][tj] += A(128 rows of this wave) x B(128 rows of this wave)^T over 64 k.
-__device__ __forceinline__ void mma_stage(f32x16 (&acc)[4][4], const bf16_t* tA, const bf16_t* tB, int wm, int wn,
-                                          int lane) {
-  const int lr = lane & 31, hk = lane >> 5;
-#pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    bf16x8 a[4], bq[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      a[t] = *(const bf16x8*)(tA + lds_off(wm * 128 + t * 32 + lr, kk * 2 + hk));
-      bq[t] = *(const bf16x8*)(tB + lds_off(wn * 128 + t * 32 + lr, kk * 2 + hk));
-    }
-#pragma unroll
-    for (int ti = 0; ti < 4; ++ti)
-#pragma unroll
-      for (int tj = 0; tj < 4; ++tj)
-        acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ti], bq[tj], acc[ti][tj], 0, 0, 0);
-  }
-}
-
-// Sum each of v[0..15] over the 32 lanes of a half-wave.  On return lane l holds, in the result, the total
-// of register index (l & 31) >> 1 (both lanes of a pair hold the same value).
-__device__ __forceinline__ float halfwave_sum16(const float (&v)[16], int lane) {
-  float r8[8], r4[4], r2[2];
-  const bool b4 = lane & 16, b3 = lane & 8, b2 = lane & 4, b1 = lane & 2;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) {
-    const float mine = b4 ? v[i + 8] : v[i], send = b4 ? v[i] : v[i + 8];
-    r8[i] = mine + __shfl_xor(send, 16);
-  }
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float mine = b3 ? r8[i + 4] : r8[i], send = b3 ? r8[i] : r8[i + 4];
-    r4[i] = mine + __shfl_xor(send, 8);
-  }
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const float mine = b2 ? r4[i + 2] : r4[i], send = b2 ? r4[i] : r4[i + 2];
-    r2[i] = mine + __shfl_xor(send, 4);
-  }
-  const float mine = b1 ? r2[1] : r2[0], send = b1 ? r2[0] : r2[1];
-  float r = mine + __shfl_xor(send, 2);
-  r += __shfl_xor(r, 1);
-  return r;   // register index = b1 + 2 b2 + 4 b3 + 8 b4 = (lane & 31) >> 1
-}
-
-// ------------------------------------------------------------------------------------------
-struct StripArgs {
-  const bf16_t* anchors[2];     // first local row of the anchor side (image rows for strip 0, text rows for strip 1)
-  const bf16_t* contrasts[2];   // row 0 of the contrast side (texts for strip 0, images for strip 1)
-  int64_t ld_anchor[2], ld_contrast[2];
-  const float* diag;            // s_pp per local anchor
-  const float* kscale[2];       // log2(e) / tau of the anchor for each strip
-  bf16_t* E[2];                 // [b][ldE] out
-  int64_t ldE;
-  float* sums;                  // [4][nparts][bstride] out
-  int nparts;
-  int64_t bstride, b, B, d, off;
-  int nAT, nCT;
-};
-
-template <bool GUARD>
-__device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)[4][4], const float* sdiag,
-                                               const float* sk, float (*sred)[2][256], int strip, int64_t m0,
-                                               int64_t n0, int wm, int wn, int lane) {
-  const int lr = lane & 31, hk = lane >> 5;
-  bf16_t* __restrict__ E = a.E[strip];
-#pragma unroll
-  for (int ti = 0; ti < 4; ++ti) {
-    float sg[16], sh[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { sg[v] = 0.f; sh[v] = 0.f; }
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int rl = wm * 128 + ti * 32 + 8 * q + 4 * hk;           // first of 4 consecutive tile rows
-      const float4 dg = *(const float4*)(sdiag + rl);
-      const float4 ks = *(const float4*)(sk + rl);
-      const float dgv[4] = {dg.x, dg.y, dg.z, dg.w}, ksv[4] = {ks.x, ks.y, ks.z, ks.w};
-#pragma unroll
-      for (int tj = 0; tj < 4; ++tj) {
-        const int64_t n = n0 + wn * 128 + tj * 32 + lr;             // global contrast row
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-          const int v = 4 * q + t;
-          const int64_t m = m0 + rl + t;                            // local anchor
-          const float x = acc[ti][tj][v] - dgv[t];
-          float e = __builtin_amdgcn_exp2f(x * ksv[t]);
-          if (GUARD) {
-            const bool ok = (n < a.B) && (m < a.b) && (n != a.off + m);
-            e = ok ? e : 0.f;
-            if (m < a.b && n < a.ldE) E[m * a.ldE + n] = f2bf(e);
-          } else {
-            E[m * a.ldE + n] = f2bf(e);
-          }
-          sg[v] += e;
-          sh[v] += x * e;
-        }
-      }
-    }
-    const float tg = halfwave_sum16(sg, lane);
-    const float th = halfwave_sum16(sh, lane);
-    if ((lr & 1) == 0) {
-      const int v = lr >> 1;
-      const int row = wm * 128 + ti * 32 + 8 * (v >> 2) + 4 * hk + (v & 3);
-      sred[wn][0][row] = tg;
-      sred[wn][1][row] = th;
-    }
-  }
-}
-
-__global__ void __launch_bounds__(256) k_strips_bf16(StripArgs a) {
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][kTileElems];   // [stage][anchors | contrasts]
-  __shared__ __attribute__((aligned(16))) float sdiag[256];
-  __shared__ __attribute__((aligned(16))) float sk[256];
-  __shared__ float sred[2][2][256];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
-  const int strip = blockIdx.y;
-  // workgroups that share a contrast tile sit on the same XCD (round-robin dispatch: id mod 8) back to back
-  const int xcd = blockIdx.x & 7, jj = blockIdx.x >> 3;
-  const int at = jj % a.nAT;
-  const int ct = (jj / a.nAT) * 8 + xcd;
-  if (ct >= a.nCT) return;
-  const int64_t m0 = (int64_t)at * TM, n0 = (int64_t)ct * TN;
-
-  {
-    const int64_t m = m0 + tid;
-    sdiag[tid] = m < a.b ? a.diag[m] : 0.f;
-    sk[tid] = m < a.b ? a.kscale[strip][m] : 0.f;
-  }
-
-  const bf16_t* __restrict__ A = a.anchors[strip];
-  const bf16_t* __restrict__ X = a.contrasts[strip];
-  const int64_t lda = a.ld_anchor[strip], ldx = a.ld_contrast[strip];
-
-  f32x16 acc[4][4];
+__device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+}
 
-  const int KT = (int)((a.d + TK - 1) / TK);
-  u32x4 ra[8], rb[8];
-  gload_rows(ra, A, lda, m0, a.b, 0, a.d, tid);
-  gload_rows(rb, X, ldx, n0, a.B, 0, a.d, tid);
-  lds_store_rows(lds[0][0], ra, tid);
-  lds_store_rows(lds[0][1], rb, tid);
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < KT;
-    if (more) {
-      gload_rows(ra, A, lda, m0, a.b, (int64_t)(kt + 1) * TK, a.d, tid);
-      gload_rows(rb, X, ldx, n0, a.B, (int64_t)(kt + 1) * TK, a.d, tid);
+// ----------------------------------------------------------------------------------------------------------------
+// Operand sources.  Each describes, for one workgroup tile, how a stage is brought into an LDS slot (dma: 8 wave
+// loads per thread and stage, indices 0..3 = A operand, 4..7 = B operand; fill_guarded: the same image through
+// registers with zero fill) and how a wave reads its MFMA operands from the slot.
+//
+// Strip kernel: both operands are K-contiguous row tiles.  A operand = 256 contrast rows, B operand = 256 anchor rows.
+struct StripTile {
+  const bf16_t* ga[4];   // per-thread source of the 4 A-operand wave loads of stage 0
+  const bf16_t* gb[4];
+  uint32_t la[4], lb[4]; // LDS byte offsets inside a slot
+  int wr, wc_, lr, hk;   // wave row/col block, lane split
+  // guarded path
+  const bf16_t *A, *X;
+  int64_t lda, ldx, a_row0, a_rows, x_row0, x_rows, d;
+
+  __device__ __forceinline__ void setup(const bf16_t* Xc, int64_t ldx_, int64_t c0, int64_t B, const bf16_t* An,
+                                        int64_t lda_, int64_t a0, int64_t b, int64_t d_, int tid) {
+    const int wave = tid >> 6, lane = tid & 63;
+    wr = wave >> 1; wc_ = wave & 1; lr = lane & 31; hk = lane >> 5;
+    X = Xc; ldx = ldx_; x_row0 = c0; x_rows = B; A = An; lda = lda_; a_row0 = a0; a_rows = b; d = d_;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int j = wave * 4 + i;                      // wave load j covers rows 16 j .. 16 j + 15 of the tile
+      const int row = 16 * j + (lane >> 2);
+      const int chunk = ((lane & 3) ^ (row >> 1)) & 3; // logical chunk fetched into position (lane & 3)
+      ga[i] = Xc + (c0 + row) * ldx_ + chunk * 8;
+      gb[i] = An + (a0 + row) * lda_ + chunk * 8;
+      la[i] = (uint32_t)(j * 1024);
+      lb[i] = (uint32_t)(kOpBytes + j * 1024);
     }
-    mma_stage(acc, lds[cur][0], lds[cur][1], wm, wn, lane);
-    if (more) {
-      lds_store_rows(lds[cur ^ 1][0], ra, tid);
-      lds_store_rows(lds[cur ^ 1][1], rb, tid);
+  }
+  __device__ __forceinline__ void dma(int i, int stage, uint32_t slot) const {
+    if (i < 4) dma16(ga[i] + (int64_t)stage * BK, slot + la[i]);
+    else dma16(gb[i - 4] + (int64_t)stage * BK, slot + lb[i - 4]);
+  }
+  __device__ __forceinline__ void fill_guarded(int stage, char* slot, int tid) const {
+    const int chunk = tid & 3;
+    const int64_t k = (int64_t)stage * BK + chunk * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = (tid >> 2) + 64 * i;
+      u32x4 va = {0u, 0u, 0u, 0u}, vb = {0u, 0u, 0u, 0u};
+      if (k < d && x_row0 + row < x_rows) va = *(const u32x4*)(X + (x_row0 + row) * ldx + k);
+      if (k < d && a_row0 + row < a_rows) vb = *(const u32x4*)(A + (a_row0 + row) * lda + k);
+      *(u32x4*)(slot + rt_off(row, chunk)) = va;
+      *(u32x4*)(slot + kOpBytes + rt_off(row, chunk)) = vb;
     }
-    __syncthreads();
+  }
+  __device__ __forceinline__ bf16x8 read_a(const char* slot, int t, int kk) const {
+    return *(const bf16x8*)(slot + rt_off(wr * 128 + t * 32 + lr, kk * 2 + hk));
+  }
+  __device__ __forceinline__ bf16x8 read_b(const char* slot, int t, int kk) const {
+    return *(const bf16x8*)(slot + kOpBytes + rt_off(wc_ * 128 + t * 32 + lr, kk * 2 + hk));
+  }
+};
+
+// Contraction kernel: A operand = 8 anchor blocks x 2 column blocks of Efrag per stage (fragments are copied as they
+// are), B operand = 32 rows x 256 columns of X in its natural layout, read with transposing LDS reads.
+struct ContractTile {
+  const bf16_t* ga[4];
+  const bf16_t* gb_lo[4];  // source of the B wave loads for stage rows that are contrasts (global rows)
+  int64_t gb_step;         // elements per stage along the rows of X
+  int64_t local_shift;     // (off - ldE) * ldx: added for stages in the local-anchor column range
+  int first_local_stage;   // stages >= this read X rows off + (k - ldE)
+  uint32_t la[4], lb[4];
+  int wm, wn, lane;
+  // guarded path
+  const bf16_t* X;
+  int64_t ldx, n0, N, B, bloc, off, ldE;
+
+  __device__ __forceinline__ void setup(const bf16_t* E, int64_t nCB, int64_t ab0, const bf16_t* X_, int64_t ldx_,
+                                        int64_t n0_, int64_t N_, int64_t B_, int64_t bloc_, int64_t off_,
+                                        int64_t ldE_, int tid) {
+    const int wave = tid >> 6;
+    lane = tid & 63; wm = wave >> 1; wn = wave & 1;
+    X = X_; ldx = ldx_; n0 = n0_; N = N_; B = B_; bloc = bloc_; off = off_; ldE = ldE_;
+    gb_step = (int64_t)BK * ldx_;
+    local_shift = (off_ - ldE_) * ldx_;
+    first_local_stage = (int)(ldE_ / BK);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int f = wave * 4 + i;                       // fragment f = 2 * (anchor block) + (column block in stage)
+      ga[i] = E + (((ab0 + (f >> 1)) * nCB + (f & 1)) * 64 + lane) * 8;
+      la[i] = (uint32_t)(f * 1024);
+      const int k = 2 * f + (lane >> 5);                // wave load f covers stage rows 2 f, 2 f + 1
+      const int piece = (lane & 31) ^ ((k & 3) << 1);   // logical piece fetched into position (lane & 31)
+      gb_lo[i] = X_ + (int64_t)k * ldx_ + n0_ + piece * 8;
+      lb[i] = (uint32_t)(kOpBytes + f * 1024);
+    }
+  }
+  __device__ __forceinline__ void dma(int i, int stage, uint32_t slot) const {
+    if (i < 4) {
+      dma16(ga[i] + (int64_t)stage * (2 * 64 * 8), slot + la[i]);
+    } else {
+      const bf16_t* g = gb_lo[i - 4] + (int64_t)stage * gb_step;
+      if (stage >= first_local_stage) g += local_shift;
+      dma16(g, slot + lb[i - 4]);
+    }
+  }
+  __device__ __forceinline__ void fill_guarded(int stage, char* slot, int tid) const {
+    const int wave = tid >> 6;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int f = wave * 4 + i;
+      *(u32x4*)(slot + f * 1024 + lane * 16) = *(const u32x4*)(ga[i] + (int64_t)stage * (2 * 64 * 8));
+      const int k = 2 * f + (lane >> 5);
+      const int piece = (lane & 31) ^ ((k & 3) << 1);
+      const int64_t c = (int64_t)stage * BK + k;        // extended column
+      const int64_t row = c < ldE ? c : off + (c - ldE);
+      const bool ok = (c < ldE ? c < B : (c - ldE) < bloc) && (n0 + piece * 8 < N);
+      u32x4 v = {0u, 0u, 0u, 0u};
+      if (ok) v = *(const u32x4*)(X + row * ldx + n0 + piece * 8);
+      *(u32x4*)(slot + kOpBytes + f * 1024 + lane * 16) = v;
+    }
+  }
+  __device__ __forceinline__ bf16x8 read_a(const char* slot, int t, int kk) const {
+    return *(const bf16x8*)(slot + (((wm * 4 + t) * 2 + kk) * 1024 + lane * 16));
+  }
+  // slots e = 0..3 <-> rows 16 kk + 4 h + e, slots 4..7 <-> rows 16 kk + 8 + 4 h + (e - 4): two transposing reads,
+  // each taking 4 rows x 16 columns per group of 16 lanes (source lane s: row s / 4, columns 4 (s % 4) ..).
+  __device__ __forceinline__ bf16x8 read_b(const char* slot, int t, int kk) const {
+    const int h = lane >> 5, s = lane & 15;
+    const int n = wn * 128 + t * 32 + ((lane >> 4) & 1) * 16 + 4 * (s & 3);   // first of 4 columns read by this lane
+    const int k = 16 * kk + 4 * h + (s >> 2);
+    const char* base = slot + kOpBytes + ((n & 7) << 1);
+    lds_v4s* p0 = (lds_v4s*)(uintptr_t)lds_addr(base + nt_off(k, n >> 3));
+    lds_v4s* p1 = (lds_v4s*)(uintptr_t)lds_addr(base + nt_off(k + 8, n >> 3));
+    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p0);
+    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p1);
+    u32x4 r;
+    const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+    r[0] = l2[0]; r[1] = l2[1]; r[2] = h2[0]; r[3] = h2[1];
+    return __builtin_bit_cast(bf16x8, r);
+  }
+};
+
+#define FC_MM(ti, tj, A_, B_) acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A_[ti], B_[tj], acc[ti][tj], 0, 0, 0)
+
+// One 32-deep stage of the ring: 16 MFMAs on the operands already in registers while the operands of the second
+// 16-deep step are read; then "stage s+1 has landed" (vmcnt) + barrier, which also retires slot (s-1) for reuse; then
+// 16 MFMAs while the first operands of stage s+1 are read and the 8 wave loads of stage s+3 are issued.
+#define FC_STAGE(T, MORE, DMA)                                                                                      \
+  {                                                                                                                 \
+    const char* sl = ring + (s & 3) * kStageBytes;                                                                  \
+    FC_MM(0, 0, a0, b0); FC_MM(0, 1, a0, b0); FC_PIN(); a1[0] = T.read_a(sl, 0, 1); FC_PIN();                       \
+    FC_MM(0, 2, a0, b0); FC_MM(0, 3, a0, b0); FC_PIN(); b1[0] = T.read_b(sl, 0, 1); FC_PIN();                       \
+    FC_MM(1, 0, a0, b0); FC_MM(1, 1, a0, b0); FC_PIN(); a1[1] = T.read_a(sl, 1, 1); FC_PIN();                       \
+    FC_MM(1, 2, a0, b0); FC_MM(1, 3, a0, b0); FC_PIN(); b1[1] = T.read_b(sl, 1, 1); FC_PIN();                       \
+    FC_MM(2, 0, a0, b0); FC_MM(2, 1, a0, b0); FC_PIN(); a1[2] = T.read_a(sl, 2, 1); FC_PIN();                       \
+    FC_MM(2, 2, a0, b0); FC_MM(2, 3, a0, b0); FC_PIN(); b1[2] = T.read_b(sl, 2, 1); FC_PIN();                       \
+    FC_MM(3, 0, a0, b0); FC_MM(3, 1, a0, b0); FC_PIN(); a1[3] = T.read_a(sl, 3, 1); FC_PIN();                       \
+    FC_MM(3, 2, a0, b0); FC_MM(3, 3, a0, b0); FC_PIN(); b1[3] = T.read_b(sl, 3, 1); FC_PIN();                       \
+    if (DMA) FC_WAIT_VMCNT8(); else FC_WAIT_VMCNT0();                                                               \
+    __syncthreads();                                                                                                \
+    FC_PIN();                                                                                                       \
+    const char* nx = ring + ((s + 1) & 3) * kStageBytes;                                                            \
+    const uint32_t dslot = ring_addr + (uint32_t)((s + 3) & 3) * kStageBytes;                                       \
+    FC_MM(0, 0, a1, b1); FC_MM(0, 1, a1, b1); FC_PIN(); if (MORE) a0[0] = T.read_a(nx, 0, 0); FC_PIN(); if (DMA) T.dma(0, s0 + s + 3, dslot); FC_PIN(); \
+    FC_MM(0, 2, a1, b1); FC_MM(0, 3, a1, b1); FC_PIN(); if (MORE) b0[0] = T.read_b(nx, 0, 0); FC_PIN(); if (DMA) T.dma(4, s0 + s + 3, dslot); FC_PIN(); \
+    FC_MM(1, 0, a1, b1); FC_MM(1, 1, a1, b1); FC_PIN(); if (MORE) a0[1] = T.read_a(nx, 1, 0); FC_PIN(); if (DMA) T.dma(1, s0 + s + 3, dslot); FC_PIN(); \
+    FC_MM(1, 2, a1, b1); FC_MM(1, 3, a1, b1); FC_PIN(); if (MORE) b0[1] = T.read_b(nx, 1, 0); FC_PIN(); if (DMA) T.dma(5, s0 + s + 3, dslot); FC_PIN(); \
+    FC_MM(2, 0, a1, b1); FC_MM(2, 1, a1, b1); FC_PIN(); if (MORE) a0[2] = T.read_a(nx, 2, 0); FC_PIN(); if (DMA) T.dma(2, s0 + s + 3, dslot); FC_PIN(); \
+    FC_MM(2, 2, a1, b1); FC_MM(2, 3, a1, b1); FC_PIN(); if (MORE) b0[2] = T.read_b(nx, 2, 0); FC_PIN(); if (DMA) T.dma(6, s0 + s + 3, dslot); FC_PIN(); \
+    FC_MM(3, 0, a1, b1); FC_MM(3, 1, a1, b1); FC_PIN(); if (MORE) a0[3] = T.read_a(nx, 3, 0); FC_PIN(); if (DMA) T.dma(3, s0 + s + 3, dslot); FC_PIN(); \
+    FC_MM(3, 2, a1, b1); FC_MM(3, 3, a1, b1); FC_PIN(); if (MORE) b0[3] = T.read_b(nx, 3, 0); FC_PIN(); if (DMA) T.dma(7, s0 + s + 3, dslot); FC_PIN(); \
   }
 
-  // tiles that touch the own-column diagonal or a ragged edge take the guarded epilogue
-  const bool ragged = (m0 + TM > a.b) || (n0 + TN > a.B);
-  const bool diagonal = (n0 < a.off + m0 + TM) && (n0 + TN > a.off + m0);
-  if (ragged || diagonal)
-    strip_epilogue<true>(a, acc, sdiag, sk, sred, strip, m0, n0, wm, wn, lane);
-  else
-    strip_epilogue<false>(a, acc, sdiag, sk, sred, strip, m0, n0, wm, wn, lane);
-  __syncthreads();
-  {
-    const int64_t m = m0 + tid;
-    if (m < a.b) {
+// Issue the wave loads of the first min(S, 3) stages [s0, ...) of a tile into ring slots 0, 1, 2.
+template <typename Tile>
+__device__ __forceinline__ void ring_prologue(const Tile& T, uint32_t ring_addr, int s0, int S) {
 #pragma unroll
-      for (int q = 0; q < 2; ++q)
-        a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + m] = sred[0][q][tid] + sred[1][q][tid];
+  for (int p = 0; p < 3; ++p)
+    if (p < S) {
+#pragma unroll
+      for (int i = 0; i < 8; ++i) T.dma(i, s0 + p, ring_addr + p * kStageBytes);
     }
+}
+
+// acc += (A operand tile) x (B operand tile)^T over stages [s0, s0 + S); the prologue must have been issued, and
+// nothing else may have touched the ring since.  On return no wave reads the ring any more.
+template <typename Tile>
+__device__ __forceinline__ void ring_mainloop(f32x16 (&acc)[4][4], const Tile& T, char* ring, uint32_t ring_addr,
+                                              int s0, int S) {
+  FC_WAIT_VMCNT0();
+  __syncthreads();
+  bf16x8 a0[4], b0[4], a1[4], b1[4];
+#pragma unroll
+  for (int t = 0; t < 4; ++t) { a0[t] = T.read_a(ring, t, 0); b0[t] = T.read_b(ring, t, 0); }
+  int s = 0;
+  for (; s + 3 < S; ++s) FC_STAGE(T, true, true)
+  for (; s + 1 < S; ++s) FC_STAGE(T, true, false)
+  FC_STAGE(T, false, false)
+}
+
+// Same contraction for tiles with a ragged edge: one stage at a time through registers, zero fill outside.
+template <typename Tile>
+__device__ __forceinline__ void guarded_mainloop(f32x16 (&acc)[4][4], const Tile& T, char* ring, int s0, int S,
+                                                 int tid) {
+  bf16x8 a[4], bq[4];
+  for (int s = 0; s < S; ++s) {
+    __syncthreads();
+    T.fill_guarded(s0 + s, ring, tid);
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) { a[t] = T.read_a(ring, t, kk); bq[t] = T.read_b(ring, t, kk); }
+#pragma unroll
+      for (int ti = 0; ti < 4; ++ti)
+#pragma unroll
+        for (int tj = 0; tj < 4; ++tj) FC_MM(ti, tj, a, bq);
+    }
+  }
+  __syncthreads();
+}
+
+// ----------------------------------------------------------------------------------------------------------------
+struct StripArgs {
+  const bf16_t* anchors[2];     // first local row of the anchor side (image rows for strip 0, text rows for strip 1)
+  const bf16_t* contrasts[2];   // row 0 of the contrast side (texts for strip 0, images for strip 1)
+  int64_t ld_anchor[2], ld_contrast[2];
+  const float* diag;            // s_pp per local anchor
+  const float* kscale[2];       // log2(e) / tau of the anchor for each strip
+  bf16_t* E[2];                 // Efrag per strip
+  int64_t nCB;                  // column blocks (of 16) per anchor block in Efrag
+  int64_t ldE;                  // contrast columns present in Efrag (multiple of 64, >= B)
+  float* sums;                  // [4][nparts][bstride] out
+  int nparts;
+  int64_t bstride, b, B, d, off;
+  int nAT, nCT, ntiles;
+};
+
+// Accumulator (ti, tj, v) of lane (lr, hk): contrast c0 + wr 128 + ti 32 + 8 (v >> 2) + 4 hk + (v & 3), anchor
+// a0 + wc 128 + tj 32 + lr.  t = (s - s_pp) log2(e)/tau, l = 2^t.  GUARD: zero outside the batch and on the anchor's
+// own column (B_{i-} excludes i).
+template <bool GUARD>
+__device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)[4][4], const float* sk,
+                                               const float* sdk, float (*sred)[2][256], int strip, int64_t a0,
+                                               int64_t c0, int wr, int wc, int lane) {
+  const int lr = lane & 31, hk = lane >> 5;
+  bf16_t* __restrict__ E = a.E[strip];
+  // 16 independent partial sums per anchor block and quantity: a dependent VALU op issues only every ~36 cycles on a
+  // lone wavefront, so serial accumulation chains would dominate this phase
+  float sgv[4][16], stv[4][16], kk[4], dk[4];
+#pragma unroll
+  for (int tj = 0; tj < 4; ++tj) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { sgv[tj][v] = 0.f; stv[tj][v] = 0.f; }
+    kk[tj] = sk[wc * 128 + tj * 32 + lr];
+    dk[tj] = sdk[wc * 128 + tj * 32 + lr];
+  }
+  // fragment (ab, cb) of this lane: E + ((ab nCB + cb) 64 + lane) 8; ab and cb are wave-uniform
+  const int64_t ab0 = (a0 + wc * 128) >> 5, cb0 = (c0 + wr * 128) >> 4;
+  bf16_t* __restrict__ Elane = E + lane * 8;
+#pragma unroll
+  for (int ti = 0; ti < 4; ++ti) {
+    const int64_t crow = c0 + wr * 128 + ti * 32 + 4 * hk;
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      const int64_t anchor = a0 + wc * 128 + tj * 32 + lr;
+      float t[16], e[16];
+#pragma unroll
+      for (int v = 0; v < 16; ++v) t[v] = fmaf(acc[ti][tj][v], kk[tj], -dk[tj]);
+#pragma unroll
+      for (int v = 0; v < 16; ++v) e[v] = __builtin_amdgcn_exp2f(t[v]);
+      if (GUARD) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int64_t c = crow + 8 * (v >> 2) + (v & 3);
+          const bool ok = (c < a.B) && (anchor < a.b) && (c != a.off + anchor);
+          e[v] = ok ? e[v] : 0.f;
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        sgv[tj][v] += e[v];
+        stv[tj][v] = fmaf(t[v], e[v], stv[tj][v]);
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        bf16x8 pk;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) pk[q] = (__bf16)e[8 * j + q];
+        const int64_t cb = cb0 + 2 * ti + j;
+        if (!GUARD || 16 * cb < a.ldE) *(bf16x8*)(Elane + ((ab0 + tj) * a.nCB + cb) * 512) = pk;
+      }
+    }
+  }
+#pragma unroll
+  for (int tj = 0; tj < 4; ++tj) {
+#pragma unroll
+    for (int w = 8; w > 0; w >>= 1)
+#pragma unroll
+      for (int v = 0; v < w; ++v) { sgv[tj][v] += sgv[tj][v + w]; stv[tj][v] += stv[tj][v + w]; }
+    const float sg = sgv[tj][0] + __shfl_xor(sgv[tj][0], 32);
+    const float st = stv[tj][0] + __shfl_xor(stv[tj][0], 32);
+    if (hk == 0) {
+      sred[wr][0][wc * 128 + tj * 32 + lr] = sg;
+      sred[wr][1][wc * 128 + tj * 32 + lr] = kk[tj] > 0.f ? st / kk[tj] : 0.f;   // sum of (s - s_pp) l
+    }
+  }
+}
+
+__global__ void __launch_bounds__(256) k_strips_bf16(StripArgs a) {
+  __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
+  __shared__ float sk[256];
+  __shared__ float sdk[256];
+  __shared__ float sred[2][2][256];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave >> 1, wc = wave & 1;
+  const uint32_t ring_addr = lds_addr(ring);
+  const int S = (int)((a.d + BK - 1) / BK);
+  // persistent workgroups; ids that share an XCD (id mod 8 under round-robin dispatch) take neighbouring tiles, and
+  // neighbouring tiles are the anchor tiles of one contrast tile, so a contrast tile is fetched once per L2
+  const int G = gridDim.x;
+  const int vid = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+  const int per_strip = a.nAT * a.nCT;
+
+  StripTile T;
+  bool prefetched = false;
+  for (int t = vid; t < a.ntiles; t += G) {
+    const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
+    const int64_t a0 = (int64_t)at * 256, c0 = (int64_t)ct * 256;
+    const bool fast = (a0 + 256 <= a.b) && (c0 + 256 <= a.B) && (a.d % BK == 0);
+    {
+      const int64_t m = a0 + tid;
+      const float kv = m < a.b ? a.kscale[strip][m] : 0.f;
+      sk[tid] = kv;
+      sdk[tid] = m < a.b ? a.diag[m] * kv : 0.f;
+    }
+    f32x16 acc[4][4];
+    zero_acc(acc);
+    if (!prefetched)
+      T.setup(a.contrasts[strip], a.ld_contrast[strip], c0, a.B, a.anchors[strip], a.ld_anchor[strip], a0, a.b, a.d, tid);
+    if (fast) {
+      if (!prefetched) ring_prologue(T, ring_addr, 0, S);
+      ring_mainloop(acc, T, ring, ring_addr, 0, S);
+    } else {
+      guarded_mainloop(acc, T, ring, 0, S, tid);
+    }
+    // start fetching the next tile while this one's exponentials are evaluated
+    prefetched = false;
+    const int tn = t + G;
+    if (tn < a.ntiles) {
+      const int nstrip = tn / per_strip, nat = tn % a.nAT, nct = (tn / a.nAT) % a.nCT;
+      const int64_t na0 = (int64_t)nat * 256, nc0 = (int64_t)nct * 256;
+      if ((na0 + 256 <= a.b) && (nc0 + 256 <= a.B) && (a.d % BK == 0)) {
+        T.setup(a.contrasts[nstrip], a.ld_contrast[nstrip], nc0, a.B, a.anchors[nstrip], a.ld_anchor[nstrip], na0, a.b,
+                a.d, tid);
+        ring_prologue(T, ring_addr, 0, S);
+        prefetched = true;
+      }
+    }
+    const bool diagonal = (c0 < a.off + a0 + 256) && (c0 + 256 > a.off + a0);
+    if (!fast || diagonal) strip_epilogue<true>(a, acc, sk, sdk, sred, strip, a0, c0, wr, wc, lane);
+    else strip_epilogue<false>(a, acc, sk, sdk, sred, strip, a0, c0, wr, wc, lane);
+    __syncthreads();
+    {
+      const int64_t m = a0 + tid;
+      if (m < a.b) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+          a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + m] = sred[0][q][tid] + sred[1][q][tid];
+      }
+    }
+    __syncthreads();
   }
 }
 
@@ -286,158 +460,149 @@ void launch_strips_bf16(const StepCtx& c) {
   a.kscale[1] = (const float*)(c.ws + L.k2);
   a.E[0] = (bf16_t*)(c.ws + L.E[0]);
   a.E[1] = (bf16_t*)(c.ws + L.E[1]);
+  a.nCB = (L.ldE + L.ldW) / 16;
   a.ldE = L.ldE;
   a.sums = (float*)(c.ws + L.sums);
   a.nparts = L.nparts; a.bstride = L.bstride; a.b = L.b; a.B = L.B; a.d = L.d; a.off = L.off;
-  a.nAT = (int)((L.b + TM - 1) / TM);
-  a.nCT = (int)((L.B + TN - 1) / TN);
-  const unsigned gx = 8u * (unsigned)a.nAT * (unsigned)((a.nCT + 7) / 8);
-  hipLaunchKernelGGL(k_strips_bf16, dim3(gx, 2), dim3(256), 0, c.s, a);
+  a.nAT = (int)((L.b + 255) / 256);
+  a.nCT = (int)((L.B + 255) / 256);
+  a.ntiles = 2 * a.nAT * a.nCT;
+  const int grid = a.ntiles < 256 ? a.ntiles : 256;
+  hipLaunchKernelGGL(k_strips_bf16, dim3((unsigned)grid), dim3(256), 0, c.s, a);
 }
 
-// ------------------------------------------------------------------------------------------
-// WT[side][r][q] = c_other[q] * l_other(q, off + r)  for local anchors q != r (the stored strips already hold 0
-// at q == r), zero for q >= b.  side 0 feeds d_img (other = text side: c2, l2), side 1 feeds d_txt.
-__global__ void __launch_bounds__(256) k_local_bf16(const bf16_t* __restrict__ E1, const bf16_t* __restrict__ E2,
-                                                    int64_t ldE, const float* __restrict__ c1,
-                                                    const float* __restrict__ c2, int64_t off, int64_t b,
-                                                    bf16_t* __restrict__ WT0, bf16_t* __restrict__ WT1, int64_t ldW) {
-  __shared__ float tile[64][65];
-  const int side = blockIdx.z;
-  const bf16_t* __restrict__ E = side == 0 ? E2 : E1;
-  const float* __restrict__ cc = side == 0 ? c2 : c1;
-  bf16_t* __restrict__ WT = side == 0 ? WT0 : WT1;
-  const int64_t r0 = (int64_t)blockIdx.x * 64, q0 = (int64_t)blockIdx.y * 64;
-  const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+// ----------------------------------------------------------------------------------------------------------------
+// One thread per (local anchor r, block of 16 local anchors q): reads l_other(q, off + r) from the other strip's
+// Efrag, scales by c_other[q] / c_own[r], and writes the two 16-byte halves of the fragment row in the extended
+// column range of the own strip.  The other strip already holds 0 at q == r.
+__global__ void __launch_bounds__(256) k_local_bf16(const bf16_t* __restrict__ E0, const bf16_t* __restrict__ E1,
+                                                    bf16_t* __restrict__ W0, bf16_t* __restrict__ W1, int64_t nCB,
+                                                    int64_t ldE, int64_t ldW, const float* __restrict__ c1,
+                                                    const float* __restrict__ c2, int64_t off, int64_t b) {
+  const int side = blockIdx.y;
+  const bf16_t* __restrict__ Esrc = side == 0 ? E1 : E0;   // d_img needs l2 (text strip), d_txt needs l1
+  bf16_t* __restrict__ Edst = side == 0 ? W0 : W1;
+  const float* __restrict__ c_own = side == 0 ? c1 : c2;
+  const float* __restrict__ c_oth = side == 0 ? c2 : c1;
+  const int64_t nqb = ldW / 16;
+  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (id >= b * nqb) return;
+  const int64_t r = id / nqb, qb = id % nqb;
+  const int64_t c = off + r;                                // the column of local row p_r in the other strip
+  const int64_t cb_src = c >> 4;
+  const int o_src = (int)(c & 15), h_src = (o_src >> 2) & 1, e_src = ((o_src >> 3) << 2) + (o_src & 3);
+  const float inv_own = 1.0f / c_own[r];
+  uint16_t out[2][8];
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int64_t q = q0 + y + 4 * i, r = r0 + x;
+  for (int o = 0; o < 16; ++o) {
+    const int64_t q = qb * 16 + o;
     float v = 0.f;
-    if (q < b && r < b) v = cc[q] * bf2f(E[q * ldE + off + r]);
-    tile[y + 4 * i][x] = v;          // [q][r]
+    if (q < b) v = c_oth[q] * bf2f(Esrc[(((q >> 5) * nCB + cb_src) * 64 + (q & 31) + 32 * h_src) * 8 + e_src]) * inv_own;
+    out[(o >> 2) & 1][((o >> 3) << 2) + (o & 3)] = f2bf(v);
   }
-  __syncthreads();
+  const int64_t cb_dst = (ldE >> 4) + qb;
 #pragma unroll
-  for (int i = 0; i < 16; ++i) {
-    const int64_t r = r0 + y + 4 * i, q = q0 + x;
-    if (r < b && q < ldW) WT[r * ldW + q] = f2bf(tile[x][y + 4 * i]);
+  for (int h = 0; h < 2; ++h) {
+    u32x4 w;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)out[h][2 * i] | ((uint32_t)out[h][2 * i + 1] << 16);
+    *(u32x4*)(Edst + (((r >> 5) * nCB + cb_dst) * 64 + (r & 31) + 32 * h) * 8) = w;
   }
 }
 
 void launch_local_bf16(const StepCtx& c) {
   const Layout& L = c.L;
-  dim3 grid((unsigned)((L.b + 63) / 64), (unsigned)(L.ldW / 64), 2);
+  const int64_t n = L.b * (L.ldW / 16);
+  dim3 grid((unsigned)((n + 255) / 256), 2);
   hipLaunchKernelGGL(k_local_bf16, grid, dim3(256), 0, c.s, (const bf16_t*)(c.ws + L.E[0]),
-                     (const bf16_t*)(c.ws + L.E[1]), L.ldE, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
-                     L.off, L.b, (bf16_t*)(c.ws + L.WT[0]), (bf16_t*)(c.ws + L.WT[1]), L.ldW);
+                     (const bf16_t*)(c.ws + L.E[1]), (bf16_t*)(c.ws + L.E[0]), (bf16_t*)(c.ws + L.E[1]),
+                     (L.ldE + L.ldW) / 16, L.ldE, L.ldW, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.off,
+                     L.b);
 }
 
-// ------------------------------------------------------------------------------------------
-struct GemmJob {
-  const bf16_t* A;    // [M][lda], K contiguous; readable and zero beyond K up to a_kvalid (multiple of 8)
-  const bf16_t* Bm;   // [K][ldb], N contiguous
+// ----------------------------------------------------------------------------------------------------------------
+struct ContractJob {
+  const bf16_t* E;    // Efrag of this strip
+  const bf16_t* X;    // the matrix whose rows the strip weights: texts for strip 0, images for strip 1
   float* C;           // [nsplit][M][ldc]
-  int64_t lda, ldb, ldc, a_kvalid, M, N, K, kslice;
+  int64_t ldx, ldc;
   size_t split_stride;
-  int nsplit, tiles_m, wg_begin, wg_end;
 };
-struct GemmArgs {
-  GemmJob job[4];
-  int njobs;
+struct ContractArgs {
+  ContractJob job[2];
+  int64_t nCB, M, N, B, bloc, off, ldE;
+  int stages, slice, nsplit, tiles_m, tiles_n;   // stages: total 32-deep stages; slice: stages per split
+  int all_rows_valid;                            // B == ldE and b == ldW: no zero rows inside the column range
 };
 
-__global__ void __launch_bounds__(256) k_gemm_nn_bf16(GemmArgs g) {
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2][2][kTileElems];
+__global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
+  __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  int ji = 0;
-#pragma unroll
-  for (int i = 1; i < 4; ++i)
-    if (i < g.njobs && (int)blockIdx.x >= g.job[i].wg_begin) ji = i;
-  const GemmJob& J = g.job[ji];
-  const int local = (int)blockIdx.x - J.wg_begin;
-  const int split = local % J.nsplit;           // consecutive ids -> different XCDs -> different K slices
-  const int tile = local / J.nsplit;
-  const int64_t m0 = (int64_t)(tile % J.tiles_m) * TM, n0 = (int64_t)(tile / J.tiles_m) * TN;
-  const int64_t kbeg = (int64_t)split * J.kslice;
-  const int64_t kend = kbeg + J.kslice < J.K ? kbeg + J.kslice : J.K;
-  const int64_t a_kend = kbeg + J.kslice < J.a_kvalid ? kbeg + J.kslice : J.a_kvalid;
+  const uint32_t ring_addr = lds_addr(ring);
+  const int per_job = g.nsplit * g.tiles_m * g.tiles_n;
+  const int ji = (int)blockIdx.x / per_job;
+  const int local = (int)blockIdx.x % per_job;
+  const ContractJob& J = g.job[ji];
+  const int split = local % g.nsplit;            // consecutive ids -> different XCDs -> different column slices
+  const int tile = local / g.nsplit;
+  const int64_t m0 = (int64_t)(tile % g.tiles_m) * 256, n0 = (int64_t)(tile / g.tiles_m) * 256;
+  const int s0 = split * g.slice;
+  const int S = (s0 + g.slice <= g.stages ? g.slice : g.stages - s0);
 
   f32x16 acc[4][4];
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-
-  const int KT = (int)((kend - kbeg + TK - 1) / TK);
-  u32x4 ra[8], rb[8];
-  if (KT > 0) {
-    gload_rows(ra, J.A, J.lda, m0, J.M, kbeg, a_kend, tid);
-    gload_cols(rb, J.Bm, J.ldb, kbeg, kend, n0, J.N, tid);
-    lds_store_rows(lds[0][0], ra, tid);
-    lds_store_cols_transposed(lds[0][1], rb, tid);
-  }
-  __syncthreads();
-  for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    const bool more = kt + 1 < KT;
-    if (more) {
-      gload_rows(ra, J.A, J.lda, m0, J.M, kbeg + (int64_t)(kt + 1) * TK, a_kend, tid);
-      gload_cols(rb, J.Bm, J.ldb, kbeg + (int64_t)(kt + 1) * TK, kend, n0, J.N, tid);
+  zero_acc(acc);
+  if (S > 0) {
+    ContractTile T;
+    T.setup(J.E, g.nCB, m0 >> 5, J.X, J.ldx, n0, g.N, g.B, g.bloc, g.off, g.ldE, tid);
+    if (g.all_rows_valid && n0 + 256 <= g.N) {
+      ring_prologue(T, ring_addr, s0, S);
+      ring_mainloop(acc, T, ring, ring_addr, s0, S);
+    } else {
+      guarded_mainloop(acc, T, ring, s0, S, tid);
     }
-    mma_stage(acc, lds[cur][0], lds[cur][1], wm, wn, lane);
-    if (more) {
-      lds_store_rows(lds[cur ^ 1][0], ra, tid);
-      lds_store_cols_transposed(lds[cur ^ 1][1], rb, tid);
-    }
-    __syncthreads();
   }
-
+  // C[m][n]: m = m0 + wm 128 + ti 32 + 8 q + 4 hk + t, n = n0 + wn 128 + tj 32 + lr.  Everything but (hk, lr) is
+  // wave-uniform, so each store is a uniform base plus a small per-lane offset.
   float* __restrict__ C = J.C + (size_t)split * J.split_stride;
   const int lr = lane & 31, hk = lane >> 5;
+  const int64_t lane_off = (int64_t)(4 * hk) * J.ldc + lr;
+  const bool full = (m0 + 256 <= g.M) && (n0 + 256 <= g.N);
 #pragma unroll
   for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
     for (int tj = 0; tj < 4; ++tj) {
-      const int64_t n = n0 + wn * 128 + tj * 32 + lr;
+      const int64_t nb = n0 + wn * 128 + tj * 32;
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int64_t m = m0 + wm * 128 + ti * 32 + 8 * (v >> 2) + 4 * hk + (v & 3);
-        if (m < J.M && n < J.N) C[m * J.ldc + n] = acc[ti][tj][v];
+        const int64_t mb = m0 + wm * 128 + ti * 32 + 8 * (v >> 2) + (v & 3);
+        float* rowp = C + mb * J.ldc + nb;
+        if (full || (mb + 4 * hk < g.M && nb + lr < g.N)) rowp[lane_off] = acc[ti][tj][v];
       }
     }
 }
 
 void launch_contract_bf16(const StepCtx& c) {
   const Layout& L = c.L;
-  const bf16_t* img = (const bf16_t*)c.buf.img_glob;
-  const bf16_t* txt = (const bf16_t*)c.buf.txt_glob;
-  GemmArgs g;
-  g.njobs = 4;
-  const int tiles_m = (int)((L.b + TM - 1) / TM), tiles_n = (int)((L.d + TN - 1) / TN);
-  int wg = 0;
-  for (int s = 0; s < 2; ++s) {           // sum_j l(r, j) x_j over all contrasts, split over j
-    GemmJob& J = g.job[s];
-    J.A = (const bf16_t*)(c.ws + L.E[s]);  J.lda = L.ldE;  J.a_kvalid = L.ldE;
-    J.Bm = s == 0 ? txt : img;             J.ldb = s == 0 ? c.cfg.ld_txt : c.cfg.ld_img;
-    J.C = (float*)(c.ws + L.Opart[s]);     J.ldc = L.d;
-    J.split_stride = (size_t)L.b * (size_t)L.d;
-    J.M = L.b; J.N = L.d; J.K = L.B; J.kslice = L.kslice; J.nsplit = L.nsplit; J.tiles_m = tiles_m;
-    J.wg_begin = wg;  wg += tiles_m * tiles_n * L.nsplit;  J.wg_end = wg;
+  ContractArgs g;
+  for (int s = 0; s < 2; ++s) {
+    g.job[s].E = (const bf16_t*)(c.ws + L.E[s]);
+    g.job[s].X = (const bf16_t*)(s == 0 ? c.buf.txt_glob : c.buf.img_glob);
+    g.job[s].ldx = s == 0 ? c.cfg.ld_txt : c.cfg.ld_img;
+    g.job[s].C = (float*)(c.ws + L.Opart[s]);
+    g.job[s].ldc = L.d;
+    g.job[s].split_stride = (size_t)L.b * (size_t)L.d;
   }
-  for (int s = 0; s < 2; ++s) {           // local contrast-side term: WT[s] x (local rows of the same matrix)
-    GemmJob& J = g.job[2 + s];
-    J.A = (const bf16_t*)(c.ws + L.WT[s]); J.lda = L.ldW;  J.a_kvalid = L.ldW;
-    J.Bm = s == 0 ? txt + L.off * c.cfg.ld_txt : img + L.off * c.cfg.ld_img;
-    J.ldb = s == 0 ? c.cfg.ld_txt : c.cfg.ld_img;
-    J.C = (float*)(c.ws + L.A6[s]);        J.ldc = L.d;
-    J.split_stride = 0;
-    J.M = L.b; J.N = L.d; J.K = L.b; J.kslice = (int64_t)round_up((size_t)L.b, TK); J.nsplit = 1; J.tiles_m = tiles_m;
-    J.wg_begin = wg;  wg += tiles_m * tiles_n;  J.wg_end = wg;
-  }
-  hipLaunchKernelGGL(k_gemm_nn_bf16, dim3((unsigned)wg), dim3(256), 0, c.s, g);
+  g.nCB = (L.ldE + L.ldW) / 16;
+  g.M = L.b; g.N = L.d; g.B = L.B; g.bloc = L.b; g.off = L.off; g.ldE = L.ldE;
+  g.stages = (int)((L.ldE + L.ldW) / BK);
+  g.slice = (int)L.kslice;
+  g.nsplit = L.nsplit;
+  g.tiles_m = (int)((L.b + 255) / 256);
+  g.tiles_n = (int)((L.d + 255) / 256);
+  g.all_rows_valid = (L.B == L.ldE) && (L.b == L.ldW);
+  const unsigned grid = 2u * (unsigned)(g.nsplit * g.tiles_m * g.tiles_n);
+  hipLaunchKernelGGL(k_contract_bf16, dim3(grid), dim3(256), 0, c.s, g);
 }
 
 }  // namespace fc

@@ -330,13 +330,13 @@ void launch_grad_f32(const StepCtx& c) {
 }
 
 // ------------------------------------------------------------------------------------------
-// MFMA path, last phase.  d_img[r] = c1_r * (sum over splits of E1 x txt)[r] + A6_img[r] - dcoef_r txt_p,
-// and the mirror image; block (0,0) also writes the scalars.
+// MFMA path, last phase.  d_img[r] = c1_r * (sum over splits of the contraction)[r] - dcoef_r txt_p, and the mirror
+// image (the contraction already carries the local contrast-side term divided by c_r); block (0,0) also writes the
+// scalars.
 __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict__ img, const bf16_t* __restrict__ txt,
                                                        int64_t ld_img, int64_t ld_txt, int64_t off, int64_t b, int64_t d,
                                                        const float* __restrict__ O1, const float* __restrict__ O2,
-                                                       int nsplit, const float* __restrict__ A6_1,
-                                                       const float* __restrict__ A6_2, const float* __restrict__ c1,
+                                                       int nsplit, const float* __restrict__ c1,
                                                        const float* __restrict__ c2, const float* __restrict__ dcoef,
                                                        float* __restrict__ d_img, float* __restrict__ d_txt,
                                                        const float* __restrict__ red, int nblocks, int version,
@@ -347,7 +347,6 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
   const int64_t p = off + r;
   const bf16_t* xp = side == 0 ? txt + p * ld_txt : img + p * ld_img;
   const float* O = (side == 0 ? O1 : O2) + r * d;
-  const float* A6 = (side == 0 ? A6_1 : A6_2) + r * d;
   const float cown = side == 0 ? c1[r] : c2[r];
   const float dc = dcoef[r];
   float* out = (side == 0 ? d_img : d_txt) + r * d;
@@ -358,15 +357,14 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
       const float4 v = *(const float4*)(O + (size_t)s * split_stride + c0);
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
-    const float4 a6 = *(const float4*)(A6 + c0);
     const uint2 xr = *(const uint2*)(xp + c0);
     const float x0 = __uint_as_float(xr.x << 16), x1 = __uint_as_float(xr.x & 0xffff0000u);
     const float x2 = __uint_as_float(xr.y << 16), x3 = __uint_as_float(xr.y & 0xffff0000u);
     float4 o;
-    o.x = fmaf(cown, acc.x, a6.x) - dc * x0;
-    o.y = fmaf(cown, acc.y, a6.y) - dc * x1;
-    o.z = fmaf(cown, acc.z, a6.z) - dc * x2;
-    o.w = fmaf(cown, acc.w, a6.w) - dc * x3;
+    o.x = cown * acc.x - dc * x0;
+    o.y = cown * acc.y - dc * x1;
+    o.z = cown * acc.z - dc * x2;
+    o.w = cown * acc.w - dc * x3;
     *(float4*)(out + c0) = o;
   }
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
@@ -378,8 +376,7 @@ void launch_finalize_bf16(const StepCtx& c) {
   dim3 grid((unsigned)L.b, 2), block(256);
   hipLaunchKernelGGL(k_finalize_bf16, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, (const float*)(c.ws + L.Opart[0]),
-                     (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.A6[0]),
-                     (const float*)(c.ws + L.A6[1]), (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
+                     (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
                      L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau);
 }
