@@ -43,6 +43,8 @@ constexpr int kRingBytes = 4 * kStageBytes;  // 128 KiB
 #define FC_PIN() __builtin_amdgcn_sched_barrier(0)
 #define FC_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0f70)
 #define FC_WAIT_VMCNT8() __builtin_amdgcn_s_waitcnt(0x0f78)
+#define FC_WAIT_VMCNT16() __builtin_amdgcn_s_waitcnt(0x4f70)
+#define FC_WAIT_VMCNT34() __builtin_amdgcn_s_waitcnt(0x8f72)   // vmcnt = 34 = 0b100010: low bits 2, high bits 2
 
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
@@ -51,10 +53,18 @@ __device__ __forceinline__ uint32_t lds_addr(const void* p) {
 // Completion is tracked by vmcnt; the compiler does not see the LDS write, so every use below is fenced by an
 // explicit s_waitcnt vmcnt + barrier.  M0 (the LDS base of the transfer) is written here and used by nothing else
 // in these kernels.
-__device__ __forceinline__ void dma16(const void* g, uint32_t lds_byte_addr) {
-  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+// The source address is a wave-uniform base (kept in SGPRs) plus a per-lane 32-bit byte offset.
+__device__ __forceinline__ void dma16(const void* uniform_base, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                :
-               : "v"(g), "s"(__builtin_amdgcn_readfirstlane(lds_byte_addr))
+               : "v"(lane_byte_off), "s"(uniform_base), "s"(__builtin_amdgcn_readfirstlane(lds_byte_addr))
+               : "memory");
+}
+// Same for 4 bytes per lane (per-anchor scalars of the next tile).
+__device__ __forceinline__ void dma4(const void* uniform_base, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
+  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
+               :
+               : "v"(lane_byte_off), "s"(uniform_base), "s"(__builtin_amdgcn_readfirstlane(lds_byte_addr))
                : "memory");
 }
 __device__ __forceinline__ float bf2f(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
@@ -67,6 +77,20 @@ __device__ __forceinline__ int rt_off(int row, int chunk) { return row * 64 + ((
 // piece position p ^ ((k & 3) << 1), so that the four rows of a transposing read hit different banks.
 __device__ __forceinline__ int nt_off(int k, int piece) { return k * 512 + ((piece ^ ((k & 3) << 1)) << 4); }
 
+// One accumulator element out of its AGPR at the point of use.  Left to itself the register allocator copies large
+// parts of the accumulator block into VGPRs right after the main loop, which costs more VGPRs than there are.
+__device__ __forceinline__ float acc_read(float in_agpr) {
+  float x;
+  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(in_agpr));
+  return x;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+  bf16x2 p;
+  p[0] = (__bf16)lo;
+  p[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, p);
+}
 __device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -83,33 +107,35 @@ __device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
 //
 // Strip kernel: both operands are K-contiguous row tiles.  A operand = 256 contrast rows, B operand = 256 anchor rows.
 struct StripTile {
-  const bf16_t* ga[4];   // per-thread source of the 4 A-operand wave loads of stage 0
-  const bf16_t* gb[4];
-  uint32_t la[4], lb[4]; // LDS byte offsets inside a slot
+  const bf16_t *X, *A;   // wave-uniform: first contrast row / first anchor row of the tile
+  int64_t ldx, lda;
+  uint32_t oa[4], ob[4]; // per-lane byte offsets of the 4 + 4 wave loads of a stage (relative to X / A, stage 0)
+  uint32_t la[4], lb[4]; // LDS byte offsets inside a slot (wave-uniform)
   int wr, wc_, lr, hk;   // wave row/col block, lane split
-  // guarded path
-  const bf16_t *A, *X;
-  int64_t lda, ldx, a_row0, a_rows, x_row0, x_rows, d;
+  int64_t x_rows, a_rows, d;   // valid rows below X / A, contraction length (guarded path)
 
+  // Xc / An: row 0 of the contrast / anchor matrix; c0 / a0: first row of the tile; B / b: rows of the matrices.
   __device__ __forceinline__ void setup(const bf16_t* Xc, int64_t ldx_, int64_t c0, int64_t B, const bf16_t* An,
                                         int64_t lda_, int64_t a0, int64_t b, int64_t d_, int tid) {
-    const int wave = tid >> 6, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;   // wave-uniform, kept in SGPRs
     wr = wave >> 1; wc_ = wave & 1; lr = lane & 31; hk = lane >> 5;
-    X = Xc; ldx = ldx_; x_row0 = c0; x_rows = B; A = An; lda = lda_; a_row0 = a0; a_rows = b; d = d_;
+    X = Xc + c0 * ldx_; ldx = ldx_; x_rows = B - c0;
+    A = An + a0 * lda_; lda = lda_; a_rows = b - a0;
+    d = d_;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = wave * 4 + i;                      // wave load j covers rows 16 j .. 16 j + 15 of the tile
       const int row = 16 * j + (lane >> 2);
       const int chunk = ((lane & 3) ^ (row >> 1)) & 3; // logical chunk fetched into position (lane & 3)
-      ga[i] = Xc + (c0 + row) * ldx_ + chunk * 8;
-      gb[i] = An + (a0 + row) * lda_ + chunk * 8;
+      oa[i] = (uint32_t)(row * (int)ldx_ + chunk * 8) * 2u;
+      ob[i] = (uint32_t)(row * (int)lda_ + chunk * 8) * 2u;
       la[i] = (uint32_t)(j * 1024);
       lb[i] = (uint32_t)(kOpBytes + j * 1024);
     }
   }
   __device__ __forceinline__ void dma(int i, int stage, uint32_t slot) const {
-    if (i < 4) dma16(ga[i] + (int64_t)stage * BK, slot + la[i]);
-    else dma16(gb[i - 4] + (int64_t)stage * BK, slot + lb[i - 4]);
+    if (i < 4) dma16(X + (int64_t)stage * BK, oa[i], slot + la[i]);
+    else dma16(A + (int64_t)stage * BK, ob[i - 4], slot + lb[i - 4]);
   }
   __device__ __forceinline__ void fill_guarded(int stage, char* slot, int tid) const {
     const int chunk = tid & 3;
@@ -118,8 +144,8 @@ struct StripTile {
     for (int i = 0; i < 4; ++i) {
       const int row = (tid >> 2) + 64 * i;
       u32x4 va = {0u, 0u, 0u, 0u}, vb = {0u, 0u, 0u, 0u};
-      if (k < d && x_row0 + row < x_rows) va = *(const u32x4*)(X + (x_row0 + row) * ldx + k);
-      if (k < d && a_row0 + row < a_rows) vb = *(const u32x4*)(A + (a_row0 + row) * lda + k);
+      if (k < d && row < x_rows) va = *(const u32x4*)(X + row * ldx + k);
+      if (k < d && row < a_rows) vb = *(const u32x4*)(A + row * lda + k);
       *(u32x4*)(slot + rt_off(row, chunk)) = va;
       *(u32x4*)(slot + kOpBytes + rt_off(row, chunk)) = vb;
     }
@@ -135,59 +161,56 @@ struct StripTile {
 // Contraction kernel: A operand = 8 anchor blocks x 2 column blocks of Efrag per stage (fragments are copied as they
 // are), B operand = 32 rows x 256 columns of X in its natural layout, read with transposing LDS reads.
 struct ContractTile {
-  const bf16_t* ga[4];
-  const bf16_t* gb_lo[4];  // source of the B wave loads for stage rows that are contrasts (global rows)
-  int64_t gb_step;         // elements per stage along the rows of X
-  int64_t local_shift;     // (off - ldE) * ldx: added for stages in the local-anchor column range
-  int first_local_stage;   // stages >= this read X rows off + (k - ldE)
+  const bf16_t* Efr;       // wave-uniform: fragment (ab0, column block 0) of the strip
+  const bf16_t* Xn;        // wave-uniform: X + n0
+  int64_t ldx;
+  int64_t local_rows;      // off - ldE: row shift for stages in the local-anchor column range
+  int first_local_stage;
+  uint32_t oa[4], ob[4];   // per-lane byte offsets of the wave loads (A: relative to Efr; B: relative to row 0 of a stage)
   uint32_t la[4], lb[4];
   int wm, wn, lane;
-  // guarded path
-  const bf16_t* X;
-  int64_t ldx, n0, N, B, bloc, off, ldE;
+  int64_t n0, N, B, bloc, off, ldE;   // guarded path
 
   __device__ __forceinline__ void setup(const bf16_t* E, int64_t nCB, int64_t ab0, const bf16_t* X_, int64_t ldx_,
                                         int64_t n0_, int64_t N_, int64_t B_, int64_t bloc_, int64_t off_,
                                         int64_t ldE_, int tid) {
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in SGPRs
     lane = tid & 63; wm = wave >> 1; wn = wave & 1;
-    X = X_; ldx = ldx_; n0 = n0_; N = N_; B = B_; bloc = bloc_; off = off_; ldE = ldE_;
-    gb_step = (int64_t)BK * ldx_;
-    local_shift = (off_ - ldE_) * ldx_;
+    Efr = E + ab0 * nCB * 512; Xn = X_ + n0_; ldx = ldx_;
+    n0 = n0_; N = N_; B = B_; bloc = bloc_; off = off_; ldE = ldE_;
+    local_rows = off_ - ldE_;
     first_local_stage = (int)(ldE_ / BK);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int f = wave * 4 + i;                       // fragment f = 2 * (anchor block) + (column block in stage)
-      ga[i] = E + (((ab0 + (f >> 1)) * nCB + (f & 1)) * 64 + lane) * 8;
+      oa[i] = (uint32_t)(((f >> 1) * (int)nCB + (f & 1)) * 512 + lane * 8) * 2u;
       la[i] = (uint32_t)(f * 1024);
       const int k = 2 * f + (lane >> 5);                // wave load f covers stage rows 2 f, 2 f + 1
       const int piece = (lane & 31) ^ ((k & 3) << 1);   // logical piece fetched into position (lane & 31)
-      gb_lo[i] = X_ + (int64_t)k * ldx_ + n0_ + piece * 8;
+      ob[i] = (uint32_t)(k * (int)ldx_ + piece * 8) * 2u;
       lb[i] = (uint32_t)(kOpBytes + f * 1024);
     }
   }
+  __device__ __forceinline__ const bf16_t* stage_rows(int stage) const {   // X row of stage row 0, plus n0
+    const int64_t row = (int64_t)stage * BK + (stage >= first_local_stage ? local_rows : 0);
+    return Xn + row * ldx;
+  }
   __device__ __forceinline__ void dma(int i, int stage, uint32_t slot) const {
-    if (i < 4) {
-      dma16(ga[i] + (int64_t)stage * (2 * 64 * 8), slot + la[i]);
-    } else {
-      const bf16_t* g = gb_lo[i - 4] + (int64_t)stage * gb_step;
-      if (stage >= first_local_stage) g += local_shift;
-      dma16(g, slot + lb[i - 4]);
-    }
+    if (i < 4) dma16(Efr + (int64_t)stage * 1024, oa[i], slot + la[i]);
+    else dma16(stage_rows(stage), ob[i - 4], slot + lb[i - 4]);
   }
   __device__ __forceinline__ void fill_guarded(int stage, char* slot, int tid) const {
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int f = wave * 4 + i;
-      *(u32x4*)(slot + f * 1024 + lane * 16) = *(const u32x4*)(ga[i] + (int64_t)stage * (2 * 64 * 8));
+      *(u32x4*)(slot + f * 1024 + lane * 16) = *(const u32x4*)((const char*)(Efr + (int64_t)stage * 1024) + oa[i]);
       const int k = 2 * f + (lane >> 5);
       const int piece = (lane & 31) ^ ((k & 3) << 1);
       const int64_t c = (int64_t)stage * BK + k;        // extended column
-      const int64_t row = c < ldE ? c : off + (c - ldE);
       const bool ok = (c < ldE ? c < B : (c - ldE) < bloc) && (n0 + piece * 8 < N);
       u32x4 v = {0u, 0u, 0u, 0u};
-      if (ok) v = *(const u32x4*)(X + row * ldx + n0 + piece * 8);
+      if (ok) v = *(const u32x4*)((const char*)stage_rows(stage) + ob[i]);
       *(u32x4*)(slot + kOpBytes + f * 1024 + lane * 16) = v;
     }
   }
@@ -217,7 +240,9 @@ struct ContractTile {
 // One 32-deep stage of the ring: 16 MFMAs on the operands already in registers while the operands of the second
 // 16-deep step are read; then "stage s+1 has landed" (vmcnt) + barrier, which also retires slot (s-1) for reuse; then
 // 16 MFMAs while the first operands of stage s+1 are read and the 8 wave loads of stage s+3 are issued.
-#define FC_STAGE(T, MORE, DMA)                                                                                      \
+// WAIT: 0 = stage s+1 is already known to have landed, 1 = vmcnt(8) (only the loads of stage s+2 may be in flight),
+// 2 = vmcnt(0).
+#define FC_STAGE(T, MORE, DMA, WAIT)                                                                                     \
   {                                                                                                                 \
     const char* sl = ring + (s & 3) * kStageBytes;                                                                  \
     FC_MM(0, 0, a0, b0); FC_MM(0, 1, a0, b0); FC_PIN(); a1[0] = T.read_a(sl, 0, 1); FC_PIN();                       \
@@ -228,7 +253,7 @@ struct ContractTile {
     FC_MM(2, 2, a0, b0); FC_MM(2, 3, a0, b0); FC_PIN(); b1[2] = T.read_b(sl, 2, 1); FC_PIN();                       \
     FC_MM(3, 0, a0, b0); FC_MM(3, 1, a0, b0); FC_PIN(); a1[3] = T.read_a(sl, 3, 1); FC_PIN();                       \
     FC_MM(3, 2, a0, b0); FC_MM(3, 3, a0, b0); FC_PIN(); b1[3] = T.read_b(sl, 3, 1); FC_PIN();                       \
-    if (DMA) FC_WAIT_VMCNT8(); else FC_WAIT_VMCNT0();                                                               \
+    if (WAIT == 1) FC_WAIT_VMCNT8(); else if (WAIT == 2) FC_WAIT_VMCNT0();                                          \
     __syncthreads();                                                                                                \
     FC_PIN();                                                                                                       \
     const char* nx = ring + ((s + 1) & 3) * kStageBytes;                                                            \
@@ -255,19 +280,26 @@ __device__ __forceinline__ void ring_prologue(const Tile& T, uint32_t ring_addr,
 }
 
 // acc += (A operand tile) x (B operand tile)^T over stages [s0, s0 + S); the prologue must have been issued, and
-// nothing else may have touched the ring since.  On return no wave reads the ring any more.
-template <typename Tile>
+// nothing else may have touched the ring since.  LANDED: this wave already knows that its own prologue loads are
+// complete (it has consumed a younger load; vector memory operations complete in order), and younger stores may
+// still be in flight, which the first two stages then do not wait for.  On return no wave reads the ring any more.
+template <bool LANDED, typename Tile>
 __device__ __forceinline__ void ring_mainloop(f32x16 (&acc)[4][4], const Tile& T, char* ring, uint32_t ring_addr,
                                               int s0, int S) {
-  FC_WAIT_VMCNT0();
+  if (!LANDED) {
+    if (S >= 3) FC_WAIT_VMCNT16(); else FC_WAIT_VMCNT0();   // stage 0 has landed; stages 1, 2 may be in flight
+  }
   __syncthreads();
   bf16x8 a0[4], b0[4], a1[4], b1[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) { a0[t] = T.read_a(ring, t, 0); b0[t] = T.read_b(ring, t, 0); }
   int s = 0;
-  for (; s + 3 < S; ++s) FC_STAGE(T, true, true)
-  for (; s + 1 < S; ++s) FC_STAGE(T, true, false)
-  FC_STAGE(T, false, false)
+  if (LANDED) {
+    for (; s < 2 && s + 3 < S; ++s) FC_STAGE(T, true, true, 0)
+  }
+  for (; s + 3 < S; ++s) FC_STAGE(T, true, true, 1)
+  for (; s + 1 < S; ++s) FC_STAGE(T, true, false, 2)
+  FC_STAGE(T, false, false, 2)
 }
 
 // Same contraction for tiles with a ragged edge: one stage at a time through registers, zero fill outside.
@@ -313,136 +345,170 @@ struct StripArgs {
 // own column (B_{i-} excludes i).
 template <bool GUARD>
 __device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)[4][4], const float* sk,
-                                               const float* sdk, float (*sred)[2][256], int strip, int64_t a0,
+                                               const float* sdiag, float (*sred)[2][256], int strip, int64_t a0,
                                                int64_t c0, int wr, int wc, int lane) {
   const int lr = lane & 31, hk = lane >> 5;
   bf16_t* __restrict__ E = a.E[strip];
-  // 16 independent partial sums per anchor block and quantity: a dependent VALU op issues only every ~36 cycles on a
-  // lone wavefront, so serial accumulation chains would dominate this phase
-  float sgv[4][16], stv[4][16], kk[4], dk[4];
-#pragma unroll
-  for (int tj = 0; tj < 4; ++tj) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) { sgv[tj][v] = 0.f; stv[tj][v] = 0.f; }
-    kk[tj] = sk[wc * 128 + tj * 32 + lr];
-    dk[tj] = sdk[wc * 128 + tj * 32 + lr];
-  }
   // fragment (ab, cb) of this lane: E + ((ab nCB + cb) 64 + lane) 8; ab and cb are wave-uniform
   const int64_t ab0 = (a0 + wc * 128) >> 5, cb0 = (c0 + wr * 128) >> 4;
-  bf16_t* __restrict__ Elane = E + lane * 8;
+  const int B = (int)a.B, b = (int)a.b, off = (int)a.off;   // all below 2^24
 #pragma unroll
-  for (int ti = 0; ti < 4; ++ti) {
-    const int64_t crow = c0 + wr * 128 + ti * 32 + 4 * hk;
+  for (int tj = 0; tj < 4; ++tj) {
+    const int al = wc * 128 + tj * 32 + lr;
+    const float kk = sk[al], dk = sdiag[al] * kk;   // log2(e)/tau and s_pp log2(e)/tau of this anchor
+    const int anchor = (int)a0 + al;
+    // 4 independent partial sums per quantity: a dependent VALU op issues only every ~36 cycles on a lone
+    // wavefront, so one serial accumulation chain per sum would dominate this phase
+    float sgv[4] = {0.f, 0.f, 0.f, 0.f}, stv[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int tj = 0; tj < 4; ++tj) {
-      const int64_t anchor = a0 + wc * 128 + tj * 32 + lr;
-      float t[16], e[16];
+    for (int ti = 0; ti < 4; ++ti) {
+      const int crow = (int)c0 + wr * 128 + ti * 32 + 4 * hk;
+      // groups of 4 accumulators (v = 4 g + q <-> contrast crow + 8 g + q), pinned apart to keep live ranges short
+      uint32_t pk[8];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) t[v] = fmaf(acc[ti][tj][v], kk[tj], -dk[tj]);
+      for (int g = 0; g < 4; ++g) {
+        float t[4], e[4];
 #pragma unroll
-      for (int v = 0; v < 16; ++v) e[v] = __builtin_amdgcn_exp2f(t[v]);
-      if (GUARD) {
+        for (int q = 0; q < 4; ++q) t[q] = fmaf(acc_read(acc[ti][tj][4 * g + q]), kk, -dk);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int64_t c = crow + 8 * (v >> 2) + (v & 3);
-          const bool ok = (c < a.B) && (anchor < a.b) && (c != a.off + anchor);
-          e[v] = ok ? e[v] : 0.f;
+        for (int q = 0; q < 4; ++q) e[q] = __builtin_amdgcn_exp2f(t[q]);
+        if (GUARD) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int c = crow + 8 * g + q;
+            const bool ok = (c < B) && (anchor < b) && (c != off + anchor);
+            e[q] = ok ? e[q] : 0.f;
+          }
         }
-      }
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        sgv[tj][v] += e[v];
-        stv[tj][v] = fmaf(t[v], e[v], stv[tj][v]);
+        for (int q = 0; q < 4; ++q) {
+          sgv[q] += e[q];
+          stv[q] = fmaf(t[q], e[q], stv[q]);
+        }
+        pk[2 * g] = pack_bf16x2(e[0], e[1]);
+        pk[2 * g + 1] = pack_bf16x2(e[2], e[3]);
+        FC_PIN();
       }
 #pragma unroll
       for (int j = 0; j < 2; ++j) {
-        bf16x8 pk;
-#pragma unroll
-        for (int q = 0; q < 8; ++q) pk[q] = (__bf16)e[8 * j + q];
         const int64_t cb = cb0 + 2 * ti + j;
-        if (!GUARD || 16 * cb < a.ldE) *(bf16x8*)(Elane + ((ab0 + tj) * a.nCB + cb) * 512) = pk;
+        bf16_t* frag = E + ((ab0 + tj) * a.nCB + cb) * 512;   // wave-uniform
+        const u32x4 w = {pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]};
+        if (!GUARD || 16 * cb < a.ldE) *(u32x4*)(frag + lane * 8) = w;
       }
+      FC_PIN();
     }
-  }
-#pragma unroll
-  for (int tj = 0; tj < 4; ++tj) {
-#pragma unroll
-    for (int w = 8; w > 0; w >>= 1)
-#pragma unroll
-      for (int v = 0; v < w; ++v) { sgv[tj][v] += sgv[tj][v + w]; stv[tj][v] += stv[tj][v + w]; }
-    const float sg = sgv[tj][0] + __shfl_xor(sgv[tj][0], 32);
-    const float st = stv[tj][0] + __shfl_xor(stv[tj][0], 32);
+    const float sgl = (sgv[0] + sgv[1]) + (sgv[2] + sgv[3]);
+    const float stl = (stv[0] + stv[1]) + (stv[2] + stv[3]);
+    const float sg = sgl + __shfl_xor(sgl, 32);
+    const float st = stl + __shfl_xor(stl, 32);
     if (hk == 0) {
-      sred[wr][0][wc * 128 + tj * 32 + lr] = sg;
-      sred[wr][1][wc * 128 + tj * 32 + lr] = kk[tj] > 0.f ? st / kk[tj] : 0.f;   // sum of (s - s_pp) l
+      sred[wr][0][al] = sg;
+      sred[wr][1][al] = kk > 0.f ? st * __builtin_amdgcn_rcpf(kk) : 0.f;   // sum of (s - s_pp) l
     }
   }
 }
 
+__device__ __forceinline__ bool strip_tile_is_interior(const StripArgs& a, int64_t a0, int64_t c0) {
+  return (a0 + 256 <= a.b) && (c0 + 256 <= a.B) && (a.d % BK == 0);
+}
+
+// Interior tiles: persistent workgroups, LDS ring, next tile's first stages (and its per-anchor scalars) fetched
+// under the exponentials of the current one.
 __global__ void __launch_bounds__(256) k_strips_bf16(StripArgs a) {
   __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
-  __shared__ float sk[256];
-  __shared__ float sdk[256];
+  __shared__ __attribute__((aligned(256))) float sk[2][256];      // log2(e)/tau per anchor of the tile, double buffered
+  __shared__ __attribute__((aligned(256))) float sdiag[2][256];   // s_pp per anchor of the tile
   __shared__ float sred[2][2][256];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave >> 1, wc = wave & 1;
   const uint32_t ring_addr = lds_addr(ring);
-  const int S = (int)((a.d + BK - 1) / BK);
-  // persistent workgroups; ids that share an XCD (id mod 8 under round-robin dispatch) take neighbouring tiles, and
-  // neighbouring tiles are the anchor tiles of one contrast tile, so a contrast tile is fetched once per L2
+  const int S = (int)(a.d / BK);
+  // ids that share an XCD (id mod 8 under round-robin dispatch) take neighbouring tiles, and neighbouring tiles are
+  // the anchor tiles of one contrast tile, so a contrast tile is fetched once per L2
   const int G = gridDim.x;
   const int vid = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
   const int per_strip = a.nAT * a.nCT;
 
   StripTile T;
-  bool prefetched = false;
-  for (int t = vid; t < a.ntiles; t += G) {
+  // request everything the main loop and the epilogue of tile `tt` need: 3 stages + 2 x 256 scalars (26 wave loads)
+  auto request = [&](int tt, int buf) {
+    const int strip = tt / per_strip, at = tt % a.nAT, ct = (tt / a.nAT) % a.nCT;
+    T.setup(a.contrasts[strip], a.ld_contrast[strip], (int64_t)ct * 256, a.B, a.anchors[strip], a.ld_anchor[strip],
+            (int64_t)at * 256, a.b, a.d, tid);
+    ring_prologue(T, ring_addr, 0, S);
+    dma4(a.kscale[strip] + at * 256 + wave * 64, lane * 4, lds_addr(&sk[buf][wave * 64]));
+    dma4(a.diag + at * 256 + wave * 64, lane * 4, lds_addr(&sdiag[buf][wave * 64]));
+  };
+  auto next_interior = [&](int tt) {
+    while (tt < a.ntiles &&
+           !strip_tile_is_interior(a, (int64_t)(tt % a.nAT) * 256, (int64_t)((tt / a.nAT) % a.nCT) * 256))
+      tt += G;
+    return tt;
+  };
+
+  int t = next_interior(vid);
+  if (t >= a.ntiles) return;
+  int buf = 0;
+  request(t, buf);
+  FC_WAIT_VMCNT0();
+  while (t < a.ntiles) {
     const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
     const int64_t a0 = (int64_t)at * 256, c0 = (int64_t)ct * 256;
-    const bool fast = (a0 + 256 <= a.b) && (c0 + 256 <= a.B) && (a.d % BK == 0);
-    {
-      const int64_t m = a0 + tid;
-      const float kv = m < a.b ? a.kscale[strip][m] : 0.f;
-      sk[tid] = kv;
-      sdk[tid] = m < a.b ? a.diag[m] * kv : 0.f;
-    }
     f32x16 acc[4][4];
     zero_acc(acc);
-    if (!prefetched)
-      T.setup(a.contrasts[strip], a.ld_contrast[strip], c0, a.B, a.anchors[strip], a.ld_anchor[strip], a0, a.b, a.d, tid);
-    if (fast) {
-      if (!prefetched) ring_prologue(T, ring_addr, 0, S);
-      ring_mainloop(acc, T, ring, ring_addr, 0, S);
-    } else {
-      guarded_mainloop(acc, T, ring, 0, S, tid);
-    }
-    // start fetching the next tile while this one's exponentials are evaluated
-    prefetched = false;
-    const int tn = t + G;
-    if (tn < a.ntiles) {
-      const int nstrip = tn / per_strip, nat = tn % a.nAT, nct = (tn / a.nAT) % a.nCT;
-      const int64_t na0 = (int64_t)nat * 256, nc0 = (int64_t)nct * 256;
-      if ((na0 + 256 <= a.b) && (nc0 + 256 <= a.B) && (a.d % BK == 0)) {
-        T.setup(a.contrasts[nstrip], a.ld_contrast[nstrip], nc0, a.B, a.anchors[nstrip], a.ld_anchor[nstrip], na0, a.b,
-                a.d, tid);
-        ring_prologue(T, ring_addr, 0, S);
-        prefetched = true;
-      }
-    }
+    ring_mainloop<true>(acc, T, ring, ring_addr, 0, S);
+    const int tn = next_interior(t + G);
+    if (tn < a.ntiles) request(tn, buf ^ 1);
     const bool diagonal = (c0 < a.off + a0 + 256) && (c0 + 256 > a.off + a0);
-    if (!fast || diagonal) strip_epilogue<true>(a, acc, sk, sdk, sred, strip, a0, c0, wr, wc, lane);
-    else strip_epilogue<false>(a, acc, sk, sdk, sred, strip, a0, c0, wr, wc, lane);
+    if (diagonal) strip_epilogue<true>(a, acc, sk[buf], sdiag[buf], sred, strip, a0, c0, wr, wc, lane);
+    else strip_epilogue<false>(a, acc, sk[buf], sdiag[buf], sred, strip, a0, c0, wr, wc, lane);
     __syncthreads();
-    {
-      const int64_t m = a0 + tid;
-      if (m < a.b) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q)
-          a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + m] = sred[0][q][tid] + sred[1][q][tid];
-      }
-    }
-    __syncthreads();
+    for (int q = 0; q < 2; ++q)
+      a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a0 + tid] = sred[0][q][tid] + sred[1][q][tid];
+    // Every wave has issued, after its 26 requests for the next tile, exactly 32 fragment stores and 2 sum stores;
+    // vector memory operations complete in order, so "at most 34 outstanding" means the requests have landed
+    // while the stores may still be in flight.
+    FC_WAIT_VMCNT34();
+    t = tn;
+    buf ^= 1;
+  }
+}
+
+// Tiles with a ragged edge (anchors, contrasts or width not a multiple of the tile): one workgroup per tile,
+// guarded loads, guarded epilogue.
+__global__ void __launch_bounds__(256) k_strips_edge_bf16(StripArgs a) {
+  __shared__ __attribute__((aligned(1024))) char ring[kStageBytes];
+  __shared__ float sk[256];
+  __shared__ float sdiag[256];
+  __shared__ float sred[2][2][256];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wr = wave >> 1, wc = wave & 1;
+  const int t = blockIdx.x;
+  const int per_strip = a.nAT * a.nCT;
+  const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
+  const int64_t a0 = (int64_t)at * 256, c0 = (int64_t)ct * 256;
+  if (strip_tile_is_interior(a, a0, c0)) return;
+  const int S = (int)((a.d + BK - 1) / BK);
+  {
+    const int64_t m = a0 + tid;
+    sk[tid] = m < a.b ? a.kscale[strip][m] : 0.f;
+    sdiag[tid] = m < a.b ? a.diag[m] : 0.f;
+  }
+  StripTile T;
+  T.setup(a.contrasts[strip], a.ld_contrast[strip], c0, a.B, a.anchors[strip], a.ld_anchor[strip], a0, a.b, a.d, tid);
+  f32x16 acc[4][4];
+  zero_acc(acc);
+  guarded_mainloop(acc, T, ring, 0, S, tid);
+  strip_epilogue<true>(a, acc, sk, sdiag, sred, strip, a0, c0, wr, wc, lane);
+  __syncthreads();
+  const int64_t m = a0 + tid;
+  if (m < a.b) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + m] = sred[0][q][tid] + sred[1][q][tid];
   }
 }
 
@@ -467,8 +533,13 @@ void launch_strips_bf16(const StepCtx& c) {
   a.nAT = (int)((L.b + 255) / 256);
   a.nCT = (int)((L.B + 255) / 256);
   a.ntiles = 2 * a.nAT * a.nCT;
-  const int grid = a.ntiles < 256 ? a.ntiles : 256;
-  hipLaunchKernelGGL(k_strips_bf16, dim3((unsigned)grid), dim3(256), 0, c.s, a);
+  const bool any_interior = L.b >= 256 && L.B >= 256 && L.d % BK == 0;
+  const bool any_edge = (L.b % 256) || (L.B % 256) || (L.d % BK);
+  if (any_interior) {
+    const int grid = a.ntiles < 256 ? a.ntiles : 256;
+    hipLaunchKernelGGL(k_strips_bf16, dim3((unsigned)grid), dim3(256), 0, c.s, a);
+  }
+  if (any_edge) hipLaunchKernelGGL(k_strips_edge_bf16, dim3((unsigned)a.ntiles), dim3(256), 0, c.s, a);
 }
 
 // ----------------------------------------------------------------------------------------------------------------
@@ -557,7 +628,7 @@ __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
     T.setup(J.E, g.nCB, m0 >> 5, J.X, J.ldx, n0, g.N, g.B, g.bloc, g.off, g.ldE, tid);
     if (g.all_rows_valid && n0 + 256 <= g.N) {
       ring_prologue(T, ring_addr, s0, S);
-      ring_mainloop(acc, T, ring, ring_addr, s0, S);
+      ring_mainloop<false>(acc, T, ring, ring_addr, s0, S);
     } else {
       guarded_mainloop(acc, T, ring, s0, S, tid);
     }
