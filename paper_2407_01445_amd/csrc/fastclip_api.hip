@@ -74,7 +74,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
     L->nsplit = 0;
     L->kslice = 0;
   }
-  L->nstate_blocks = (int)((cfg.b + 31) / 32);
+  L->nstate_blocks = (int)((cfg.b + kStateAnchors - 1) / kStateAnchors);
   L->diag = take(fb); L->tau1 = take(fb); L->tau2 = take(fb); L->k1 = take(fb); L->k2 = take(fb);
   L->sums = take(fb * 4 * (size_t)L->nparts);
   L->c1 = take(fb); L->c2 = take(fb); L->dcoef = take(fb);

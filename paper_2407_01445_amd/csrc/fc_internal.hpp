@@ -12,6 +12,7 @@ typedef uint16_t bf16_t;  // raw bf16 bits in memory
 
 constexpr int kTileContrasts = 256;  // contrast rows per workgroup tile of the strip kernel
 constexpr int kMaxSplit = 64;
+constexpr int kStateAnchors = 8;     // anchors per block of the state kernel
 
 static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 

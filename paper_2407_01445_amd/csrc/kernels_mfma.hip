@@ -70,12 +70,18 @@ __device__ __forceinline__ void dma4(const void* uniform_base, uint32_t lane_byt
 __device__ __forceinline__ float bf2f(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
 __device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
 
+// LDS has 64 banks of 4 bytes (256 bytes per cycle); a 16-byte-per-lane read is served 16 lanes at a time, an
+// 8-byte-per-lane read 32 lanes at a time.
 // LDS image of a K-contiguous operand tile (256 rows x 32 k, 64 bytes per row): 16-byte chunk c of row r sits at
-// chunk position c ^ ((r >> 1) & 3), which makes both the row-wise fills and the MFMA operand reads conflict-free.
-__device__ __forceinline__ int rt_off(int row, int chunk) { return row * 64 + (((chunk ^ (row >> 1)) & 3) << 4); }
+// chunk position c ^ ((r >> 2) & 3): the 16 consecutive rows that one MFMA operand read touches per cycle then
+// cover all 16 chunk slots of a 256-byte bank window.
+__device__ __forceinline__ int rt_swz(int row) { return (row >> 2) & 3; }
+__device__ __forceinline__ int rt_off(int row, int chunk) { return row * 64 + ((chunk ^ rt_swz(row)) << 4); }
 // LDS image of a [32 k][256 n] tile of a row-major matrix (512 bytes per k row): 16-byte piece p of row k sits at
-// piece position p ^ ((k & 3) << 1), so that the four rows of a transposing read hit different banks.
-__device__ __forceinline__ int nt_off(int k, int piece) { return k * 512 + ((piece ^ ((k & 3) << 1)) << 4); }
+// piece position p ^ ((k & 3) << 2), so that the 4 rows x 64 bytes which a transposing read touches per cycle cover
+// a whole bank window.
+__device__ __forceinline__ int nt_swz(int k) { return (k & 3) << 2; }
+__device__ __forceinline__ int nt_off(int k, int piece) { return k * 512 + ((piece ^ nt_swz(k)) << 4); }
 
 // One accumulator element out of its AGPR at the point of use.  Left to itself the register allocator copies large
 // parts of the accumulator block into VGPRs right after the main loop, which costs more VGPRs than there are.
@@ -126,7 +132,7 @@ struct StripTile {
     for (int i = 0; i < 4; ++i) {
       const int j = wave * 4 + i;                      // wave load j covers rows 16 j .. 16 j + 15 of the tile
       const int row = 16 * j + (lane >> 2);
-      const int chunk = ((lane & 3) ^ (row >> 1)) & 3; // logical chunk fetched into position (lane & 3)
+      const int chunk = (lane & 3) ^ rt_swz(row);      // logical chunk fetched into position (lane & 3)
       oa[i] = (uint32_t)(row * (int)ldx_ + chunk * 8) * 2u;
       ob[i] = (uint32_t)(row * (int)lda_ + chunk * 8) * 2u;
       la[i] = (uint32_t)(j * 1024);
@@ -186,7 +192,7 @@ struct ContractTile {
       oa[i] = (uint32_t)(((f >> 1) * (int)nCB + (f & 1)) * 512 + lane * 8) * 2u;
       la[i] = (uint32_t)(f * 1024);
       const int k = 2 * f + (lane >> 5);                // wave load f covers stage rows 2 f, 2 f + 1
-      const int piece = (lane & 31) ^ ((k & 3) << 1);   // logical piece fetched into position (lane & 31)
+      const int piece = (lane & 31) ^ nt_swz(k);        // logical piece fetched into position (lane & 31)
       ob[i] = (uint32_t)(k * (int)ldx_ + piece * 8) * 2u;
       lb[i] = (uint32_t)(kOpBytes + f * 1024);
     }
@@ -206,7 +212,7 @@ struct ContractTile {
       const int f = wave * 4 + i;
       *(u32x4*)(slot + f * 1024 + lane * 16) = *(const u32x4*)((const char*)(Efr + (int64_t)stage * 1024) + oa[i]);
       const int k = 2 * f + (lane >> 5);
-      const int piece = (lane & 31) ^ ((k & 3) << 1);
+      const int piece = (lane & 31) ^ nt_swz(k);
       const int64_t c = (int64_t)stage * BK + k;        // extended column
       const bool ok = (c < ldE ? c < B : (c - ldE) < bloc) && (n0 + piece * 8 < N);
       u32x4 v = {0u, 0u, 0u, 0u};
@@ -543,52 +549,71 @@ void launch_strips_bf16(const StepCtx& c) {
 }
 
 // ----------------------------------------------------------------------------------------------------------------
-// One thread per (local anchor r, block of 16 local anchors q): reads l_other(q, off + r) from the other strip's
-// Efrag, scales by c_other[q] / c_own[r], and writes the two 16-byte halves of the fragment row in the extended
-// column range of the own strip.  The other strip already holds 0 at q == r.
+// Local contrast-side operand.  Block (rb, qb, side): the 64 x 64 block W'[r][q] = c_other[q] l_other(q, off + r) /
+// c_own[r] (r in [64 rb, +64), q in [64 qb, +64)), read as whole 16-byte fragment chunks of the other strip (which
+// already holds 0 at q == r), transposed through LDS, and written as fragment rows into the extended column range of
+// the own strip.  Zero for q >= b.
 __global__ void __launch_bounds__(256) k_local_bf16(const bf16_t* __restrict__ E0, const bf16_t* __restrict__ E1,
                                                     bf16_t* __restrict__ W0, bf16_t* __restrict__ W1, int64_t nCB,
-                                                    int64_t ldE, int64_t ldW, const float* __restrict__ c1,
+                                                    int64_t ldE, const float* __restrict__ c1,
                                                     const float* __restrict__ c2, int64_t off, int64_t b) {
-  const int side = blockIdx.y;
+  __shared__ float tile[64][65];   // [r][q]
+  const int side = blockIdx.z;
   const bf16_t* __restrict__ Esrc = side == 0 ? E1 : E0;   // d_img needs l2 (text strip), d_txt needs l1
   bf16_t* __restrict__ Edst = side == 0 ? W0 : W1;
   const float* __restrict__ c_own = side == 0 ? c1 : c2;
   const float* __restrict__ c_oth = side == 0 ? c2 : c1;
-  const int64_t nqb = ldW / 16;
-  const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  if (id >= b * nqb) return;
-  const int64_t r = id / nqb, qb = id % nqb;
-  const int64_t c = off + r;                                // the column of local row p_r in the other strip
-  const int64_t cb_src = c >> 4;
-  const int o_src = (int)(c & 15), h_src = (o_src >> 2) & 1, e_src = ((o_src >> 3) << 2) + (o_src & 3);
-  const float inv_own = 1.0f / c_own[r];
-  uint16_t out[2][8];
+  const int64_t r0 = (int64_t)blockIdx.x * 64, q0 = (int64_t)blockIdx.y * 64;
+  const int64_t cfirst = off + r0;                    // columns cfirst .. cfirst + 63 of the other strip
+  const int64_t cb_first = cfirst >> 4, cb_last = (cfirst + 63) >> 4;   // at most 5 column blocks
+  for (int i = threadIdx.x; i < 64 * 10; i += 256) {
+    const int ql = i & 63, ch = i >> 6;
+    const int64_t cb = cb_first + (ch >> 1);
+    const int h = ch & 1;
+    const int64_t q = q0 + ql;
+    if (cb > cb_last) continue;
+    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+    float cq = 0.f;
+    if (q < b) {
+      raw = *(const uint4*)(Esrc + (((q >> 5) * nCB + cb) * 64 + (q & 31) + 32 * h) * 8);
+      cq = c_oth[q];
+    }
+    const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
-  for (int o = 0; o < 16; ++o) {
-    const int64_t q = qb * 16 + o;
-    float v = 0.f;
-    if (q < b) v = c_oth[q] * bf2f(Esrc[(((q >> 5) * nCB + cb_src) * 64 + (q & 31) + 32 * h_src) * 8 + e_src]) * inv_own;
-    out[(o >> 2) & 1][((o >> 3) << 2) + (o & 3)] = f2bf(v);
+    for (int e = 0; e < 8; ++e) {
+      const int64_t c = 16 * cb + 8 * (e >> 2) + 4 * h + (e & 3);
+      const int64_t rl = c - cfirst;
+      const uint32_t bits = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
+      if (rl >= 0 && rl < 64) tile[rl][ql] = cq * __uint_as_float(bits);
+    }
   }
-  const int64_t cb_dst = (ldE >> 4) + qb;
+  __syncthreads();
+  const int rl = threadIdx.x >> 2, qpart = threadIdx.x & 3;
+  const int64_t r = r0 + rl;
+  if (r >= b) return;
+  const float inv_own = 1.0f / c_own[r];
+  uint32_t out[2][4];
 #pragma unroll
-  for (int h = 0; h < 2; ++h) {
-    u32x4 w;
+  for (int hh = 0; hh < 2; ++hh)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) w[i] = (uint32_t)out[h][2 * i] | ((uint32_t)out[h][2 * i + 1] << 16);
-    *(u32x4*)(Edst + (((r >> 5) * nCB + cb_dst) * 64 + (r & 31) + 32 * h) * 8) = w;
+    for (int e2 = 0; e2 < 4; ++e2) {       // slots e = 2 e2, 2 e2 + 1 of half hh <-> o = 8 (e / 4) + 4 hh + (e % 4)
+      const int o_lo = 8 * ((2 * e2) >> 2) + 4 * hh + ((2 * e2) & 3);
+      out[hh][e2] = pack_bf16x2(tile[rl][16 * qpart + o_lo] * inv_own, tile[rl][16 * qpart + o_lo + 1] * inv_own);
+    }
+  const int64_t cb_dst = (ldE >> 4) + ((q0 + 16 * qpart) >> 4);
+#pragma unroll
+  for (int hh = 0; hh < 2; ++hh) {
+    const u32x4 w = {out[hh][0], out[hh][1], out[hh][2], out[hh][3]};
+    *(u32x4*)(Edst + (((r >> 5) * nCB + cb_dst) * 64 + (r & 31) + 32 * hh) * 8) = w;
   }
 }
 
 void launch_local_bf16(const StepCtx& c) {
   const Layout& L = c.L;
-  const int64_t n = L.b * (L.ldW / 16);
-  dim3 grid((unsigned)((n + 255) / 256), 2);
+  dim3 grid((unsigned)((L.b + 63) / 64), (unsigned)(L.ldW / 64), 2);
   hipLaunchKernelGGL(k_local_bf16, grid, dim3(256), 0, c.s, (const bf16_t*)(c.ws + L.E[0]),
                      (const bf16_t*)(c.ws + L.E[1]), (bf16_t*)(c.ws + L.E[0]), (bf16_t*)(c.ws + L.E[1]),
-                     (L.ldE + L.ldW) / 16, L.ldE, L.ldW, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.off,
-                     L.b);
+                     (L.ldE + L.ldW) / 16, L.ldE, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.off, L.b);
 }
 
 // ----------------------------------------------------------------------------------------------------------------

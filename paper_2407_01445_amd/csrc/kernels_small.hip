@@ -25,6 +25,28 @@ __device__ inline float load_elem(const bf16_t* p) { return __uint_as_float((uin
 // prep: one wavefront per local anchor r.  s_pp = <img_p, txt_p> (the s_ii of Sec. 3), the
 // temperatures that enter l1 / l2 of this anchor (Proc. 1: global tau, or tau_1[idx], tau_2[idx]),
 // and k = log2(e) / tau for the exp2-based evaluation in the MFMA path.
+__device__ inline double row_dot(const float* pi, const float* pt, int64_t d, int lane) {
+  double acc = 0.0;
+  for (int64_t k = lane; k < d; k += 64) acc += (double)pi[k] * (double)pt[k];
+  return acc;
+}
+// bf16 rows: d and the row strides are multiples of 8 and the bases 16-byte aligned, so 8 elements per load
+__device__ inline double row_dot(const bf16_t* pi, const bf16_t* pt, int64_t d, int lane) {
+  double acc = 0.0;
+  for (int64_t k = (int64_t)lane * 8; k < d; k += 512) {
+    const uint4 a = *(const uint4*)(pi + k), b = *(const uint4*)(pt + k);
+    const uint32_t aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {b.x, b.y, b.z, b.w};
+    float part = 0.f;   // 8 exact bf16 x bf16 products
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      part = fmaf(__uint_as_float(aw[w] << 16), __uint_as_float(bw[w] << 16), part);
+      part = fmaf(__uint_as_float(aw[w] & 0xffff0000u), __uint_as_float(bw[w] & 0xffff0000u), part);
+    }
+    acc += (double)part;
+  }
+  return acc;
+}
+
 template <typename T>
 __global__ void __launch_bounds__(256) k_prep(const T* __restrict__ img, const T* __restrict__ txt, int64_t ld_img,
                                               int64_t ld_txt, int64_t off, int64_t b, int64_t d,
@@ -35,13 +57,8 @@ __global__ void __launch_bounds__(256) k_prep(const T* __restrict__ img, const T
   const int lane = threadIdx.x & 63;
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= b) return;
-  const T* pi = img + (off + r) * ld_img;
-  const T* pt = txt + (off + r) * ld_txt;
-  double acc = 0.0;
-  for (int64_t k = lane; k < d; k += 64) acc += (double)load_elem(pi + k) * (double)load_elem(pt + k);
-  acc = wave_sum(acc);
-  if (lane == 0) {
-    float t1, t2;
+  float t1 = 0.f, t2 = 0.f;
+  if (lane == 0) {        // issue the temperature gather before the dot product so that the latencies overlap
     if (version == FASTCLIP_V2) {
       const int64_t n = idx[r];
       t1 = tau_img[n];
@@ -49,6 +66,9 @@ __global__ void __launch_bounds__(256) k_prep(const T* __restrict__ img, const T
     } else {
       t1 = t2 = tau[0];
     }
+  }
+  const double acc = wave_sum(row_dot(img + (off + r) * ld_img, txt + (off + r) * ld_txt, d, lane));
+  if (lane == 0) {
     diag[r] = (float)acc;
     tau1[r] = t1;
     tau2[r] = t2;
@@ -147,33 +167,34 @@ __device__ inline float ema_update(float u_old, float g, float gamma) {
   return u_old == 0.0f ? g : fmaf(gamma, g, (1.0f - gamma) * u_old);
 }
 
-// 256 threads = 32 anchors x 8 groups over the partial sums.
+// 256 threads = 8 anchors x 32 lanes over the partial sums (thread = 8 * lane + anchor); threads 0..7 then do the
+// per-anchor work.  kStateAnchors anchors and one pair of scalar partials per block.
 __global__ void __launch_bounds__(256) k_state(StateArgs a) {
-  __shared__ float part[4][8][32];
-  __shared__ float scal[2][32];
-  const int al = threadIdx.x & 31, grp = threadIdx.x >> 5;
-  const int64_t r = (int64_t)blockIdx.x * 32 + al;
+  __shared__ float part[4][4][8];
+  __shared__ float scal[2][8];
+  const int al = threadIdx.x & 7, pl = threadIdx.x >> 3, wave = threadIdx.x >> 6;
+  const int64_t r = (int64_t)blockIdx.x * kStateAnchors + al;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
   if (r < a.b) {
-    for (int pt = grp; pt < a.nparts; pt += 8) {
+    for (int pt = pl; pt < a.nparts; pt += 32) {
 #pragma unroll
       for (int q = 0; q < 4; ++q) acc[q] += a.sums[((size_t)q * a.nparts + pt) * a.bstride + r];
     }
   }
 #pragma unroll
-  for (int q = 0; q < 4; ++q) part[q][grp][al] = acc[q];
+  for (int q = 0; q < 4; ++q) {       // the 8 partial-sum lanes of this wave, then the 4 waves through LDS
+    acc[q] += __shfl_xor(acc[q], 8);
+    acc[q] += __shfl_xor(acc[q], 16);
+    acc[q] += __shfl_xor(acc[q], 32);
+    if ((threadIdx.x & 63) < 8) part[q][wave][al] = acc[q];
+  }
   __syncthreads();
-  if (threadIdx.x < 32) {
+  if (threadIdx.x < 8) {
     float lsum = 0.f, hsum = 0.f;
     if (r < a.b) {
       float s[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        float t = 0.f;
-#pragma unroll
-        for (int g = 0; g < 8; ++g) t += part[q][g][al];
-        s[q] = t;
-      }
+      for (int q = 0; q < 4; ++q) s[q] = (part[q][0][al] + part[q][1][al]) + (part[q][2][al] + part[q][3][al]);
       const float invM = 1.0f / a.M;
       const float g1 = s[0] * invM, h1 = s[1] * invM, g2 = s[2] * invM, h2 = s[3] * invM;
       const int64_t n = a.idx[r];
@@ -209,7 +230,7 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
   __syncthreads();
   if (threadIdx.x == 0) {
     double x = 0.0, y = 0.0;
-    for (int i = 0; i < 32; ++i) { x += (double)scal[0][i]; y += (double)scal[1][i]; }
+    for (int i = 0; i < 8; ++i) { x += (double)scal[0][i]; y += (double)scal[1][i]; }
     a.red[2 * blockIdx.x + 0] = (float)x;
     a.red[2 * blockIdx.x + 1] = (float)y;
   }
@@ -255,13 +276,15 @@ void launch_state_flat(const int64_t* idx, int64_t n, int64_t N, float gamma, fl
 }
 
 // ------------------------------------------------------------------------------------------
-// Scalars (one thread): loss of the local batch with g replaced by u^{t+1}; Eq. 8 (V0), Eq. 10 (V3).
+// Scalars (called by one whole wavefront): loss of the local batch with g replaced by u^{t+1}; Eq. 8 (V0), Eq. 10 (V3).
 __device__ void write_scalars(const float* red, int nblocks, int64_t b, int version, const float* tau, float rho,
                               float* loss, float* d_tau) {
+  const int lane = threadIdx.x & 63;
   double A = 0.0, H = 0.0;
-  for (int i = 0; i < nblocks; ++i) { A += (double)red[2 * i]; H += (double)red[2 * i + 1]; }
-  A /= (double)b;
-  H /= (double)b;
+  for (int i = lane; i < nblocks; i += 64) { A += (double)red[2 * i]; H += (double)red[2 * i + 1]; }
+  A = wave_sum(A) / (double)b;
+  H = wave_sum(H) / (double)b;
+  if (lane != 0) return;
   if (version == FASTCLIP_V2) { *loss = (float)A; return; }
   const double t = (double)tau[0];
   if (version == FASTCLIP_V1) { *loss = (float)(t * A); return; }
@@ -315,7 +338,7 @@ __global__ void __launch_bounds__(256) k_grad_f32(const float* __restrict__ img,
     }
     __syncthreads();
   }
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64)
     write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
 }
 
@@ -367,7 +390,7 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
     o.w = cown * acc.w - dc * x3;
     *(float4*)(out + c0) = o;
   }
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0)
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64)
     write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
 }
 
