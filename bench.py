@@ -46,6 +46,8 @@ def main():
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg4 (bf16 workloads of BASELINE.json)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-state-bench", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run a device-to-device copy of 1 GiB a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -58,6 +60,15 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    if args.calibrate_copy:
+        n = 1 << 28                                    # 2^28 fp32 = 1 GiB read + 1 GiB written per copy
+        src = torch.rand(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "copy", "bytes_read": 4 * n, "bytes_written": 4 * n, "copies": 5}))
+        return
     fc.load()
     dev = "cuda:0"
     torch.cuda.set_device(0)
