@@ -23,9 +23,13 @@ if ROOT not in sys.path:
 PEAK_BF16_FLOPS = 2.5e15     # MI355X dense bf16 MFMA
 PEAK_HBM_BYTES = 8.0e12      # MI355X HBM3E
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), keyed by (workload, phase); absent = not measured.
-MEASURED_TRAFFIC = {}
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this script (KiB per
+# dispatch, FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 after calibration against a 1 GiB device copy;
+# the summaries are kept under profiles/), keyed by (workload, phase); absent = not measured.
+MEASURED_TRAFFIC = {
+    ("cfg4", "strips"): (100860.7 * 2.0 + 133120.0) * 1024,
+    ("cfg4", "contract"): (135429.1 * 2.0 + 65536.0) * 1024,
+}
 
 
 def algorithmic_flops(B, b, d):
@@ -130,7 +134,7 @@ def main():
     alg = algorithmic_flops(B, b, d)
     dom = max(("strips", "contract"), key=lambda k: phase_ms.get(k, 0.0))
     achieved = alg[dom] / (phase_ms[dom] * 1e-3) / 1e12
-    roofline = {"kernel": {"strips": "k_strips_bf16", "contract": "k_gemm_nn_bf16"}[dom], "bound": "mfma",
+    roofline = {"kernel": {"strips": "k_strips_bf16", "contract": "k_contract_bf16"}[dom], "bound": "mfma",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
                 "frac": round(achieved * 1e12 / PEAK_BF16_FLOPS, 4),
                 "traffic": MEASURED_TRAFFIC.get((name, dom)),

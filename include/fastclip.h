@@ -36,8 +36,9 @@ typedef enum {
   FASTCLIP_ERR_SHAPE = 2,       /* B<2, b<1, off<0, off+b>B, d<1, ld<d, N<1, bad struct_size */
   FASTCLIP_ERR_VALUE = 3,       /* gamma not in (0,1], eps<0, NaN scalar, unknown version or dtype */
   FASTCLIP_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than fastclip_workspace_bytes() */
-  FASTCLIP_ERR_UNSUPPORTED = 5, /* bf16 path: d or a row stride not a multiple of 8, or a matrix base
-                                   not 16-byte aligned; any path: B, b or d above 2^24 */
+  FASTCLIP_ERR_UNSUPPORTED = 5, /* bf16 path: d or a row stride not a multiple of 8, a matrix base not
+                                   16-byte aligned, B + b or a row stride above 2^22; any path: B, b or d
+                                   above 2^24, a row stride above 2^30, d_img / d_txt not 16-byte aligned */
   FASTCLIP_ERR_LAUNCH = 6,      /* the HIP runtime reported an error */
   FASTCLIP_ERR_INDEX = 7        /* fastclip_check_indices: out-of-range or repeated index */
 } fastclip_status;

@@ -27,6 +27,11 @@ fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* buf
     return FASTCLIP_ERR_UNSUPPORTED;
   if (cfg->emb_dtype == FASTCLIP_BF16 && (cfg->d % 8 || cfg->ld_img % 8 || cfg->ld_txt % 8))
     return FASTCLIP_ERR_UNSUPPORTED;
+  // the MFMA kernels address a tile panel (256 rows, or 8 anchor blocks of the stored strips) with 32-bit byte
+  // offsets per lane
+  const int64_t lim22 = (int64_t)1 << 22;
+  if (cfg->emb_dtype == FASTCLIP_BF16 && (cfg->B + cfg->b > lim22 || cfg->ld_img > lim22 || cfg->ld_txt > lim22))
+    return FASTCLIP_ERR_UNSUPPORTED;
   if (bufs) {
     if (!bufs->img_glob || !bufs->txt_glob || !bufs->idx || !bufs->u_img || !bufs->u_txt ||
         !bufs->d_img || !bufs->d_txt || !bufs->loss)

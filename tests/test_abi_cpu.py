@@ -63,6 +63,7 @@ def test_valid_config_and_workspace_size():
     (dict(emb_dtype=3), fc.ERR_VALUE), (dict(tau_grad_scale=float("nan")), fc.ERR_VALUE),
     (dict(d=100, ld_img=100, ld_txt=100), fc.ERR_UNSUPPORTED), (dict(ld_img=516), fc.ERR_UNSUPPORTED),
     (dict(B=(1 << 24) + 8, b=8), fc.ERR_UNSUPPORTED),
+    (dict(B=(1 << 22), b=8), fc.ERR_UNSUPPORTED), (dict(ld_img=(1 << 22) + 8), fc.ERR_UNSUPPORTED),
 ])
 def test_bad_configs_are_rejected(over, status):
     cfg = good_cfg(**over)

@@ -107,6 +107,10 @@ BF16_SMALL = [
     (520, 520, 0, 64),
     (1000, 64, 936, 136),
     (257, 257, 0, 8),
+    # whole 256-tiles (the unguarded persistent kernels) next to ragged ones, widths that are whole / ragged stages
+    (768, 512, 256, 128),
+    (1024, 300, 512, 256),
+    (900, 512, 388, 96),
 ]
 
 
