@@ -24,87 +24,9 @@
 // global_load_lds_dwordx4 (no VGPR staging) three stages ahead; one barrier per stage; LDS operand reads of the next
 // 16-deep step are issued between the MFMAs of the current one.  Tiles that touch a ragged edge use guarded
 // register loads into the same LDS images, one stage at a time.
-#include "fc_internal.hpp"
+#include "mfma_common.hpp"
 
 namespace fc {
-
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4;
-typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2;
-typedef short v4s __attribute__((ext_vector_type(4)));
-typedef __attribute__((address_space(3))) v4s lds_v4s;
-
-constexpr int BK = 32;                       // contraction depth of one LDS stage
-constexpr int kOpBytes = 256 * BK * 2;       // one operand tile of a stage: 16 KiB
-constexpr int kStageBytes = 2 * kOpBytes;    // 32 KiB
-constexpr int kRingBytes = 4 * kStageBytes;  // 128 KiB
-
-#define FC_PIN() __builtin_amdgcn_sched_barrier(0)
-#define FC_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0f70)
-#define FC_WAIT_VMCNT8() __builtin_amdgcn_s_waitcnt(0x0f78)
-#define FC_WAIT_VMCNT16() __builtin_amdgcn_s_waitcnt(0x4f70)
-#define FC_WAIT_VMCNT34() __builtin_amdgcn_s_waitcnt(0x8f72)   // vmcnt = 34 = 0b100010: low bits 2, high bits 2
-
-__device__ __forceinline__ uint32_t lds_addr(const void* p) {
-  return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
-}
-// 16 bytes per lane from global memory straight into LDS at lds_byte_addr + 16 * lane (wave-uniform address).
-// Completion is tracked by vmcnt; the compiler does not see the LDS write, so every use below is fenced by an
-// explicit s_waitcnt vmcnt + barrier.  M0 (the LDS base of the transfer) is written here and used by nothing else
-// in these kernels.
-// The source address is a wave-uniform base (kept in SGPRs) plus a per-lane 32-bit byte offset.
-__device__ __forceinline__ void dma16(const void* uniform_base, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
-               :
-               : "v"(lane_byte_off), "s"(uniform_base), "s"(__builtin_amdgcn_readfirstlane(lds_byte_addr))
-               : "memory");
-}
-// Same for 4 bytes per lane (per-anchor scalars of the next tile).
-__device__ __forceinline__ void dma4(const void* uniform_base, uint32_t lane_byte_off, uint32_t lds_byte_addr) {
-  asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1"
-               :
-               : "v"(lane_byte_off), "s"(uniform_base), "s"(__builtin_amdgcn_readfirstlane(lds_byte_addr))
-               : "memory");
-}
-__device__ __forceinline__ float bf2f(uint16_t x) { return __uint_as_float((uint32_t)x << 16); }
-__device__ __forceinline__ uint16_t f2bf(float x) { return __builtin_bit_cast(uint16_t, (__bf16)x); }
-
-// LDS has 64 banks of 4 bytes (256 bytes per cycle); a 16-byte-per-lane read is served 16 lanes at a time, an
-// 8-byte-per-lane read 32 lanes at a time.
-// LDS image of a K-contiguous operand tile (256 rows x 32 k, 64 bytes per row): 16-byte chunk c of row r sits at
-// chunk position c ^ ((r >> 2) & 3): the 16 consecutive rows that one MFMA operand read touches per cycle then
-// cover all 16 chunk slots of a 256-byte bank window.
-__device__ __forceinline__ int rt_swz(int row) { return (row >> 2) & 3; }
-__device__ __forceinline__ int rt_off(int row, int chunk) { return row * 64 + ((chunk ^ rt_swz(row)) << 4); }
-// LDS image of a [32 k][256 n] tile of a row-major matrix (512 bytes per k row): 16-byte piece p of row k sits at
-// piece position p ^ ((k & 3) << 2), so that the 4 rows x 64 bytes which a transposing read touches per cycle cover
-// a whole bank window.
-__device__ __forceinline__ int nt_swz(int k) { return (k & 3) << 2; }
-__device__ __forceinline__ int nt_off(int k, int piece) { return k * 512 + ((piece ^ nt_swz(k)) << 4); }
-
-// One accumulator element out of its AGPR at the point of use.  Left to itself the register allocator copies large
-// parts of the accumulator block into VGPRs right after the main loop, which costs more VGPRs than there are.
-__device__ __forceinline__ float acc_read(float in_agpr) {
-  float x;
-  asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(in_agpr));
-  return x;
-}
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
-  bf16x2 p;
-  p[0] = (__bf16)lo;
-  p[1] = (__bf16)hi;
-  return __builtin_bit_cast(uint32_t, p);
-}
-__device__ __forceinline__ void zero_acc(f32x16 (&acc)[4][4]) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
-}
 
 // ----------------------------------------------------------------------------------------------------------------
 // Operand sources.  Each describes, for one workgroup tile, how a stage is brought into an LDS slot (dma: 8 wave
@@ -331,21 +253,6 @@ __device__ __forceinline__ void guarded_mainloop(f32x16 (&acc)[4][4], const Tile
 }
 
 // ----------------------------------------------------------------------------------------------------------------
-struct StripArgs {
-  const bf16_t* anchors[2];     // first local row of the anchor side (image rows for strip 0, text rows for strip 1)
-  const bf16_t* contrasts[2];   // row 0 of the contrast side (texts for strip 0, images for strip 1)
-  int64_t ld_anchor[2], ld_contrast[2];
-  const float* diag;            // s_pp per local anchor
-  const float* kscale[2];       // log2(e) / tau of the anchor for each strip
-  bf16_t* E[2];                 // Efrag per strip
-  int64_t nCB;                  // column blocks (of 16) per anchor block in Efrag
-  int64_t ldE;                  // contrast columns present in Efrag (multiple of 64, >= B)
-  float* sums;                  // [4][nparts][bstride] out
-  int nparts;
-  int64_t bstride, b, B, d, off;
-  int nAT, nCT, ntiles;
-};
-
 // Accumulator (ti, tj, v) of lane (lr, hk): contrast c0 + wr 128 + ti 32 + 8 (v >> 2) + 4 hk + (v & 3), anchor
 // a0 + wc 128 + tj 32 + lr.  t = (s - s_pp) log2(e)/tau, l = 2^t.  GUARD: zero outside the batch and on the anchor's
 // own column (B_{i-} excludes i).
@@ -415,74 +322,6 @@ __device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)
   }
 }
 
-__device__ __forceinline__ bool strip_tile_is_interior(const StripArgs& a, int64_t a0, int64_t c0) {
-  return (a0 + 256 <= a.b) && (c0 + 256 <= a.B) && (a.d % BK == 0);
-}
-
-// Interior tiles: persistent workgroups, LDS ring, next tile's first stages (and its per-anchor scalars) fetched
-// under the exponentials of the current one.
-__global__ void __launch_bounds__(256) k_strips_bf16(StripArgs a) {
-  __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
-  __shared__ __attribute__((aligned(256))) float sk[2][256];      // log2(e)/tau per anchor of the tile, double buffered
-  __shared__ __attribute__((aligned(256))) float sdiag[2][256];   // s_pp per anchor of the tile
-  __shared__ float sred[2][2][256];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wr = wave >> 1, wc = wave & 1;
-  const uint32_t ring_addr = lds_addr(ring);
-  const int S = (int)(a.d / BK);
-  // ids that share an XCD (id mod 8 under round-robin dispatch) take neighbouring tiles, and neighbouring tiles are
-  // the anchor tiles of one contrast tile, so a contrast tile is fetched once per L2
-  const int G = gridDim.x;
-  const int vid = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
-  const int per_strip = a.nAT * a.nCT;
-
-  StripTile T;
-  // request everything the main loop and the epilogue of tile `tt` need: 3 stages + 2 x 256 scalars (26 wave loads)
-  auto request = [&](int tt, int buf) {
-    const int strip = tt / per_strip, at = tt % a.nAT, ct = (tt / a.nAT) % a.nCT;
-    T.setup(a.contrasts[strip], a.ld_contrast[strip], (int64_t)ct * 256, a.B, a.anchors[strip], a.ld_anchor[strip],
-            (int64_t)at * 256, a.b, a.d, tid);
-    ring_prologue(T, ring_addr, 0, S);
-    dma4(a.kscale[strip] + at * 256 + wave * 64, lane * 4, lds_addr(&sk[buf][wave * 64]));
-    dma4(a.diag + at * 256 + wave * 64, lane * 4, lds_addr(&sdiag[buf][wave * 64]));
-  };
-  auto next_interior = [&](int tt) {
-    while (tt < a.ntiles &&
-           !strip_tile_is_interior(a, (int64_t)(tt % a.nAT) * 256, (int64_t)((tt / a.nAT) % a.nCT) * 256))
-      tt += G;
-    return tt;
-  };
-
-  int t = next_interior(vid);
-  if (t >= a.ntiles) return;
-  int buf = 0;
-  request(t, buf);
-  FC_WAIT_VMCNT0();
-  while (t < a.ntiles) {
-    const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
-    const int64_t a0 = (int64_t)at * 256, c0 = (int64_t)ct * 256;
-    f32x16 acc[4][4];
-    zero_acc(acc);
-    ring_mainloop<true>(acc, T, ring, ring_addr, 0, S);
-    const int tn = next_interior(t + G);
-    if (tn < a.ntiles) request(tn, buf ^ 1);
-    const bool diagonal = (c0 < a.off + a0 + 256) && (c0 + 256 > a.off + a0);
-    if (diagonal) strip_epilogue<true>(a, acc, sk[buf], sdiag[buf], sred, strip, a0, c0, wr, wc, lane);
-    else strip_epilogue<false>(a, acc, sk[buf], sdiag[buf], sred, strip, a0, c0, wr, wc, lane);
-    __syncthreads();
-#pragma unroll
-    for (int q = 0; q < 2; ++q)
-      a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a0 + tid] = sred[0][q][tid] + sred[1][q][tid];
-    // Every wave has issued, after its 26 requests for the next tile, exactly 32 fragment stores and 2 sum stores;
-    // vector memory operations complete in order, so "at most 34 outstanding" means the requests have landed
-    // while the stores may still be in flight.
-    FC_WAIT_VMCNT34();
-    t = tn;
-    buf ^= 1;
-  }
-}
-
 // Tiles with a ragged edge (anchors, contrasts or width not a multiple of the tile): one workgroup per tile,
 // guarded loads, guarded epilogue.
 __global__ void __launch_bounds__(256) k_strips_edge_bf16(StripArgs a) {
@@ -539,12 +378,9 @@ void launch_strips_bf16(const StepCtx& c) {
   a.nAT = (int)((L.b + 255) / 256);
   a.nCT = (int)((L.B + 255) / 256);
   a.ntiles = 2 * a.nAT * a.nCT;
-  const bool any_interior = L.b >= 256 && L.B >= 256 && L.d % BK == 0;
-  const bool any_edge = (L.b % 256) || (L.B % 256) || (L.d % BK);
-  if (any_interior) {
-    const int grid = a.ntiles < 256 ? a.ntiles : 256;
-    hipLaunchKernelGGL(k_strips_bf16, dim3((unsigned)grid), dim3(256), 0, c.s, a);
-  }
+  const bool any_interior = L.b >= 256 && L.B >= 256 && L.d % 64 == 0 && L.d >= 128;
+  const bool any_edge = (L.b % 256) || (L.B % 256) || !any_interior;
+  if (any_interior) launch_strips_interior_bf16(a, c.s);
   if (any_edge) hipLaunchKernelGGL(k_strips_edge_bf16, dim3((unsigned)a.ntiles), dim3(256), 0, c.s, a);
 }
 

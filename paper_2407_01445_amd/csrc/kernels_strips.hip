@@ -1,0 +1,297 @@
+// k_strips_bf16: the similarity strips of Proc. 1 on whole 256 x 256 tiles (gfx950, wave64, MFMA 32x32x16 bf16).
+//
+// For every tile (strip, 256 anchors, 256 contrasts) the kernel forms s = x_contrast . x_anchor in registers, then
+// l = exp((s - s_pp) / tau_p) (Sec. 3), adds l and (s - s_pp) l into per-anchor partial sums (Proc. 1; the sums behind
+// Eqs. 8-10), and stores l rounded to bf16 in the fragment order the gradient contraction reads.
+//
+// Shape of the work.  One workgroup of EIGHT waves per compute unit computes a 256 x 256 tile (the largest that the
+// accumulator registers of a compute unit hold, hence the fewest operand bytes per flop); a wave owns 64 contrasts x
+// 128 anchors = 2 x 4 accumulator blocks (128 AGPRs), so every SIMD runs two waves and always has a second
+// instruction stream when one waits for LDS data.
+//
+// Data movement.  Operands go global -> LDS with direct-to-LDS loads, 64 deep in k per stage: every row contributes
+// one whole 128-byte line per stage (half-line requests reach only about 60 % of the load path's rate), 64 KiB per
+// stage, two slots.  The requests form one continuous stream over stages and tiles: three quarters into stage g all
+// waves have read slot g % 2 for the last time (one barrier, which also publishes stage g + 1), and stage g + 2 is
+// requested into it, so the epilogue of a tile runs with the next tile's first two stages already requested.  Past
+// the last tile the stream keeps re-requesting its last stage (nobody reads it), which keeps every s_waitcnt
+// immediate constant.  Vector memory operations complete in order, so "stage g + 1 has landed" is
+// s_waitcnt vmcnt(n) with n = the number of operations issued after that stage's loads.
+#include "mfma_common.hpp"
+
+namespace fc {
+
+constexpr int kSK = 64;                         // contraction depth of a stage: 128 bytes per row
+constexpr int kSOp = 256 * kSK * 2;             // one operand of a stage: 32 KiB
+constexpr int kSStage = 2 * kSOp;               // 64 KiB
+constexpr int kSRing = 2 * kSStage;             // 128 KiB
+
+// LDS image of an operand of a stage (256 rows x 128 bytes): 16-byte chunk c of row r sits at chunk position
+// c ^ ((r >> 1) & 7), so that the 16 consecutive rows one operand read touches per cycle cover all 16 chunk slots
+// of a 256-byte bank window.
+__device__ __forceinline__ int st_swz(int row) { return (row >> 1) & 7; }
+
+// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt and lgkmcnt left open)
+#define FC_WAIT_VMCNT1() __builtin_amdgcn_s_waitcnt(0x0f71)
+#define FC_WAIT_VMCNT18() __builtin_amdgcn_s_waitcnt(0x4f72)
+
+// 16 bytes per lane from uniform_base + lane_byte_off into LDS at (lds_uniform + IMM) + 16 * lane.
+template <int IMM>
+__device__ __forceinline__ void dma16i(const void* uniform_base, uint32_t lane_byte_off, uint32_t lds_uniform) {
+  asm volatile("s_add_u32 m0, %2, %3\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+               :
+               : "v"(lane_byte_off), "s"(uniform_base), "s"(lds_uniform), "n"(IMM)
+               : "memory", "scc");
+}
+
+__device__ __forceinline__ void zero_acc24(f32x16 (&acc)[2][4]) {
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+}
+
+#define FC_HMM(ti, tj, A_, B_) \
+  acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A_[ti], B_[tj], acc[ti][tj], 0, 0, 0)
+#define FC_LDS16(p) (*(const bf16x8*)(p))
+
+// Epilogue of one wave (64 contrasts x 128 anchors).  Accumulator (ti, tj, v) of lane (lr, hk): contrast
+// c_first + 32 ti + 8 (v >> 2) + 4 hk + (v & 3), anchor anchor0 + 32 tj + lr.  t = (s - s_pp) log2(e)/tau, l = 2^t.
+// MASK: the anchor's own column may fall among these contrasts (B_{i-} excludes i): l := 0 there.
+// frag0: fragment (anchor block of tj = 0, column block of c_first) of the stored strip; row_bytes: bytes from one
+// anchor block to the next.  sg / st: sums of l and t l per anchor (added to).
+template <bool MASK>
+__device__ __forceinline__ void half_epilogue(f32x16 (&acc)[2][4], const float* sk, const float* sdiag,
+                                              float (&sg)[4], float (&st)[4], char* frag0, int64_t row_bytes,
+                                              int c_first, int own0, int al0, int lane) {
+  const int lr = lane & 31, hk = lane >> 5;
+#pragma unroll
+  for (int tj = 0; tj < 4; ++tj) {
+    const int al = al0 + tj * 32 + lr;
+    const float kk = sk[al], dk = sdiag[al] * kk;   // log2(e)/tau and s_pp log2(e)/tau of this anchor
+    const int own = own0 + tj * 32 + lr;            // global row of the anchor itself
+    char* fr = frag0 + tj * row_bytes;              // wave-uniform
+    float sgv[4] = {0.f, 0.f, 0.f, 0.f}, stv[4] = {0.f, 0.f, 0.f, 0.f};   // independent chains
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti) {
+      const int crow = c_first + ti * 32 + 4 * hk;
+      uint32_t pk[8];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float t[4], e[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t[q] = fmaf(acc_read(acc[ti][tj][4 * g + q]), kk, -dk);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) e[q] = __builtin_amdgcn_exp2f(t[q]);
+        if (MASK) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) e[q] = (crow + 8 * g + q != own) ? e[q] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          sgv[q] += e[q];
+          stv[q] = fmaf(t[q], e[q], stv[q]);
+        }
+        pk[2 * g] = pack_bf16x2(e[0], e[1]);
+        pk[2 * g + 1] = pack_bf16x2(e[2], e[3]);
+        FC_PIN();
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const u32x4 w = {pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]};
+        *(u32x4*)(fr + (2 * ti + j) * 1024 + lane * 16) = w;
+      }
+      FC_PIN();
+    }
+    sg[tj] += (sgv[0] + sgv[1]) + (sgv[2] + sgv[3]);
+    st[tj] += (stv[0] + stv[1]) + (stv[2] + stv[3]);
+  }
+}
+
+__global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
+  __shared__ __attribute__((aligned(1024))) char ring[kSRing];
+  __shared__ __attribute__((aligned(256))) float sk[2][256];      // log2(e)/tau per anchor of the tile, double buffered
+  __shared__ __attribute__((aligned(256))) float sdiag[2][256];   // s_pp per anchor of the tile
+  __shared__ float sred[4][2][256];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wr = wave >> 1, wc = wave & 1, lr = lane & 31, hk = lane >> 5;
+  const uint32_t ring_addr = lds_addr(ring);
+  const int S = (int)(a.d / kSK);   // >= 2
+  // ids that share an XCD (id mod 8 under round-robin dispatch) take neighbouring tiles, and neighbouring tiles are
+  // the anchor tiles of one contrast tile, so a contrast tile is fetched once per L2
+  const int G = gridDim.x;
+  const int vid = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+  const int per_strip = a.nAT * a.nCT;
+  auto next_interior = [&](int tt) {
+    while (tt < a.ntiles &&
+           !strip_tile_is_interior(a, (int64_t)(tt % a.nAT) * 256, (int64_t)((tt / a.nAT) % a.nCT) * 256))
+      tt += G;
+    return tt;
+  };
+
+  // ---- the request stream --------------------------------------------------------------------------------------
+  // wave w requests rows 32 w .. 32 w + 31 of both operands: 4 + 4 wave loads of 8 rows x 128 bytes; lane l of a
+  // wave load fetches chunk (l & 7) ^ swz of row (l >> 3), i.e. 8 consecutive lanes cover one whole line.
+  const uint32_t mX = ring_addr + (uint32_t)(4 * wave) * 1024u;              // LDS targets inside slot 0
+  const uint32_t mA = mX + (uint32_t)kSOp;
+  uint32_t ox[4], oa[4];   // per-lane byte offsets of the wave loads within a stage
+  const bf16_t *qx, *qa;   // wave-uniform: operands of the next stage to request
+  int q_left, q_tile;
+  auto request_tile = [&](int tt) {
+    const int strip = tt / per_strip, at = tt % a.nAT, ct = (tt / a.nAT) % a.nCT;
+    const int64_t ldx = a.ld_contrast[strip], lda = a.ld_anchor[strip];
+    qx = a.contrasts[strip] + (int64_t)ct * 256 * ldx;
+    qa = a.anchors[strip] + (int64_t)at * 256 * lda;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 8 * (4 * wave + i) + (lane >> 3);
+      const int chunk = (lane & 7) ^ st_swz(row);
+      ox[i] = (uint32_t)(row * (int)ldx + (chunk << 3)) * 2u;
+      oa[i] = (uint32_t)(row * (int)lda + (chunk << 3)) * 2u;
+    }
+    q_left = S; q_tile = tt;
+  };
+  // after the 8 wave loads of a stage: step the stream
+  auto request_advance = [&]() {
+    if (q_tile >= a.ntiles) return;          // past the end: keep re-requesting the last stage
+    if (--q_left > 0) { qx += kSK; qa += kSK; return; }
+    const int tn = next_interior(q_tile + G);
+    if (tn < a.ntiles) request_tile(tn); else q_tile = tn;
+  };
+#define FC_REQ_X(i, slot) dma16i<(i) * 1024>(qx, ox[i], mX + (slot))
+#define FC_REQ_A(i, slot) dma16i<(i) * 1024>(qa, oa[i], mA + (slot))
+#define FC_REQ_ALL(slot)                                                          \
+  FC_REQ_X(0, slot); FC_REQ_A(0, slot); FC_REQ_X(1, slot); FC_REQ_A(1, slot);     \
+  FC_REQ_X(2, slot); FC_REQ_A(2, slot); FC_REQ_X(3, slot); FC_REQ_A(3, slot)
+
+  int t = next_interior(vid);
+  if (t >= a.ntiles) return;
+  request_tile(t);
+  FC_REQ_ALL(0u);
+  request_advance();
+  FC_REQ_ALL((uint32_t)kSStage);
+  request_advance();
+
+  // ---- operand reads.  Chunk 2 j + hk of a row for the 16-deep step j sits at position ((hk ^ swz) ^ 2 j): the
+  // address for step j is the address for step 0 with bits 5..6 XORed by j; bit 16 selects the slot.
+  const uint32_t bx = (uint32_t)((wr * 64 + lr) * 128 + ((hk ^ st_swz(wr * 64 + lr)) << 4));
+  const uint32_t ba = (uint32_t)kSOp + (uint32_t)((wc * 128 + lr) * 128 + ((hk ^ st_swz(wc * 128 + lr)) << 4));
+
+  uint32_t cs = 0u, ns = (uint32_t)kSStage;   // slots of stages g, g + 1 (bit 16)
+  FC_WAIT_VMCNT8();   // stage 0 of the stream has landed (stage 1 may be in flight)
+  __syncthreads();
+  bf16x8 x0[2], a0[4], x1[2], a1[4];
+  x0[0] = FC_LDS16(ring + bx); x0[1] = FC_LDS16(ring + bx + 4096);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + ba + j * 4096);
+
+// One 16-deep step: 8 MFMAs on operand set P while operand set Q is read for the following step from px / pa.
+#define FC_STEP(XP, AP, XQ, AQ, px, pa)                                          \
+  FC_HMM(0, 0, XP, AP); FC_PIN(); XQ[0] = FC_LDS16(px);         FC_PIN();         \
+  FC_HMM(0, 1, XP, AP); FC_PIN(); AQ[0] = FC_LDS16(pa);         FC_PIN();         \
+  FC_HMM(0, 2, XP, AP); FC_PIN(); XQ[1] = FC_LDS16(px + 4096);  FC_PIN();         \
+  FC_HMM(0, 3, XP, AP); FC_PIN(); AQ[1] = FC_LDS16(pa + 4096);  FC_PIN();         \
+  FC_HMM(1, 0, XP, AP); FC_PIN(); AQ[2] = FC_LDS16(pa + 8192);  FC_PIN();         \
+  FC_HMM(1, 1, XP, AP); FC_PIN(); AQ[3] = FC_LDS16(pa + 12288); FC_PIN();         \
+  FC_HMM(1, 2, XP, AP);                                                          \
+  FC_HMM(1, 3, XP, AP); FC_PIN()
+
+  // The barrier of stream stage g waits for the loads of stage g + 1; nothing is issued after them except, at a tile
+  // change, the 16 fragment stores and 1 sum store of the finished tile and the scalar load of the new one
+  // (kind 1: 18 per wave), or, for the first tile, the scalar load alone (kind 2).  S >= 2 keeps these episodes apart.
+  int pend_kind = 2;
+  int buf = 0;
+  while (t < a.ntiles) {
+    const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
+    const int a_first = at * 256, c_tile = ct * 256;
+    // per-anchor scalars of this tile: covered by the wait of the tile's second stage
+    if (wave < 4) dma4(a.kscale[strip] + a_first + wave * 64, lane * 4, lds_addr(&sk[buf][wave * 64]));
+    else dma4(a.diag + a_first + (wave - 4) * 64, lane * 4, lds_addr(&sdiag[buf][(wave - 4) * 64]));
+    f32x16 acc[2][4];
+    zero_acc24(acc);
+#pragma unroll 1
+    for (int s = 0; s < S; ++s) {
+      {
+        const char* px = ring + ((bx ^ 32u) ^ cs);
+        const char* pa = ring + ((ba ^ 32u) ^ cs);
+        FC_STEP(x0, a0, x1, a1, px, pa);
+      }
+      {
+        const char* px = ring + ((bx ^ 64u) ^ cs);
+        const char* pa = ring + ((ba ^ 64u) ^ cs);
+        FC_STEP(x1, a1, x0, a0, px, pa);
+      }
+      {
+        const char* px = ring + ((bx ^ 96u) ^ cs);
+        const char* pa = ring + ((ba ^ 96u) ^ cs);
+        FC_STEP(x0, a0, x1, a1, px, pa);
+      }
+      // stage g + 1 has landed for this wave; the barrier (which every wave reaches with its LDS reads complete)
+      // makes that true for all waves and retires the current slot: nobody reads it after this point
+      if (pend_kind == 0) FC_WAIT_VMCNT0();
+      else if (pend_kind == 1) FC_WAIT_VMCNT18();
+      else FC_WAIT_VMCNT1();
+      pend_kind = 0;
+      __syncthreads();
+      FC_PIN();
+      {
+        // last step; meanwhile read the first step's operands of stage g + 1 and request stage g + 2 into the slot
+        // just retired
+        const char* px = ring + (bx ^ ns);
+        const char* pa = ring + (ba ^ ns);
+        FC_HMM(0, 0, x1, a1); FC_PIN(); x0[0] = FC_LDS16(px);         FC_PIN(); FC_REQ_X(0, cs); FC_PIN();
+        FC_HMM(0, 1, x1, a1); FC_PIN(); a0[0] = FC_LDS16(pa);         FC_PIN(); FC_REQ_A(0, cs); FC_PIN();
+        FC_HMM(0, 2, x1, a1); FC_PIN(); x0[1] = FC_LDS16(px + 4096);  FC_PIN(); FC_REQ_X(1, cs); FC_PIN();
+        FC_HMM(0, 3, x1, a1); FC_PIN(); a0[1] = FC_LDS16(pa + 4096);  FC_PIN(); FC_REQ_A(1, cs); FC_PIN();
+        FC_HMM(1, 0, x1, a1); FC_PIN(); a0[2] = FC_LDS16(pa + 8192);  FC_PIN(); FC_REQ_X(2, cs); FC_PIN();
+        FC_HMM(1, 1, x1, a1); FC_PIN(); a0[3] = FC_LDS16(pa + 12288); FC_PIN(); FC_REQ_A(2, cs); FC_PIN();
+        FC_HMM(1, 2, x1, a1); FC_PIN(); FC_REQ_X(3, cs); FC_PIN();
+        FC_HMM(1, 3, x1, a1); FC_PIN(); FC_REQ_A(3, cs); FC_PIN();
+      }
+      request_advance();
+      const uint32_t tmp = cs; cs = ns; ns = tmp;
+    }
+    // exponentials, sums and fragment stores of this tile (16 stores per lane)
+    float sg[4] = {0.f, 0.f, 0.f, 0.f}, st[4] = {0.f, 0.f, 0.f, 0.f};
+    const int c_first = c_tile + wr * 64;
+    char* frag0 = (char*)a.E[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCB + (c_first >> 4)) * 1024;
+    const int64_t row_bytes = a.nCB * 1024;
+    const int own0 = (int)a.off + a_first + wc * 128;
+    const bool diagonal = (c_first < own0 + 128) && (c_first + 64 > own0);
+    if (diagonal) half_epilogue<true>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+    else half_epilogue<false>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+    // per-anchor sums of the tile: lanes hk = 0 / 1 hold the two halves of each 8-row group, waves wr = 0 .. 3 the
+    // four 64-row blocks
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      const int al = wc * 128 + tj * 32 + lr;
+      const float kk = sk[buf][al];
+      const float g2 = sg[tj] + __shfl_xor(sg[tj], 32);
+      const float t2 = st[tj] + __shfl_xor(st[tj], 32);
+      if (hk == 0) {
+        sred[wr][0][al] = g2;
+        sred[wr][1][al] = kk > 0.f ? t2 * __builtin_amdgcn_rcpf(kk) : 0.f;   // sum of (s - s_pp) l
+      }
+    }
+    __syncthreads();
+    {
+      const int q = tid >> 8, m = tid & 255;
+      a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a_first + m] =
+          (sred[0][q][m] + sred[1][q][m]) + (sred[2][q][m] + sred[3][q][m]);
+    }
+    pend_kind = 1;
+    t = next_interior(t + G);
+    buf ^= 1;
+  }
+  FC_WAIT_VMCNT0();   // the trailing re-requests write LDS: they must land before the workgroup gives it back
+}
+
+void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s) {
+  const int grid = a.ntiles < 256 ? a.ntiles : 256;
+  hipLaunchKernelGGL(k_strips_bf16, dim3((unsigned)grid), dim3(512), 0, s, a);
+}
+
+}  // namespace fc
