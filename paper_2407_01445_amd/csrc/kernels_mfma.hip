@@ -166,68 +166,78 @@ struct ContractTile {
 #define FC_MM(ti, tj, A_, B_) acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A_[ti], B_[tj], acc[ti][tj], 0, 0, 0)
 
 // One 32-deep stage of the ring: 16 MFMAs on the operands already in registers while the operands of the second
-// 16-deep step are read; then "stage s+1 has landed" (vmcnt) + barrier, which also retires slot (s-1) for reuse; then
-// 16 MFMAs while the first operands of stage s+1 are read and the 8 wave loads of stage s+3 are issued.
-// WAIT: 0 = stage s+1 is already known to have landed, 1 = vmcnt(8) (only the loads of stage s+2 may be in flight),
-// 2 = vmcnt(0).
-#define FC_STAGE(T, MORE, DMA, WAIT)                                                                                     \
+// 16-deep step are read; then "stage s+1 has landed" (vmcnt) + barrier, which also retires the slot of stage s-1; then
+// 16 MFMAs while the first operands of stage s+1 are read.  The 8 wave loads of a stage x are spread over a whole
+// stage time, one per four MFMAs, so that the load unit sees a steady trickle instead of a burst that blocks the
+// wave's issue: the four A-operand loads in the second half of stage x-4 (DMAA, into the slot just retired), the four
+// B-operand loads in the first half of stage x-3 (DMAB).  cur / nxt / prv / pp: byte offsets of the slots of stages
+// s, s+1, s-1, s-2 in a ring of five.  WAIT: loads that may stay in flight at the barrier (those of stages s+2 and
+// s+3): 16, 8 or 0.
+#define FC_STAGE(T, MORE, DMAB, DMAA, WAIT)                                                                         \
   {                                                                                                                 \
-    const char* sl = ring + (s & 3) * kStageBytes;                                                                  \
+    const char* sl = ring + cur;                                                                                    \
+    const uint32_t bslot = ring_addr + pp;                                                                          \
     FC_MM(0, 0, a0, b0); FC_MM(0, 1, a0, b0); FC_PIN(); a1[0] = T.read_a(sl, 0, 1); FC_PIN();                       \
-    FC_MM(0, 2, a0, b0); FC_MM(0, 3, a0, b0); FC_PIN(); b1[0] = T.read_b(sl, 0, 1); FC_PIN();                       \
+    FC_MM(0, 2, a0, b0); FC_MM(0, 3, a0, b0); FC_PIN(); b1[0] = T.read_b(sl, 0, 1); FC_PIN(); if (DMAB) T.dma(4, s0 + s + 3, bslot); FC_PIN(); \
     FC_MM(1, 0, a0, b0); FC_MM(1, 1, a0, b0); FC_PIN(); a1[1] = T.read_a(sl, 1, 1); FC_PIN();                       \
-    FC_MM(1, 2, a0, b0); FC_MM(1, 3, a0, b0); FC_PIN(); b1[1] = T.read_b(sl, 1, 1); FC_PIN();                       \
+    FC_MM(1, 2, a0, b0); FC_MM(1, 3, a0, b0); FC_PIN(); b1[1] = T.read_b(sl, 1, 1); FC_PIN(); if (DMAB) T.dma(5, s0 + s + 3, bslot); FC_PIN(); \
     FC_MM(2, 0, a0, b0); FC_MM(2, 1, a0, b0); FC_PIN(); a1[2] = T.read_a(sl, 2, 1); FC_PIN();                       \
-    FC_MM(2, 2, a0, b0); FC_MM(2, 3, a0, b0); FC_PIN(); b1[2] = T.read_b(sl, 2, 1); FC_PIN();                       \
+    FC_MM(2, 2, a0, b0); FC_MM(2, 3, a0, b0); FC_PIN(); b1[2] = T.read_b(sl, 2, 1); FC_PIN(); if (DMAB) T.dma(6, s0 + s + 3, bslot); FC_PIN(); \
     FC_MM(3, 0, a0, b0); FC_MM(3, 1, a0, b0); FC_PIN(); a1[3] = T.read_a(sl, 3, 1); FC_PIN();                       \
-    FC_MM(3, 2, a0, b0); FC_MM(3, 3, a0, b0); FC_PIN(); b1[3] = T.read_b(sl, 3, 1); FC_PIN();                       \
-    if (WAIT == 1) FC_WAIT_VMCNT8(); else if (WAIT == 2) FC_WAIT_VMCNT0();                                          \
+    FC_MM(3, 2, a0, b0); FC_MM(3, 3, a0, b0); FC_PIN(); b1[3] = T.read_b(sl, 3, 1); FC_PIN(); if (DMAB) T.dma(7, s0 + s + 3, bslot); FC_PIN(); \
+    if (WAIT == 16) FC_WAIT_VMCNT16(); else if (WAIT == 8) FC_WAIT_VMCNT8(); else FC_WAIT_VMCNT0();                 \
     __syncthreads();                                                                                                \
     FC_PIN();                                                                                                       \
-    const char* nx = ring + ((s + 1) & 3) * kStageBytes;                                                            \
-    const uint32_t dslot = ring_addr + (uint32_t)((s + 3) & 3) * kStageBytes;                                       \
-    FC_MM(0, 0, a1, b1); FC_MM(0, 1, a1, b1); FC_PIN(); if (MORE) a0[0] = T.read_a(nx, 0, 0); FC_PIN(); if (DMA) T.dma(0, s0 + s + 3, dslot); FC_PIN(); \
-    FC_MM(0, 2, a1, b1); FC_MM(0, 3, a1, b1); FC_PIN(); if (MORE) b0[0] = T.read_b(nx, 0, 0); FC_PIN(); if (DMA) T.dma(4, s0 + s + 3, dslot); FC_PIN(); \
-    FC_MM(1, 0, a1, b1); FC_MM(1, 1, a1, b1); FC_PIN(); if (MORE) a0[1] = T.read_a(nx, 1, 0); FC_PIN(); if (DMA) T.dma(1, s0 + s + 3, dslot); FC_PIN(); \
-    FC_MM(1, 2, a1, b1); FC_MM(1, 3, a1, b1); FC_PIN(); if (MORE) b0[1] = T.read_b(nx, 1, 0); FC_PIN(); if (DMA) T.dma(5, s0 + s + 3, dslot); FC_PIN(); \
-    FC_MM(2, 0, a1, b1); FC_MM(2, 1, a1, b1); FC_PIN(); if (MORE) a0[2] = T.read_a(nx, 2, 0); FC_PIN(); if (DMA) T.dma(2, s0 + s + 3, dslot); FC_PIN(); \
-    FC_MM(2, 2, a1, b1); FC_MM(2, 3, a1, b1); FC_PIN(); if (MORE) b0[2] = T.read_b(nx, 2, 0); FC_PIN(); if (DMA) T.dma(6, s0 + s + 3, dslot); FC_PIN(); \
-    FC_MM(3, 0, a1, b1); FC_MM(3, 1, a1, b1); FC_PIN(); if (MORE) a0[3] = T.read_a(nx, 3, 0); FC_PIN(); if (DMA) T.dma(3, s0 + s + 3, dslot); FC_PIN(); \
-    FC_MM(3, 2, a1, b1); FC_MM(3, 3, a1, b1); FC_PIN(); if (MORE) b0[3] = T.read_b(nx, 3, 0); FC_PIN(); if (DMA) T.dma(7, s0 + s + 3, dslot); FC_PIN(); \
+    const char* nx = ring + nxt;                                                                                    \
+    const uint32_t aslot = ring_addr + prv;                                                                         \
+    FC_MM(0, 0, a1, b1); FC_MM(0, 1, a1, b1); FC_PIN(); if (MORE) a0[0] = T.read_a(nx, 0, 0); FC_PIN();             \
+    FC_MM(0, 2, a1, b1); FC_MM(0, 3, a1, b1); FC_PIN(); if (MORE) b0[0] = T.read_b(nx, 0, 0); FC_PIN(); if (DMAA) T.dma(0, s0 + s + 4, aslot); FC_PIN(); \
+    FC_MM(1, 0, a1, b1); FC_MM(1, 1, a1, b1); FC_PIN(); if (MORE) a0[1] = T.read_a(nx, 1, 0); FC_PIN();             \
+    FC_MM(1, 2, a1, b1); FC_MM(1, 3, a1, b1); FC_PIN(); if (MORE) b0[1] = T.read_b(nx, 1, 0); FC_PIN(); if (DMAA) T.dma(1, s0 + s + 4, aslot); FC_PIN(); \
+    FC_MM(2, 0, a1, b1); FC_MM(2, 1, a1, b1); FC_PIN(); if (MORE) a0[2] = T.read_a(nx, 2, 0); FC_PIN();             \
+    FC_MM(2, 2, a1, b1); FC_MM(2, 3, a1, b1); FC_PIN(); if (MORE) b0[2] = T.read_b(nx, 2, 0); FC_PIN(); if (DMAA) T.dma(2, s0 + s + 4, aslot); FC_PIN(); \
+    FC_MM(3, 0, a1, b1); FC_MM(3, 1, a1, b1); FC_PIN(); if (MORE) a0[3] = T.read_a(nx, 3, 0); FC_PIN();             \
+    FC_MM(3, 2, a1, b1); FC_MM(3, 3, a1, b1); FC_PIN(); if (MORE) b0[3] = T.read_b(nx, 3, 0); FC_PIN(); if (DMAA) T.dma(3, s0 + s + 4, aslot); FC_PIN(); \
+    pp = prv; prv = cur; cur = nxt;                                                                                 \
+    nxt = (nxt + (uint32_t)kStageBytes == (uint32_t)kRingBytes) ? 0u : nxt + (uint32_t)kStageBytes;                 \
+    ++s;                                                                                                            \
   }
 
-// Issue the wave loads of the first min(S, 3) stages [s0, ...) of a tile into ring slots 0, 1, 2.
+// Issue the wave loads of the first stages [s0, ...) of a tile into ring slots 0 .. 3: stages 0 .. 2 whole and of
+// stage 3 the A-operand half (its B-operand half follows in the first half of stage 0, as for every later stage);
+// tiles of at most 4 stages are requested whole.
 template <typename Tile>
 __device__ __forceinline__ void ring_prologue(const Tile& T, uint32_t ring_addr, int s0, int S) {
 #pragma unroll
-  for (int p = 0; p < 3; ++p)
+  for (int p = 0; p < 4; ++p)
     if (p < S) {
 #pragma unroll
-      for (int i = 0; i < 8; ++i) T.dma(i, s0 + p, ring_addr + p * kStageBytes);
+      for (int i = 0; i < 8; ++i)
+        if (p < 3 || i < 4 || S == 4) T.dma(i, s0 + p, ring_addr + p * kStageBytes);
     }
 }
 
 // acc += (A operand tile) x (B operand tile)^T over stages [s0, s0 + S); the prologue must have been issued, and
-// nothing else may have touched the ring since.  LANDED: this wave already knows that its own prologue loads are
-// complete (it has consumed a younger load; vector memory operations complete in order), and younger stores may
-// still be in flight, which the first two stages then do not wait for.  On return no wave reads the ring any more.
-template <bool LANDED, typename Tile>
+// nothing else may have touched the ring since.  Vector memory operations complete in order, so every wait names
+// the number of younger loads that may stay in flight.  On return no wave reads the ring any more.
+template <typename Tile>
 __device__ __forceinline__ void ring_mainloop(f32x16 (&acc)[4][4], const Tile& T, char* ring, uint32_t ring_addr,
                                               int s0, int S) {
-  if (!LANDED) {
-    if (S >= 3) FC_WAIT_VMCNT16(); else FC_WAIT_VMCNT0();   // stage 0 has landed; stages 1, 2 may be in flight
-  }
+  // stage 0 has landed; stages 1, 2 and (half or all of) 3 may be in flight
+  if (S >= 5) FC_WAIT_VMCNT20(); else if (S == 4) FC_WAIT_VMCNT24(); else FC_WAIT_VMCNT0();
   __syncthreads();
   bf16x8 a0[4], b0[4], a1[4], b1[4];
 #pragma unroll
   for (int t = 0; t < 4; ++t) { a0[t] = T.read_a(ring, t, 0); b0[t] = T.read_b(ring, t, 0); }
+  uint32_t cur = 0u, nxt = (uint32_t)kStageBytes, prv = 4u * (uint32_t)kStageBytes, pp = 3u * (uint32_t)kStageBytes;
   int s = 0;
-  if (LANDED) {
-    for (; s < 2 && s + 3 < S; ++s) FC_STAGE(T, true, true, 0)
-  }
-  for (; s + 3 < S; ++s) FC_STAGE(T, true, true, 1)
-  for (; s + 1 < S; ++s) FC_STAGE(T, true, false, 2)
-  FC_STAGE(T, false, false, 2)
+  while (s + 4 < S) FC_STAGE(T, true, true, true, 16)               // s = 0 .. S-5
+  while (s + 4 == S && S >= 5) FC_STAGE(T, true, true, false, 16)   // s = S-4: the last B-operand loads
+  while (s + 3 < S) FC_STAGE(T, true, false, false, 16)             // S == 4 only
+  while (s + 2 < S) FC_STAGE(T, true, false, false, 8)
+  while (s + 1 < S) FC_STAGE(T, true, false, false, 0)
+  FC_STAGE(T, false, false, false, 0)
+  __syncthreads();
 }
 
 // Same contraction for tiles with a ragged edge: one stage at a time through registers, zero fill outside.
@@ -489,7 +499,7 @@ __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
     T.setup(J.E, g.nCB, m0 >> 5, J.X, J.ldx, n0, g.N, g.B, g.bloc, g.off, g.ldE, tid);
     if (g.all_rows_valid && n0 + 256 <= g.N) {
       ring_prologue(T, ring_addr, s0, S);
-      ring_mainloop<false>(acc, T, ring, ring_addr, s0, S);
+      ring_mainloop(acc, T, ring, ring_addr, s0, S);
     } else {
       guarded_mainloop(acc, T, ring, s0, S, tid);
     }

@@ -188,21 +188,27 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
 #pragma unroll
   for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + ba + j * 4096);
 
-// One 16-deep step: 8 MFMAs on operand set P while operand set Q is read for the following step from px / pa.
-#define FC_STEP(XP, AP, XQ, AQ, px, pa)                                          \
-  FC_HMM(0, 0, XP, AP); FC_PIN(); XQ[0] = FC_LDS16(px);         FC_PIN();         \
-  FC_HMM(0, 1, XP, AP); FC_PIN(); AQ[0] = FC_LDS16(pa);         FC_PIN();         \
-  FC_HMM(0, 2, XP, AP); FC_PIN(); XQ[1] = FC_LDS16(px + 4096);  FC_PIN();         \
-  FC_HMM(0, 3, XP, AP); FC_PIN(); AQ[1] = FC_LDS16(pa + 4096);  FC_PIN();         \
-  FC_HMM(1, 0, XP, AP); FC_PIN(); AQ[2] = FC_LDS16(pa + 8192);  FC_PIN();         \
-  FC_HMM(1, 1, XP, AP); FC_PIN(); AQ[3] = FC_LDS16(pa + 12288); FC_PIN();         \
-  FC_HMM(1, 2, XP, AP);                                                          \
-  FC_HMM(1, 3, XP, AP); FC_PIN()
+// One 16-deep step: 8 MFMAs on operand set P while operand set Q is read for the following step from px / pa;
+// D0 .. D7 are statements (requests or nothing) placed one per MFMA.
+#define FC_NONE (void)0
+#define FC_STEP(XP, AP, XQ, AQ, px, pa, D0, D1, D2, D3, D4, D5, D6, D7)                               \
+  FC_HMM(0, 0, XP, AP); FC_PIN(); XQ[0] = FC_LDS16(px);         FC_PIN(); D0; FC_PIN();              \
+  FC_HMM(0, 1, XP, AP); FC_PIN(); AQ[0] = FC_LDS16(pa);         FC_PIN(); D1; FC_PIN();              \
+  FC_HMM(0, 2, XP, AP); FC_PIN(); XQ[1] = FC_LDS16(px + 4096);  FC_PIN(); D2; FC_PIN();              \
+  FC_HMM(0, 3, XP, AP); FC_PIN(); AQ[1] = FC_LDS16(pa + 4096);  FC_PIN(); D3; FC_PIN();              \
+  FC_HMM(1, 0, XP, AP); FC_PIN(); AQ[2] = FC_LDS16(pa + 8192);  FC_PIN(); D4; FC_PIN();              \
+  FC_HMM(1, 1, XP, AP); FC_PIN(); AQ[3] = FC_LDS16(pa + 12288); FC_PIN(); D5; FC_PIN();              \
+  FC_HMM(1, 2, XP, AP); FC_PIN(); D6; FC_PIN();                                                      \
+  FC_HMM(1, 3, XP, AP); FC_PIN(); D7; FC_PIN()
+#define FC_STEP_PLAIN(XP, AP, XQ, AQ, px, pa) \
+  FC_STEP(XP, AP, XQ, AQ, px, pa, FC_NONE, FC_NONE, FC_NONE, FC_NONE, FC_NONE, FC_NONE, FC_NONE, FC_NONE)
 
   // The barrier of stream stage g waits for the loads of stage g + 1; nothing is issued after them except, at a tile
   // change, the 16 fragment stores and 1 sum store of the finished tile and the scalar load of the new one
   // (kind 1: 18 per wave), or, for the first tile, the scalar load alone (kind 2).  S >= 2 keeps these episodes apart.
   int pend_kind = 2;
+  const bool early = wave < 4;
+  bool late_pending = false;
   int buf = 0;
   while (t < a.ntiles) {
     const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
@@ -217,17 +223,22 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
       {
         const char* px = ring + ((bx ^ 32u) ^ cs);
         const char* pa = ring + ((ba ^ 32u) ^ cs);
-        FC_STEP(x0, a0, x1, a1, px, pa);
+        // waves 4 .. 7 request their part of stage g + 1 here (into the other slot, retired by the previous barrier)
+        FC_STEP(x0, a0, x1, a1, px, pa, if (late_pending) FC_REQ_X(0, ns), if (late_pending) FC_REQ_A(0, ns),
+                if (late_pending) FC_REQ_X(1, ns), if (late_pending) FC_REQ_A(1, ns), if (late_pending) FC_REQ_X(2, ns),
+                if (late_pending) FC_REQ_A(2, ns), if (late_pending) FC_REQ_X(3, ns), if (late_pending) FC_REQ_A(3, ns));
+        if (late_pending) request_advance();
+        late_pending = false;
       }
       {
         const char* px = ring + ((bx ^ 64u) ^ cs);
         const char* pa = ring + ((ba ^ 64u) ^ cs);
-        FC_STEP(x1, a1, x0, a0, px, pa);
+        FC_STEP_PLAIN(x1, a1, x0, a0, px, pa);
       }
       {
         const char* px = ring + ((bx ^ 96u) ^ cs);
         const char* pa = ring + ((ba ^ 96u) ^ cs);
-        FC_STEP(x0, a0, x1, a1, px, pa);
+        FC_STEP_PLAIN(x0, a0, x1, a1, px, pa);
       }
       // stage g + 1 has landed for this wave; the barrier (which every wave reaches with its LDS reads complete)
       // makes that true for all waves and retires the current slot: nobody reads it after this point
@@ -239,19 +250,18 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
       FC_PIN();
       {
         // last step; meanwhile read the first step's operands of stage g + 1 and request stage g + 2 into the slot
-        // just retired
+        // just retired.  The two waves of a SIMD take turns: waves 0 .. 3 request now, waves 4 .. 7 during the next
+        // step, so a wave that queues behind the load unit always leaves its neighbour free to issue MFMAs - except
+        // before an epilogue, whose stores must stay behind the requests.
         const char* px = ring + (bx ^ ns);
         const char* pa = ring + (ba ^ ns);
-        FC_HMM(0, 0, x1, a1); FC_PIN(); x0[0] = FC_LDS16(px);         FC_PIN(); FC_REQ_X(0, cs); FC_PIN();
-        FC_HMM(0, 1, x1, a1); FC_PIN(); a0[0] = FC_LDS16(pa);         FC_PIN(); FC_REQ_A(0, cs); FC_PIN();
-        FC_HMM(0, 2, x1, a1); FC_PIN(); x0[1] = FC_LDS16(px + 4096);  FC_PIN(); FC_REQ_X(1, cs); FC_PIN();
-        FC_HMM(0, 3, x1, a1); FC_PIN(); a0[1] = FC_LDS16(pa + 4096);  FC_PIN(); FC_REQ_A(1, cs); FC_PIN();
-        FC_HMM(1, 0, x1, a1); FC_PIN(); a0[2] = FC_LDS16(pa + 8192);  FC_PIN(); FC_REQ_X(2, cs); FC_PIN();
-        FC_HMM(1, 1, x1, a1); FC_PIN(); a0[3] = FC_LDS16(pa + 12288); FC_PIN(); FC_REQ_A(2, cs); FC_PIN();
-        FC_HMM(1, 2, x1, a1); FC_PIN(); FC_REQ_X(3, cs); FC_PIN();
-        FC_HMM(1, 3, x1, a1); FC_PIN(); FC_REQ_A(3, cs); FC_PIN();
+        const bool now = early || (s + 1 == S);
+        FC_STEP(x1, a1, x0, a0, px, pa, if (now) FC_REQ_X(0, cs), if (now) FC_REQ_A(0, cs), if (now) FC_REQ_X(1, cs),
+                if (now) FC_REQ_A(1, cs), if (now) FC_REQ_X(2, cs), if (now) FC_REQ_A(2, cs), if (now) FC_REQ_X(3, cs),
+                if (now) FC_REQ_A(3, cs));
+        if (now) request_advance();
+        late_pending = !now;
       }
-      request_advance();
       const uint32_t tmp = cs; cs = ns; ns = tmp;
     }
     // exponentials, sums and fragment stores of this tile (16 stores per lane)

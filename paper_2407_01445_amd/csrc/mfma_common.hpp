@@ -15,12 +15,14 @@ typedef __attribute__((address_space(3))) v4s lds_v4s;
 constexpr int BK = 32;                       // contraction depth of one LDS stage
 constexpr int kOpBytes = 256 * BK * 2;       // one operand tile of a stage: 16 KiB
 constexpr int kStageBytes = 2 * kOpBytes;    // 32 KiB
-constexpr int kRingBytes = 4 * kStageBytes;  // 128 KiB
+constexpr int kRingBytes = 5 * kStageBytes;  // 160 KiB: all of the LDS of a compute unit
 
 #define FC_PIN() __builtin_amdgcn_sched_barrier(0)
 #define FC_WAIT_VMCNT0() __builtin_amdgcn_s_waitcnt(0x0f70)
 #define FC_WAIT_VMCNT8() __builtin_amdgcn_s_waitcnt(0x0f78)
 #define FC_WAIT_VMCNT16() __builtin_amdgcn_s_waitcnt(0x4f70)
+#define FC_WAIT_VMCNT20() __builtin_amdgcn_s_waitcnt(0x4f74)
+#define FC_WAIT_VMCNT24() __builtin_amdgcn_s_waitcnt(0x4f78)
 #define FC_WAIT_VMCNT34() __builtin_amdgcn_s_waitcnt(0x8f72)   // vmcnt = 34 = 0b100010: low bits 2, high bits 2
 
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
