@@ -1,10 +1,11 @@
 // bf16 MFMA kernels of the FCCO step for gfx950 (wave64, v_mfma_f32_32x32x16_bf16).
 //
-//  k_strips_bf16    S^T tile = contrasts x anchors^T from LDS-staged operands (256 x 256 per workgroup), then in
-//                   registers l = exp((s - s_ii)/tau) (Sec. 3), per-anchor sums of l and of (s - s_ii) l (Proc. 1
-//                   and the nabla_3 l sums of Eqs. 8-10), and l rounded to bf16 stored as the operand of the
-//                   gradient contraction.  The similarity matrix itself never reaches memory.  Anchors run along
-//                   lanes, so the sums are lane-local and every store is a contiguous 1 KiB per wavefront.
+//  k_strips_edge_bf16  the strip tiles with a ragged edge (whole tiles: k_strips_bf16 in kernels_strips.hip):
+//                   S^T tile = contrasts x anchors^T (256 x 256 per workgroup), then in registers
+//                   l = exp((s - s_ii)/tau) (Sec. 3), per-anchor sums of l and of (s - s_ii) l (Proc. 1 and the
+//                   nabla_3 l sums of Eqs. 8-10), and l rounded to bf16 stored as the operand of the gradient
+//                   contraction.  The similarity matrix itself never reaches memory.  Anchors run along lanes, so
+//                   the sums are lane-local and every store is a contiguous 1 KiB per wavefront.
 //  k_local_bf16     the local contrast-side operand of Eqs. 3 / 5 / 7: c_other[q] l_other(q, p_r) / c_own[r], written
 //                   behind the strip as extra contraction columns, so that one contraction yields
 //                   sum_j l(r,j) x_j + (1/c_r) sum_q c_q l(q,p_r) x_q.
@@ -20,9 +21,9 @@
 // MFMA layout facts used (32x32x16, wave64): lane l supplies row/column (l & 31) of its operand and 8 contraction
 // slots selected by (l >> 5); accumulator register v of lane l is D[8 (v >> 2) + 4 (l >> 5) + (v & 3)][l & 31].
 //
-// Main loop (interior tiles): a ring of four 32 KiB LDS slots, each one 32-deep stage of both operands, filled by
-// global_load_lds_dwordx4 (no VGPR staging) three stages ahead; one barrier per stage; LDS operand reads of the next
-// 16-deep step are issued between the MFMAs of the current one.  Tiles that touch a ragged edge use guarded
+// Main loop of the contraction (whole tiles): a ring of five 32 KiB LDS slots, each one 32-deep stage of both operands,
+// filled by global_load_lds_dwordx4 (no VGPR staging) four stages ahead; one barrier per stage; LDS operand reads of
+// the next 16-deep step are issued between the MFMAs of the current one.  Tiles that touch a ragged edge use guarded
 // register loads into the same LDS images, one stage at a time.
 #include "mfma_common.hpp"
 
