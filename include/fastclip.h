@@ -148,6 +148,10 @@ float fastclip_gamma_cosine(int64_t t, int64_t iters_per_epoch, int64_t decay_ep
 
 const char* fastclip_status_string(fastclip_status s);
 
+/* Text of the HIP error behind the most recent FASTCLIP_ERR_LAUNCH on the calling thread
+ * ("no error" if there was none).  The string is static; pure host function. */
+const char* fastclip_last_hip_error(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -47,6 +47,9 @@ def load(build_if_missing: bool = True):
             raise RuntimeError("libfastclip.so is not built: run __graft_entry__.build()")
         from .build import build
         build()
+    # torch ships its own HIP runtime; it has to be in the process before the library is, so that the library's
+    # kernels and torch's device pointers and streams belong to one and the same runtime
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     cfgp, bufp = C.POINTER(fastclip_config), C.POINTER(fastclip_buffers)
     lib.fastclip_workspace_bytes.restype = C.c_size_t
@@ -69,6 +72,8 @@ def load(build_if_missing: bool = True):
     lib.fastclip_gamma_cosine.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_float]
     lib.fastclip_status_string.restype = C.c_char_p
     lib.fastclip_status_string.argtypes = [C.c_int]
+    lib.fastclip_last_hip_error.restype = C.c_char_p
+    lib.fastclip_last_hip_error.argtypes = []
     _lib = lib
     return lib
 
@@ -76,7 +81,10 @@ def load(build_if_missing: bool = True):
 class FastclipError(RuntimeError):
     def __init__(self, status: int):
         self.status = status
-        super().__init__("fastclip: %s (status %d)" % (fastclip_status_string(status), status))
+        detail = ""
+        if status == ERR_LAUNCH:
+            detail = ": " + fastclip_last_hip_error()
+        super().__init__("fastclip: %s (status %d)%s" % (fastclip_status_string(status), status, detail))
 
 
 def make_config(*, version, emb_dtype, B, b, off, d, N, gamma, eps, rho=0.0, tau_grad_scale=1.0,
@@ -164,6 +172,10 @@ def fastclip_check_indices(idx, b, N, workspace, workspace_bytes=None, stream=No
 
 def fastclip_gamma_cosine(t, iters_per_epoch, decay_epochs, gamma_min) -> float:
     return float(load().fastclip_gamma_cosine(int(t), int(iters_per_epoch), int(decay_epochs), float(gamma_min)))
+
+
+def fastclip_last_hip_error() -> str:
+    return load().fastclip_last_hip_error().decode()
 
 
 def fastclip_status_string(status: int) -> str:

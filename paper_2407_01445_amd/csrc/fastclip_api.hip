@@ -10,6 +10,19 @@ namespace fc {
 
 static bool bad_float(float x) { return !(x == x) || isinf(x); }
 
+static thread_local hipError_t g_last_hip_error = hipSuccess;
+// Reads and clears the runtime's error state; remembers a failure for fastclip_last_hip_error.
+static fastclip_status launch_status() {
+  const hipError_t e = hipGetLastError();
+  if (e == hipSuccess) return FASTCLIP_OK;
+  g_last_hip_error = e;
+  return FASTCLIP_ERR_LAUNCH;
+}
+static fastclip_status hip_failed(hipError_t e) {
+  g_last_hip_error = e;
+  return FASTCLIP_ERR_LAUNCH;
+}
+
 fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
   if (!cfg) return FASTCLIP_ERR_NULL;
   if (cfg->struct_size != sizeof(fastclip_config) || cfg->reserved != 0) return FASTCLIP_ERR_SHAPE;
@@ -133,10 +146,11 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
     launch_state(c);                      mark(FASTCLIP_PHASE_STATE);
     launch_grad_f32(c);                   mark(FASTCLIP_PHASE_FINALIZE);
   }
-  fastclip_status rc = hipGetLastError() == hipSuccess ? FASTCLIP_OK : FASTCLIP_ERR_LAUNCH;
+  fastclip_status rc = launch_status();
   if (phase_ms) {
     for (int i = 0; i < FASTCLIP_N_PHASES; ++i) phase_ms[i] = 0.0f;
-    if (hipStreamSynchronize(c.s) != hipSuccess) rc = FASTCLIP_ERR_LAUNCH;
+    const hipError_t es = hipStreamSynchronize(c.s);
+    if (es != hipSuccess) rc = hip_failed(es);
     for (int i = 0; i + 1 < nev; ++i) {
       float ms = 0.0f;
       if (rc == FASTCLIP_OK && hipEventElapsedTime(&ms, ev[i], ev[i + 1]) == hipSuccess) phase_ms[phase_of[i]] += ms;
@@ -195,7 +209,7 @@ fastclip_status fastclip_state_update(const int64_t* idx, int64_t n, int64_t N, 
   (void)hipGetLastError();
   fc::launch_state_flat(idx, n, N, gamma, M, sum_img, sum_txt, u_img, u_txt, u_new_img, u_new_txt,
                         (hipStream_t)stream);
-  return hipGetLastError() == hipSuccess ? FASTCLIP_OK : FASTCLIP_ERR_LAUNCH;
+  return fc::launch_status();
 }
 
 static size_t table_slots(int64_t b) {
@@ -220,9 +234,11 @@ fastclip_status fastclip_check_indices(const int64_t* idx, int64_t b, int64_t N,
   (void)hipGetLastError();
   fc::launch_check_indices(idx, b, N, workspace, s);
   int flag = 0;
-  if (hipGetLastError() != hipSuccess) return FASTCLIP_ERR_LAUNCH;
-  if (hipMemcpyAsync(&flag, workspace, sizeof(int), hipMemcpyDeviceToHost, s) != hipSuccess) return FASTCLIP_ERR_LAUNCH;
-  if (hipStreamSynchronize(s) != hipSuccess) return FASTCLIP_ERR_LAUNCH;
+  if (fc::launch_status() != FASTCLIP_OK) return FASTCLIP_ERR_LAUNCH;
+  hipError_t e = hipMemcpyAsync(&flag, workspace, sizeof(int), hipMemcpyDeviceToHost, s);
+  if (e != hipSuccess) return fc::hip_failed(e);
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) return fc::hip_failed(e);
   return flag ? FASTCLIP_ERR_INDEX : FASTCLIP_OK;
 }
 
@@ -234,6 +250,8 @@ float fastclip_gamma_cosine(int64_t t, int64_t iters_per_epoch, int64_t decay_ep
   const double c = cos(M_PI * (double)epoch / (double)decay_epochs);
   return (float)(0.5 * (1.0 + c) * (1.0 - (double)gamma_min) + (double)gamma_min);
 }
+
+const char* fastclip_last_hip_error(void) { return hipGetErrorString(fc::g_last_hip_error); }
 
 const char* fastclip_status_string(fastclip_status s) {
   switch (s) {
