@@ -146,59 +146,74 @@ struct ContractTile {
   __device__ __forceinline__ bf16x8 read_a(const char* slot, int t, int kk) const {
     return *(const bf16x8*)(slot + (((wm * 4 + t) * 2 + kk) * 1024 + lane * 16));
   }
-  // slots e = 0..3 <-> rows 16 kk + 4 h + e, slots 4..7 <-> rows 16 kk + 8 + 4 h + (e - 4): two transposing reads,
-  // each taking 4 rows x 16 columns per group of 16 lanes (source lane s: row s / 4, columns 4 (s % 4) ..).
-  __device__ __forceinline__ bf16x8 read_b(const char* slot, int t, int kk) const {
+  // slots e = 0..3 <-> rows 16 kk + 4 h + e, slots 4..7 <-> rows 16 kk + 8 + 4 h + (e - 4): two transposing reads
+  // (half 0 / 1), each taking 4 rows x 16 columns per group of 16 lanes (source lane s: row s / 4, columns 4 (s % 4) ..).
+  __device__ __forceinline__ u32x2 read_b_half(const char* slot, int t, int kk, int half) const {
     const int h = lane >> 5, s = lane & 15;
     const int n = wn * 128 + t * 32 + ((lane >> 4) & 1) * 16 + 4 * (s & 3);   // first of 4 columns read by this lane
-    const int k = 16 * kk + 4 * h + (s >> 2);
+    const int k = 16 * kk + 8 * half + 4 * h + (s >> 2);
     const char* base = slot + kOpBytes + ((n & 7) << 1);
-    lds_v4s* p0 = (lds_v4s*)(uintptr_t)lds_addr(base + nt_off(k, n >> 3));
-    lds_v4s* p1 = (lds_v4s*)(uintptr_t)lds_addr(base + nt_off(k + 8, n >> 3));
-    const v4s lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p0);
-    const v4s hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(p1);
-    u32x4 r;
-    const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
-    r[0] = l2[0]; r[1] = l2[1]; r[2] = h2[0]; r[3] = h2[1];
-    return __builtin_bit_cast(bf16x8, r);
+    lds_v4s* p = (lds_v4s*)(uintptr_t)lds_addr(base + nt_off(k, n >> 3));
+    return __builtin_bit_cast(u32x2, __builtin_amdgcn_ds_read_tr16_b64_v4i16(p));
+  }
+  __device__ __forceinline__ bf16x8 read_b(const char* slot, int t, int kk) const {
+    return join_halves(read_b_half(slot, t, kk, 0), read_b_half(slot, t, kk, 1));
   }
 };
 
 #define FC_MM(ti, tj, A_, B_) acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A_[ti], B_[tj], acc[ti][tj], 0, 0, 0)
+// The same with the B operand held as the two halves that the transposing reads deliver.
+#define FC_MMH(ti, tj, A_, BL_, BH_) \
+  acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A_[ti], join_halves(BL_[tj], BH_[tj]), acc[ti][tj], 0, 0, 0)
 
 // One 32-deep stage of the ring: 16 MFMAs on the operands already in registers while the operands of the second
 // 16-deep step are read; then "stage s+1 has landed" (vmcnt) + barrier, which also retires the slot of stage s-1; then
-// 16 MFMAs while the first operands of stage s+1 are read.  The 8 wave loads of a stage x are spread over a whole
-// stage time, one per four MFMAs, so that the load unit sees a steady trickle instead of a burst that blocks the
-// wave's issue: the four A-operand loads in the second half of stage x-4 (DMAA, into the slot just retired), the four
-// B-operand loads in the first half of stage x-3 (DMAB).  cur / nxt / prv / pp: byte offsets of the slots of stages
-// s, s+1, s-1, s-2 in a ring of five.  WAIT: loads that may stay in flight at the barrier (those of stages s+2 and
-// s+3): 16, 8 or 0.
+// 16 MFMAs while the first operands of stage s+1 are read.  A lone wavefront per SIMD issues in order: whatever sits
+// between two MFMAs delays the second one once it takes longer than the first one runs (32 cycles), so the 4 + 8 LDS
+// reads and the 4 wave loads of a half stage are dealt out ONE per MFMA.  The 8 wave loads of a stage x are spread
+// over a whole stage time, so that the load unit sees a steady trickle instead of a burst: the four A-operand loads
+// in the second half of stage x-4 (DMAA, into the slot just retired), the four B-operand loads in the first half of
+// stage x-3 (DMAB).  cur / nxt / prv / pp: byte offsets of the slots of stages s, s+1, s-1, s-2 in a ring of five.
+// WAIT: loads that may stay in flight at the barrier (those of stages s+2 and s+3): 16, 8 or 0.
+// The barrier is the bare instruction: the LDS reads of the first half need not have returned (their slot is written
+// again only after the NEXT stage's barrier, and their consumers wait for them by themselves), so there is no
+// "wait for all LDS traffic" in front of it as __syncthreads() would put.
+// One MFMA followed by one other statement.
+#define FC_SLOT(ti, tj, AP, BLP, BHP, STMT) FC_MMH(ti, tj, AP, BLP, BHP); FC_PIN(); STMT; FC_PIN();
+// 16 MFMAs on operand set (AP, BLP, BHP) while the set (AQ, BLQ, BHQ) is read from slot `src`, step KQ, in the order in
+// which the following half stage consumes it (its MFMAs run over tj fastest), and D0 .. D3 are issued.
+#define FC_HALF(AP, BLP, BHP, AQ, BLQ, BHQ, src, KQ, RD, D0, D1, D2, D3)                                            \
+    FC_SLOT(0, 0, AP, BLP, BHP, if (RD) BLQ[0] = T.read_b_half(src, 0, KQ, 0))                                      \
+    FC_SLOT(0, 1, AP, BLP, BHP, if (RD) BHQ[0] = T.read_b_half(src, 0, KQ, 1))                                      \
+    FC_SLOT(0, 2, AP, BLP, BHP, if (RD) AQ[0] = T.read_a(src, 0, KQ))                                               \
+    FC_SLOT(0, 3, AP, BLP, BHP, D0)                                                                                 \
+    FC_SLOT(1, 0, AP, BLP, BHP, if (RD) BLQ[1] = T.read_b_half(src, 1, KQ, 0))                                      \
+    FC_SLOT(1, 1, AP, BLP, BHP, if (RD) BHQ[1] = T.read_b_half(src, 1, KQ, 1))                                      \
+    FC_SLOT(1, 2, AP, BLP, BHP, if (RD) BLQ[2] = T.read_b_half(src, 2, KQ, 0))                                      \
+    FC_SLOT(1, 3, AP, BLP, BHP, D1)                                                                                 \
+    FC_SLOT(2, 0, AP, BLP, BHP, if (RD) BHQ[2] = T.read_b_half(src, 2, KQ, 1))                                      \
+    FC_SLOT(2, 1, AP, BLP, BHP, if (RD) BLQ[3] = T.read_b_half(src, 3, KQ, 0))                                      \
+    FC_SLOT(2, 2, AP, BLP, BHP, if (RD) BHQ[3] = T.read_b_half(src, 3, KQ, 1))                                      \
+    FC_SLOT(2, 3, AP, BLP, BHP, D2)                                                                                 \
+    FC_SLOT(3, 0, AP, BLP, BHP, if (RD) AQ[1] = T.read_a(src, 1, KQ))                                               \
+    FC_SLOT(3, 1, AP, BLP, BHP, if (RD) AQ[2] = T.read_a(src, 2, KQ))                                               \
+    FC_SLOT(3, 2, AP, BLP, BHP, if (RD) AQ[3] = T.read_a(src, 3, KQ))                                               \
+    FC_SLOT(3, 3, AP, BLP, BHP, D3)
 #define FC_STAGE(T, MORE, DMAB, DMAA, WAIT)                                                                         \
   {                                                                                                                 \
     const char* sl = ring + cur;                                                                                    \
     const uint32_t bslot = ring_addr + pp;                                                                          \
-    FC_MM(0, 0, a0, b0); FC_MM(0, 1, a0, b0); FC_PIN(); a1[0] = T.read_a(sl, 0, 1); FC_PIN();                       \
-    FC_MM(0, 2, a0, b0); FC_MM(0, 3, a0, b0); FC_PIN(); b1[0] = T.read_b(sl, 0, 1); FC_PIN(); if (DMAB) T.dma(4, s0 + s + 3, bslot); FC_PIN(); \
-    FC_MM(1, 0, a0, b0); FC_MM(1, 1, a0, b0); FC_PIN(); a1[1] = T.read_a(sl, 1, 1); FC_PIN();                       \
-    FC_MM(1, 2, a0, b0); FC_MM(1, 3, a0, b0); FC_PIN(); b1[1] = T.read_b(sl, 1, 1); FC_PIN(); if (DMAB) T.dma(5, s0 + s + 3, bslot); FC_PIN(); \
-    FC_MM(2, 0, a0, b0); FC_MM(2, 1, a0, b0); FC_PIN(); a1[2] = T.read_a(sl, 2, 1); FC_PIN();                       \
-    FC_MM(2, 2, a0, b0); FC_MM(2, 3, a0, b0); FC_PIN(); b1[2] = T.read_b(sl, 2, 1); FC_PIN(); if (DMAB) T.dma(6, s0 + s + 3, bslot); FC_PIN(); \
-    FC_MM(3, 0, a0, b0); FC_MM(3, 1, a0, b0); FC_PIN(); a1[3] = T.read_a(sl, 3, 1); FC_PIN();                       \
-    FC_MM(3, 2, a0, b0); FC_MM(3, 3, a0, b0); FC_PIN(); b1[3] = T.read_b(sl, 3, 1); FC_PIN(); if (DMAB) T.dma(7, s0 + s + 3, bslot); FC_PIN(); \
+    FC_HALF(a0, bl0, bh0, a1, bl1, bh1, sl, 1, true, if (DMAB) T.dma(4, s0 + s + 3, bslot),                         \
+            if (DMAB) T.dma(5, s0 + s + 3, bslot), if (DMAB) T.dma(6, s0 + s + 3, bslot),                           \
+            if (DMAB) T.dma(7, s0 + s + 3, bslot))                                                                  \
     if (WAIT == 16) FC_WAIT_VMCNT16(); else if (WAIT == 8) FC_WAIT_VMCNT8(); else FC_WAIT_VMCNT0();                 \
-    __syncthreads();                                                                                                \
+    __builtin_amdgcn_s_barrier();                                                                                   \
     FC_PIN();                                                                                                       \
     const char* nx = ring + nxt;                                                                                    \
     const uint32_t aslot = ring_addr + prv;                                                                         \
-    FC_MM(0, 0, a1, b1); FC_MM(0, 1, a1, b1); FC_PIN(); if (MORE) a0[0] = T.read_a(nx, 0, 0); FC_PIN();             \
-    FC_MM(0, 2, a1, b1); FC_MM(0, 3, a1, b1); FC_PIN(); if (MORE) b0[0] = T.read_b(nx, 0, 0); FC_PIN(); if (DMAA) T.dma(0, s0 + s + 4, aslot); FC_PIN(); \
-    FC_MM(1, 0, a1, b1); FC_MM(1, 1, a1, b1); FC_PIN(); if (MORE) a0[1] = T.read_a(nx, 1, 0); FC_PIN();             \
-    FC_MM(1, 2, a1, b1); FC_MM(1, 3, a1, b1); FC_PIN(); if (MORE) b0[1] = T.read_b(nx, 1, 0); FC_PIN(); if (DMAA) T.dma(1, s0 + s + 4, aslot); FC_PIN(); \
-    FC_MM(2, 0, a1, b1); FC_MM(2, 1, a1, b1); FC_PIN(); if (MORE) a0[2] = T.read_a(nx, 2, 0); FC_PIN();             \
-    FC_MM(2, 2, a1, b1); FC_MM(2, 3, a1, b1); FC_PIN(); if (MORE) b0[2] = T.read_b(nx, 2, 0); FC_PIN(); if (DMAA) T.dma(2, s0 + s + 4, aslot); FC_PIN(); \
-    FC_MM(3, 0, a1, b1); FC_MM(3, 1, a1, b1); FC_PIN(); if (MORE) a0[3] = T.read_a(nx, 3, 0); FC_PIN();             \
-    FC_MM(3, 2, a1, b1); FC_MM(3, 3, a1, b1); FC_PIN(); if (MORE) b0[3] = T.read_b(nx, 3, 0); FC_PIN(); if (DMAA) T.dma(3, s0 + s + 4, aslot); FC_PIN(); \
+    FC_HALF(a1, bl1, bh1, a0, bl0, bh0, nx, 0, MORE, if (DMAA) T.dma(0, s0 + s + 4, aslot),                         \
+            if (DMAA) T.dma(1, s0 + s + 4, aslot), if (DMAA) T.dma(2, s0 + s + 4, aslot),                           \
+            if (DMAA) T.dma(3, s0 + s + 4, aslot))                                                                  \
     pp = prv; prv = cur; cur = nxt;                                                                                 \
     nxt = (nxt + (uint32_t)kStageBytes == (uint32_t)kRingBytes) ? 0u : nxt + (uint32_t)kStageBytes;                 \
     ++s;                                                                                                            \
@@ -227,9 +242,14 @@ __device__ __forceinline__ void ring_mainloop(f32x16 (&acc)[4][4], const Tile& T
   // stage 0 has landed; stages 1, 2 and (half or all of) 3 may be in flight
   if (S >= 5) FC_WAIT_VMCNT20(); else if (S == 4) FC_WAIT_VMCNT24(); else FC_WAIT_VMCNT0();
   __syncthreads();
-  bf16x8 a0[4], b0[4], a1[4], b1[4];
+  bf16x8 a0[4], a1[4];
+  u32x2 bl0[4], bh0[4], bl1[4], bh1[4];
 #pragma unroll
-  for (int t = 0; t < 4; ++t) { a0[t] = T.read_a(ring, t, 0); b0[t] = T.read_b(ring, t, 0); }
+  for (int t = 0; t < 4; ++t) {
+    a0[t] = T.read_a(ring, t, 0);
+    bl0[t] = T.read_b_half(ring, t, 0, 0);
+    bh0[t] = T.read_b_half(ring, t, 0, 1);
+  }
   uint32_t cur = 0u, nxt = (uint32_t)kStageBytes, prv = 4u * (uint32_t)kStageBytes, pp = 3u * (uint32_t)kStageBytes;
   int s = 0;
   while (s + 4 < S) FC_STAGE(T, true, true, true, 16)               // s = 0 .. S-5

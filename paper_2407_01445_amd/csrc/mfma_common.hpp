@@ -69,6 +69,10 @@ __device__ __forceinline__ float acc_read(float in_agpr) {
   asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(x) : "a"(in_agpr));
   return x;
 }
+__device__ __forceinline__ bf16x8 join_halves(u32x2 lo, u32x2 hi) {
+  const u32x4 r = {lo[0], lo[1], hi[0], hi[1]};
+  return __builtin_bit_cast(bf16x8, r);
+}
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
   typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
   bf16x2 p;
