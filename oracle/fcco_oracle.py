@@ -30,9 +30,14 @@ notes of this repository):
     replaced by g whatever gamma is;
   * the estimator uses u^{t+1} as a constant (no gradient through u) and the
     temperature(s) of the current call;
-  * one worker's estimator is normalised by its local batch size b; only the
+  * one worker's estimator is normalised by its local batch size b; only
+    gradients of local rows are produced.  Without gathered state only the
     loss terms of the local anchors enter (Eq. 2 in full and the i-in-B_k part
-    of Eq. 3), and only gradients of local rows are produced;
+    of Eq. 3).  With the gathered u^{t+1} of every global anchor (u_glob_*;
+    Alg. 1 line 8) Eq. 3 / 5 / 7 enters in full: every global anchor i, local
+    or not, has the local rows among its contrasts.  For individual
+    temperatures the remote anchors' tau_1, tau_2 are gathered the same way
+    (the paper's Eq. 7 uses tau_{1,i}, tau_{2,i} of the anchor i);
   * the scalar "loss" is the objective (GCL, RGCL, RGCL-g, or GCL without its
     leading tau for v0) with g(S_{i-}) replaced by u^{t+1} and the dataset
     average replaced by the local-batch average;
@@ -43,8 +48,11 @@ independent scalar evaluation, central finite differences of losses written
 straight from GCL / RGCL / RGCL-g, reduction to softmax cross-entropy
 (MBCL with eps = 1/M), hand-expanded B = 2 and B = 3 cases, invariants
 (u > 0, untouched state, permutation, image/text swap, Euler identity),
-the two-visit recurrence of Eq. 1, and the closed-form values of the gamma
-schedule.  Nothing here is "parity unpinned".
+the two-visit recurrence of Eq. 1, the closed-form values of the gamma
+schedule, and for the gathered-state mode the agreement of the workers' shares
+with the single-worker gradient of the same global batch plus finite
+differences of the all-anchor frozen-u surrogate.  Nothing here is "parity
+unpinned".
 """
 from __future__ import annotations
 
@@ -91,7 +99,8 @@ def ema_update(u_arr, idx, g, gamma):
 
 
 def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0.0,
-              tau=None, tau_img=None, tau_txt=None, tau_grad_scale=1.0):
+              tau=None, tau_img=None, tau_txt=None, tau_grad_scale=1.0,
+              u_glob_img=None, u_glob_txt=None, tau_glob_img=None, tau_glob_txt=None):
     """One FCCO step of worker k.  Updates u_img / u_txt IN PLACE at idx.
 
     img, txt   [B, d] global image / text embeddings (any float dtype; used as float64)
@@ -102,6 +111,12 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
                V1 (GCL, constant tau; Eqs. 2, 3)
                V2 (RGCL, per-sample tau_img/tau_txt [N]; Eqs. 6, 7, 9)
                V3 (RGCL-g, learnable global tau; Eqs. 2, 3, 10)
+    u_glob_img/txt  optional [B]: u^{t+1} of every row of the global batch as gathered from
+               all workers (Alg. 1 line 8); the entries of the local rows are ignored (this
+               call's own new values are used).  When given, the contrast-side estimator of
+               Eq. 3 / 5 / 7 runs over every global anchor instead of the local ones only.
+    tau_glob_img/txt  [B], V2 with u_glob_* only: tau_1, tau_2 of every row of the global
+               batch (entries of the local rows ignored).
     Returns a dict with g_img, g_txt, h_img, h_txt, u_new_img, u_new_txt, d_img,
     d_txt ([b, d]), loss, and d_tau (v0, v3) or d_tau_img, d_tau_txt ([b], v2).
     """
@@ -158,15 +173,47 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
     # d l2(i,j)/d e_{1,i} = -l2 e_{2,i} / tau, and the mirror images for e_{2,i}.
     d_img = c1[:, None] * (E1 @ txt - (M * g1)[:, None] * T_loc) - (c2 * M * g2)[:, None] * T_loc
     d_txt = c2[:, None] * (E2 @ img - (M * g2)[:, None] * I_loc) - (c1 * M * g1)[:, None] * I_loc
-    # Eq. 3 / 5 / 7 restricted to local anchors i: local row p is a contrast of the
-    # other local anchors r'.  l2(r', p) = exp((s_{p p'} - s_{p'p'}) / tau2_{r'}) moves image
-    # row p, l1(r', p) = exp((s_{p'p} - s_{p'p'}) / tau1_{r'}) moves text row p.
-    L2 = np.exp((S1[:, rows] - s_pp[None, :]) / tau2[None, :]) * c2[None, :]
-    L1 = np.exp((S2[:, rows] - s_pp[None, :]) / tau1[None, :]) * c1[None, :]
-    np.fill_diagonal(L2, 0.0)
-    np.fill_diagonal(L1, 0.0)
-    d_img += L2 @ T_loc
-    d_txt += L1 @ I_loc
+    if u_glob_img is None and u_glob_txt is None:
+        # Eq. 3 / 5 / 7 restricted to local anchors i: local row p is a contrast of the
+        # other local anchors r'.  l2(r', p) = exp((s_{p p'} - s_{p'p'}) / tau2_{r'}) moves image
+        # row p, l1(r', p) = exp((s_{p'p} - s_{p'p'}) / tau1_{r'}) moves text row p.
+        L2 = np.exp((S1[:, rows] - s_pp[None, :]) / tau2[None, :]) * c2[None, :]
+        L1 = np.exp((S2[:, rows] - s_pp[None, :]) / tau1[None, :]) * c1[None, :]
+        np.fill_diagonal(L2, 0.0)
+        np.fill_diagonal(L1, 0.0)
+        d_img += L2 @ T_loc
+        d_txt += L1 @ I_loc
+    else:
+        # Eq. 3 / 5 / 7 in full.  Anchor i runs over the whole global batch; its coefficient is
+        # kappa_i / (|B_k| |B_{i-}| (eps + u_i^{t+1})) with the u^{t+1} gathered from its worker
+        # (this call's own values for the local rows).  l2(i, p) = exp((s_{p i} - s_ii) / tau2_i)
+        # moves image row p towards/away from text row i; l1(i, p) = exp((s_{i p} - s_ii) / tau1_i)
+        # moves text row p along image row i.  The anchor itself is not among its contrasts.
+        s_all = np.einsum("ik,ik->i", img, txt)
+        u1_all = np.array(u_glob_img, dtype=np.float64)
+        u2_all = np.array(u_glob_txt, dtype=np.float64)
+        assert u1_all.shape == (B,) and u2_all.shape == (B,)
+        u1_all[rows], u2_all[rows] = u1, u2
+        if version == V2:
+            t1_all = np.array(tau_glob_img, dtype=np.float64)
+            t2_all = np.array(tau_glob_txt, dtype=np.float64)
+            assert t1_all.shape == (B,) and t2_all.shape == (B,)
+            t1_all[rows], t2_all[rows] = tau1, tau2
+        else:
+            t1_all = np.full(B, float(tau))
+            t2_all = np.full(B, float(tau))
+        c1_all = 1.0 / (b * M * (eps + u1_all))
+        c2_all = 1.0 / (b * M * (eps + u2_all))
+        if version == V0:
+            c1_all, c2_all = c1_all / t1_all, c2_all / t2_all
+        for r in range(b):
+            p = rows[r]
+            w2 = c2_all * np.exp((S1[r] - s_all) / t2_all)       # over anchors i: S1[r, i] = s_{p i}
+            w1 = c1_all * np.exp((S2[r] - s_all) / t1_all)       # S2[r, i] = s_{i p}
+            w2[p] = 0.0
+            w1[p] = 0.0
+            d_img[r] += w2 @ txt
+            d_txt[r] += w1 @ img
 
     out = dict(g_img=g1, g_txt=g2, h_img=h1, h_txt=h2, u_new_img=u1, u_new_txt=u2,
                d_img=d_img, d_txt=d_txt)

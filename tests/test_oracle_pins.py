@@ -405,3 +405,98 @@ def test_check_indices():
     assert not check_indices(np.array([3, 1, 3]), 4)
     assert not check_indices(np.array([4, 1]), 4)
     assert not check_indices(np.array([-1, 1]), 4)
+
+
+# --------------------------------------------- 8. gathered state: Eq. 3 / 5 / 7 over every global anchor
+def _split_problem(version, seed=91):
+    """A global batch of 12 pairs owned by 3 workers of 4, with history in u and distinct temperatures."""
+    B, K, d, N, eps, rho, tau, gamma = 12, 3, 4, 40, 1e-3, 6.0, 0.11, 0.35
+    img, txt = rand_problem(seed, B, d)
+    rng = np.random.default_rng(seed + 1)
+    idx_all = rng.choice(N, B, replace=False)
+    tau_img = rng.uniform(0.08, 0.2, N)
+    tau_txt = rng.uniform(0.08, 0.2, N)
+    u_img = rng.uniform(0.2, 3.0, N)
+    u_txt = rng.uniform(0.2, 3.0, N)
+    u_img[idx_all[5]] = 0.0                       # one first visit among the remote anchors of workers 0 and 2
+    return dict(B=B, K=K, b=B // K, d=d, N=N, eps=eps, rho=rho, tau=tau, gamma=gamma, img=img, txt=txt,
+                idx_all=idx_all, tau_img=tau_img, tau_txt=tau_txt, u_img=u_img, u_txt=u_txt, version=version)
+
+
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_gathered_state_shares_add_up_to_the_single_worker_gradient(version):
+    """Eq. 2 + Eq. 3 with every global anchor is the whole gradient of the global batch: worker k's
+    rows of the single-worker run (b = B, normalised by 1/B) equal b/B times worker k's share computed
+    with the gathered u^{t+1} (and tau) of all anchors."""
+    P = _split_problem(version)
+    B, b = P["B"], P["b"]
+    full, _, _ = run(version, P["img"], P["txt"], 0, B, P["idx_all"], P["N"], P["gamma"], P["eps"], P["rho"],
+                     tau=P["tau"], tau_img=P["tau_img"], tau_txt=P["tau_txt"], u_img=P["u_img"].copy(),
+                     u_txt=P["u_txt"].copy())
+    for k in range(P["K"]):
+        off = k * b
+        idx = P["idx_all"][off:off + b]
+        junk = np.full(b, 123.0)                  # the local entries of the gathered arrays must be ignored
+        ug1, ug2 = full["u_new_img"].copy(), full["u_new_txt"].copy()
+        tg1, tg2 = P["tau_img"][P["idx_all"]].copy(), P["tau_txt"][P["idx_all"]].copy()
+        for arr in (ug1, ug2, tg1, tg2):
+            arr[off:off + b] = junk
+        share = fcco_step(P["img"], P["txt"], off, b, idx, P["u_img"].copy(), P["u_txt"].copy(), version=version,
+                          gamma=P["gamma"], eps=P["eps"], rho=P["rho"], tau=P["tau"], tau_img=P["tau_img"],
+                          tau_txt=P["tau_txt"], u_glob_img=ug1, u_glob_txt=ug2,
+                          tau_glob_img=tg1 if version == V2 else None, tau_glob_txt=tg2 if version == V2 else None)
+        np.testing.assert_allclose(share["u_new_img"], full["u_new_img"][off:off + b], rtol=1e-13)
+        np.testing.assert_allclose(share["d_img"] * b / B, full["d_img"][off:off + b], rtol=1e-10, atol=1e-14)
+        np.testing.assert_allclose(share["d_txt"] * b / B, full["d_txt"][off:off + b], rtol=1e-10, atol=1e-14)
+        # and the share without gathered state is a different (smaller) estimator
+        local_only = fcco_step(P["img"], P["txt"], off, b, idx, P["u_img"].copy(), P["u_txt"].copy(),
+                               version=version, gamma=P["gamma"], eps=P["eps"], rho=P["rho"], tau=P["tau"],
+                               tau_img=P["tau_img"], tau_txt=P["tau_txt"])
+        assert np.max(np.abs(local_only["d_img"] - share["d_img"])) > 1e-3 * np.max(np.abs(share["d_img"]))
+
+
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_gathered_state_gradient_is_the_all_anchor_frozen_u_surrogate(version):
+    """Central differences of (1/b) sum over ALL global anchors i of kappa_i [g1_i/(eps+u1_i) + g2_i/(eps+u2_i)]
+    with u held at the gathered values, with respect to the local rows (Eqs. 2-7 with u constant)."""
+    P = _split_problem(version, seed=17)
+    B, b, off = P["B"], P["b"], 4
+    idx = P["idx_all"][off:off + b]
+    rng = np.random.default_rng(3)
+    ug1, ug2 = rng.uniform(0.3, 2.0, B), rng.uniform(0.3, 2.0, B)       # what the other workers report
+    tg1, tg2 = P["tau_img"][P["idx_all"]], P["tau_txt"][P["idx_all"]]
+    out = fcco_step(P["img"], P["txt"], off, b, idx, P["u_img"].copy(), P["u_txt"].copy(), version=version,
+                    gamma=P["gamma"], eps=P["eps"], rho=P["rho"], tau=P["tau"], tau_img=P["tau_img"],
+                    tau_txt=P["tau_txt"], u_glob_img=ug1, u_glob_txt=ug2,
+                    tau_glob_img=tg1 if version == V2 else None, tau_glob_txt=tg2 if version == V2 else None)
+    u1, u2 = ug1.copy(), ug2.copy()
+    u1[off:off + b], u2[off:off + b] = out["u_new_img"], out["u_new_txt"]
+    img, txt = P["img"], P["txt"]
+
+    def surrogate():
+        total = 0.0
+        for i in range(B):
+            t1 = P["tau"] if version != V2 else tg1[i]
+            t2 = P["tau"] if version != V2 else tg2[i]
+            g1, g2 = g_by_definition(img, txt, i, t1, t2)
+            k1 = 1.0 if version == V0 else t1
+            k2 = 1.0 if version == V0 else t2
+            total += k1 * g1 / (P["eps"] + u1[i]) + k2 * g2 / (P["eps"] + u2[i])
+        return total / b
+
+    rows = list(range(off, off + b))
+    np.testing.assert_allclose(out["d_img"], fd_rows(surrogate, img, rows), rtol=2e-6, atol=1e-9)
+    np.testing.assert_allclose(out["d_txt"], fd_rows(surrogate, txt, rows), rtol=2e-6, atol=1e-9)
+
+
+def test_gathered_state_with_b_equal_B_changes_nothing():
+    """With a single worker every anchor is local: the gathered arrays are ignored entirely."""
+    P = _split_problem(V3, seed=5)
+    B = P["B"]
+    a, _, _ = run(V3, P["img"], P["txt"], 0, B, P["idx_all"], P["N"], P["gamma"], P["eps"], P["rho"], tau=P["tau"],
+                  u_img=P["u_img"].copy(), u_txt=P["u_txt"].copy())
+    c = fcco_step(P["img"], P["txt"], 0, B, P["idx_all"], P["u_img"].copy(), P["u_txt"].copy(), version=V3,
+                  gamma=P["gamma"], eps=P["eps"], rho=P["rho"], tau=P["tau"], u_glob_img=np.full(B, 7.0),
+                  u_glob_txt=np.full(B, 9.0))
+    np.testing.assert_allclose(c["d_img"], a["d_img"], rtol=1e-12, atol=1e-16)
+    np.testing.assert_allclose(c["d_txt"], a["d_txt"], rtol=1e-12, atol=1e-16)
