@@ -33,7 +33,7 @@ extern "C" {
 typedef enum {
   FASTCLIP_OK = 0,
   FASTCLIP_ERR_NULL = 1,        /* a required pointer is NULL */
-  FASTCLIP_ERR_SHAPE = 2,       /* B<2, b<1, off<0, off+b>B, d<1, ld<d, N<1, bad struct_size */
+  FASTCLIP_ERR_SHAPE = 2,       /* B<2, b<1, off<0, off+b>B, d<1, ld<d, N<1, bad struct_size, unknown flag */
   FASTCLIP_ERR_VALUE = 3,       /* gamma not in (0,1], eps<0, NaN scalar, unknown version or dtype */
   FASTCLIP_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than fastclip_workspace_bytes() */
   FASTCLIP_ERR_UNSUPPORTED = 5, /* bf16 path: d or a row stride not a multiple of 8, a matrix base not
@@ -55,11 +55,22 @@ typedef enum { FASTCLIP_V0 = 0, FASTCLIP_V1 = 1, FASTCLIP_V2 = 2, FASTCLIP_V3 = 
  * where they are operands of the gradient contractions). */
 typedef enum { FASTCLIP_F32 = 0, FASTCLIP_BF16 = 1 } fastclip_dtype;
 
+/* fastclip_config.flags.
+ * FASTCLIP_GATHERED_STATE: the caller supplies u^{t+1} of EVERY row of the global batch as
+ * gathered from all workers (Alg. 1 line 8; u_glob_img / u_glob_txt, and for V2 the rows'
+ * temperatures tau_glob_img / tau_glob_txt).  The contrast-side estimator (Eq. 3, 5, 7) then
+ * runs over every global anchor i, so that d_img / d_txt are worker k's complete
+ * G_{w,a,k} + G_{w,b,k} with respect to its rows; without the flag only the anchors i in B_k
+ * enter it.  A worker obtains the arrays by running the step of its own anchors first
+ * (u_new_img / u_new_txt) and gathering; on a single GPU holding the whole batch (b == B) the
+ * flag changes nothing and the arrays are not read. */
+#define FASTCLIP_GATHERED_STATE 1
+
 typedef struct {
   uint32_t struct_size;      /* sizeof(fastclip_config) */
   int32_t  version;          /* fastclip_version_t */
   int32_t  emb_dtype;        /* fastclip_dtype */
-  int32_t  reserved;         /* must be 0 */
+  int32_t  flags;            /* 0, or FASTCLIP_GATHERED_STATE; any other bit is an error */
   int64_t  B, b, off, d;     /* global rows, local anchors, first local row, embedding width */
   int64_t  ld_img, ld_txt;   /* row strides of img_glob / txt_glob in elements, >= d */
   int64_t  N;                /* length of the state arrays */
@@ -90,6 +101,13 @@ typedef struct {
   float*         u_new_img;  /* [b] out, optional: u_1^{t+1} of the local anchors in batch order
                                 (what a multi-worker caller would All_Gather, Alg. 1 line 8) */
   float*         u_new_txt;  /* [b] out, optional */
+  const float*   u_glob_img; /* [B] FASTCLIP_GATHERED_STATE: u_1^{t+1} of every global row, > 0 (or eps > 0);
+                                the entries of the local rows off .. off+b-1 are ignored (this call's own
+                                new values are used).  Never written */
+  const float*   u_glob_txt; /* [B] likewise u_2^{t+1} */
+  const float*   tau_glob_img; /* [B] FASTCLIP_GATHERED_STATE with V2: tau_1 of every global row (local entries
+                                  ignored); NULL otherwise */
+  const float*   tau_glob_txt; /* [B] likewise tau_2 */
 } fastclip_buffers;
 
 /* Bytes of device workspace fastclip_step needs for this configuration; 0 if the

@@ -14,20 +14,22 @@ LIB_PATH = os.path.join(_PKG, "libfastclip.so")
 
 OK, ERR_NULL, ERR_SHAPE, ERR_VALUE, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_INDEX = range(8)
 V0, V1, V2, V3 = 0, 1, 2, 3
+GATHERED_STATE = 1
 F32, BF16 = 0, 1
 N_PHASES = 8
 
 
 class fastclip_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("version", C.c_int32), ("emb_dtype", C.c_int32),
-                ("reserved", C.c_int32),
+                ("flags", C.c_int32),
                 ("B", C.c_int64), ("b", C.c_int64), ("off", C.c_int64), ("d", C.c_int64),
                 ("ld_img", C.c_int64), ("ld_txt", C.c_int64), ("N", C.c_int64),
                 ("gamma", C.c_float), ("eps", C.c_float), ("rho", C.c_float), ("tau_grad_scale", C.c_float)]
 
 
 _BUF_FIELDS = ["img_glob", "txt_glob", "idx", "u_img", "u_txt", "tau", "tau_img", "tau_txt", "d_img", "d_txt",
-               "loss", "d_tau", "d_tau_img", "d_tau_txt", "g_img", "g_txt", "u_new_img", "u_new_txt"]
+               "loss", "d_tau", "d_tau_img", "d_tau_txt", "g_img", "g_txt", "u_new_img", "u_new_txt",
+               "u_glob_img", "u_glob_txt", "tau_glob_img", "tau_glob_txt"]
 
 
 class fastclip_buffers(C.Structure):
@@ -88,8 +90,8 @@ class FastclipError(RuntimeError):
 
 
 def make_config(*, version, emb_dtype, B, b, off, d, N, gamma, eps, rho=0.0, tau_grad_scale=1.0,
-                ld_img=None, ld_txt=None) -> fastclip_config:
-    return fastclip_config(C.sizeof(fastclip_config), int(version), int(emb_dtype), 0, int(B), int(b), int(off),
+                ld_img=None, ld_txt=None, flags=0) -> fastclip_config:
+    return fastclip_config(C.sizeof(fastclip_config), int(version), int(emb_dtype), int(flags), int(B), int(b), int(off),
                            int(d), int(d if ld_img is None else ld_img), int(d if ld_txt is None else ld_txt),
                            int(N), float(gamma), float(eps), float(rho), float(tau_grad_scale))
 

@@ -25,7 +25,7 @@ static fastclip_status hip_failed(hipError_t e) {
 
 fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
   if (!cfg) return FASTCLIP_ERR_NULL;
-  if (cfg->struct_size != sizeof(fastclip_config) || cfg->reserved != 0) return FASTCLIP_ERR_SHAPE;
+  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~FASTCLIP_GATHERED_STATE)) return FASTCLIP_ERR_SHAPE;
   if (cfg->B < 2 || cfg->b < 1 || cfg->off < 0 || cfg->off + cfg->b > cfg->B || cfg->d < 1 ||
       cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1)
     return FASTCLIP_ERR_SHAPE;
@@ -55,6 +55,10 @@ fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* buf
       if (!bufs->tau) return FASTCLIP_ERR_NULL;
       if ((cfg->version == FASTCLIP_V0 || cfg->version == FASTCLIP_V3) && !bufs->d_tau) return FASTCLIP_ERR_NULL;
     }
+    if (cfg->flags & FASTCLIP_GATHERED_STATE) {
+      if (!bufs->u_glob_img || !bufs->u_glob_txt) return FASTCLIP_ERR_NULL;
+      if (cfg->version == FASTCLIP_V2 && (!bufs->tau_glob_img || !bufs->tau_glob_txt)) return FASTCLIP_ERR_NULL;
+    }
     if (cfg->emb_dtype == FASTCLIP_BF16 &&
         (((uintptr_t)bufs->img_glob & 15) || ((uintptr_t)bufs->txt_glob & 15)))
       return FASTCLIP_ERR_UNSUPPORTED;
@@ -68,6 +72,8 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   L->B = cfg.B; L->b = cfg.b; L->off = cfg.off; L->d = cfg.d; L->N = cfg.N;
   L->bf16 = cfg.emb_dtype == FASTCLIP_BF16;
   L->bstride = (int64_t)round_up((size_t)cfg.b, 64);
+  L->gathered = (cfg.flags & FASTCLIP_GATHERED_STATE) && cfg.b < cfg.B;
+  L->ncol = (int64_t)round_up((size_t)cfg.B, kTileContrasts);
   size_t at = 0;
   auto take = [&](size_t bytes) { size_t o = at; at += round_up(bytes, 256); return o; };
   const size_t fb = sizeof(float) * (size_t)L->bstride;
@@ -107,6 +113,17 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   } else {
     for (int s = 0; s < 2; ++s) L->E[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
   }
+  if (L->gathered) {
+    L->colp = take(sizeof(float) * 2 * 4 * (size_t)L->ncol);
+    if (L->bf16) {
+      const size_t rows = round_up((size_t)cfg.b, 256);
+      for (int s = 0; s < 2; ++s) L->F[s] = take(esz * rows * (size_t)L->ldE);
+      for (int s = 0; s < 2; ++s)
+        L->OpartF[s] = take(sizeof(float) * (size_t)L->nsplit * (size_t)cfg.b * (size_t)cfg.d);
+    } else {
+      for (int s = 0; s < 2; ++s) L->F[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
+    }
+  }
   L->total = at;
 }
 
@@ -134,7 +151,9 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
     if (phase >= 0) { (void)hipEventCreate(&ev[nev]); (void)hipEventRecord(ev[nev], c.s); phase_of[nev - 1] = phase; ++nev; }
   };
   mark(-1);
-  launch_prep(c);                         mark(FASTCLIP_PHASE_PREP);
+  launch_prep(c);
+  if (c.L.gathered) launch_prep_cols(c);
+  mark(FASTCLIP_PHASE_PREP);
   if (c.L.bf16) {
     launch_strips_bf16(c);                mark(FASTCLIP_PHASE_STRIPS);
     launch_state(c);                      mark(FASTCLIP_PHASE_STATE);

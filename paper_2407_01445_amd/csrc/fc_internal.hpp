@@ -27,12 +27,21 @@ struct Layout {
   int nsplit;        // split of the contraction over its column range
   int64_t kslice;    // 32-deep stages per split
   int nstate_blocks; // blocks of the state kernel (one scalar partial each)
+  int gathered;      // 1: contrast-side estimator over every global anchor (FASTCLIP_GATHERED_STATE and b < B)
+  int64_t ncol;      // gathered: entries per column-parameter array (B rounded up to whole 256-column tiles)
   size_t diag, tau1, tau2, k1, k2;   // float[bstride]
   size_t sums;                       // float[4][nparts][bstride]: sum e1, sum x1 e1, sum e2, sum x2 e2
   size_t c1, c2, dcoef;              // float[bstride]
   size_t red;                        // float[nstate_blocks][2]
   size_t E[2];                       // fp32 path: float [b][ldE]; MFMA path: fragment-ordered bf16 strips
   size_t Opart[2];                   // float [nsplit][b][d]   (MFMA path)
+  // gathered: per global row j (= contrast column of the strips) and side s, in tiles of 256 columns
+  // [s][tile][4][256]: log2(e)/tau_j, s_jj log2(e)/tau_j, c_j (0 for local rows and beyond B), unused.
+  // Side 0 describes the text anchors j (l2(j, .), weights of d_img), side 1 the image anchors (l1(j, .), d_txt).
+  size_t colp;
+  size_t F[2];                       // gathered: the second stored strip c_j l(j, p_r), same form as E without
+                                     // the local-anchor columns
+  size_t OpartF[2];                  // float [nsplit][b][d]   (MFMA path, gathered)
   size_t total;
 };
 
@@ -50,6 +59,7 @@ struct StepCtx {
 };
 
 void launch_prep(const StepCtx& c);            // s_ii, temperature gather / broadcast
+void launch_prep_cols(const StepCtx& c);       // gathered: s_jj, temperature and coefficient of every global anchor
 void launch_strips_f32(const StepCtx& c);      // accuracy path: exp strips + row sums
 void launch_strips_bf16(const StepCtx& c);     // MFMA path: exp strips + row sums
 void launch_state(const StepCtx& c);           // Eq. 1, coefficients, scalar partials

@@ -296,6 +296,9 @@ __device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)
   // fragment (ab, cb) of this lane: E + ((ab nCB + cb) 64 + lane) 8; ab and cb are wave-uniform
   const int64_t ab0 = (a0 + wc * 128) >> 5, cb0 = (c0 + wr * 128) >> 4;
   const int B = (int)a.B, b = (int)a.b, off = (int)a.off;   // all below 2^24
+  // gathered state: column parameters of this tile (log2(e)/tau_j, s_jj log2(e)/tau_j, c_j), second strip F
+  const float* __restrict__ colp = a.colp ? a.colp + ((int64_t)strip * a.nCT + (c0 >> 8)) * 1024 : nullptr;
+  bf16_t* __restrict__ F = a.F[strip];
 #pragma unroll
   for (int tj = 0; tj < 4; ++tj) {
     const int al = wc * 128 + tj * 32 + lr;
@@ -308,14 +311,31 @@ __device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)
     for (int ti = 0; ti < 4; ++ti) {
       const int crow = (int)c0 + wr * 128 + ti * 32 + 4 * hk;
       // groups of 4 accumulators (v = 4 g + q <-> contrast crow + 8 g + q), pinned apart to keep live ranges short
-      uint32_t pk[8];
+      uint32_t pk[8], pf[8];
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        float t[4], e[4];
+        float sv[4], t[4], e[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) t[q] = fmaf(acc_read(acc[ti][tj][4 * g + q]), kk, -dk);
+        for (int q = 0; q < 4; ++q) sv[q] = acc_read(acc[ti][tj][4 * g + q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t[q] = fmaf(sv[q], kk, -dk);
 #pragma unroll
         for (int q = 0; q < 4; ++q) e[q] = __builtin_amdgcn_exp2f(t[q]);
+        if (colp) {   // wave-uniform
+          const int cl = wr * 128 + ti * 32 + 4 * hk + 8 * g;   // column inside the tile, multiple of 4
+          const float4 ck = *(const float4*)(colp + cl), cd = *(const float4*)(colp + 256 + cl),
+                       cc = *(const float4*)(colp + 512 + cl);
+          const float ckq[4] = {ck.x, ck.y, ck.z, ck.w}, cdq[4] = {cd.x, cd.y, cd.z, cd.w},
+                      ccq[4] = {cc.x, cc.y, cc.z, cc.w};
+          float f[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            f[q] = ccq[q] * __builtin_amdgcn_exp2f(fmaf(sv[q], ckq[q], -cdq[q]));
+            if (GUARD) f[q] = anchor < b ? f[q] : 0.f;
+          }
+          pf[2 * g] = pack_bf16x2(f[0], f[1]);
+          pf[2 * g + 1] = pack_bf16x2(f[2], f[3]);
+        }
         if (GUARD) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
@@ -339,6 +359,10 @@ __device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)
         bf16_t* frag = E + ((ab0 + tj) * a.nCB + cb) * 512;   // wave-uniform
         const u32x4 w = {pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]};
         if (!GUARD || 16 * cb < a.ldE) *(u32x4*)(frag + lane * 8) = w;
+        if (colp && (!GUARD || 16 * cb < a.ldE)) {
+          const u32x4 wf = {pf[4 * j], pf[4 * j + 1], pf[4 * j + 2], pf[4 * j + 3]};
+          *(u32x4*)(F + (((ab0 + tj) * a.nCBF + cb) * 64 + lane) * 8) = wf;
+        }
       }
       FC_PIN();
     }
@@ -409,6 +433,10 @@ void launch_strips_bf16(const StepCtx& c) {
   a.nAT = (int)((L.b + 255) / 256);
   a.nCT = (int)((L.B + 255) / 256);
   a.ntiles = 2 * a.nAT * a.nCT;
+  a.colp = L.gathered ? (const float*)(c.ws + L.colp) : nullptr;
+  a.F[0] = L.gathered ? (bf16_t*)(c.ws + L.F[0]) : nullptr;
+  a.F[1] = L.gathered ? (bf16_t*)(c.ws + L.F[1]) : nullptr;
+  a.nCBF = L.ldE / 16;
   const bool any_interior = L.b >= 256 && L.B >= 256 && L.d % 64 == 0 && L.d >= 128;
   const bool any_edge = (L.b % 256) || (L.B % 256) || !any_interior;
   if (any_interior) launch_strips_interior_bf16(a, c.s);
@@ -485,17 +513,20 @@ void launch_local_bf16(const StepCtx& c) {
 
 // ----------------------------------------------------------------------------------------------------------------
 struct ContractJob {
-  const bf16_t* E;    // Efrag of this strip
+  const bf16_t* E;    // fragment-ordered strip: l of the local anchors (+ local operand columns), or the gathered-state
+                      // strip of remote anchors' weights
   const bf16_t* X;    // the matrix whose rows the strip weights: texts for strip 0, images for strip 1
   float* C;           // [nsplit][M][ldc]
   int64_t ldx, ldc;
   size_t split_stride;
+  int64_t nCB;        // column blocks (of 16) per anchor block of E
+  int stages, slice;  // 32-deep stages in all; stages per split
+  int all_rows_valid; // no zero rows inside the column range (B == ldE, and b == ldW where E has local columns)
 };
 struct ContractArgs {
-  ContractJob job[2];
-  int64_t nCB, M, N, B, bloc, off, ldE;
-  int stages, slice, nsplit, tiles_m, tiles_n;   // stages: total 32-deep stages; slice: stages per split
-  int all_rows_valid;                            // B == ldE and b == ldW: no zero rows inside the column range
+  ContractJob job[4];   // 0, 1: the two strips; 2, 3: their gathered-state strips (njobs == 4)
+  int64_t M, N, B, bloc, off, ldE;
+  int nsplit, tiles_m, tiles_n;
 };
 
 __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
@@ -510,15 +541,15 @@ __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
   const int split = local % g.nsplit;            // consecutive ids -> different XCDs -> different column slices
   const int tile = local / g.nsplit;
   const int64_t m0 = (int64_t)(tile % g.tiles_m) * 256, n0 = (int64_t)(tile / g.tiles_m) * 256;
-  const int s0 = split * g.slice;
-  const int S = (s0 + g.slice <= g.stages ? g.slice : g.stages - s0);
+  const int s0 = split * J.slice;
+  const int S = (s0 + J.slice <= J.stages ? J.slice : J.stages - s0);
 
   f32x16 acc[4][4];
   zero_acc(acc);
   if (S > 0) {
     ContractTile T;
-    T.setup(J.E, g.nCB, m0 >> 5, J.X, J.ldx, n0, g.N, g.B, g.bloc, g.off, g.ldE, tid);
-    if (g.all_rows_valid && n0 + 256 <= g.N) {
+    T.setup(J.E, J.nCB, m0 >> 5, J.X, J.ldx, n0, g.N, g.B, g.bloc, g.off, g.ldE, tid);
+    if (J.all_rows_valid && n0 + 256 <= g.N) {
       ring_prologue(T, ring_addr, s0, S);
       ring_mainloop(acc, T, ring, ring_addr, s0, S);
     } else {
@@ -548,23 +579,28 @@ __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
 void launch_contract_bf16(const StepCtx& c) {
   const Layout& L = c.L;
   ContractArgs g;
-  for (int s = 0; s < 2; ++s) {
-    g.job[s].E = (const bf16_t*)(c.ws + L.E[s]);
-    g.job[s].X = (const bf16_t*)(s == 0 ? c.buf.txt_glob : c.buf.img_glob);
-    g.job[s].ldx = s == 0 ? c.cfg.ld_txt : c.cfg.ld_img;
-    g.job[s].C = (float*)(c.ws + L.Opart[s]);
-    g.job[s].ldc = L.d;
-    g.job[s].split_stride = (size_t)L.b * (size_t)L.d;
+  const int njobs = L.gathered ? 4 : 2;
+  for (int j = 0; j < njobs; ++j) {
+    const int s = j & 1;
+    const bool rem = j >= 2;
+    ContractJob& J = g.job[j];
+    J.E = (const bf16_t*)(c.ws + (rem ? L.F[s] : L.E[s]));
+    J.X = (const bf16_t*)(s == 0 ? c.buf.txt_glob : c.buf.img_glob);
+    J.ldx = s == 0 ? c.cfg.ld_txt : c.cfg.ld_img;
+    J.C = (float*)(c.ws + (rem ? L.OpartF[s] : L.Opart[s]));
+    J.ldc = L.d;
+    J.split_stride = (size_t)L.b * (size_t)L.d;
+    J.nCB = (rem ? L.ldE : L.ldE + L.ldW) / 16;
+    J.stages = (int)((rem ? L.ldE : L.ldE + L.ldW) / BK);
+    J.slice = rem ? (int)((J.stages + L.nsplit - 1) / L.nsplit) : (int)L.kslice;
+    J.all_rows_valid = (L.B == L.ldE) && (rem || L.b == L.ldW);
   }
-  g.nCB = (L.ldE + L.ldW) / 16;
+  for (int j = njobs; j < 4; ++j) g.job[j] = g.job[0];
   g.M = L.b; g.N = L.d; g.B = L.B; g.bloc = L.b; g.off = L.off; g.ldE = L.ldE;
-  g.stages = (int)((L.ldE + L.ldW) / BK);
-  g.slice = (int)L.kslice;
   g.nsplit = L.nsplit;
   g.tiles_m = (int)((L.b + 255) / 256);
   g.tiles_n = (int)((L.d + 255) / 256);
-  g.all_rows_valid = (L.B == L.ldE) && (L.b == L.ldW);
-  const unsigned grid = 2u * (unsigned)(g.nsplit * g.tiles_m * g.tiles_n);
+  const unsigned grid = (unsigned)njobs * (unsigned)(g.nsplit * g.tiles_m * g.tiles_n);
   hipLaunchKernelGGL(k_contract_bf16, dim3(grid), dim3(256), 0, c.s, g);
 }
 

@@ -96,6 +96,72 @@ void launch_prep(const StepCtx& c) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Gathered state (Alg. 1 line 8; Eqs. 3 / 5 / 7 over every global anchor): one wavefront per global row j.
+// Anchor j contributes c_j l2(j, p) txt_j to the image gradient of a local row p and c_j l1(j, p) img_j to its text
+// gradient, with l2(j, p) = exp((s_pj - s_jj) / tau2_j), l1(j, p) = exp((s_jp - s_jj) / tau1_j) and
+// c_j = kappa_j / (|B_k| |B_j-| (eps + u_j^{t+1})): the strips already form s_pj and s_jp, so all they need per
+// column j is log2(e)/tau_j, s_jj log2(e)/tau_j and c_j.  Local rows get c = 0 (their u^{t+1} is only known after
+// the state phase; they go through the local operand columns), and so do the padding columns beyond B.
+template <typename T>
+__global__ void __launch_bounds__(256) k_prep_cols(const T* __restrict__ img, const T* __restrict__ txt, int64_t ld_img,
+                                                   int64_t ld_txt, int64_t B, int64_t ncol, int64_t off, int64_t b,
+                                                   int64_t d, const float* __restrict__ tau,
+                                                   const float* __restrict__ tau_glob_img,
+                                                   const float* __restrict__ tau_glob_txt,
+                                                   const float* __restrict__ u_glob_img,
+                                                   const float* __restrict__ u_glob_txt, int version, float eps,
+                                                   float bm, float* __restrict__ colp) {
+  const int lane = threadIdx.x & 63;
+  const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (j >= ncol) return;
+  float k1 = 0.f, k2 = 0.f, d1 = 0.f, d2 = 0.f, c1 = 0.f, c2 = 0.f;
+  const bool remote = j < B && (j < off || j >= off + b);
+  if (remote) {                                  // wave-uniform
+    float t1 = 0.f, t2 = 0.f, u1 = 0.f, u2 = 0.f;
+    if (lane == 0) {
+      if (version == FASTCLIP_V2) { t1 = tau_glob_img[j]; t2 = tau_glob_txt[j]; }
+      else t1 = t2 = tau[0];
+      u1 = u_glob_img[j];
+      u2 = u_glob_txt[j];
+    }
+    const double s_jj = wave_sum(row_dot(img + j * ld_img, txt + j * ld_txt, d, lane));
+    if (lane == 0) {
+      k1 = kLog2e / t1;
+      k2 = kLog2e / t2;
+      d1 = (float)(s_jj * (double)k1);
+      d2 = (float)(s_jj * (double)k2);
+      c1 = 1.0f / (bm * (eps + u1));
+      c2 = 1.0f / (bm * (eps + u2));
+      if (version == FASTCLIP_V0) { c1 /= t1; c2 /= t2; }
+    }
+  }
+  if (lane == 0) {
+    const int64_t ntile = ncol >> 8, tile = j >> 8, in = j & 255;
+    float* p0 = colp + ((0 * ntile + tile) * 4) * 256 + in;   // side 0: text anchors (tau_2, u_2)
+    float* p1 = colp + ((1 * ntile + tile) * 4) * 256 + in;   // side 1: image anchors (tau_1, u_1)
+    p0[0] = k2; p0[256] = d2; p0[512] = c2; p0[768] = 0.f;
+    p1[0] = k1; p1[256] = d1; p1[512] = c1; p1[768] = 0.f;
+  }
+}
+
+void launch_prep_cols(const StepCtx& c) {
+  const Layout& L = c.L;
+  float* colp = (float*)(c.ws + L.colp);
+  const float bm = (float)L.b * (float)(L.B - 1);
+  dim3 grid((unsigned)((L.ncol + 3) / 4)), block(256);
+  if (L.bf16)
+    hipLaunchKernelGGL(k_prep_cols<bf16_t>, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob,
+                       (const bf16_t*)c.buf.txt_glob, c.cfg.ld_img, c.cfg.ld_txt, L.B, L.ncol, L.off, L.b, L.d,
+                       c.buf.tau, c.buf.tau_glob_img, c.buf.tau_glob_txt, c.buf.u_glob_img, c.buf.u_glob_txt,
+                       c.cfg.version, c.cfg.eps, bm, colp);
+  else
+    hipLaunchKernelGGL(k_prep_cols<float>, grid, block, 0, c.s, (const float*)c.buf.img_glob,
+                       (const float*)c.buf.txt_glob, c.cfg.ld_img, c.cfg.ld_txt, L.B, L.ncol, L.off, L.b, L.d,
+                       c.buf.tau, c.buf.tau_glob_img, c.buf.tau_glob_txt, c.buf.u_glob_img, c.buf.u_glob_txt,
+                       c.cfg.version, c.cfg.eps, bm, colp);
+}
+
+// ------------------------------------------------------------------------------------------
 // Accuracy path, strips (Proc. 1).  Block (r, side): anchor r against every contrast row j != p;
 // side 0: image anchor vs texts (l1), side 1: text anchor vs images (l2).  One wavefront per
 // contrast row, fp64 accumulation; stores l as fp32 and the two row sums.
@@ -104,7 +170,9 @@ __global__ void __launch_bounds__(256) k_strips_f32(const float* __restrict__ im
                                                     int64_t d, const float* __restrict__ diag,
                                                     const float* __restrict__ tau1, const float* __restrict__ tau2,
                                                     float* __restrict__ E1, float* __restrict__ E2, int64_t ldE,
-                                                    float* __restrict__ sums, int64_t bstride) {
+                                                    float* __restrict__ sums, int64_t bstride,
+                                                    const float* __restrict__ colp, int64_t ncol,
+                                                    float* __restrict__ F1, float* __restrict__ F2) {
   const int64_t r = blockIdx.x;
   const int side = blockIdx.y;
   const int64_t p = off + r;
@@ -112,6 +180,7 @@ __global__ void __launch_bounds__(256) k_strips_f32(const float* __restrict__ im
   const float* X = side == 0 ? txt : img;
   const int64_t ldx = side == 0 ? ld_txt : ld_img;
   float* E = (side == 0 ? E1 : E2) + r * ldE;
+  float* F = colp ? (side == 0 ? F1 : F2) + r * ldE : nullptr;   // gathered: c_j l(j, p) of every remote anchor j
   const double s_pp = (double)diag[r];
   const double tau = (double)(side == 0 ? tau1[r] : tau2[r]);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -124,6 +193,11 @@ __global__ void __launch_bounds__(256) k_strips_f32(const float* __restrict__ im
     const double xs = acc - s_pp;
     const double e = j == p ? 0.0 : exp(xs / tau);
     if (lane == 0) E[j] = (float)e;
+    if (F && lane == 0) {
+      const float* cp = colp + (((int64_t)side * (ncol >> 8) + (j >> 8)) * 4) * 256 + (j & 255);
+      const double cj = (double)cp[512];
+      F[j] = cj == 0.0 ? 0.f : (float)(cj * exp2(acc * (double)cp[0] - (double)cp[256]));
+    }
     sg += e;
     sh += xs * e;
   }
@@ -143,7 +217,9 @@ void launch_strips_f32(const StepCtx& c) {
   hipLaunchKernelGGL(k_strips_f32, grid, block, 0, c.s, (const float*)c.buf.img_glob, (const float*)c.buf.txt_glob,
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.B, L.d, (const float*)(c.ws + L.diag),
                      (const float*)(c.ws + L.tau1), (const float*)(c.ws + L.tau2), (float*)(c.ws + L.E[0]),
-                     (float*)(c.ws + L.E[1]), L.ldE, (float*)(c.ws + L.sums), L.bstride);
+                     (float*)(c.ws + L.E[1]), L.ldE, (float*)(c.ws + L.sums), L.bstride,
+                     L.gathered ? (const float*)(c.ws + L.colp) : nullptr, L.ncol,
+                     L.gathered ? (float*)(c.ws + L.F[0]) : nullptr, L.gathered ? (float*)(c.ws + L.F[1]) : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -305,10 +381,12 @@ __global__ void __launch_bounds__(256) k_grad_f32(const float* __restrict__ img,
                                                   const float* __restrict__ dcoef, float* __restrict__ d_img,
                                                   float* __restrict__ d_txt, const float* __restrict__ red, int nblocks,
                                                   int version, const float* __restrict__ tau, float rho,
-                                                  float* __restrict__ loss, float* __restrict__ d_tau) {
+                                                  float* __restrict__ loss, float* __restrict__ d_tau,
+                                                  const float* __restrict__ F1, const float* __restrict__ F2) {
   const int64_t r = blockIdx.x;
   const int side = blockIdx.y;
   const int64_t p = off + r;
+  const float* Fown = F1 ? (side == 0 ? F1 : F2) + r * ldE : nullptr;   // gathered: remote anchors' weights
   const float* X = side == 0 ? txt : img;       // rows that the exp weights multiply
   const int64_t ldx = side == 0 ? ld_txt : ld_img;
   const float* Eown = (side == 0 ? E1 : E2) + r * ldE;       // l of this anchor over all contrasts
@@ -328,6 +406,8 @@ __global__ void __launch_bounds__(256) k_grad_f32(const float* __restrict__ img,
       for (int64_t j = grp; j < B; j += groups) acc += (double)Eown[j] * (double)X[j * ldx + col];
       for (int64_t q = grp; q < b; q += groups)
         acc6 += (double)coth[q] * (double)Eoth[q * ldE + p] * (double)X[(off + q) * ldx + col];
+      if (Fown)
+        for (int64_t j = grp; j < B; j += groups) acc6 += (double)Fown[j] * (double)X[j * ldx + col];
     }
     red2[threadIdx.x] = (double)cown[r] * acc + acc6;
     __syncthreads();
@@ -349,7 +429,9 @@ void launch_grad_f32(const StepCtx& c) {
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.B, L.d, (const float*)(c.ws + L.E[0]),
                      (const float*)(c.ws + L.E[1]), L.ldE, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
-                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau);
+                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau,
+                     L.gathered ? (const float*)(c.ws + L.F[0]) : nullptr,
+                     L.gathered ? (const float*)(c.ws + L.F[1]) : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -364,12 +446,14 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
                                                        float* __restrict__ d_img, float* __restrict__ d_txt,
                                                        const float* __restrict__ red, int nblocks, int version,
                                                        const float* __restrict__ tau, float rho, float* __restrict__ loss,
-                                                       float* __restrict__ d_tau) {
+                                                       float* __restrict__ d_tau, const float* __restrict__ OF1,
+                                                       const float* __restrict__ OF2) {
   const int64_t r = blockIdx.x;
   const int side = blockIdx.y;
   const int64_t p = off + r;
   const bf16_t* xp = side == 0 ? txt + p * ld_txt : img + p * ld_img;
   const float* O = (side == 0 ? O1 : O2) + r * d;
+  const float* OF = OF1 ? (side == 0 ? OF1 : OF2) + r * d : nullptr;   // gathered: remote anchors' contraction
   const float cown = side == 0 ? c1[r] : c2[r];
   const float dc = dcoef[r];
   float* out = (side == 0 ? d_img : d_txt) + r * d;
@@ -380,14 +464,20 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
       const float4 v = *(const float4*)(O + (size_t)s * split_stride + c0);
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
+    float4 rem = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (OF)
+      for (int s = 0; s < nsplit; ++s) {
+        const float4 v = *(const float4*)(OF + (size_t)s * split_stride + c0);
+        rem.x += v.x; rem.y += v.y; rem.z += v.z; rem.w += v.w;
+      }
     const uint2 xr = *(const uint2*)(xp + c0);
     const float x0 = __uint_as_float(xr.x << 16), x1 = __uint_as_float(xr.x & 0xffff0000u);
     const float x2 = __uint_as_float(xr.y << 16), x3 = __uint_as_float(xr.y & 0xffff0000u);
     float4 o;
-    o.x = cown * acc.x - dc * x0;
-    o.y = cown * acc.y - dc * x1;
-    o.z = cown * acc.z - dc * x2;
-    o.w = cown * acc.w - dc * x3;
+    o.x = fmaf(cown, acc.x, rem.x) - dc * x0;
+    o.y = fmaf(cown, acc.y, rem.y) - dc * x1;
+    o.z = fmaf(cown, acc.z, rem.z) - dc * x2;
+    o.w = fmaf(cown, acc.w, rem.w) - dc * x3;
     *(float4*)(out + c0) = o;
   }
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64)
@@ -401,7 +491,9 @@ void launch_finalize_bf16(const StepCtx& c) {
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, (const float*)(c.ws + L.Opart[0]),
                      (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
-                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau);
+                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau,
+                     L.gathered ? (const float*)(c.ws + L.OpartF[0]) : nullptr,
+                     L.gathered ? (const float*)(c.ws + L.OpartF[1]) : nullptr);
 }
 
 // ------------------------------------------------------------------------------------------

@@ -17,6 +17,9 @@
 // the last tile the stream keeps re-requesting its last stage (nobody reads it), which keeps every s_waitcnt
 // immediate constant.  Vector memory operations complete in order, so "stage g + 1 has landed" is
 // s_waitcnt vmcnt(n) with n = the number of operations issued after that stage's loads.
+//
+// REMOTE (gathered state): every element additionally yields the weight of Eqs. 3 / 5 / 7 with which its contrast
+// column, taken as an anchor of another worker, moves the local row; it goes to a second strip of the same form.
 #include "mfma_common.hpp"
 
 namespace fc {
@@ -110,11 +113,80 @@ __device__ __forceinline__ void half_epilogue(f32x16 (&acc)[2][4], const float* 
   }
 }
 
+// The same with the second strip of the gathered-state mode: besides l of the anchor (row parameters) every element
+// also yields f = c_j 2^(s k_j - d_j), the weight with which contrast column j, taken as an ANCHOR, moves the local
+// row (Eqs. 3 / 5 / 7); scol = the tile's column parameters [4][256] in LDS, cl0 = this lane's first column inside
+// the tile for ti = 0, g = 0.  No mask is needed for f: the own column is a local row, whose c is 0.
+template <bool MASK>
+__device__ __forceinline__ void half_epilogue_remote(f32x16 (&acc)[2][4], const float* sk, const float* sdiag,
+                                                     const float* scol, float (&sg)[4], float (&st)[4], char* frag0,
+                                                     int64_t row_bytes, char* fragF0, int64_t row_bytesF, int c_first,
+                                                     int own0, int al0, int cl0, int lane) {
+  const int lr = lane & 31, hk = lane >> 5;
+#pragma unroll
+  for (int tj = 0; tj < 4; ++tj) {
+    const int al = al0 + tj * 32 + lr;
+    const float kk = sk[al], dk = sdiag[al] * kk;
+    const int own = own0 + tj * 32 + lr;
+    char* fr = frag0 + tj * row_bytes;              // wave-uniform
+    char* frF = fragF0 + tj * row_bytesF;
+    float sgv[4] = {0.f, 0.f, 0.f, 0.f}, stv[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ti = 0; ti < 2; ++ti) {
+      const int crow = c_first + ti * 32 + 4 * hk;
+      uint32_t pk[8], pf[8];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int cl = cl0 + ti * 32 + 8 * g;
+        const float4 ck = *(const float4*)(scol + cl), cd = *(const float4*)(scol + 256 + cl),
+                     cc = *(const float4*)(scol + 512 + cl);
+        const float ckq[4] = {ck.x, ck.y, ck.z, ck.w}, cdq[4] = {cd.x, cd.y, cd.z, cd.w},
+                    ccq[4] = {cc.x, cc.y, cc.z, cc.w};
+        float sv[4], t[4], e[4], f[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sv[q] = acc_read(acc[ti][tj][4 * g + q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t[q] = fmaf(sv[q], kk, -dk);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) e[q] = __builtin_amdgcn_exp2f(t[q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) f[q] = ccq[q] * __builtin_amdgcn_exp2f(fmaf(sv[q], ckq[q], -cdq[q]));
+        if (MASK) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) e[q] = (crow + 8 * g + q != own) ? e[q] : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          sgv[q] += e[q];
+          stv[q] = fmaf(t[q], e[q], stv[q]);
+        }
+        pk[2 * g] = pack_bf16x2(e[0], e[1]);
+        pk[2 * g + 1] = pack_bf16x2(e[2], e[3]);
+        pf[2 * g] = pack_bf16x2(f[0], f[1]);
+        pf[2 * g + 1] = pack_bf16x2(f[2], f[3]);
+        FC_PIN();
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const u32x4 w = {pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]};
+        *(u32x4*)(fr + (2 * ti + j) * 1024 + lane * 16) = w;
+        const u32x4 wf = {pf[4 * j], pf[4 * j + 1], pf[4 * j + 2], pf[4 * j + 3]};
+        *(u32x4*)(frF + (2 * ti + j) * 1024 + lane * 16) = wf;
+      }
+      FC_PIN();
+    }
+    sg[tj] += (sgv[0] + sgv[1]) + (sgv[2] + sgv[3]);
+    st[tj] += (stv[0] + stv[1]) + (stv[2] + stv[3]);
+  }
+}
+
+template <bool REMOTE>
 __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   __shared__ __attribute__((aligned(1024))) char ring[kSRing];
   __shared__ __attribute__((aligned(256))) float sk[2][256];      // log2(e)/tau per anchor of the tile, double buffered
   __shared__ __attribute__((aligned(256))) float sdiag[2][256];   // s_pp per anchor of the tile
   __shared__ float sred[4][2][256];
+  __shared__ __attribute__((aligned(256))) float scol[REMOTE ? 2 : 1][REMOTE ? 4 : 1][256];   // column parameters
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave >> 1, wc = wave & 1, lr = lane & 31, hk = lane >> 5;
@@ -206,6 +278,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   // The barrier of stream stage g waits for the loads of stage g + 1; nothing is issued after them except, at a tile
   // change, the 16 fragment stores and 1 sum store of the finished tile and the scalar load of the new one
   // (kind 1: 18 per wave), or, for the first tile, the scalar load alone (kind 2).  S >= 2 keeps these episodes apart.
+  // REMOTE: 32 fragment stores and 3 scalar loads, i.e. 36 and 3.
   int pend_kind = 2;
   const bool early = wave < 4;
   bool late_pending = false;
@@ -216,6 +289,11 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
     // per-anchor scalars of this tile: covered by the wait of the tile's second stage
     if (wave < 4) dma4(a.kscale[strip] + a_first + wave * 64, lane * 4, lds_addr(&sk[buf][wave * 64]));
     else dma4(a.diag + a_first + (wave - 4) * 64, lane * 4, lds_addr(&sdiag[buf][(wave - 4) * 64]));
+    if (REMOTE) {   // the tile's column parameters, 4 KiB: two 256-byte pieces per wave
+      const float* cp = a.colp + ((int64_t)strip * a.nCT + ct) * 1024;
+      dma4(cp + wave * 64, lane * 4, lds_addr(&scol[buf][0][0] + wave * 64));
+      dma4(cp + (wave + 8) * 64, lane * 4, lds_addr(&scol[buf][0][0] + (wave + 8) * 64));
+    }
     f32x16 acc[2][4];
     zero_acc24(acc);
 #pragma unroll 1
@@ -243,8 +321,8 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
       // stage g + 1 has landed for this wave; the barrier (which every wave reaches with its LDS reads complete)
       // makes that true for all waves and retires the current slot: nobody reads it after this point
       if (pend_kind == 0) FC_WAIT_VMCNT0();
-      else if (pend_kind == 1) FC_WAIT_VMCNT18();
-      else FC_WAIT_VMCNT1();
+      else if (pend_kind == 1) { if (REMOTE) FC_WAIT_VMCNT36(); else FC_WAIT_VMCNT18(); }
+      else { if (REMOTE) FC_WAIT_VMCNT3(); else FC_WAIT_VMCNT1(); }
       pend_kind = 0;
       __syncthreads();
       FC_PIN();
@@ -271,8 +349,21 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
     const int64_t row_bytes = a.nCB * 1024;
     const int own0 = (int)a.off + a_first + wc * 128;
     const bool diagonal = (c_first < own0 + 128) && (c_first + 64 > own0);
-    if (diagonal) half_epilogue<true>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
-    else half_epilogue<false>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+    if (REMOTE) {
+      char* fragF0 = (char*)a.F[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
+      const int64_t row_bytesF = a.nCBF * 1024;
+      const int cl0 = wr * 64 + 4 * (lane >> 5);
+      if (diagonal)
+        half_epilogue_remote<true>(acc, sk[buf], sdiag[buf], &scol[REMOTE ? buf : 0][0][0], sg, st, frag0, row_bytes,
+                                   fragF0, row_bytesF, c_first, own0, wc * 128, cl0, lane);
+      else
+        half_epilogue_remote<false>(acc, sk[buf], sdiag[buf], &scol[REMOTE ? buf : 0][0][0], sg, st, frag0, row_bytes,
+                                    fragF0, row_bytesF, c_first, own0, wc * 128, cl0, lane);
+    } else if (diagonal) {
+      half_epilogue<true>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+    } else {
+      half_epilogue<false>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+    }
     // per-anchor sums of the tile: lanes hk = 0 / 1 hold the two halves of each 8-row group, waves wr = 0 .. 3 the
     // four 64-row blocks
 #pragma unroll
@@ -301,7 +392,8 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
 
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s) {
   const int grid = a.ntiles < 256 ? a.ntiles : 256;
-  hipLaunchKernelGGL(k_strips_bf16, dim3((unsigned)grid), dim3(512), 0, s, a);
+  if (a.colp) hipLaunchKernelGGL(k_strips_bf16<true>, dim3((unsigned)grid), dim3(512), 0, s, a);
+  else hipLaunchKernelGGL(k_strips_bf16<false>, dim3((unsigned)grid), dim3(512), 0, s, a);
 }
 
 }  // namespace fc

@@ -103,6 +103,11 @@ struct StripArgs {
   int nparts;
   int64_t bstride, b, B, d, off;
   int nAT, nCT, ntiles;
+  // gathered state (Eqs. 3 / 5 / 7 over every global anchor), colp == nullptr otherwise
+  const float* colp;            // [2][nCT][4][256]: per strip and contrast column j: log2(e)/tau_j, s_jj log2(e)/tau_j,
+                                // c_j (0 where column j takes no part), unused
+  bf16_t* F[2];                 // second stored strip c_j l(j, p_r), fragment order, nCBF column blocks per anchor block
+  int64_t nCBF;
 };
 
 // Whole 256 x 256 tiles go to the persistent kernel, tiles with a ragged edge to the guarded one.
@@ -111,5 +116,7 @@ __host__ __device__ __forceinline__ bool strip_tile_is_interior(const StripArgs&
 }
 
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s);   // kernels_strips.hip
+#define FC_WAIT_VMCNT3() __builtin_amdgcn_s_waitcnt(0x0f73)
+#define FC_WAIT_VMCNT36() __builtin_amdgcn_s_waitcnt(0x8f74)   // vmcnt = 36 = 0b100100: low bits 4, high bits 2
 
 }  // namespace fc

@@ -28,7 +28,9 @@ class GpuStep:
     """Device-resident state and buffers for repeated fastclip_step calls on one workload shape."""
 
     def __init__(self, *, B, b, off, d, N, dtype, version, eps, rho=0.0, tau=0.07, tau_grad_scale=1.0,
-                 ld_img=None, ld_txt=None, u_img0=None, u_txt0=None, tau_img0=None, tau_txt0=None):
+                 ld_img=None, ld_txt=None, u_img0=None, u_txt0=None, tau_img0=None, tau_txt0=None, gathered=None):
+        """gathered: None, or dict(u_img=[B], u_txt=[B], tau_img=[B] or None, tau_txt=[B] or None) = the state
+        gathered from all workers (the step then runs with FASTCLIP_GATHERED_STATE)."""
         self.B, self.b, self.off, self.d, self.N = B, b, off, d, N
         self.dtype, self.version = dtype, version
         self.eps, self.rho, self.scale = eps, rho, tau_grad_scale
@@ -54,11 +56,19 @@ class GpuStep:
         self.u_new_txt = torch.full((b,), nan, **f32)
         self.cfg = None
         self.ws = None
+        self.flags = 0
+        self.u_glob_img = self.u_glob_txt = self.tau_glob_img = self.tau_glob_txt = None
+        if gathered is not None:
+            self.flags = fc.GATHERED_STATE
+            up = lambda a: None if a is None else torch.from_numpy(np.asarray(a, np.float32)).to(DEV)
+            self.u_glob_img, self.u_glob_txt = up(gathered["u_img"]), up(gathered["u_txt"])
+            self.tau_glob_img, self.tau_glob_txt = up(gathered.get("tau_img")), up(gathered.get("tau_txt"))
 
     def config(self, gamma):
         return fc.make_config(version=self.version, emb_dtype=fc.BF16 if self.dtype == "bf16" else fc.F32,
                               B=self.B, b=self.b, off=self.off, d=self.d, N=self.N, gamma=gamma, eps=self.eps,
-                              rho=self.rho, tau_grad_scale=self.scale, ld_img=self.ld_img, ld_txt=self.ld_txt)
+                              rho=self.rho, tau_grad_scale=self.scale, ld_img=self.ld_img, ld_txt=self.ld_txt,
+                              flags=self.flags)
 
     def set_inputs(self, img32, txt32, idx):
         self.img = to_dev_matrix(img32, self.dtype, self.ld_img)
@@ -70,7 +80,9 @@ class GpuStep:
                                tau=self.tau, tau_img=self.tau_img, tau_txt=self.tau_txt, d_img=self.d_img,
                                d_txt=self.d_txt, loss=self.loss, d_tau=self.d_tau, d_tau_img=self.d_tau_img,
                                d_tau_txt=self.d_tau_txt, g_img=self.g_img, g_txt=self.g_txt,
-                               u_new_img=self.u_new_img, u_new_txt=self.u_new_txt)
+                               u_new_img=self.u_new_img, u_new_txt=self.u_new_txt, u_glob_img=self.u_glob_img,
+                               u_glob_txt=self.u_glob_txt, tau_glob_img=self.tau_glob_img,
+                               tau_glob_txt=self.tau_glob_txt)
 
     def step(self, gamma, timed=False):
         cfg = self.config(gamma)

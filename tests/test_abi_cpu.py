@@ -40,7 +40,7 @@ def test_library_exports_every_declared_function():
 
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(fc.fastclip_config) == 16 + 7 * 8 + 4 * 4
-    assert C.sizeof(fc.fastclip_buffers) == 18 * 8
+    assert C.sizeof(fc.fastclip_buffers) == 22 * 8
 
 
 def test_valid_config_and_workspace_size():
@@ -77,14 +77,34 @@ def test_f32_path_accepts_any_width():
     assert fc.fastclip_validate(good_cfg(emb_dtype=fc.F32, d=19, ld_img=23, ld_txt=19), None) == fc.OK
 
 
-def test_struct_size_and_reserved_are_checked():
+def test_struct_size_and_flags_are_checked():
     cfg = good_cfg()
     cfg.struct_size = 8
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
     cfg = good_cfg()
-    cfg.reserved = 1
+    cfg.flags = 2
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
     assert fc.fastclip_validate(None, None) == fc.ERR_NULL
+
+
+@pytest.mark.parametrize("version", [fc.V2, fc.V3])
+def test_gathered_state_needs_its_arrays_and_more_workspace(version):
+    plain = good_cfg(version=version, B=2048, b=512, off=512)
+    cfg = good_cfg(version=version, B=2048, b=512, off=512, flags=fc.GATHERED_STATE)
+    assert fc.fastclip_validate(cfg, None) == fc.OK
+    assert fc.fastclip_workspace_bytes(cfg) > fc.fastclip_workspace_bytes(plain) > 0
+    assert fc.fastclip_validate(cfg, fake_bufs(cfg)) == fc.OK
+    assert fc.fastclip_validate(cfg, fake_bufs(cfg, u_glob_img=None)) == fc.ERR_NULL
+    assert fc.fastclip_validate(cfg, fake_bufs(cfg, u_glob_txt=None)) == fc.ERR_NULL
+    want = fc.ERR_NULL if version == fc.V2 else fc.OK
+    assert fc.fastclip_validate(cfg, fake_bufs(cfg, tau_glob_img=None)) == want
+    assert fc.fastclip_validate(cfg, fake_bufs(cfg, tau_glob_txt=None)) == want
+    # without the flag the arrays are not required
+    assert fc.fastclip_validate(plain, fake_bufs(plain, u_glob_img=None, u_glob_txt=None, tau_glob_img=None,
+                                                 tau_glob_txt=None)) == fc.OK
+    # a single worker holding the whole batch has no remote anchors: same workspace as without the flag
+    whole = good_cfg(version=version, b=1024, off=0, flags=fc.GATHERED_STATE)
+    assert fc.fastclip_workspace_bytes(whole) == fc.fastclip_workspace_bytes(good_cfg(version=version, b=1024, off=0))
 
 
 @pytest.mark.parametrize("version,field,status", [

@@ -12,7 +12,7 @@ from oracle import V0, V1, V2, V3, ema_update, fcco_step, gamma_cosine
 from paper_2407_01445_amd import binding as fc
 from paper_2407_01445_amd.workloads import WORKLOADS, draw_indices, make_embeddings, step_seed
 
-from gpu_harness import DEV, GpuStep, compare, rel_each
+from gpu_harness import DEV, GpuStep, compare, rel_each, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -143,6 +143,83 @@ def test_bf16_repeatable_bit_for_bit():
     res = []
     for _ in range(2):
         g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=V3, eps=1e-14, rho=6.5)
+        g.set_inputs(img, txt, idx)
+        g.step(0.7)
+        res.append((g.d_img.cpu(), g.d_txt.cpu(), g.u_img.cpu(), g.loss.cpu(), g.d_tau.cpu()))
+    for x, y in zip(*res):
+        assert torch.equal(x, y)
+
+
+# ------------------------------------------------------------------------------- gathered state (Eqs. 3/5/7 in full)
+def gathered_inputs(rng, B, version):
+    """What the other workers report: u^{t+1} of every global row, and for V2 the rows' temperatures; the entries
+    of the local rows are poison on the GPU side (they must not be read) and arbitrary on the oracle side."""
+    ug1 = rng.uniform(0.05, 2.0, B).astype(np.float32)
+    ug2 = rng.uniform(0.05, 2.0, B).astype(np.float32)
+    tg1 = rng.uniform(0.05, 0.1, B).astype(np.float32) if version == V2 else None
+    tg2 = rng.uniform(0.05, 0.1, B).astype(np.float32) if version == V2 else None
+    return ug1, ug2, tg1, tg2
+
+
+def run_gathered(B, b, off, d, version, dtype, tol, N=5000, ld_pad=0):
+    rng = np.random.default_rng(7 * B + version)
+    img, txt = make_embeddings(B + d + 1, B, d, 0.5, dtype)
+    idx = draw_indices(B + 2, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    ug1, ug2, tg1, tg2 = gathered_inputs(rng, B, version)
+
+    def poisoned(a):
+        if a is None:
+            return None
+        a = a.copy()
+        a[off:off + b] = np.nan
+        return a
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
+                tau_grad_scale=1.0 / N, ld_img=d + ld_pad, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img,
+                tau_txt0=t_txt, gathered=dict(u_img=poisoned(ug1), u_txt=poisoned(ug2), tau_img=poisoned(tg1),
+                                              tau_txt=poisoned(tg2)))
+    g.set_inputs(img, txt, idx)
+    g.step(0.6)
+    u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+    f64 = lambda a: None if a is None else a.astype(np.float64)
+    want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, u_img, u_txt, version=version,
+                     gamma=0.6, eps=g.eps, rho=g.rho, tau=float(np.float32(0.07)), tau_img=f64(t_img),
+                     tau_txt=f64(t_txt), tau_grad_scale=g.scale, u_glob_img=f64(ug1), u_glob_txt=f64(ug2),
+                     tau_glob_img=f64(tg1), tau_glob_txt=f64(tg2))
+    got = g.outputs()
+    compare(got, want, version, tol, "gathered %s %s v%d" % (dtype, (B, b, off, d), version))
+    check_state(g, u0i, u0t, idx, u_img, u_txt, tol)
+    # the remote anchors' part is a sizeable share of the gradient: a path that dropped it could not pass
+    local_only = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, u0i.astype(np.float64),
+                           u0t.astype(np.float64), version=version, gamma=0.6, eps=g.eps, rho=g.rho,
+                           tau=float(np.float32(0.07)), tau_img=f64(t_img), tau_txt=f64(t_txt), tau_grad_scale=g.scale)
+    for k in ("d_img", "d_txt"):
+        assert rel_l2(local_only[k], want[k]) > 20 * rel_l2(got[k], want[k])
+
+
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_f32_gathered_state(version):
+    run_gathered(37, 11, 13, 19, version, "f32", TOL_F32, N=200, ld_pad=5)
+
+
+@pytest.mark.parametrize("B,b,off,d", [(700, 300, 133, 72), (1000, 64, 936, 136), (768, 256, 256, 128),
+                                       (1024, 300, 512, 256), (1536, 512, 512, 192)])
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_bf16_gathered_state(B, b, off, d, version):
+    run_gathered(B, b, off, d, version, "bf16", TOL_BF16, ld_pad=8)
+
+
+def test_gathered_state_with_whole_batch_is_the_plain_step():
+    """b == B: no remote anchors; the flag changes nothing and the gathered arrays are not read."""
+    B, d, N = 520, 64, 5000
+    img, txt = make_embeddings(11, B, d, 0.5, "bf16")
+    idx = draw_indices(12, B, N)
+    res = []
+    for gathered in (None, dict(u_img=np.full(B, np.nan), u_txt=np.full(B, np.nan))):
+        g = GpuStep(B=B, b=B, off=0, d=d, N=N, dtype="bf16", version=V3, eps=1e-14, rho=6.5, gathered=gathered)
         g.set_inputs(img, txt, idx)
         g.step(0.7)
         res.append((g.d_img.cpu(), g.d_txt.cpu(), g.u_img.cpu(), g.loss.cpu(), g.d_tau.cpu()))
