@@ -32,13 +32,17 @@ MEASURED_TRAFFIC = {
 }
 
 
-def algorithmic_flops(B, b, d):
+
+def algorithmic_flops(B, b, d, gathered=False):
     """Flop the method needs per step and phase (recomputation and padding not counted): one
     'unit' = 2 b B d.  Full batch (b == B): similarity once, then W T and W^T I.  Local share:
-    two strips, two anchor-side contractions, and the local contrast-side block (4 b^2 d)."""
+    two strips, two anchor-side contractions, and the local contrast-side block (4 b^2 d); with
+    gathered state the contrast side runs over all B anchors instead (2 more units)."""
     unit = 2.0 * b * B * d
     if b == B:
         return {"strips": unit, "contract": 2 * unit}
+    if gathered:
+        return {"strips": 2 * unit, "contract": 4 * unit}
     return {"strips": 2 * unit, "contract": 2 * unit + 4.0 * b * b * d}
 
 
@@ -48,6 +52,9 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg4 (bf16 workloads of BASELINE.json)")
+    ap.add_argument("--gathered", action="store_true",
+                    help="time the step with FASTCLIP_GATHERED_STATE (contrast side over every global anchor); "
+                         "not the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-state-bench", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -93,6 +100,13 @@ def main():
     d_img, d_txt = torch.empty(b, d, **f32), torch.empty(b, d, **f32)
     loss, d_tau = torch.empty(1, **f32), torch.empty(1, **f32)
     d_tau_img, d_tau_txt = torch.empty(b, **f32), torch.empty(b, **f32)
+    gath = {}
+    if args.gathered:
+        rs = np.random.default_rng(step_seed(name, 77))
+        mk = lambda lo, hi: torch.from_numpy(rs.uniform(lo, hi, B).astype(np.float32)).to(dev)
+        gath = dict(u_glob_img=mk(0.05, 2.0), u_glob_txt=mk(0.05, 2.0))
+        if version == fc.V2:
+            gath.update(tau_glob_img=mk(0.05, 0.1), tau_glob_txt=mk(0.05, 0.1))
     n_sets = W + 2 * K
     idx_sets = [torch.from_numpy(draw_indices(step_seed(name, t) + 500, b, N)).to(dev) for t in range(n_sets)]
 
@@ -102,12 +116,13 @@ def main():
 
     def cfg_at(t):
         return fc.make_config(version=version, emb_dtype=fc.BF16 if w["dtype"] == "bf16" else fc.F32, B=B, b=b,
-                              off=off, d=d, N=N, gamma=gamma_at(t), eps=w["eps"], rho=w["rho"], tau_grad_scale=1.0 / N)
+                              off=off, d=d, N=N, gamma=gamma_at(t), eps=w["eps"], rho=w["rho"], tau_grad_scale=1.0 / N,
+                              flags=fc.GATHERED_STATE if args.gathered else 0)
 
     def bufs_at(t):
         return fc.make_buffers(img_glob=img, txt_glob=txt, idx=idx_sets[t], u_img=u_img, u_txt=u_txt, tau=tau,
                                tau_img=tau_img, tau_txt=tau_txt, d_img=d_img, d_txt=d_txt, loss=loss, d_tau=d_tau,
-                               d_tau_img=d_tau_img, d_tau_txt=d_tau_txt)
+                               d_tau_img=d_tau_img, d_tau_txt=d_tau_txt, **gath)
 
     ws = torch.empty(fc.fastclip_workspace_bytes(cfg_at(0)), dtype=torch.uint8, device=dev)
     cfgs = [cfg_at(t) for t in range(n_sets)]
@@ -131,13 +146,13 @@ def main():
     for t in range(W + K, W + 2 * K):
         for k, v in fc.fastclip_step_timed(cfgs[t], bufs[t], ws).items():
             phase_ms[k] = phase_ms.get(k, 0.0) + v / K
-    alg = algorithmic_flops(B, b, d)
+    alg = algorithmic_flops(B, b, d, args.gathered)
     dom = max(("strips", "contract"), key=lambda k: phase_ms.get(k, 0.0))
     achieved = alg[dom] / (phase_ms[dom] * 1e-3) / 1e12
     roofline = {"kernel": {"strips": "k_strips_bf16", "contract": "k_contract_bf16"}[dom], "bound": "mfma",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
                 "frac": round(achieved * 1e12 / PEAK_BF16_FLOPS, 4),
-                "traffic": MEASURED_TRAFFIC.get((name, dom)),
+                "traffic": None if args.gathered else MEASURED_TRAFFIC.get((name, dom)),
                 "algorithmic_flop_per_launch": alg[dom], "avg_launch_ms": round(phase_ms[dom], 5),
                 "timing": "HIP events around each kernel on the launch stream, %d extra steps" % K}
     gemm_ms = phase_ms["strips"] + phase_ms["contract"]
@@ -150,7 +165,8 @@ def main():
            "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
            "scaling": "weak", "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
            "config": {"workload": "%s: b=%d local anchors x B=%d global pairs, d=%d %s, N=%d state entries, "
-                                  "FastCLIP-v%d" % (name, b, B, d, w["dtype"], N, version),
+                                  "FastCLIP-v%d%s" % (name, b, B, d, w["dtype"], N, version,
+                                                      ", gathered state of all workers" if args.gathered else ""),
                       "B": B, "b": b, "off": off, "d": d, "N": N, "version": version},
            "roofline": roofline, "gemm_phases": gemm_phases,
            "phase_ms": {k: round(v, 5) for k, v in phase_ms.items()}}

@@ -228,11 +228,18 @@ def test_gathered_state_with_whole_batch_is_the_plain_step():
 
 
 # ------------------------------------------------------------------------------- full-size workloads
-def run_workload(name, steps_checked, n_steps):
+def run_workload(name, steps_checked, n_steps, gathered=False):
     w = WORKLOADS[name]
     B, b, off, d, N, version = w["B"], w["b"], w["off"], w["d"], w["N"], w["version"]
+    gath, gath64 = None, {}
+    if gathered:
+        ug1, ug2, tg1, tg2 = gathered_inputs(np.random.default_rng(step_seed(name, 77)), B, version)
+        gath = dict(u_img=ug1, u_txt=ug2, tau_img=tg1, tau_txt=tg2)
+        gath64 = dict(u_glob_img=ug1.astype(np.float64), u_glob_txt=ug2.astype(np.float64),
+                      tau_glob_img=None if tg1 is None else tg1.astype(np.float64),
+                      tau_glob_txt=None if tg2 is None else tg2.astype(np.float64))
     g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=w["dtype"], version=version, eps=w["eps"], rho=w["rho"],
-                tau=w["tau"], tau_grad_scale=1.0 / N)
+                tau=w["tau"], tau_grad_scale=1.0 / N, gathered=gath)
     tau32 = float(np.float32(w["tau"]))
     for step in range(n_steps):
         gamma = w["gamma"] if not isinstance(w["gamma"], tuple) else gamma_cosine(step, 1, w["gamma"][1], w["gamma"][2])
@@ -254,8 +261,8 @@ def run_workload(name, steps_checked, n_steps):
         tau_c = np.full(b, tau32)
         want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, np.arange(b), u_img_c, u_txt_c,
                          version=version, gamma=gamma, eps=w["eps"], rho=w["rho"], tau=tau32, tau_img=tau_c,
-                         tau_txt=tau_c, tau_grad_scale=1.0 / N)
-        compare(g.outputs(), want, version, TOL_BF16, "%s step %d" % (name, step))
+                         tau_txt=tau_c, tau_grad_scale=1.0 / N, **gath64)
+        compare(g.outputs(), want, version, TOL_BF16, "%s%s step %d" % (name, " gathered" if gathered else "", step))
         # state: scattered values are the reported ones, everything else is bit-identical
         assert torch.equal(g.u_img[idx_t], g.u_new_img) and torch.equal(g.u_txt[idx_t], g.u_new_txt)
         keep_img[idx_t] = g.u_new_img
@@ -281,6 +288,14 @@ def test_cfg3_full_size():
 
 def test_cfg4_full_size():
     run_workload("cfg4", {0, 1}, 2)
+
+
+def test_cfg2_full_size_gathered_state():
+    run_workload("cfg2", {0, 2}, 3, gathered=True)
+
+
+def test_cfg4_full_size_gathered_state():
+    run_workload("cfg4", {1}, 2, gathered=True)
 
 
 # ------------------------------------------------------------------------------- auxiliary entry points
