@@ -234,3 +234,69 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
     else:
         raise ValueError("unknown version")
     return out
+
+
+# ----------------------------------------------------------------------------------------------
+# Temperature update (Alg. 1 line 12, Proc. "temperature_update" with Proc. "parameter_update")
+SGDM, LAMB, LION, ADAMW = 1, 2, 3, 4
+
+
+def parameter_update(theta, grad, m, v, *, optimizer, lr, step, beta1, beta2, eps=1e-8, weight_decay=0.0):
+    """One step of Proc. "parameter_update" on an array (or scalar) theta with gradient estimator grad.
+
+    m, v are the optimizer states before the step (v is ignored by SGD with momentum and Lion);
+    `step` is t + 1, the 1-based count that the bias corrections of AdamW / LAMB use.  For SGD with
+    momentum beta1 plays the role of the momentum parameter mu.  LAMB is taken with the layer factor
+    alpha = 1, which the paper prescribes for the temperature and which makes it AdamW.
+    Returns (theta_new, m_new, v_new) as float64 arrays.
+    """
+    theta = np.asarray(theta, dtype=np.float64)
+    grad = np.asarray(grad, dtype=np.float64)
+    m = np.asarray(m, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    if optimizer == SGDM:
+        m_new = beta1 * m + grad + weight_decay * theta
+        return theta - lr * m_new, m_new, v
+    if optimizer == LION:
+        c = beta1 * m + (1.0 - beta1) * grad
+        m_new = beta2 * m + (1.0 - beta2) * grad
+        return theta - lr * (np.sign(c) + weight_decay * theta), m_new, v
+    if optimizer in (ADAMW, LAMB):
+        m_new = beta1 * m + (1.0 - beta1) * grad
+        v_new = beta2 * v + (1.0 - beta2) * grad * grad
+        m_hat = m_new / (1.0 - beta1 ** step)
+        v_hat = v_new / (1.0 - beta2 ** step)
+        r = m_hat / (np.sqrt(v_hat) + eps)
+        return theta - lr * (r + weight_decay * theta), m_new, v_new
+    raise ValueError("unknown optimizer")
+
+
+def temperature_update(version, grads, *, optimizer, lr, step, beta1, beta2, eps=1e-8, tau_min=0.0,
+                       lr_drop_below=0.0, lr_drop_factor=1.0, tau=None, m=None, v=None,
+                       tau_img=None, tau_txt=None, idx=None, m_img=None, v_img=None, m_txt=None, v_txt=None):
+    """Proc. "temperature_update" for one worker, weight decay 0.
+
+    V1: nothing changes.  V0 / V3: the scalar tau is stepped with grads["d_tau"] (Eq. 8 / Eq. 10; with
+    several workers the caller averages it first) and returned as (tau_new, m_new, v_new).  V2: the
+    entries idx of tau_img / tau_txt (and of their optimizer states, all length-N arrays) are stepped IN
+    PLACE with grads["d_tau_img"], grads["d_tau_txt"] (Eq. 9); all other entries are untouched.
+    Readings: the constraint tau >= tau_0 of GCL / RGCL / RGCL-g is kept by projecting after the step
+    (max(tau, tau_min)); the rule "the learning rate of tau drops to a third once tau is below 0.03" is
+    applied to the value of tau before the step (lr * lr_drop_factor when tau < lr_drop_below)."""
+    kw = dict(optimizer=optimizer, step=step, beta1=beta1, beta2=beta2, eps=eps)
+    if version == V1:
+        return None
+    if version in (V0, V3):
+        lr_now = lr * lr_drop_factor if float(tau) < lr_drop_below else lr
+        t_new, m_new, v_new = parameter_update(tau, grads["d_tau"], m, v, lr=lr_now, **kw)
+        return float(max(t_new, tau_min)), float(m_new), float(v_new)
+    idx = np.asarray(idx, dtype=np.int64)
+    for t_arr, m_arr, v_arr, g in ((tau_img, m_img, v_img, grads["d_tau_img"]),
+                                   (tau_txt, m_txt, v_txt, grads["d_tau_txt"])):
+        old = np.asarray(t_arr[idx], dtype=np.float64)
+        lr_now = np.where(old < lr_drop_below, lr * lr_drop_factor, lr)
+        t_new, m_new, v_new = parameter_update(old, g, m_arr[idx], v_arr[idx], lr=lr_now, **kw)
+        t_arr[idx] = np.maximum(t_new, tau_min)
+        m_arr[idx] = m_new
+        v_arr[idx] = v_new
+    return None

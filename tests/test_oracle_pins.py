@@ -500,3 +500,88 @@ def test_gathered_state_with_b_equal_B_changes_nothing():
                   u_glob_txt=np.full(B, 9.0))
     np.testing.assert_allclose(c["d_img"], a["d_img"], rtol=1e-12, atol=1e-16)
     np.testing.assert_allclose(c["d_txt"], a["d_txt"], rtol=1e-12, atol=1e-16)
+
+
+# --------------------------------------------- 9. temperature update (Proc. parameter_update / temperature_update)
+from oracle import ADAMW, LAMB, LION, SGDM, parameter_update, temperature_update  # noqa: E402
+
+
+def test_adamw_matches_the_library_optimizer_on_a_scalar():
+    """AdamW with weight decay 0 (the temperature's setting) against torch.optim.AdamW, several steps."""
+    rng = np.random.default_rng(2)
+    grads = rng.standard_normal(6) * 0.3
+    th = torch.tensor([0.07], dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.AdamW([th], lr=2e-4, betas=(0.9, 0.98), eps=1e-6, weight_decay=0.0)
+    theta, m, v = 0.07, 0.0, 0.0
+    for t, g in enumerate(grads):
+        th.grad = torch.tensor([g], dtype=torch.float64)
+        opt.step()
+        theta, m, v = parameter_update(theta, g, m, v, optimizer=ADAMW, lr=2e-4, step=t + 1, beta1=0.9, beta2=0.98,
+                                       eps=1e-6)
+        assert float(theta) == pytest.approx(th.item(), rel=1e-12)
+    # LAMB with the layer factor 1 (what the paper prescribes for tau) is the same update
+    a = parameter_update(0.05, 0.3, 0.01, 0.02, optimizer=LAMB, lr=1e-3, step=4, beta1=0.9, beta2=0.99, eps=1e-8)
+    b = parameter_update(0.05, 0.3, 0.01, 0.02, optimizer=ADAMW, lr=1e-3, step=4, beta1=0.9, beta2=0.99, eps=1e-8)
+    assert all(float(x) == float(y) for x, y in zip(a, b))
+
+
+def test_adamw_first_step_closed_form_and_weight_decay():
+    # step 1 from zero state: m_hat = G, v_hat = G^2, so theta moves by lr * G / (|G| + eps)
+    th, m, v = parameter_update(np.array([0.07, 0.05]), np.array([2.0, -0.5]), 0.0, 0.0, optimizer=ADAMW, lr=1e-2,
+                                step=1, beta1=0.9, beta2=0.999, eps=1e-8)
+    np.testing.assert_allclose(th, [0.07 - 1e-2 * 2.0 / (2.0 + 1e-8), 0.05 + 1e-2 * 0.5 / (0.5 + 1e-8)], rtol=1e-14)
+    np.testing.assert_allclose(m, [0.2, -0.05], rtol=1e-14)
+    np.testing.assert_allclose(v, [0.004, 0.00025], rtol=1e-12)
+    th2, _, _ = parameter_update(0.5, 0.0, 0.0, 0.0, optimizer=ADAMW, lr=0.1, step=1, beta1=0.9, beta2=0.999,
+                                 eps=1e-8, weight_decay=0.2)
+    assert float(th2) == pytest.approx(0.5 - 0.1 * 0.2 * 0.5, rel=1e-14)        # decoupled decay only
+
+
+def test_sgd_with_momentum_matches_the_library_optimizer():
+    grads = [0.4, -0.1, 0.25, 0.3]
+    th = torch.tensor([0.05], dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.SGD([th], lr=1e-3, momentum=0.9)
+    theta, m = 0.05, 0.0
+    for g in grads:
+        th.grad = torch.tensor([g], dtype=torch.float64)
+        opt.step()
+        theta, m, _ = parameter_update(theta, g, m, 0.0, optimizer=SGDM, lr=1e-3, step=1, beta1=0.9, beta2=0.0)
+        assert float(theta) == pytest.approx(th.item(), rel=1e-13)
+
+
+def test_lion_two_steps_by_hand():
+    b1, b2, lr = 0.9, 0.99, 1e-3
+    th, m, _ = parameter_update(0.07, 0.5, 0.0, 0.0, optimizer=LION, lr=lr, step=1, beta1=b1, beta2=b2)
+    assert float(th) == pytest.approx(0.07 - lr) and float(m) == pytest.approx(0.005)
+    # second step: the interpolation c = b1 m + (1 - b1) G is negative although m is positive
+    th2, m2, _ = parameter_update(th, -0.2, m, 0.0, optimizer=LION, lr=lr, step=2, beta1=b1, beta2=b2)
+    assert b1 * 0.005 + (1 - b1) * -0.2 < 0
+    assert float(th2) == pytest.approx(0.07 - lr + lr) and float(m2) == pytest.approx(b2 * 0.005 + (1 - b2) * -0.2)
+
+
+def test_temperature_update_procedure():
+    kw = dict(optimizer=ADAMW, lr=1e-2, step=1, beta1=0.9, beta2=0.999, eps=1e-8)
+    # V1: constant temperature
+    assert temperature_update(V1, {}, tau=0.07, m=0.0, v=0.0, **kw) is None
+    # V3, first step with positive gradient: tau goes down by lr; projection onto tau >= tau_0
+    t_new, m_new, v_new = temperature_update(V3, {"d_tau": 3.0}, tau=0.07, m=0.0, v=0.0, **kw)
+    assert t_new == pytest.approx(0.06, rel=1e-7) and m_new == pytest.approx(0.3) and v_new == pytest.approx(0.009)
+    t_new, _, _ = temperature_update(V3, {"d_tau": 3.0}, tau=0.07, m=0.0, v=0.0, tau_min=0.065, **kw)
+    assert t_new == 0.065
+    # the reduced learning rate below the threshold (decided on tau before the step)
+    t_new, _, _ = temperature_update(V0, {"d_tau": 3.0}, tau=0.029, m=0.0, v=0.0, lr_drop_below=0.03,
+                                     lr_drop_factor=1.0 / 3.0, **kw)
+    assert t_new == pytest.approx(0.029 - 1e-2 / 3.0, rel=1e-6)
+    # V2: only the batch entries of tau and of the optimizer state move
+    N, idx = 10, np.array([7, 2, 5])
+    t1, t2 = np.full(N, 0.07), np.full(N, 0.05)
+    m1, v1, m2, v2 = np.zeros(N), np.zeros(N), np.zeros(N), np.zeros(N)
+    g = {"d_tau_img": np.array([1.0, -2.0, 0.5]), "d_tau_txt": np.array([-1.0, 4.0, 0.25])}
+    temperature_update(V2, g, tau_img=t1, tau_txt=t2, idx=idx, m_img=m1, v_img=v1, m_txt=m2, v_txt=v2,
+                       tau_min=0.045, **kw)
+    untouched = np.setdiff1d(np.arange(N), idx)
+    assert (t1[untouched] == 0.07).all() and (t2[untouched] == 0.05).all() and (m1[untouched] == 0).all()
+    np.testing.assert_allclose(t1[idx], [0.06, 0.08, 0.06], rtol=1e-6)
+    np.testing.assert_allclose(t2[idx], [0.06, 0.045, 0.045], rtol=1e-6)            # 0.04 projected up to tau_0
+    np.testing.assert_allclose(m1[idx], 0.1 * g["d_tau_img"], rtol=1e-12)
+    np.testing.assert_allclose(v2[idx], 0.001 * g["d_tau_txt"] ** 2, rtol=1e-9)
