@@ -142,6 +142,57 @@ fastclip_status fastclip_step_timed(const fastclip_config* cfg, const fastclip_b
                                     float* phase_ms);
 const char* fastclip_phase_name(int phase);
 
+/* ---- temperature update (Alg. 1 line 12: Proc. "temperature_update" with Proc. "parameter_update", weight decay 0) ----
+ * V1 keeps tau.  V0 / V3 step the global tau with d_tau (Eq. 8 / Eq. 10).  V2 steps tau_1[idx[r]], tau_2[idx[r]] with
+ * d_tau_img[r], d_tau_txt[r] (Eq. 9) and touches no other entry.  After the step the temperature is projected onto
+ * tau >= tau_min (the constraint tau >= tau_0 of the objectives).  lr_drop_below / lr_drop_factor: the learning rate is
+ * multiplied by lr_drop_factor for a temperature that is below lr_drop_below before the step (Sec. 4 / App. B: a third
+ * once tau < 0.03 for V3); set lr_drop_below = 0 to switch that off. */
+typedef enum {
+  FASTCLIP_TAU_SGDM = 1,   /* m = beta1 m + G;  tau -= lr m                         (beta1 = momentum) */
+  FASTCLIP_TAU_LAMB = 2,   /* with the layer factor alpha = 1 prescribed for tau: identical to AdamW */
+  FASTCLIP_TAU_LION = 3,   /* c = beta1 m + (1-beta1) G;  m = beta2 m + (1-beta2) G;  tau -= lr sign(c) */
+  FASTCLIP_TAU_ADAMW = 4   /* m, v moments with bias correction 1 - beta^step;  tau -= lr m^ / (sqrt(v^) + eps) */
+} fastclip_tau_optimizer;
+
+typedef struct {             /* host scalars */
+  uint32_t struct_size;      /* sizeof(fastclip_tau_update) */
+  int32_t  optimizer;        /* fastclip_tau_optimizer */
+  int64_t  step;             /* t + 1 >= 1: exponent of the bias corrections */
+  float    lr, beta1, beta2, eps;
+  float    tau_min;
+  float    lr_drop_below, lr_drop_factor;
+  float    reserved;         /* must be 0 */
+} fastclip_tau_update;
+
+typedef struct {             /* DEVICE memory owned by the caller, updated in place */
+  float* tau;                /* [1]  V0, V3 */
+  float* m;                  /* [1]  first-moment / momentum state of tau */
+  float* v;                  /* [1]  second-moment state (AdamW, LAMB; may be NULL otherwise) */
+  float* tau_img;            /* [N]  V2: tau_1 */
+  float* tau_txt;            /* [N]  V2: tau_2 */
+  float* m_img;  float* v_img;   /* [N] states of tau_1 (v_* may be NULL for SGDM / LION) */
+  float* m_txt;  float* v_txt;   /* [N] states of tau_2 */
+} fastclip_tau_state;
+
+/* The update alone, from gradients that a previous fastclip_step wrote (a caller with several workers averages
+ * d_tau over the workers in between; d_tau_img / d_tau_txt need no averaging).  d_tau: [1] device (V0, V3);
+ * d_tau_img, d_tau_txt: [b] device, batch order, with idx [b] (V2).  Asynchronous on `stream`; V1 returns
+ * FASTCLIP_OK and does nothing. */
+fastclip_status fastclip_temperature_update(int32_t version, const fastclip_tau_update* upd,
+                                            const fastclip_tau_state* state, const int64_t* idx, int64_t b,
+                                            int64_t N, const float* d_tau, const float* d_tau_img,
+                                            const float* d_tau_txt, void* stream);
+
+/* fastclip_step followed by the temperature update of the same iteration, for a single worker (no averaging of
+ * d_tau in between).  For V2 the update is part of the state phase: the kernel that gathers u by idx and scatters
+ * u^{t+1} also steps tau_1, tau_2 and their moments at the same indices.  bufs->tau (V0, V3) must be state->tau,
+ * bufs->tau_img / tau_txt (V2) must be state->tau_img / tau_txt; the step itself uses the temperatures as they were
+ * before the call, and every output of fastclip_step is produced as usual. */
+fastclip_status fastclip_step_update_tau(const fastclip_config* cfg, const fastclip_buffers* bufs,
+                                         const fastclip_tau_update* upd, const fastclip_tau_state* state,
+                                         void* workspace, size_t workspace_bytes, void* stream);
+
 /* Eq. 1 alone, for n anchors whose exp-sums are already known (the state phase of
  * fastclip_step run on its own; used to measure the gather/update/scatter kernel on many
  * indices).  sum_img[r] / sum_txt[r] hold M * g_1 / M * g_2 of anchor r (device, [n]);

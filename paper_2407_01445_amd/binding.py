@@ -36,6 +36,23 @@ class fastclip_buffers(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in _BUF_FIELDS]
 
 
+TAU_SGDM, TAU_LAMB, TAU_LION, TAU_ADAMW = 1, 2, 3, 4
+
+
+class fastclip_tau_update(C.Structure):
+    _fields_ = [("struct_size", C.c_uint32), ("optimizer", C.c_int32), ("step", C.c_int64),
+                ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("tau_min", C.c_float), ("lr_drop_below", C.c_float), ("lr_drop_factor", C.c_float),
+                ("reserved", C.c_float)]
+
+
+_TAU_STATE_FIELDS = ["tau", "m", "v", "tau_img", "tau_txt", "m_img", "v_img", "m_txt", "v_txt"]
+
+
+class fastclip_tau_state(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in _TAU_STATE_FIELDS]
+
+
 _lib = None
 
 
@@ -74,6 +91,12 @@ def load(build_if_missing: bool = True):
     lib.fastclip_gamma_cosine.argtypes = [C.c_int64, C.c_int64, C.c_int64, C.c_float]
     lib.fastclip_status_string.restype = C.c_char_p
     lib.fastclip_status_string.argtypes = [C.c_int]
+    updp, tstp = C.POINTER(fastclip_tau_update), C.POINTER(fastclip_tau_state)
+    lib.fastclip_temperature_update.restype = C.c_int
+    lib.fastclip_temperature_update.argtypes = [C.c_int32, updp, tstp, C.c_void_p, C.c_int64, C.c_int64, C.c_void_p,
+                                                C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.fastclip_step_update_tau.restype = C.c_int
+    lib.fastclip_step_update_tau.argtypes = [cfgp, bufp, updp, tstp, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.fastclip_last_hip_error.restype = C.c_char_p
     lib.fastclip_last_hip_error.argtypes = []
     _lib = lib
@@ -114,6 +137,20 @@ def make_buffers(**tensors) -> fastclip_buffers:
     return fastclip_buffers(*[_ptr(tensors.get(n)) for n in _BUF_FIELDS])
 
 
+def make_tau_update(*, optimizer, step, lr, beta1, beta2, eps=1e-8, tau_min=0.0, lr_drop_below=0.0,
+                    lr_drop_factor=1.0) -> fastclip_tau_update:
+    return fastclip_tau_update(C.sizeof(fastclip_tau_update), int(optimizer), int(step), float(lr), float(beta1),
+                               float(beta2), float(eps), float(tau_min), float(lr_drop_below), float(lr_drop_factor), 0.0)
+
+
+def make_tau_state(**tensors) -> fastclip_tau_state:
+    """Field name -> CUDA tensor (or raw device address, or None)."""
+    unknown = set(tensors) - set(_TAU_STATE_FIELDS)
+    if unknown:
+        raise TypeError("unknown temperature state field(s): %s" % sorted(unknown))
+    return fastclip_tau_state(*[_ptr(tensors.get(n)) for n in _TAU_STATE_FIELDS])
+
+
 def _stream(stream):
     if stream is None:
         import torch
@@ -134,6 +171,27 @@ def fastclip_step(cfg, bufs, workspace, workspace_bytes=None, stream=None, check
     """workspace: CUDA uint8 tensor (or raw address with workspace_bytes given)."""
     nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
     st = int(load().fastclip_step(C.byref(cfg), C.byref(bufs), _ptr(workspace), nbytes, _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+def fastclip_step_update_tau(cfg, bufs, upd, state, workspace, workspace_bytes=None, stream=None, check=True) -> int:
+    nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
+    st = int(load().fastclip_step_update_tau(C.byref(cfg), C.byref(bufs), C.byref(upd) if upd is not None else None,
+                                             C.byref(state) if state is not None else None, _ptr(workspace), nbytes,
+                                             _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+def fastclip_temperature_update(version, upd, state, idx, b, N, d_tau, d_tau_img, d_tau_txt, stream=None,
+                                check=True) -> int:
+    st = int(load().fastclip_temperature_update(int(version), C.byref(upd) if upd is not None else None,
+                                                C.byref(state) if state is not None else None, _ptr(idx), int(b),
+                                                int(N), _ptr(d_tau), _ptr(d_tau_img), _ptr(d_tau_txt),
+                                                _stream(stream)))
     if check and st != OK:
         raise FastclipError(st)
     return st

@@ -67,6 +67,38 @@ fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* buf
   return FASTCLIP_OK;
 }
 
+fastclip_status validate_tau_update(int32_t version, const fastclip_tau_update* upd, const fastclip_tau_state* st) {
+  if (!upd || !st) return FASTCLIP_ERR_NULL;
+  if (upd->struct_size != sizeof(fastclip_tau_update) || upd->reserved != 0.0f) return FASTCLIP_ERR_SHAPE;
+  if (version < FASTCLIP_V0 || version > FASTCLIP_V3) return FASTCLIP_ERR_VALUE;
+  if (upd->optimizer < FASTCLIP_TAU_SGDM || upd->optimizer > FASTCLIP_TAU_ADAMW) return FASTCLIP_ERR_VALUE;
+  const float f[7] = {upd->lr, upd->beta1, upd->beta2, upd->eps, upd->tau_min, upd->lr_drop_below, upd->lr_drop_factor};
+  for (float x : f)
+    if (bad_float(x)) return FASTCLIP_ERR_VALUE;
+  if (upd->step < 1 || upd->lr < 0.0f || upd->eps < 0.0f || upd->beta1 < 0.0f || upd->beta1 >= 1.0f ||
+      upd->beta2 < 0.0f || upd->beta2 >= 1.0f || upd->lr_drop_factor < 0.0f)
+    return FASTCLIP_ERR_VALUE;
+  const bool two = upd->optimizer == FASTCLIP_TAU_ADAMW || upd->optimizer == FASTCLIP_TAU_LAMB;
+  if (version == FASTCLIP_V2) {
+    if (!st->tau_img || !st->tau_txt || !st->m_img || !st->m_txt) return FASTCLIP_ERR_NULL;
+    if (two && (!st->v_img || !st->v_txt)) return FASTCLIP_ERR_NULL;
+  } else if (version != FASTCLIP_V1) {
+    if (!st->tau || !st->m || (two && !st->v)) return FASTCLIP_ERR_NULL;
+  }
+  return FASTCLIP_OK;
+}
+
+TauUpd make_tau_upd(const fastclip_tau_update& upd) {
+  TauUpd u;
+  u.optimizer = upd.optimizer;
+  u.lr = upd.lr; u.beta1 = upd.beta1; u.beta2 = upd.beta2; u.eps = upd.eps;
+  // bias corrections 1 / (1 - beta^step) of Proc. "parameter_update", in double on the host
+  u.corr1 = (float)(1.0 / (1.0 - pow((double)upd.beta1, (double)upd.step)));
+  u.corr2 = (float)(1.0 / (1.0 - pow((double)upd.beta2, (double)upd.step)));
+  u.tau_min = upd.tau_min; u.drop_below = upd.lr_drop_below; u.drop_factor = upd.lr_drop_factor;
+  return u;
+}
+
 void make_layout(const fastclip_config& cfg, Layout* L) {
   memset(L, 0, sizeof(*L));
   L->B = cfg.B; L->b = cfg.b; L->off = cfg.off; L->d = cfg.d; L->N = cfg.N;
@@ -128,13 +160,25 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
 }
 
 static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffers* bufs, void* workspace,
-                                size_t workspace_bytes, void* stream, float* phase_ms) {
+                                size_t workspace_bytes, void* stream, float* phase_ms,
+                                const fastclip_tau_update* upd = nullptr, const fastclip_tau_state* tst = nullptr) {
   fastclip_status st = validate(cfg, bufs);
   if (st != FASTCLIP_OK) return st;
   if (!bufs) return FASTCLIP_ERR_NULL;
   StepCtx c;
   c.cfg = *cfg;
   c.buf = *bufs;
+  memset(&c.tau_upd, 0, sizeof(c.tau_upd));
+  memset(&c.tau_st, 0, sizeof(c.tau_st));
+  if (upd || tst) {
+    st = validate_tau_update(cfg->version, upd, tst);
+    if (st != FASTCLIP_OK) return st;
+    // the step must read the very temperatures that the update writes
+    if (cfg->version == FASTCLIP_V2 ? (tst->tau_img != bufs->tau_img || tst->tau_txt != bufs->tau_txt)
+                                    : (cfg->version != FASTCLIP_V1 && tst->tau != bufs->tau))
+      return FASTCLIP_ERR_VALUE;
+    if (cfg->version != FASTCLIP_V1) { c.tau_upd = make_tau_upd(*upd); c.tau_st = *tst; }
+  }
   make_layout(*cfg, &c.L);
   if (!workspace) return FASTCLIP_ERR_NULL;
   if (workspace_bytes < c.L.total || ((uintptr_t)workspace & 255)) return FASTCLIP_ERR_WORKSPACE;
@@ -159,12 +203,15 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
     launch_state(c);                      mark(FASTCLIP_PHASE_STATE);
     launch_local_bf16(c);                 mark(FASTCLIP_PHASE_LOCAL);
     launch_contract_bf16(c);              mark(FASTCLIP_PHASE_CONTRACT);
-    launch_finalize_bf16(c);              mark(FASTCLIP_PHASE_FINALIZE);
+    launch_finalize_bf16(c);
   } else {
     launch_strips_f32(c);                 mark(FASTCLIP_PHASE_STRIPS);
     launch_state(c);                      mark(FASTCLIP_PHASE_STATE);
-    launch_grad_f32(c);                   mark(FASTCLIP_PHASE_FINALIZE);
+    launch_grad_f32(c);
   }
+  // global temperature: stepped once its gradient is complete (V2 was stepped in the state phase)
+  if (c.tau_upd.optimizer && c.cfg.version != FASTCLIP_V2) launch_tau_scalar(c.tau_upd, c.tau_st, c.buf.d_tau, c.s);
+  mark(FASTCLIP_PHASE_FINALIZE);
   fastclip_status rc = launch_status();
   if (phase_ms) {
     for (int i = 0; i < FASTCLIP_N_PHASES; ++i) phase_ms[i] = 0.0f;
@@ -203,6 +250,34 @@ fastclip_status fastclip_step_timed(const fastclip_config* cfg, const fastclip_b
                                     size_t workspace_bytes, void* stream, float* phase_ms) {
   if (!phase_ms) return FASTCLIP_ERR_NULL;
   return fc::run_step(cfg, bufs, workspace, workspace_bytes, stream, phase_ms);
+}
+
+fastclip_status fastclip_step_update_tau(const fastclip_config* cfg, const fastclip_buffers* bufs,
+                                         const fastclip_tau_update* upd, const fastclip_tau_state* state,
+                                         void* workspace, size_t workspace_bytes, void* stream) {
+  if (!upd || !state) return FASTCLIP_ERR_NULL;
+  return fc::run_step(cfg, bufs, workspace, workspace_bytes, stream, nullptr, upd, state);
+}
+
+fastclip_status fastclip_temperature_update(int32_t version, const fastclip_tau_update* upd,
+                                            const fastclip_tau_state* state, const int64_t* idx, int64_t b,
+                                            int64_t N, const float* d_tau, const float* d_tau_img,
+                                            const float* d_tau_txt, void* stream) {
+  const fastclip_status st = fc::validate_tau_update(version, upd, state);
+  if (st != FASTCLIP_OK) return st;
+  if (version == FASTCLIP_V1) return FASTCLIP_OK;
+  (void)hipGetLastError();
+  const fc::TauUpd u = fc::make_tau_upd(*upd);
+  if (version == FASTCLIP_V2) {
+    if (!idx || !d_tau_img || !d_tau_txt) return FASTCLIP_ERR_NULL;
+    if (b < 0 || N < 1 || b > ((int64_t)1 << 31) - 1024) return FASTCLIP_ERR_SHAPE;
+    if (b == 0) return FASTCLIP_OK;
+    fc::launch_tau_sparse(u, *state, idx, b, d_tau_img, d_tau_txt, (hipStream_t)stream);
+  } else {
+    if (!d_tau) return FASTCLIP_ERR_NULL;
+    fc::launch_tau_scalar(u, *state, d_tau, (hipStream_t)stream);
+  }
+  return fc::launch_status();
 }
 
 const char* fastclip_phase_name(int phase) {

@@ -50,12 +50,22 @@ void make_layout(const fastclip_config& cfg, Layout* L);
 
 // ---- kernel launchers (each enqueues on `s` and returns; errors are read by the caller
 //      through hipGetLastError) -----------------------------------------------------------
+// Proc. "parameter_update" for a temperature, as the kernels take it (bias corrections formed on the host).
+struct TauUpd {
+  int optimizer;      // 0: no update
+  float lr, beta1, beta2, eps, corr1, corr2, tau_min, drop_below, drop_factor;
+};
+fastclip_status validate_tau_update(int32_t version, const fastclip_tau_update* upd, const fastclip_tau_state* st);
+TauUpd make_tau_upd(const fastclip_tau_update& upd);
+
 struct StepCtx {
   fastclip_config cfg;
   fastclip_buffers buf;
   Layout L;
   char* ws;
   hipStream_t s;
+  TauUpd tau_upd;            // optimizer == 0 unless called through fastclip_step_update_tau
+  fastclip_tau_state tau_st;
 };
 
 void launch_prep(const StepCtx& c);            // s_ii, temperature gather / broadcast
@@ -72,5 +82,8 @@ void launch_state_flat(const int64_t* idx, int64_t n, int64_t N, float gamma, fl
                        const float* sum_img, const float* sum_txt, float* u_img, float* u_txt,
                        float* u_new_img, float* u_new_txt, hipStream_t s);
 void launch_check_indices(const int64_t* idx, int64_t b, int64_t N, void* ws, hipStream_t s);
+void launch_tau_scalar(const TauUpd& u, const fastclip_tau_state& st, const float* d_tau, hipStream_t s);
+void launch_tau_sparse(const TauUpd& u, const fastclip_tau_state& st, const int64_t* idx, int64_t b,
+                       const float* d_tau_img, const float* d_tau_txt, hipStream_t s);
 
 }  // namespace fc

@@ -223,6 +223,59 @@ void launch_strips_f32(const StepCtx& c) {
 }
 
 // ------------------------------------------------------------------------------------------
+// Proc. "parameter_update" for one temperature with weight decay 0, then the projection onto tau >= tau_0.
+// g: gradient estimator (Eqs. 8-10).  m, v: the optimizer's state (v only for AdamW / LAMB, pv may be NULL otherwise).
+__device__ inline void tau_step(const TauUpd& u, float* ptau, float* pm, float* pv, float g) {
+  const float tau = *ptau;
+  float m = *pm;
+  const float lr = tau < u.drop_below ? u.lr * u.drop_factor : u.lr;
+  float next;
+  if (u.optimizer == FASTCLIP_TAU_SGDM) {
+    m = fmaf(u.beta1, m, g);
+    next = tau - lr * m;
+  } else if (u.optimizer == FASTCLIP_TAU_LION) {
+    const float c = fmaf(u.beta1, m, (1.0f - u.beta1) * g);
+    m = fmaf(u.beta2, m, (1.0f - u.beta2) * g);
+    next = tau - lr * (c > 0.f ? 1.f : (c < 0.f ? -1.f : 0.f));
+  } else {                                             // AdamW; LAMB with layer factor 1
+    float v = *pv;
+    m = fmaf(u.beta1, m, (1.0f - u.beta1) * g);
+    v = fmaf(u.beta2, v, (1.0f - u.beta2) * g * g);
+    *pv = v;
+    next = tau - lr * ((m * u.corr1) / (sqrtf(v * u.corr2) + u.eps));
+  }
+  *pm = m;
+  *ptau = fmaxf(next, u.tau_min);
+}
+
+// Global temperature (V0, V3): one thread.
+__global__ void k_tau_scalar(TauUpd u, float* tau, float* m, float* v, const float* d_tau) {
+  if (threadIdx.x == 0 && blockIdx.x == 0) tau_step(u, tau, m, v, d_tau[0]);
+}
+
+// Individual temperatures (V2): one thread per local anchor, both sides; gathers and scatters by dataset index.
+__global__ void __launch_bounds__(256) k_tau_sparse(TauUpd u, const int64_t* __restrict__ idx, int64_t b,
+                                                    const float* __restrict__ g_img, const float* __restrict__ g_txt,
+                                                    float* tau_img, float* tau_txt, float* m_img, float* v_img,
+                                                    float* m_txt, float* v_txt) {
+  const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (r >= b) return;
+  const int64_t n = idx[r];
+  tau_step(u, tau_img + n, m_img + n, v_img ? v_img + n : nullptr, g_img[r]);
+  tau_step(u, tau_txt + n, m_txt + n, v_txt ? v_txt + n : nullptr, g_txt[r]);
+}
+
+void launch_tau_scalar(const TauUpd& u, const fastclip_tau_state& st, const float* d_tau, hipStream_t s) {
+  hipLaunchKernelGGL(k_tau_scalar, dim3(1), dim3(64), 0, s, u, st.tau, st.m, st.v, d_tau);
+}
+
+void launch_tau_sparse(const TauUpd& u, const fastclip_tau_state& st, const int64_t* idx, int64_t b,
+                       const float* d_tau_img, const float* d_tau_txt, hipStream_t s) {
+  hipLaunchKernelGGL(k_tau_sparse, dim3((unsigned)((b + 255) / 256)), dim3(256), 0, s, u, idx, b, d_tau_img,
+                     d_tau_txt, st.tau_img, st.tau_txt, st.m_img, st.v_img, st.m_txt, st.v_txt);
+}
+
+// ------------------------------------------------------------------------------------------
 // State phase.  Eq. 1 at the batch positions (first visit: stored 0 -> g), the coefficient
 // 1/(|B_k| |B_i-| (eps+u)) of Eqs. 2-7 (with the extra 1/tau of Eqs. 4-5 for V0), Eq. 9 per anchor,
 // and per-block partial sums of the two scalars that Eqs. 8 and 10 and the loss need.
@@ -237,6 +290,9 @@ struct StateArgs {
   int version;
   float *c1, *c2, *dcoef, *red;
   float *d_tau_img, *d_tau_txt, *g_img, *g_txt, *u_new_img, *u_new_txt;
+  // V2 with the temperature update in the same pass (optimizer != 0): the temperatures and their moments at idx
+  TauUpd tau_upd;
+  float *tau_img, *tau_txt, *m_img, *v_img, *m_txt, *v_txt;
 };
 
 __device__ inline float ema_update(float u_old, float g, float gamma) {
@@ -288,9 +344,15 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
       a.dcoef[r] = c1 * s[0] + c2 * s[2];          // c1 M g1 + c2 M g2
       const float l1 = logf(e1), l2 = logf(e2);
       if (a.version == FASTCLIP_V2) {
-        a.d_tau_img[r] = a.tau_scale * (l1 + a.rho - h1 / (t1 * e1));
-        a.d_tau_txt[r] = a.tau_scale * (l2 + a.rho - h2 / (t2 * e2));
+        const float gt1 = a.tau_scale * (l1 + a.rho - h1 / (t1 * e1));
+        const float gt2 = a.tau_scale * (l2 + a.rho - h2 / (t2 * e2));
+        a.d_tau_img[r] = gt1;
+        a.d_tau_txt[r] = gt2;
         lsum = t1 * (l1 + a.rho) + t2 * (l2 + a.rho);
+        if (a.tau_upd.optimizer) {   // Proc. "temperature_update" for sample n, same gather/scatter as u
+          tau_step(a.tau_upd, a.tau_img + n, a.m_img + n, a.v_img ? a.v_img + n : nullptr, gt1);
+          tau_step(a.tau_upd, a.tau_txt + n, a.m_txt + n, a.v_txt ? a.v_txt + n : nullptr, gt2);
+        }
       } else {
         lsum = l1 + l2;
       }
@@ -324,6 +386,10 @@ void launch_state(const StepCtx& c) {
   a.red = (float*)(c.ws + L.red);
   a.d_tau_img = c.buf.d_tau_img; a.d_tau_txt = c.buf.d_tau_txt; a.g_img = c.buf.g_img; a.g_txt = c.buf.g_txt;
   a.u_new_img = c.buf.u_new_img; a.u_new_txt = c.buf.u_new_txt;
+  a.tau_upd = c.tau_upd;
+  if (c.cfg.version != FASTCLIP_V2) a.tau_upd.optimizer = 0;
+  a.tau_img = c.tau_st.tau_img; a.tau_txt = c.tau_st.tau_txt;
+  a.m_img = c.tau_st.m_img; a.v_img = c.tau_st.v_img; a.m_txt = c.tau_st.m_txt; a.v_txt = c.tau_st.v_txt;
   hipLaunchKernelGGL(k_state, dim3((unsigned)L.nstate_blocks), dim3(256), 0, c.s, a);
 }
 

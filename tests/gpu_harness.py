@@ -100,6 +100,15 @@ class GpuStep:
         torch.cuda.synchronize()
         return out
 
+    def step_update_tau(self, gamma, upd, state):
+        """fastclip_step_update_tau with this object's buffers."""
+        cfg = self.config(gamma)
+        need = fc.fastclip_workspace_bytes(cfg)
+        if self.ws is None or self.ws.numel() < need:
+            self.ws = torch.full((need // 4 + 64,), float("nan"), dtype=torch.float32, device=DEV).view(torch.uint8)[:need]
+        fc.fastclip_step_update_tau(cfg, self.buffers(), upd, state, self.ws)
+        torch.cuda.synchronize()
+
     def outputs(self):
         o = {k: getattr(self, k).cpu().numpy().astype(np.float64) for k in
              ("d_img", "d_txt", "g_img", "g_txt", "u_new_img", "u_new_txt", "d_tau_img", "d_tau_txt")}

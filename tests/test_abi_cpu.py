@@ -157,3 +157,37 @@ def test_status_strings_and_phase_names():
     assert len(seen) == 8 and "ok" in seen
     assert fc.fastclip_status_string(99) == "unknown status"
     assert fc.fastclip_phase_name(1) == "strips" and fc.fastclip_phase_name(7) == "unused"
+
+
+def test_temperature_update_argument_errors():
+    good = dict(optimizer=fc.TAU_ADAMW, step=1, lr=1e-3, beta1=0.9, beta2=0.999)
+    upd = fc.make_tau_update(**good)
+    assert C.sizeof(fc.fastclip_tau_update) == 48 and C.sizeof(fc.fastclip_tau_state) == 9 * 8
+    st3 = fc.make_tau_state(tau=0x1000, m=0x2000, v=0x3000)
+    st2 = fc.make_tau_state(tau_img=0x1000, tau_txt=0x2000, m_img=0x3000, v_img=0x4000, m_txt=0x5000, v_txt=0x6000)
+    call = lambda ver, u, s, idx=0x100, b=4, d=0x200, di=0x300, dt=0x400: fc.fastclip_temperature_update(
+        ver, u, s, idx, b, 10, d, di, dt, stream=0, check=False)
+    assert call(fc.V1, upd, st3) == fc.OK                                   # constant temperature: nothing to do
+    assert call(fc.V3, None, st3) == fc.ERR_NULL and call(fc.V3, upd, None) == fc.ERR_NULL
+    assert call(fc.V3, upd, fc.make_tau_state(tau=0x1000, m=0x2000)) == fc.ERR_NULL        # AdamW needs v
+    assert call(fc.V3, upd, st3, d=None) == fc.ERR_NULL
+    assert call(fc.V2, upd, st3) == fc.ERR_NULL                             # V2 needs the per-sample arrays
+    assert call(fc.V2, upd, st2, idx=None) == fc.ERR_NULL
+    assert call(fc.V2, upd, st2, b=-1) == fc.ERR_SHAPE
+    assert call(fc.V2, upd, st2, b=0) == fc.OK
+    assert call(7, upd, st3) == fc.ERR_VALUE
+    for bad in (dict(optimizer=0), dict(optimizer=5), dict(step=0), dict(lr=-1.0), dict(beta1=1.0), dict(beta2=-0.1),
+                dict(lr=float("nan")), dict(eps=-1.0)):
+        assert call(fc.V3, fc.make_tau_update(**{**good, **bad}), st3) == fc.ERR_VALUE, bad
+    u = fc.make_tau_update(**good)
+    u.struct_size = 8
+    assert call(fc.V3, u, st3) == fc.ERR_SHAPE
+    # SGD with momentum and Lion keep no second moment
+    sg = fc.make_tau_update(**{**good, "optimizer": fc.TAU_SGDM})
+    assert fc.fastclip_validate(good_cfg(), None) == fc.OK
+    # the fused entry point checks the step's arguments first, then that the step reads the tensors it updates
+    cfg = good_cfg(version=fc.V3)
+    bufs = fake_bufs(cfg)
+    assert fc.fastclip_step_update_tau(cfg, bufs, sg, fc.make_tau_state(tau=0x999, m=0x2000), 0x1000, 1 << 40,
+                                       stream=0, check=False) == fc.ERR_VALUE
+    assert fc.fastclip_step_update_tau(cfg, bufs, None, None, 0x1000, 1 << 40, stream=0, check=False) == fc.ERR_NULL

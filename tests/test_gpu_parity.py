@@ -8,11 +8,12 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import V0, V1, V2, V3, ema_update, fcco_step, gamma_cosine
+from oracle import (ADAMW, LAMB, LION, SGDM, V0, V1, V2, V3, ema_update, fcco_step, gamma_cosine,
+                    temperature_update)
 from paper_2407_01445_amd import binding as fc
 from paper_2407_01445_amd.workloads import WORKLOADS, draw_indices, make_embeddings, step_seed
 
-from gpu_harness import DEV, GpuStep, compare, rel_each, rel_l2
+from gpu_harness import DEV, GpuStep, compare, rel_each, rel_inf, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -225,6 +226,112 @@ def test_gathered_state_with_whole_batch_is_the_plain_step():
         res.append((g.d_img.cpu(), g.d_txt.cpu(), g.u_img.cpu(), g.loss.cpu(), g.d_tau.cpu()))
     for x, y in zip(*res):
         assert torch.equal(x, y)
+
+
+# ------------------------------------------------------------------------------- temperature update (Alg. 1 line 12)
+OPTIMIZERS = [(SGDM, dict(lr=1e-3, beta1=0.9, beta2=0.0)), (LAMB, dict(lr=1e-2, beta1=0.9, beta2=0.98, eps=1e-6)),
+              (LION, dict(lr=1e-3, beta1=0.9, beta2=0.99)), (ADAMW, dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8))]
+
+
+@pytest.mark.parametrize("opt,hp", OPTIMIZERS)
+def test_temperature_update_alone(opt, hp):
+    """Proc. temperature_update from given gradients: per-sample (V2) and global (V3) temperatures."""
+    N, b, step = 5000, 300, 7
+    rng = np.random.default_rng(100 + opt)
+    idx = draw_indices(55, b, N)
+    f32 = lambda lo, hi, n: rng.uniform(lo, hi, n).astype(np.float32)
+    host = dict(tau_img=f32(0.02, 0.1, N), tau_txt=f32(0.02, 0.1, N), m_img=f32(-1, 1, N), m_txt=f32(-1, 1, N),
+                v_img=f32(0.01, 2, N), v_txt=f32(0.01, 2, N))
+    g_img, g_txt = f32(-3, 3, b), f32(-3, 3, b)
+    extra = dict(tau_min=0.025, lr_drop_below=0.03, lr_drop_factor=1.0 / 3.0)
+    dev = {k: torch.from_numpy(v).to(DEV) for k, v in host.items()}
+    upd = fc.make_tau_update(optimizer=opt, step=step, **hp, **extra)
+    fc.fastclip_temperature_update(V2, upd, fc.make_tau_state(**dev), torch.from_numpy(idx).to(DEV), b, N, None,
+                                   torch.from_numpy(g_img).to(DEV), torch.from_numpy(g_txt).to(DEV))
+    torch.cuda.synchronize()
+    want = {k: v.astype(np.float64) for k, v in host.items()}
+    temperature_update(V2, {"d_tau_img": g_img.astype(np.float64), "d_tau_txt": g_txt.astype(np.float64)},
+                       optimizer=opt, step=step, idx=idx, **hp, **extra, **want)
+    mask = np.ones(N, bool)
+    mask[idx] = False
+    for k in host:
+        got = dev[k].cpu().numpy()
+        assert np.array_equal(got[mask].view(np.uint32), host[k][mask].view(np.uint32)), k      # untouched entries
+        if k.startswith("v_") and opt in (SGDM, LION):
+            assert np.array_equal(got.view(np.uint32), host[k].view(np.uint32))                  # no second moment
+            continue
+        # temperatures: per element.  Moments: beta m + (1 - beta) G can cancel, so the fp32 rounding error is
+        # bounded relative to the operands (max norm), not to each result
+        if k.startswith("tau"):
+            assert rel_each(got[idx], want[k][idx]) <= 1e-5, k
+        else:
+            assert rel_inf(got[idx], want[k][idx]) <= 1e-6, k
+    assert (dev["tau_img"].cpu().numpy()[idx] >= np.float32(0.025)).all()
+    # global temperature, below the threshold where the learning rate drops
+    for tau0 in (0.07, 0.029):
+        t, m, v, g = (torch.tensor([x], dtype=torch.float32, device=DEV) for x in (tau0, 0.3, 0.5, -1.7))
+        fc.fastclip_temperature_update(V3, upd, fc.make_tau_state(tau=t, m=m, v=v), None, 0, 1, g, None, None)
+        torch.cuda.synchronize()
+        wt, wm, wv = temperature_update(V3, {"d_tau": float(np.float32(-1.7))}, optimizer=opt, step=step,
+                                        tau=float(np.float32(tau0)), m=float(np.float32(0.3)),
+                                        v=float(np.float32(0.5)), **hp, **extra)
+        assert t.item() == pytest.approx(wt, rel=1e-5) and m.item() == pytest.approx(wm, rel=1e-5)
+        if opt in (ADAMW, LAMB):
+            assert v.item() == pytest.approx(wv, rel=1e-5)
+
+
+@pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (64, 64, 0, 32)), ("bf16", TOL_BF16, (700, 300, 133, 72))])
+@pytest.mark.parametrize("version", [V2, V3, V0])
+def test_step_with_temperature_update_three_iterations(dtype, tol, shape, version):
+    """fastclip_step_update_tau: step + temperature update per iteration, temperatures and moments carried on the
+    device, against the oracle's step followed by Proc. temperature_update."""
+    B, b, off, d = shape
+    N = 2000
+    rng = np.random.default_rng(9 + version)
+    hp = dict(lr=2e-3, beta1=0.9, beta2=0.98, eps=1e-6)
+    extra = dict(tau_min=0.01, lr_drop_below=0.03, lr_drop_factor=1.0 / 3.0)
+    t_img0 = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt0 = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
+                tau_grad_scale=1.0, tau_img0=t_img0, tau_txt0=t_txt0)
+    z = lambda n: torch.zeros(n, dtype=torch.float32, device=DEV)
+    if version == V2:
+        st_dev = dict(tau_img=g.tau_img, tau_txt=g.tau_txt, m_img=z(N), v_img=z(N), m_txt=z(N), v_txt=z(N))
+    else:
+        st_dev = dict(tau=g.tau, m=z(1), v=z(1))
+    state = fc.make_tau_state(**st_dev)
+    u_img, u_txt = np.zeros(N), np.zeros(N)
+    w = dict(tau=float(np.float32(0.07)), m=0.0, v=0.0, tau_img=t_img0.astype(np.float64),
+             tau_txt=t_txt0.astype(np.float64), m_img=np.zeros(N), v_img=np.zeros(N), m_txt=np.zeros(N),
+             v_txt=np.zeros(N))
+    for it in range(3):
+        img, txt = make_embeddings(300 + it, B, d, 0.5, dtype)
+        idx = draw_indices(400 + it, b, N)
+        g.set_inputs(img, txt, idx)
+        g.step_update_tau(0.7, fc.make_tau_update(optimizer=ADAMW, step=it + 1, **hp, **extra), state)
+        want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, u_img, u_txt, version=version,
+                         gamma=0.7, eps=g.eps, rho=g.rho, tau=w["tau"], tau_img=w["tau_img"], tau_txt=w["tau_txt"],
+                         tau_grad_scale=1.0)
+        compare(g.outputs(), want, version, tol, "tau update %s v%d it %d" % (dtype, version, it))
+        if version == V2:
+            temperature_update(V2, want, optimizer=ADAMW, step=it + 1, idx=idx, tau_img=w["tau_img"],
+                               tau_txt=w["tau_txt"], m_img=w["m_img"], v_img=w["v_img"], m_txt=w["m_txt"],
+                               v_txt=w["v_txt"], **hp, **extra)
+            for k in ("tau_img", "tau_txt", "m_img", "m_txt", "v_img", "v_txt"):
+                got = st_dev[k].cpu().numpy().astype(np.float64)
+                lim = 1e-4 if k.startswith("tau") else (tol if k.startswith("m") else 2 * tol)
+                assert rel_inf(got, w[k]) <= lim, (k, it, rel_inf(got, w[k]))
+                untouched = np.ones(N, bool)
+                untouched[w["m_img"] != 0] = False
+                assert np.array_equal(got[untouched], (t_img0 if k == "tau_img" else t_txt0 if k == "tau_txt"
+                                                       else np.zeros(N, np.float32))[untouched].astype(np.float64)), k
+        else:
+            w["tau"], w["m"], w["v"] = temperature_update(version, want, optimizer=ADAMW, step=it + 1, tau=w["tau"],
+                                                          m=w["m"], v=w["v"], **hp, **extra)
+            assert st_dev["tau"].item() == pytest.approx(w["tau"], rel=1e-4)
+            assert st_dev["m"].item() == pytest.approx(w["m"], rel=tol) and st_dev["v"].item() == pytest.approx(w["v"], rel=2 * tol)
+    assert st_dev["tau_img" if version == V2 else "tau"].cpu().numpy().std() >= 0      # still finite
+    assert np.isfinite(g.loss.item())
 
 
 # ------------------------------------------------------------------------------- full-size workloads
