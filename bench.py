@@ -28,7 +28,8 @@ PEAK_HBM_BYTES = 8.0e12      # MI355X HBM3E
 # the summaries are kept under profiles/), keyed by (workload, phase); absent = not measured.
 MEASURED_TRAFFIC = {
     ("cfg4", "strips"): (98627.5 * 2.0 + 133120.0) * 1024,
-    ("cfg4", "contract"): (135443.5 * 2.0 + 65536.0) * 1024,
+    ("cfg4", "contract"): (135454.6 * 2.0 + 65536.0) * 1024,
+    ("cfg4", "state_flat_2^24"): (2225831.1 * 2.0 + 1180158.5) * 1024,
 }
 
 
@@ -194,6 +195,10 @@ def main():
                                "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s",
                                "frac": round(alg_bytes / (ms * 1e-3) / PEAK_HBM_BYTES, 4),
                                "algorithmic_bytes_per_index": 40}
+        tr = MEASURED_TRAFFIC.get((name, "state_flat_2^24"))
+        if tr is not None:      # what the memory system moves for these random 4-byte accesses (rocprofv3 counters)
+            out["state_update"]["traffic"] = tr
+            out["state_update"]["traffic_frac_of_peak"] = round(tr / (ms * 1e-3) / PEAK_HBM_BYTES, 4)
         del big_idx, s1, s2, o1, o2
 
     # ---- the CPU oracle on the same workload (one full step), host cores
