@@ -25,7 +25,9 @@ notes of this repository):
   * the inner average runs over the GLOBAL batch without the anchor and is
     divided by M = B - 1 (Proc. 1, Eq. 1, Eqs. 2-3 all use B_{i-});
   * similarities are plain dot products of the rows as given (inputs are
-    already L2-normalised by the caller);
+    already L2-normalised by the caller); if the caller also hands over the
+    norms that the local rows had before normalisation, the gradients are taken
+    through the normalisation, with respect to the raw rows;
   * u^0 = 0 marks "never visited": a stored value that is exactly zero is
     replaced by g whatever gamma is;
   * the estimator uses u^{t+1} as a constant (no gradient through u) and the
@@ -100,7 +102,8 @@ def ema_update(u_arr, idx, g, gamma):
 
 def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0.0,
               tau=None, tau_img=None, tau_txt=None, tau_grad_scale=1.0,
-              u_glob_img=None, u_glob_txt=None, tau_glob_img=None, tau_glob_txt=None):
+              u_glob_img=None, u_glob_txt=None, tau_glob_img=None, tau_glob_txt=None,
+              norm_img=None, norm_txt=None):
     """One FCCO step of worker k.  Updates u_img / u_txt IN PLACE at idx.
 
     img, txt   [B, d] global image / text embeddings (any float dtype; used as float64)
@@ -117,6 +120,9 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
                Eq. 3 / 5 / 7 runs over every global anchor instead of the local ones only.
     tau_glob_img/txt  [B], V2 with u_glob_* only: tau_1, tau_2 of every row of the global
                batch (entries of the local rows ignored).
+    norm_img/txt  optional [b]: the rows of img / txt are the L2-normalised encoder outputs (cosine
+               similarity, Sec. 3) and these are the norms the local rows had before; d_img / d_txt
+               are then gradients with respect to the rows BEFORE normalisation.
     Returns a dict with g_img, g_txt, h_img, h_txt, u_new_img, u_new_txt, d_img,
     d_txt ([b, d]), loss, and d_tau (v0, v3) or d_tau_img, d_tau_txt ([b], v2).
     """
@@ -214,6 +220,14 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
             w1[p] = 0.0
             d_img[r] += w2 @ txt
             d_txt[r] += w1 @ img
+
+    if norm_img is not None or norm_txt is not None:
+        # e^ = e / |e|:  d e^ / d e = (Id - e^ e^T) / |e|, applied to the gradient with respect to e^
+        n1 = np.asarray(norm_img, dtype=np.float64)
+        n2 = np.asarray(norm_txt, dtype=np.float64)
+        assert n1.shape == (b,) and n2.shape == (b,)
+        d_img = (d_img - I_loc * np.einsum("rk,rk->r", I_loc, d_img)[:, None]) / n1[:, None]
+        d_txt = (d_txt - T_loc * np.einsum("rk,rk->r", T_loc, d_txt)[:, None]) / n2[:, None]
 
     out = dict(g_img=g1, g_txt=g2, h_img=h1, h_txt=h2, u_new_img=u1, u_new_txt=u2,
                d_img=d_img, d_txt=d_txt)

@@ -585,3 +585,30 @@ def test_temperature_update_procedure():
     np.testing.assert_allclose(t2[idx], [0.06, 0.045, 0.045], rtol=1e-6)            # 0.04 projected up to tau_0
     np.testing.assert_allclose(m1[idx], 0.1 * g["d_tau_img"], rtol=1e-12)
     np.testing.assert_allclose(v2[idx], 0.001 * g["d_tau_txt"] ** 2, rtol=1e-9)
+
+
+# --------------------------------------------- 10. gradients through the L2 normalisation (cosine similarity)
+@pytest.mark.parametrize("version", [V0, V2, V3])
+@pytest.mark.parametrize("B,b,off", [(9, 9, 0), (10, 4, 3)])
+def test_gradients_through_normalisation_match_finite_differences(version, B, b, off):
+    """Raw encoder outputs, normalised inside the loss: central differences with respect to the RAW local rows."""
+    d, N, eps, rho, tau = 4, 30, 1e-3, 6.0, 0.12
+    rng = np.random.default_rng(B + version)
+    raw_i = rng.standard_normal((B, d)) * rng.uniform(0.5, 3.0, (B, 1))       # rows of very different length
+    raw_t = raw_i + 0.5 * rng.standard_normal((B, d))
+    idx = rng.choice(N, b, replace=False)
+    t_img, t_txt = rng.uniform(0.08, 0.2, N), rng.uniform(0.08, 0.2, N)
+    unit = lambda a: a / np.linalg.norm(a, axis=1, keepdims=True)
+    rows = list(range(off, off + b))
+    out = fcco_step(unit(raw_i), unit(raw_t), off, b, idx, np.zeros(N), np.zeros(N), version=version, gamma=1.0,
+                    eps=eps, rho=rho, tau=tau, tau_img=t_img, tau_txt=t_txt,
+                    norm_img=np.linalg.norm(raw_i[rows], axis=1), norm_txt=np.linalg.norm(raw_t[rows], axis=1))
+
+    def loss():
+        return direct_loss(unit(raw_i), unit(raw_t), off, b, version, eps, rho, tau=tau, tau1=t_img[idx],
+                           tau2=t_txt[idx])
+
+    np.testing.assert_allclose(out["d_img"], fd_rows(loss, raw_i, rows), rtol=5e-6, atol=1e-9)
+    np.testing.assert_allclose(out["d_txt"], fd_rows(loss, raw_t, rows), rtol=5e-6, atol=1e-9)
+    # a gradient through the normalisation has no component along the row itself
+    assert np.max(np.abs(np.einsum("rk,rk->r", out["d_img"], raw_i[rows]))) < 1e-12
