@@ -108,6 +108,11 @@ typedef struct {
   const float*   tau_glob_img; /* [B] FASTCLIP_GATHERED_STATE with V2: tau_1 of every global row (local entries
                                   ignored); NULL otherwise */
   const float*   tau_glob_txt; /* [B] likewise tau_2 */
+  const float*   norm_img;   /* [b] optional (both or neither): the rows of img_glob / txt_glob are L2-normalised encoder
+                                outputs (cosine similarity, Sec. 3) and norm_img[r] is the norm that local image row r
+                                had before.  d_img / d_txt are then gradients with respect to the rows BEFORE
+                                normalisation: (d - e (e . d)) / norm, e = the normalised row as given */
+  const float*   norm_txt;   /* [b] likewise for the local text rows */
 } fastclip_buffers;
 
 /* Bytes of device workspace fastclip_step needs for this configuration; 0 if the

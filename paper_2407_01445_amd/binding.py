@@ -29,7 +29,7 @@ class fastclip_config(C.Structure):
 
 _BUF_FIELDS = ["img_glob", "txt_glob", "idx", "u_img", "u_txt", "tau", "tau_img", "tau_txt", "d_img", "d_txt",
                "loss", "d_tau", "d_tau_img", "d_tau_txt", "g_img", "g_txt", "u_new_img", "u_new_txt",
-               "u_glob_img", "u_glob_txt", "tau_glob_img", "tau_glob_txt"]
+               "u_glob_img", "u_glob_txt", "tau_glob_img", "tau_glob_txt", "norm_img", "norm_txt"]
 
 
 class fastclip_buffers(C.Structure):

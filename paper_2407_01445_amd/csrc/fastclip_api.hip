@@ -55,6 +55,7 @@ fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* buf
       if (!bufs->tau) return FASTCLIP_ERR_NULL;
       if ((cfg->version == FASTCLIP_V0 || cfg->version == FASTCLIP_V3) && !bufs->d_tau) return FASTCLIP_ERR_NULL;
     }
+    if ((bufs->norm_img == nullptr) != (bufs->norm_txt == nullptr)) return FASTCLIP_ERR_NULL;
     if (cfg->flags & FASTCLIP_GATHERED_STATE) {
       if (!bufs->u_glob_img || !bufs->u_glob_txt) return FASTCLIP_ERR_NULL;
       if (cfg->version == FASTCLIP_V2 && (!bufs->tau_glob_img || !bufs->tau_glob_txt)) return FASTCLIP_ERR_NULL;

@@ -448,7 +448,9 @@ __global__ void __launch_bounds__(256) k_grad_f32(const float* __restrict__ img,
                                                   float* __restrict__ d_txt, const float* __restrict__ red, int nblocks,
                                                   int version, const float* __restrict__ tau, float rho,
                                                   float* __restrict__ loss, float* __restrict__ d_tau,
-                                                  const float* __restrict__ F1, const float* __restrict__ F2) {
+                                                  const float* __restrict__ F1, const float* __restrict__ F2,
+                                                  const float* __restrict__ norm_img,
+                                                  const float* __restrict__ norm_txt) {
   const int64_t r = blockIdx.x;
   const int side = blockIdx.y;
   const int64_t p = off + r;
@@ -484,6 +486,22 @@ __global__ void __launch_bounds__(256) k_grad_f32(const float* __restrict__ img,
     }
     __syncthreads();
   }
+  if (norm_img) {
+    // gradient through e^ = e / |e|: out := (out - e^ (e^ . out)) / |e|, e^ = this side's own row (see k_finalize_bf16)
+    const float* ep = side == 0 ? img + p * ld_img : txt + p * ld_txt;
+    double dot = 0.0;
+    for (int64_t col = threadIdx.x; col < d; col += 256) dot += (double)out[col] * (double)ep[col];
+    red2[threadIdx.x] = dot;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if ((int)threadIdx.x < w) red2[threadIdx.x] += red2[threadIdx.x + w];
+      __syncthreads();
+    }
+    dot = red2[0];
+    const double inv = 1.0 / (double)(side == 0 ? norm_img[r] : norm_txt[r]);
+    for (int64_t col = threadIdx.x; col < d; col += 256)
+      out[col] = (float)(((double)out[col] - dot * (double)ep[col]) * inv);
+  }
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64)
     write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
 }
@@ -497,7 +515,7 @@ void launch_grad_f32(const StepCtx& c) {
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
                      L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau,
                      L.gathered ? (const float*)(c.ws + L.F[0]) : nullptr,
-                     L.gathered ? (const float*)(c.ws + L.F[1]) : nullptr);
+                     L.gathered ? (const float*)(c.ws + L.F[1]) : nullptr, c.buf.norm_img, c.buf.norm_txt);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -513,7 +531,8 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
                                                        const float* __restrict__ red, int nblocks, int version,
                                                        const float* __restrict__ tau, float rho, float* __restrict__ loss,
                                                        float* __restrict__ d_tau, const float* __restrict__ OF1,
-                                                       const float* __restrict__ OF2) {
+                                                       const float* __restrict__ OF2, const float* __restrict__ norm_img,
+                                                       const float* __restrict__ norm_txt) {
   const int64_t r = blockIdx.x;
   const int side = blockIdx.y;
   const int64_t p = off + r;
@@ -546,6 +565,35 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
     o.w = fmaf(cown, acc.w, rem.w) - dc * x3;
     *(float4*)(out + c0) = o;
   }
+  if (norm_img) {
+    // gradient through e^ = e / |e| (cosine similarity, Sec. 3): out := (out - e^ (e^ . out)) / |e|, e^ = this side's own row
+    __shared__ float part[4];
+    const bf16_t* ep = side == 0 ? img + p * ld_img : txt + p * ld_txt;
+    __syncthreads();                       // the block's own writes of out[] are visible to it from here on
+    float dot = 0.f;
+    for (int64_t c0 = (int64_t)threadIdx.x * 4; c0 < d; c0 += 1024) {
+      const float4 o = *(const float4*)(out + c0);
+      const uint2 er = *(const uint2*)(ep + c0);
+      dot = fmaf(o.x, __uint_as_float(er.x << 16), dot);
+      dot = fmaf(o.y, __uint_as_float(er.x & 0xffff0000u), dot);
+      dot = fmaf(o.z, __uint_as_float(er.y << 16), dot);
+      dot = fmaf(o.w, __uint_as_float(er.y & 0xffff0000u), dot);
+    }
+    dot = wave_sum(dot);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = dot;
+    __syncthreads();
+    dot = (part[0] + part[1]) + (part[2] + part[3]);
+    const float inv = 1.0f / (side == 0 ? norm_img[r] : norm_txt[r]);
+    for (int64_t c0 = (int64_t)threadIdx.x * 4; c0 < d; c0 += 1024) {
+      float4 o = *(const float4*)(out + c0);
+      const uint2 er = *(const uint2*)(ep + c0);
+      o.x = (o.x - dot * __uint_as_float(er.x << 16)) * inv;
+      o.y = (o.y - dot * __uint_as_float(er.x & 0xffff0000u)) * inv;
+      o.z = (o.z - dot * __uint_as_float(er.y << 16)) * inv;
+      o.w = (o.w - dot * __uint_as_float(er.y & 0xffff0000u)) * inv;
+      *(float4*)(out + c0) = o;
+    }
+  }
   if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64)
     write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
 }
@@ -559,7 +607,7 @@ void launch_finalize_bf16(const StepCtx& c) {
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
                      L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau,
                      L.gathered ? (const float*)(c.ws + L.OpartF[0]) : nullptr,
-                     L.gathered ? (const float*)(c.ws + L.OpartF[1]) : nullptr);
+                     L.gathered ? (const float*)(c.ws + L.OpartF[1]) : nullptr, c.buf.norm_img, c.buf.norm_txt);
 }
 
 // ------------------------------------------------------------------------------------------

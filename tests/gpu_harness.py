@@ -28,7 +28,8 @@ class GpuStep:
     """Device-resident state and buffers for repeated fastclip_step calls on one workload shape."""
 
     def __init__(self, *, B, b, off, d, N, dtype, version, eps, rho=0.0, tau=0.07, tau_grad_scale=1.0,
-                 ld_img=None, ld_txt=None, u_img0=None, u_txt0=None, tau_img0=None, tau_txt0=None, gathered=None):
+                 ld_img=None, ld_txt=None, u_img0=None, u_txt0=None, tau_img0=None, tau_txt0=None, gathered=None,
+                 norms=None):
         """gathered: None, or dict(u_img=[B], u_txt=[B], tau_img=[B] or None, tau_txt=[B] or None) = the state
         gathered from all workers (the step then runs with FASTCLIP_GATHERED_STATE)."""
         self.B, self.b, self.off, self.d, self.N = B, b, off, d, N
@@ -58,6 +59,10 @@ class GpuStep:
         self.ws = None
         self.flags = 0
         self.u_glob_img = self.u_glob_txt = self.tau_glob_img = self.tau_glob_txt = None
+        self.norm_img = self.norm_txt = None
+        if norms is not None:       # (norm_img [b], norm_txt [b]): gradients through the L2 normalisation
+            self.norm_img = torch.from_numpy(np.asarray(norms[0], np.float32)).to(DEV)
+            self.norm_txt = torch.from_numpy(np.asarray(norms[1], np.float32)).to(DEV)
         if gathered is not None:
             self.flags = fc.GATHERED_STATE
             up = lambda a: None if a is None else torch.from_numpy(np.asarray(a, np.float32)).to(DEV)
@@ -82,7 +87,7 @@ class GpuStep:
                                d_tau_txt=self.d_tau_txt, g_img=self.g_img, g_txt=self.g_txt,
                                u_new_img=self.u_new_img, u_new_txt=self.u_new_txt, u_glob_img=self.u_glob_img,
                                u_glob_txt=self.u_glob_txt, tau_glob_img=self.tau_glob_img,
-                               tau_glob_txt=self.tau_glob_txt)
+                               tau_glob_txt=self.tau_glob_txt, norm_img=self.norm_img, norm_txt=self.norm_txt)
 
     def step(self, gamma, timed=False):
         cfg = self.config(gamma)

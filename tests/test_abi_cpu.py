@@ -40,7 +40,7 @@ def test_library_exports_every_declared_function():
 
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(fc.fastclip_config) == 16 + 7 * 8 + 4 * 4
-    assert C.sizeof(fc.fastclip_buffers) == 22 * 8
+    assert C.sizeof(fc.fastclip_buffers) == 24 * 8
 
 
 def test_valid_config_and_workspace_size():
@@ -117,6 +117,13 @@ def test_gathered_state_needs_its_arrays_and_more_workspace(version):
 def test_required_pointers(version, field, status):
     cfg = good_cfg(version=version)
     assert fc.fastclip_validate(cfg, fake_bufs(cfg, **{field: None})) == status
+
+
+def test_norms_come_in_pairs():
+    cfg = good_cfg()
+    assert fc.fastclip_validate(cfg, fake_bufs(cfg, norm_img=None, norm_txt=None)) == fc.OK
+    assert fc.fastclip_validate(cfg, fake_bufs(cfg, norm_img=None)) == fc.ERR_NULL
+    assert fc.fastclip_validate(cfg, fake_bufs(cfg, norm_txt=None)) == fc.ERR_NULL
 
 
 def test_misaligned_matrices_and_workspace():

@@ -334,6 +334,53 @@ def test_step_with_temperature_update_three_iterations(dtype, tol, shape, versio
     assert np.isfinite(g.loss.item())
 
 
+# ------------------------------------------------------------------------------- cosine similarity, MBCL
+@pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (37, 11, 13, 19)), ("bf16", TOL_BF16, (700, 300, 133, 72)),
+                                             ("bf16", TOL_BF16, (768, 512, 256, 128))])
+@pytest.mark.parametrize("version", [V2, V3])
+def test_gradients_through_normalisation(dtype, tol, shape, version):
+    B, b, off, d = shape
+    N = 3000
+    rng = np.random.default_rng(B + version)
+    img, txt = make_embeddings(B + 5, B, d, 0.5, dtype)
+    idx = draw_indices(B + 6, b, N)
+    n_img = rng.uniform(0.3, 20.0, b).astype(np.float32)          # what the rows measured before normalisation
+    n_txt = rng.uniform(0.3, 20.0, b).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
+                tau_grad_scale=1.0 / N, tau_img0=t_img, tau_txt0=t_txt, norms=(n_img, n_txt))
+    g.set_inputs(img, txt, idx)
+    g.step(0.6)
+    want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, np.zeros(N), np.zeros(N),
+                     version=version, gamma=0.6, eps=g.eps, rho=g.rho, tau=float(np.float32(0.07)),
+                     tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64), tau_grad_scale=g.scale,
+                     norm_img=n_img.astype(np.float64), norm_txt=n_txt.astype(np.float64))
+    compare(g.outputs(), want, version, tol, "normalised %s %s v%d" % (dtype, shape, version))
+
+
+@pytest.mark.parametrize("dtype,tol,B,d", [("f32", TOL_F32, 64, 32), ("bf16", TOL_BF16, 520, 64)])
+def test_mini_batch_contrastive_loss_is_a_special_case(dtype, tol, B, d):
+    """The OpenCLIP-style mini-batch contrastive loss needs no code of its own: with zero state (u = g), V1 and
+    eps = 1/M the step's gradient is that of tau (CE_rows(S/tau) + CE_cols(S/tau)) (softmax cross-entropy with the
+    pairs on the diagonal), here taken from torch's log_softmax and autograd in fp64 on the CPU."""
+    tau = float(np.float32(0.07))
+    img, txt = make_embeddings(B + 31, B, d, 0.5, dtype)
+    g = GpuStep(B=B, b=B, off=0, d=d, N=B, dtype=dtype, version=V1, eps=1.0 / (B - 1), tau=0.07)
+    g.set_inputs(img, txt, np.arange(B))
+    g.step(0.3)                                                # zero state: the first visit stores g whatever gamma is
+    I = torch.tensor(img.astype(np.float64), requires_grad=True)
+    T = torch.tensor(txt.astype(np.float64), requires_grad=True)
+    S = I @ T.T / tau
+    diag = torch.arange(B)
+    ce = -(torch.log_softmax(S, dim=1)[diag, diag] + torch.log_softmax(S, dim=0)[diag, diag]).mean()
+    (tau * ce).backward()
+    assert rel_inf(g.d_img.cpu().numpy(), I.grad.numpy()) <= tol and rel_l2(g.d_img.cpu().numpy(), I.grad.numpy()) <= tol
+    assert rel_inf(g.d_txt.cpu().numpy(), T.grad.numpy()) <= tol and rel_l2(g.d_txt.cpu().numpy(), T.grad.numpy()) <= tol
+    # loss: tau/B sum [log(eps + g1) + log(eps + g2)] = tau (CE - 2 log M)
+    assert g.loss.item() == pytest.approx(tau * (ce.item() - 2.0 * np.log(B - 1)), rel=tol, abs=tol * tau)
+
+
 # ------------------------------------------------------------------------------- full-size workloads
 def run_workload(name, steps_checked, n_steps, gathered=False):
     w = WORKLOADS[name]
