@@ -33,7 +33,7 @@ extern "C" {
 typedef enum {
   FASTCLIP_OK = 0,
   FASTCLIP_ERR_NULL = 1,        /* a required pointer is NULL */
-  FASTCLIP_ERR_SHAPE = 2,       /* B<2, b<1, off<0, off+b>B, d<1, ld<d, N<1, bad struct_size, unknown flag */
+  FASTCLIP_ERR_SHAPE = 2,       /* B<2, b<1, off<0, off+b>B, d<1, ld<d, N<1, b>N, bad struct_size, unknown flag */
   FASTCLIP_ERR_VALUE = 3,       /* gamma not in (0,1], eps<0, NaN scalar, unknown version or dtype */
   FASTCLIP_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than fastclip_workspace_bytes() */
   FASTCLIP_ERR_UNSUPPORTED = 5, /* bf16 path: d or a row stride not a multiple of 8, a matrix base not
@@ -202,7 +202,8 @@ fastclip_status fastclip_step_update_tau(const fastclip_config* cfg, const fastc
  * fastclip_step run on its own; used to measure the gather/update/scatter kernel on many
  * indices).  sum_img[r] / sum_txt[r] hold M * g_1 / M * g_2 of anchor r (device, [n]);
  * u_img/u_txt [N] are updated in place at idx; u_new_img / u_new_txt [n] receive the new
- * values in batch order.  M = the divisor |B_{i-}|.  Asynchronous on `stream`. */
+ * values in batch order.  M = the divisor |B_{i-}|.  Asynchronous on `stream`.  idx holds n distinct values
+ * in [0, N) (not checked on the device); n > N cannot satisfy that and returns FASTCLIP_ERR_SHAPE. */
 fastclip_status fastclip_state_update(const int64_t* idx, int64_t n, int64_t N, float gamma, float M,
                                       const float* sum_img, const float* sum_txt,
                                       float* u_img, float* u_txt,

@@ -27,7 +27,7 @@ fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* buf
   if (!cfg) return FASTCLIP_ERR_NULL;
   if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~FASTCLIP_GATHERED_STATE)) return FASTCLIP_ERR_SHAPE;
   if (cfg->B < 2 || cfg->b < 1 || cfg->off < 0 || cfg->off + cfg->b > cfg->B || cfg->d < 1 ||
-      cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1)
+      cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1 || cfg->b > cfg->N)
     return FASTCLIP_ERR_SHAPE;
   if (cfg->version < FASTCLIP_V0 || cfg->version > FASTCLIP_V3) return FASTCLIP_ERR_VALUE;
   if (cfg->emb_dtype != FASTCLIP_F32 && cfg->emb_dtype != FASTCLIP_BF16) return FASTCLIP_ERR_VALUE;
@@ -113,9 +113,8 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   if (L->bf16) {
     L->nparts = (int)((cfg.B + kTileContrasts - 1) / kTileContrasts);
     L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
-    L->ldW = (int64_t)round_up((size_t)cfg.b, 64);
-    // split the contraction over its (extended) column range so that the two strips give about one workgroup per CU
-    const int64_t stages = (L->ldE + L->ldW) / 32;
+    // split the contraction over its column range so that the two strips give about one workgroup per CU
+    const int64_t stages = L->ldE / 32;
     const int64_t tiles = ((cfg.b + 255) / 256) * ((cfg.d + 255) / 256) * 2;
     int64_t want = (256 + tiles - 1) / tiles;
     if (want > kMaxSplit) want = kMaxSplit;
@@ -127,7 +126,6 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   } else {
     L->nparts = 1;
     L->ldE = cfg.B;
-    L->ldW = 0;
     L->nsplit = 0;
     L->kslice = 0;
   }
@@ -138,9 +136,9 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   L->red = take(sizeof(float) * 2 * (size_t)L->nstate_blocks);
   const size_t esz = L->bf16 ? sizeof(bf16_t) : sizeof(float);
   if (L->bf16) {
-    // fragment-ordered strips: anchors padded to whole 256-row tiles, columns = contrasts + local anchors
+    // fragment-ordered strips: anchors padded to whole 256-row tiles
     const size_t rows = round_up((size_t)cfg.b, 256);
-    for (int s = 0; s < 2; ++s) L->E[s] = take(esz * rows * (size_t)(L->ldE + L->ldW));
+    for (int s = 0; s < 2; ++s) L->E[s] = take(esz * rows * (size_t)L->ldE);
     for (int s = 0; s < 2; ++s)
       L->Opart[s] = take(sizeof(float) * (size_t)L->nsplit * (size_t)cfg.b * (size_t)cfg.d);
   } else {
@@ -202,7 +200,7 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
   if (c.L.bf16) {
     launch_strips_bf16(c);                mark(FASTCLIP_PHASE_STRIPS);
     launch_state(c);                      mark(FASTCLIP_PHASE_STATE);
-    launch_local_bf16(c);                 mark(FASTCLIP_PHASE_LOCAL);
+    launch_fold_bf16(c);                  mark(FASTCLIP_PHASE_LOCAL);
     launch_contract_bf16(c);              mark(FASTCLIP_PHASE_CONTRACT);
     launch_finalize_bf16(c);
   } else {
@@ -271,7 +269,7 @@ fastclip_status fastclip_temperature_update(int32_t version, const fastclip_tau_
   const fc::TauUpd u = fc::make_tau_upd(*upd);
   if (version == FASTCLIP_V2) {
     if (!idx || !d_tau_img || !d_tau_txt) return FASTCLIP_ERR_NULL;
-    if (b < 0 || N < 1 || b > ((int64_t)1 << 31) - 1024) return FASTCLIP_ERR_SHAPE;
+    if (b < 0 || N < 1 || b > N || b > ((int64_t)1 << 31) - 1024) return FASTCLIP_ERR_SHAPE;
     if (b == 0) return FASTCLIP_OK;
     fc::launch_tau_sparse(u, *state, idx, b, d_tau_img, d_tau_txt, (hipStream_t)stream);
   } else {
@@ -297,7 +295,8 @@ fastclip_status fastclip_state_update(const int64_t* idx, int64_t n, int64_t N, 
                                       const float* sum_img, const float* sum_txt, float* u_img, float* u_txt,
                                       float* u_new_img, float* u_new_txt, void* stream) {
   if (!idx || !sum_img || !sum_txt || !u_img || !u_txt || !u_new_img || !u_new_txt) return FASTCLIP_ERR_NULL;
-  if (n < 0 || N < 1 || n > ((int64_t)1 << 31) - 1024) return FASTCLIP_ERR_SHAPE;
+  // the indices are distinct values in [0, N), so there cannot be more than N of them
+  if (n < 0 || N < 1 || n > N || n > ((int64_t)1 << 31) - 1024) return FASTCLIP_ERR_SHAPE;
   if (fc::bad_float(gamma) || fc::bad_float(M) || !(gamma > 0.0f && gamma <= 1.0f) || !(M > 0.0f))
     return FASTCLIP_ERR_VALUE;
   if (n == 0) return FASTCLIP_OK;

@@ -23,7 +23,6 @@ struct Layout {
   int nparts;        // partial row sums per anchor and quantity written by the strip phase
   int64_t bstride;   // anchors padded to a multiple of 64 (stride of the per-anchor arrays)
   int64_t ldE;       // contrast columns of the stored exp strips (MFMA path: multiple of 64; fp32 path: B)
-  int64_t ldW;       // local-anchor columns appended to the strips (MFMA path, multiple of 64)
   int nsplit;        // split of the contraction over its column range
   int64_t kslice;    // 32-deep stages per split
   int nstate_blocks; // blocks of the state kernel (one scalar partial each)
@@ -74,7 +73,7 @@ void launch_strips_f32(const StepCtx& c);      // accuracy path: exp strips + ro
 void launch_strips_bf16(const StepCtx& c);     // MFMA path: exp strips + row sums
 void launch_state(const StepCtx& c);           // Eq. 1, coefficients, scalar partials
 void launch_grad_f32(const StepCtx& c);        // accuracy path: gradients + scalars
-void launch_local_bf16(const StepCtx& c);      // MFMA path: local contrast-side operand columns
+void launch_fold_bf16(const StepCtx& c);       // MFMA path: local contrast-side weights folded into the strips
 void launch_contract_bf16(const StepCtx& c);   // MFMA path: strips x X contractions
 void launch_finalize_bf16(const StepCtx& c);   // MFMA path: combine + scalars
 

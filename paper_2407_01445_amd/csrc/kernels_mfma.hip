@@ -6,17 +6,16 @@
 //                   nabla_3 l sums of Eqs. 8-10), and l rounded to bf16 stored as the operand of the gradient
 //                   contraction.  The similarity matrix itself never reaches memory.  Anchors run along lanes, so
 //                   the sums are lane-local and every store is a contiguous 1 KiB per wavefront.
-//  k_local_bf16     the local contrast-side operand of Eqs. 3 / 5 / 7: c_other[q] l_other(q, p_r) / c_own[r], written
-//                   behind the strip as extra contraction columns, so that one contraction yields
+//  k_fold_bf16      the local contrast-side term of Eqs. 3 / 5 / 7: c_other[q] l_other(q, p_r) / c_own[r] is added to
+//                   the strip element (r, off + q), which weights the same row of X, so that one contraction yields
 //                   sum_j l(r,j) x_j + (1/c_r) sum_q c_q l(q,p_r) x_q.
-//  k_contract_bf16  C[r][n] = sum_c Efrag[r][c] Xext[c][n] over the extended column range, split over c into fp32
+//  k_contract_bf16  C[r][n] = sum_c Efrag[r][c] X[c][n] over the contrast columns, split over c into fp32
 //                   partial results (Eqs. 2/4/6 plus the local part of Eqs. 3/5/7).
 //
 // Stored exp strips ("Efrag"): for anchor block ab = r / 32 and column block cb = c / 16 one 1 KiB fragment, laid out
 // exactly as the A operand of the 32x32x16 MFMA: lane L = (r % 32) + 32 h holds 8 bf16, slot e <-> column
 // 16 cb + 8 (e / 4) + 4 h + (e % 4).  The same slot order is used for the rows of X in the contraction, so the
-// permutation cancels.  Columns [0, ldE) are contrasts (global rows, zero beyond B), columns [ldE, ldE + ldW) are the
-// local anchors q of k_local_bf16 (zero beyond b).
+// permutation cancels.  Columns [0, ldE) are contrasts (global rows, zero beyond B).
 //
 // MFMA layout facts used (32x32x16, wave64): lane l supplies row/column (l & 31) of its operand and 8 contraction
 // slots selected by (l >> 5); accumulator register v of lane l is D[8 (v >> 2) + 4 (l >> 5) + (v & 3)][l & 31].
@@ -93,22 +92,17 @@ struct ContractTile {
   const bf16_t* Efr;       // wave-uniform: fragment (ab0, column block 0) of the strip
   const bf16_t* Xn;        // wave-uniform: X + n0
   int64_t ldx;
-  int64_t local_rows;      // off - ldE: row shift for stages in the local-anchor column range
-  int first_local_stage;
   uint32_t oa[4], ob[4];   // per-lane byte offsets of the wave loads (A: relative to Efr; B: relative to row 0 of a stage)
   uint32_t la[4], lb[4];
   int wm, wn, lane;
-  int64_t n0, N, B, bloc, off, ldE;   // guarded path
+  int64_t n0, N, B;   // guarded path
 
   __device__ __forceinline__ void setup(const bf16_t* E, int64_t nCB, int64_t ab0, const bf16_t* X_, int64_t ldx_,
-                                        int64_t n0_, int64_t N_, int64_t B_, int64_t bloc_, int64_t off_,
-                                        int64_t ldE_, int tid) {
+                                        int64_t n0_, int64_t N_, int64_t B_, int tid) {
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in SGPRs
     lane = tid & 63; wm = wave >> 1; wn = wave & 1;
     Efr = E + ab0 * nCB * 512; Xn = X_ + n0_; ldx = ldx_;
-    n0 = n0_; N = N_; B = B_; bloc = bloc_; off = off_; ldE = ldE_;
-    local_rows = off_ - ldE_;
-    first_local_stage = (int)(ldE_ / BK);
+    n0 = n0_; N = N_; B = B_;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int f = wave * 4 + i;                       // fragment f = 2 * (anchor block) + (column block in stage)
@@ -121,8 +115,7 @@ struct ContractTile {
     }
   }
   __device__ __forceinline__ const bf16_t* stage_rows(int stage) const {   // X row of stage row 0, plus n0
-    const int64_t row = (int64_t)stage * BK + (stage >= first_local_stage ? local_rows : 0);
-    return Xn + row * ldx;
+    return Xn + (int64_t)stage * BK * ldx;
   }
   __device__ __forceinline__ void dma(int i, int stage, uint32_t slot) const {
     if (i < 4) dma16(Efr + (int64_t)stage * 1024, oa[i], slot + la[i]);
@@ -136,8 +129,8 @@ struct ContractTile {
       *(u32x4*)(slot + f * 1024 + lane * 16) = *(const u32x4*)((const char*)(Efr + (int64_t)stage * 1024) + oa[i]);
       const int k = 2 * f + (lane >> 5);
       const int piece = (lane & 31) ^ nt_swz(k);
-      const int64_t c = (int64_t)stage * BK + k;        // extended column
-      const bool ok = (c < ldE ? c < B : (c - ldE) < bloc) && (n0 + piece * 8 < N);
+      const int64_t c = (int64_t)stage * BK + k;        // contrast column = row of X
+      const bool ok = c < B && (n0 + piece * 8 < N);
       u32x4 v = {0u, 0u, 0u, 0u};
       if (ok) v = *(const u32x4*)((const char*)stage_rows(stage) + ob[i]);
       *(u32x4*)(slot + kOpBytes + f * 1024 + lane * 16) = v;
@@ -426,7 +419,7 @@ void launch_strips_bf16(const StepCtx& c) {
   a.kscale[1] = (const float*)(c.ws + L.k2);
   a.E[0] = (bf16_t*)(c.ws + L.E[0]);
   a.E[1] = (bf16_t*)(c.ws + L.E[1]);
-  a.nCB = (L.ldE + L.ldW) / 16;
+  a.nCB = L.ldE / 16;
   a.ldE = L.ldE;
   a.sums = (float*)(c.ws + L.sums);
   a.nparts = L.nparts; a.bstride = L.bstride; a.b = L.b; a.B = L.B; a.d = L.d; a.off = L.off;
@@ -444,71 +437,89 @@ void launch_strips_bf16(const StepCtx& c) {
 }
 
 // ----------------------------------------------------------------------------------------------------------------
-// Local contrast-side operand.  Block (rb, qb, side): the 64 x 64 block W'[r][q] = c_other[q] l_other(q, off + r) /
-// c_own[r] (r in [64 rb, +64), q in [64 qb, +64)), read as whole 16-byte fragment chunks of the other strip (which
-// already holds 0 at q == r), transposed through LDS, and written as fragment rows into the extended column range of
-// the own strip.  Zero for q >= b.
-__global__ void __launch_bounds__(256) k_local_bf16(const bf16_t* __restrict__ E0, const bf16_t* __restrict__ E1,
-                                                    bf16_t* __restrict__ W0, bf16_t* __restrict__ W1, int64_t nCB,
-                                                    int64_t ldE, const float* __restrict__ c1,
-                                                    const float* __restrict__ c2, int64_t off, int64_t b) {
-  __shared__ float tile[64][65];   // [r][q]
-  const int side = blockIdx.z;
-  const bf16_t* __restrict__ Esrc = side == 0 ? E1 : E0;   // d_img needs l2 (text strip), d_txt needs l1
-  bf16_t* __restrict__ Edst = side == 0 ? W0 : W1;
-  const float* __restrict__ c_own = side == 0 ? c1 : c2;
-  const float* __restrict__ c_oth = side == 0 ? c2 : c1;
-  const int64_t r0 = (int64_t)blockIdx.x * 64, q0 = (int64_t)blockIdx.y * 64;
-  const int64_t cfirst = off + r0;                    // columns cfirst .. cfirst + 63 of the other strip
-  const int64_t cb_first = cfirst >> 4, cb_last = (cfirst + 63) >> 4;   // at most 5 column blocks
+// Local contrast-side term of Eqs. 3 / 5 / 7, folded into the stored strips.  For two local anchors r, q the image
+// row of r receives c1_r l1(r, p_q) txt_{p_q} (anchor side, Eq. 2) and c2_q l2(q, p_r) txt_{p_q} (contrast side of
+// the text anchor q, Eq. 3): the same row of X with the weight w = c1_r l1(r, p_q) + c2_q l2(q, p_r), which is also
+// the weight of img_{p_r} in the text gradient of q.  The strips hold l1(r, .) and l2(q, .) at exactly these
+// columns, so the block (rb, qb) replaces E0[r][off + q] by w / c1_r and E1[q][off + r] by w / c2_q (the contraction's
+// result is multiplied by the row's own coefficient afterwards) and one contraction per side yields both terms.
+//
+// A 64 x 64 window of a strip (rows row0 .., columns col0 ..) is read as whole 16-byte fragment chunks and laid out
+// as tile[row][column] in LDS; col0 need not be a multiple of 16, so up to 5 column blocks are touched.
+__device__ __forceinline__ void fold_load(const bf16_t* __restrict__ E, int64_t nCB, int64_t row0, int64_t col0,
+                                          int64_t rows, float (*tile)[65]) {
+  const int64_t cb_first = col0 >> 4, cb_last = (col0 + 63) >> 4;
   for (int i = threadIdx.x; i < 64 * 10; i += 256) {
-    const int ql = i & 63, ch = i >> 6;
+    const int rl = i & 63, ch = i >> 6;
     const int64_t cb = cb_first + (ch >> 1);
     const int h = ch & 1;
-    const int64_t q = q0 + ql;
-    if (cb > cb_last) continue;
-    uint4 raw = make_uint4(0u, 0u, 0u, 0u);
-    float cq = 0.f;
-    if (q < b) {
-      raw = *(const uint4*)(Esrc + (((q >> 5) * nCB + cb) * 64 + (q & 31) + 32 * h) * 8);
-      cq = c_oth[q];
-    }
+    const int64_t row = row0 + rl;
+    if (cb > cb_last || cb >= nCB || row >= rows) continue;
+    const uint4 raw = *(const uint4*)(E + (((row >> 5) * nCB + cb) * 64 + (row & 31) + 32 * h) * 8);
     const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      const int64_t c = 16 * cb + 8 * (e >> 2) + 4 * h + (e & 3);
-      const int64_t rl = c - cfirst;
+      const int64_t cl = 16 * cb + 8 * (e >> 2) + 4 * h + (e & 3) - col0;
       const uint32_t bits = (e & 1) ? (w[e >> 1] & 0xffff0000u) : (w[e >> 1] << 16);
-      if (rl >= 0 && rl < 64) tile[rl][ql] = cq * __uint_as_float(bits);
+      if (cl >= 0 && cl < 64) tile[rl][cl] = __uint_as_float(bits);
     }
   }
-  __syncthreads();
-  const int rl = threadIdx.x >> 2, qpart = threadIdx.x & 3;
-  const int64_t r = r0 + rl;
-  if (r >= b) return;
-  const float inv_own = 1.0f / c_own[r];
-  uint32_t out[2][4];
+}
+// The way back: a chunk that lies wholly inside the window's valid columns is stored as 16 bytes, any other chunk
+// element by element (its remaining elements belong to a neighbouring block, which may be storing them right now).
+__device__ __forceinline__ void fold_store(bf16_t* __restrict__ E, int64_t nCB, int64_t row0, int64_t col0,
+                                           int64_t rows, int cols, float (*tile)[65]) {
+  const int64_t cb_first = col0 >> 4, cb_last = (col0 + 63) >> 4;
+  for (int i = threadIdx.x; i < 64 * 10; i += 256) {
+    const int rl = i & 63, ch = i >> 6;
+    const int64_t cb = cb_first + (ch >> 1);
+    const int h = ch & 1;
+    const int64_t row = row0 + rl;
+    if (cb > cb_last || row >= rows) continue;
+    bf16_t* dst = E + (((row >> 5) * nCB + cb) * 64 + (row & 31) + 32 * h) * 8;
+    const int64_t cl_lo = 16 * cb + 4 * h - col0, cl_hi = cl_lo + 8;   // slots 0..3 and 4..7
+    if (cl_lo >= 0 && cl_hi + 3 < cols) {
+      const u32x4 w = {pack_bf16x2(tile[rl][cl_lo], tile[rl][cl_lo + 1]), pack_bf16x2(tile[rl][cl_lo + 2], tile[rl][cl_lo + 3]),
+                       pack_bf16x2(tile[rl][cl_hi], tile[rl][cl_hi + 1]), pack_bf16x2(tile[rl][cl_hi + 2], tile[rl][cl_hi + 3])};
+      *(u32x4*)dst = w;
+    } else {
 #pragma unroll
-  for (int hh = 0; hh < 2; ++hh)
-#pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {       // slots e = 2 e2, 2 e2 + 1 of half hh <-> o = 8 (e / 4) + 4 hh + (e % 4)
-      const int o_lo = 8 * ((2 * e2) >> 2) + 4 * hh + ((2 * e2) & 3);
-      out[hh][e2] = pack_bf16x2(tile[rl][16 * qpart + o_lo] * inv_own, tile[rl][16 * qpart + o_lo + 1] * inv_own);
+      for (int e = 0; e < 8; ++e) {
+        const int64_t cl = (e < 4 ? cl_lo : cl_hi) + (e & 3);
+        if (cl >= 0 && cl < cols) dst[e] = f2bf(tile[rl][cl]);
+      }
     }
-  const int64_t cb_dst = (ldE >> 4) + ((q0 + 16 * qpart) >> 4);
-#pragma unroll
-  for (int hh = 0; hh < 2; ++hh) {
-    const u32x4 w = {out[hh][0], out[hh][1], out[hh][2], out[hh][3]};
-    *(u32x4*)(Edst + (((r >> 5) * nCB + cb_dst) * 64 + (r & 31) + 32 * hh) * 8) = w;
   }
 }
 
-void launch_local_bf16(const StepCtx& c) {
+__global__ void __launch_bounds__(256) k_fold_bf16(bf16_t* __restrict__ E0, bf16_t* __restrict__ E1, int64_t nCB,
+                                                   const float* __restrict__ c1, const float* __restrict__ c2,
+                                                   int64_t off, int64_t b) {
+  __shared__ float t0[64][65];   // [r][q]: l1(r, off + q), then w / c1_r
+  __shared__ float t1[64][65];   // [q][r]: l2(q, off + r), then w / c2_q
+  const int64_t r0 = (int64_t)blockIdx.x * 64, q0 = (int64_t)blockIdx.y * 64;
+  fold_load(E0, nCB, r0, off + q0, b, t0);
+  fold_load(E1, nCB, q0, off + r0, b, t1);
+  __syncthreads();
+  const int nr = (int)(b - r0 < 64 ? b - r0 : 64), nq = (int)(b - q0 < 64 ? b - q0 : 64);
+  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
+    const int ql = i & 63, rl = i >> 6;
+    if (rl >= nr || ql >= nq) continue;
+    const float cr = c1[r0 + rl], cq = c2[q0 + ql];
+    const float w = fmaf(cr, t0[rl][ql], cq * t1[ql][rl]);
+    t0[rl][ql] = w / cr;
+    t1[ql][rl] = w / cq;
+  }
+  __syncthreads();
+  fold_store(E0, nCB, r0, off + q0, b, nq, t0);
+  fold_store(E1, nCB, q0, off + r0, b, nr, t1);
+}
+
+void launch_fold_bf16(const StepCtx& c) {
   const Layout& L = c.L;
-  dim3 grid((unsigned)((L.b + 63) / 64), (unsigned)(L.ldW / 64), 2);
-  hipLaunchKernelGGL(k_local_bf16, grid, dim3(256), 0, c.s, (const bf16_t*)(c.ws + L.E[0]),
-                     (const bf16_t*)(c.ws + L.E[1]), (bf16_t*)(c.ws + L.E[0]), (bf16_t*)(c.ws + L.E[1]),
-                     (L.ldE + L.ldW) / 16, L.ldE, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.off, L.b);
+  const unsigned nb = (unsigned)((L.b + 63) / 64);
+  hipLaunchKernelGGL(k_fold_bf16, dim3(nb, nb), dim3(256), 0, c.s, (bf16_t*)(c.ws + L.E[0]), (bf16_t*)(c.ws + L.E[1]),
+                     L.ldE / 16, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.off, L.b);
 }
 
 // ----------------------------------------------------------------------------------------------------------------
@@ -521,11 +532,11 @@ struct ContractJob {
   size_t split_stride;
   int64_t nCB;        // column blocks (of 16) per anchor block of E
   int stages, slice;  // 32-deep stages in all; stages per split
-  int all_rows_valid; // no zero rows inside the column range (B == ldE, and b == ldW where E has local columns)
+  int all_rows_valid; // no zero rows inside the column range (B == ldE)
 };
 struct ContractArgs {
   ContractJob job[4];   // 0, 1: the two strips; 2, 3: their gathered-state strips (njobs == 4)
-  int64_t M, N, B, bloc, off, ldE;
+  int64_t M, N, B;
   int nsplit, tiles_m, tiles_n;
 };
 
@@ -548,7 +559,7 @@ __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
   zero_acc(acc);
   if (S > 0) {
     ContractTile T;
-    T.setup(J.E, J.nCB, m0 >> 5, J.X, J.ldx, n0, g.N, g.B, g.bloc, g.off, g.ldE, tid);
+    T.setup(J.E, J.nCB, m0 >> 5, J.X, J.ldx, n0, g.N, g.B, tid);
     if (J.all_rows_valid && n0 + 256 <= g.N) {
       ring_prologue(T, ring_addr, s0, S);
       ring_mainloop(acc, T, ring, ring_addr, s0, S);
@@ -590,13 +601,13 @@ void launch_contract_bf16(const StepCtx& c) {
     J.C = (float*)(c.ws + (rem ? L.OpartF[s] : L.Opart[s]));
     J.ldc = L.d;
     J.split_stride = (size_t)L.b * (size_t)L.d;
-    J.nCB = (rem ? L.ldE : L.ldE + L.ldW) / 16;
-    J.stages = (int)((rem ? L.ldE : L.ldE + L.ldW) / BK);
-    J.slice = rem ? (int)((J.stages + L.nsplit - 1) / L.nsplit) : (int)L.kslice;
-    J.all_rows_valid = (L.B == L.ldE) && (rem || L.b == L.ldW);
+    J.nCB = L.ldE / 16;
+    J.stages = (int)(L.ldE / BK);
+    J.slice = (int)L.kslice;
+    J.all_rows_valid = L.B == L.ldE;
   }
   for (int j = njobs; j < 4; ++j) g.job[j] = g.job[0];
-  g.M = L.b; g.N = L.d; g.B = L.B; g.bloc = L.b; g.off = L.off; g.ldE = L.ldE;
+  g.M = L.b; g.N = L.d; g.B = L.B;
   g.nsplit = L.nsplit;
   g.tiles_m = (int)((L.b + 255) / 256);
   g.tiles_n = (int)((L.d + 255) / 256);

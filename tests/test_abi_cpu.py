@@ -143,6 +143,7 @@ def test_state_update_and_check_indices_argument_errors():
     lib = fc.load()
     assert lib.fastclip_state_update(None, 4, 10, 0.5, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_NULL
     assert lib.fastclip_state_update(1, -1, 10, 0.5, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_SHAPE
+    assert lib.fastclip_state_update(1, 11, 10, 0.5, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_SHAPE   # more indices than entries
     assert lib.fastclip_state_update(1, 4, 10, 0.0, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_VALUE
     assert lib.fastclip_state_update(1, 4, 10, 0.5, 0.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_VALUE
     assert lib.fastclip_state_update(1, 0, 10, 0.5, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.OK      # empty batch
