@@ -497,18 +497,29 @@ __global__ void __launch_bounds__(256) k_fold_bf16(bf16_t* __restrict__ E0, bf16
                                                    int64_t off, int64_t b) {
   __shared__ float t0[64][65];   // [r][q]: l1(r, off + q), then w / c1_r
   __shared__ float t1[64][65];   // [q][r]: l2(q, off + r), then w / c2_q
+  __shared__ float sc[4][64];    // c1_r, c2_q, 1 / c1_r, 1 / c2_q of the block's rows
   const int64_t r0 = (int64_t)blockIdx.x * 64, q0 = (int64_t)blockIdx.y * 64;
+  if (threadIdx.x < 128) {
+    const int side = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const int64_t m = (side == 0 ? r0 : q0) + l;
+    const float c = m < b ? (side == 0 ? c1 : c2)[m] : 1.0f;
+    sc[side][l] = c;
+    sc[2 + side][l] = 1.0f / c;
+  }
   fold_load(E0, nCB, r0, off + q0, b, t0);
   fold_load(E1, nCB, q0, off + r0, b, t1);
   __syncthreads();
   const int nr = (int)(b - r0 < 64 ? b - r0 : 64), nq = (int)(b - q0 < 64 ? b - q0 : 64);
-  for (int i = threadIdx.x; i < 64 * 64; i += 256) {
-    const int ql = i & 63, rl = i >> 6;
-    if (rl >= nr || ql >= nq) continue;
-    const float cr = c1[r0 + rl], cq = c2[q0 + ql];
-    const float w = fmaf(cr, t0[rl][ql], cq * t1[ql][rl]);
-    t0[rl][ql] = w / cr;
-    t1[ql][rl] = w / cq;
+  {
+    const int ql = threadIdx.x & 63;
+    const float cq = sc[1][ql], icq = sc[3][ql];
+#pragma unroll 4
+    for (int rl = threadIdx.x >> 6; rl < 64; rl += 4) {
+      if (rl >= nr || ql >= nq) continue;
+      const float w = fmaf(sc[0][rl], t0[rl][ql], cq * t1[ql][rl]);
+      t0[rl][ql] = w * sc[2][rl];
+      t1[ql][rl] = w * icq;
+    }
   }
   __syncthreads();
   fold_store(E0, nCB, r0, off + q0, b, nq, t0);
