@@ -107,22 +107,36 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   L->bstride = (int64_t)round_up((size_t)cfg.b, 64);
   L->gathered = (cfg.flags & FASTCLIP_GATHERED_STATE) && cfg.b < cfg.B;
   L->ncol = (int64_t)round_up((size_t)cfg.B, kTileContrasts);
+  // forming the similarity matrix once halves the MFMA work of the strip phase but doubles the epilogue of every
+  // tile: it pays once the tiles outnumber the compute units (below that one tile's latency is the phase's time)
+  const int64_t bt = cfg.B / kTileContrasts;
+  L->square = L->bf16 && cfg.b == cfg.B && cfg.B % kTileContrasts == 0 && cfg.d % 64 == 0 && cfg.d >= 128 &&
+              2 * bt * bt > 256;
   size_t at = 0;
   auto take = [&](size_t bytes) { size_t o = at; at += round_up(bytes, 256); return o; };
   const size_t fb = sizeof(float) * (size_t)L->bstride;
   if (L->bf16) {
     L->nparts = (int)((cfg.B + kTileContrasts - 1) / kTileContrasts);
     L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
-    // split the contraction over its column range so that the two strips give about one workgroup per CU
+    // Split of the contraction over its column range.  A workgroup owns one 256 x 256 output tile of one side and
+    // `slice` stages; the 256 compute units take the workgroups in rounds.  Cost model in units of one stage time:
+    // rounds x (slice + 12 for writing the partial tile) + 2.3 per split for the finalize pass that adds them up.
     const int64_t stages = L->ldE / 32;
     const int64_t tiles = ((cfg.b + 255) / 256) * ((cfg.d + 255) / 256) * 2;
-    int64_t want = (256 + tiles - 1) / tiles;
-    if (want > kMaxSplit) want = kMaxSplit;
-    if (want < 1) want = 1;
-    int64_t slice = (stages + want - 1) / want;
-    if (slice < 8) slice = 8;
-    L->kslice = slice;
-    L->nsplit = (int)((stages + slice - 1) / slice);
+    int64_t max_split = stages / 8;
+    if (max_split > kMaxSplit) max_split = kMaxSplit;
+    if (max_split < 1) max_split = 1;
+    int64_t best = 1;
+    double best_cost = 0.0;
+    for (int64_t ns = 1; ns <= max_split; ++ns) {
+      const int64_t slice = (stages + ns - 1) / ns;
+      const int64_t used = (stages + slice - 1) / slice;          // splits that really get stages
+      const int64_t rounds = (tiles * used + 255) / 256;
+      const double cost = (double)rounds * (double)(slice + 12) + 2.3 * (double)used;
+      if (ns == 1 || cost < best_cost) { best = ns; best_cost = cost; }
+    }
+    L->kslice = (stages + best - 1) / best;
+    L->nsplit = (int)((stages + L->kslice - 1) / L->kslice);
   } else {
     L->nparts = 1;
     L->ldE = cfg.B;
@@ -144,6 +158,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   } else {
     for (int s = 0; s < 2; ++s) L->E[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
   }
+  if (L->square) L->F[0] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
   if (L->gathered) {
     L->colp = take(sizeof(float) * 2 * 4 * (size_t)L->ncol);
     if (L->bf16) {

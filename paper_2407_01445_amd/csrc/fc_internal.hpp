@@ -27,6 +27,8 @@ struct Layout {
   int64_t kslice;    // 32-deep stages per split
   int nstate_blocks; // blocks of the state kernel (one scalar partial each)
   int gathered;      // 1: contrast-side estimator over every global anchor (FASTCLIP_GATHERED_STATE and b < B)
+  int square;        // 1: MFMA path, b == B and only whole tiles: the similarity matrix is formed once (F[0] holds
+                     //    l2(j, p) in the layout of E[0] until the fold transposes it into E[1])
   int64_t ncol;      // gathered: entries per column-parameter array (B rounded up to whole 256-column tiles)
   size_t diag, tau1, tau2, k1, k2;   // float[bstride]
   size_t sums;                       // float[4][nparts][bstride]: sum e1, sum x1 e1, sum e2, sum x2 e2

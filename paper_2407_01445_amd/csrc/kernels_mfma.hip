@@ -425,9 +425,10 @@ void launch_strips_bf16(const StepCtx& c) {
   a.nparts = L.nparts; a.bstride = L.bstride; a.b = L.b; a.B = L.B; a.d = L.d; a.off = L.off;
   a.nAT = (int)((L.b + 255) / 256);
   a.nCT = (int)((L.B + 255) / 256);
-  a.ntiles = 2 * a.nAT * a.nCT;
+  a.square = L.square;
+  a.ntiles = (L.square ? 1 : 2) * a.nAT * a.nCT;
   a.colp = L.gathered ? (const float*)(c.ws + L.colp) : nullptr;
-  a.F[0] = L.gathered ? (bf16_t*)(c.ws + L.F[0]) : nullptr;
+  a.F[0] = (L.gathered || L.square) ? (bf16_t*)(c.ws + L.F[0]) : nullptr;
   a.F[1] = L.gathered ? (bf16_t*)(c.ws + L.F[1]) : nullptr;
   a.nCBF = L.ldE / 16;
   const bool any_interior = L.b >= 256 && L.B >= 256 && L.d % 64 == 0 && L.d >= 128;
@@ -526,9 +527,58 @@ __global__ void __launch_bounds__(256) k_fold_bf16(bf16_t* __restrict__ E0, bf16
   fold_store(E1, nCB, q0, off + r0, b, nr, t1);
 }
 
+// The same when the whole batch is local and the similarity matrix was formed once: F0[r][q] holds l2(q, p_r) in the
+// layout of E0 (off == 0), so w = c1_r E0[r][q] + c2_q F0[r][q]; w / c1_r goes back to E0[r][q] and w / c2_q, transposed,
+// to E1[q][r], which nothing has written before.  b is a multiple of 256 here.
+__global__ void __launch_bounds__(256) k_fold_square_bf16(bf16_t* __restrict__ E0, const bf16_t* __restrict__ F0,
+                                                          bf16_t* __restrict__ E1, int64_t nCB,
+                                                          const float* __restrict__ c1, const float* __restrict__ c2,
+                                                          int64_t b) {
+  __shared__ float t0[64][65];   // [r][q]: l1(r, q), then w / c1_r
+  __shared__ float t1[64][65];   // [r][q]: l2(q, r); then [q][r]: w / c2_q
+  __shared__ float sc[4][64];
+  const int64_t r0 = (int64_t)blockIdx.x * 64, q0 = (int64_t)blockIdx.y * 64;
+  if (threadIdx.x < 128) {
+    const int side = threadIdx.x >> 6, l = threadIdx.x & 63;
+    const float c = (side == 0 ? c1 : c2)[(side == 0 ? r0 : q0) + l];
+    sc[side][l] = c;
+    sc[2 + side][l] = 1.0f / c;
+  }
+  fold_load(E0, nCB, r0, q0, b, t0);
+  fold_load(F0, nCB, r0, q0, b, t1);
+  __syncthreads();
+  float keep[16];
+  {
+    const int ql = threadIdx.x & 63;
+    const float cq = sc[1][ql], icq = sc[3][ql];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int rl = (threadIdx.x >> 6) + 4 * i;
+      const float w = fmaf(sc[0][rl], t0[rl][ql], cq * t1[rl][ql]);
+      t0[rl][ql] = w * sc[2][rl];
+      keep[i] = w * icq;
+    }
+  }
+  __syncthreads();               // every thread has read its part of t1 in the [r][q] order
+  {
+    const int ql = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) t1[ql][(threadIdx.x >> 6) + 4 * i] = keep[i];
+  }
+  __syncthreads();
+  fold_store(E0, nCB, r0, q0, b, 64, t0);
+  fold_store(E1, nCB, q0, r0, b, 64, t1);
+}
+
 void launch_fold_bf16(const StepCtx& c) {
   const Layout& L = c.L;
   const unsigned nb = (unsigned)((L.b + 63) / 64);
+  if (L.square) {
+    hipLaunchKernelGGL(k_fold_square_bf16, dim3(nb, nb), dim3(256), 0, c.s, (bf16_t*)(c.ws + L.E[0]),
+                       (const bf16_t*)(c.ws + L.F[0]), (bf16_t*)(c.ws + L.E[1]), L.ldE / 16,
+                       (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.b);
+    return;
+  }
   hipLaunchKernelGGL(k_fold_bf16, dim3(nb, nb), dim3(256), 0, c.s, (bf16_t*)(c.ws + L.E[0]), (bf16_t*)(c.ws + L.E[1]),
                      L.ldE / 16, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.off, L.b);
 }

@@ -18,8 +18,12 @@
 // immediate constant.  Vector memory operations complete in order, so "stage g + 1 has landed" is
 // s_waitcnt vmcnt(n) with n = the number of operations issued after that stage's loads.
 //
-// REMOTE (gathered state): every element additionally yields the weight of Eqs. 3 / 5 / 7 with which its contrast
+// MODE 1 (gathered state): every element additionally yields the weight of Eqs. 3 / 5 / 7 with which its contrast
 // column, taken as an anchor of another worker, moves the local row; it goes to a second strip of the same form.
+// MODE 2 (the whole batch is local, b == B): the text strip is the transpose of the image strip, so only the image
+// strip is formed; every element s_pj yields l1(p, j) (row parameters, summed along the row as before) and l2(j, p)
+// (column parameters: text anchor j against image p), which is stored as a second strip of the same form and summed
+// down the columns.
 #include "mfma_common.hpp"
 
 namespace fc {
@@ -36,6 +40,7 @@ __device__ __forceinline__ int st_swz(int row) { return (row >> 1) & 7; }
 
 // s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt and lgkmcnt left open)
 #define FC_WAIT_VMCNT1() __builtin_amdgcn_s_waitcnt(0x0f71)
+#define FC_WAIT_VMCNT2() __builtin_amdgcn_s_waitcnt(0x0f72)
 #define FC_WAIT_VMCNT18() __builtin_amdgcn_s_waitcnt(0x4f72)
 
 // 16 bytes per lane from uniform_base + lane_byte_off into LDS at (lds_uniform + IMM) + 16 * lane.
@@ -180,13 +185,103 @@ __device__ __forceinline__ void half_epilogue_remote(f32x16 (&acc)[2][4], const 
   }
 }
 
-template <bool REMOTE>
+// Sum of v[i] over the 32 lanes that share (lane >> 5), for 16 values at once: each step halves the number of values
+// a lane carries (the lower half of a lane pair keeps the first half of the values, the upper half the second), so
+// 16 values cost 16 exchanges instead of 80.  On return v[0] of lane l is the total of value number (l & 31) >> 1.
+template <int HALF, int MASK>
+__device__ __forceinline__ void lanes32_halve(float (&v)[16], int lane) {
+  const bool upper = (lane & MASK) != 0;
+#pragma unroll
+  for (int i = 0; i < HALF; ++i) {
+    const float send = upper ? v[i] : v[i + HALF];
+    const float keep = upper ? v[i + HALF] : v[i];
+    v[i] = keep + __shfl_xor(send, MASK);
+  }
+}
+__device__ __forceinline__ void lanes32_sum(float (&v)[16], int lane) {
+  lanes32_halve<8, 16>(v, lane);
+  lanes32_halve<4, 8>(v, lane);
+  lanes32_halve<2, 4>(v, lane);
+  lanes32_halve<1, 2>(v, lane);
+  v[0] += __shfl_xor(v[0], 1);
+}
+
+// Second pass over the accumulators of one wave when the whole batch is local (the first pass is half_epilogue, with
+// the image anchors' row parameters).  Every element s_pj also yields f = l2(j, p) = 2^((s - s_jj) log2(e)/tau2_j) of
+// the TEXT anchor j = its contrast column; f is stored in a second strip of the same form (fragF0) and summed over the
+// anchors of the wave: scol_k / scol_d hold log2(e)/tau2_j and s_jj of the tile's 256 columns, cl0 = this lane's
+// first column in the tile for ti = 0, g = 0; sredc[quantity][column] receives the wave's column sums of f and of
+// (s - s_jj) f.  MASK: the tile holds diagonal elements j == p, which are not in B_{j-}: f := 0.
+template <bool MASK>
+__device__ __forceinline__ void half_epilogue_cols(f32x16 (&acc)[2][4], const float* scol_k, const float* scol_d,
+                                                   float (*sredc)[256], char* fragF0, int64_t row_bytesF, int c_first,
+                                                   int own0, int cl0, int lane) {
+  const int lr = lane & 31, hk = lane >> 5;
+#pragma unroll
+  for (int ti = 0; ti < 2; ++ti) {
+    const int crow = c_first + ti * 32 + 4 * hk;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {            // the 16-byte fragment store j holds the groups g = 2 j, 2 j + 1
+      const int cl = cl0 + ti * 32 + 16 * j;
+      const float4 k0 = *(const float4*)(scol_k + cl), k1 = *(const float4*)(scol_k + cl + 8);
+      const float4 d0 = *(const float4*)(scol_d + cl), d1 = *(const float4*)(scol_d + cl + 8);
+      const float ck[8] = {k0.x, k0.y, k0.z, k0.w, k1.x, k1.y, k1.z, k1.w};
+      const float cdk[8] = {d0.x * k0.x, d0.y * k0.y, d0.z * k0.z, d0.w * k0.w,
+                            d1.x * k1.x, d1.y * k1.y, d1.z * k1.z, d1.w * k1.w};
+      float cs[16];                          // column sums of this lane: f of 8 columns, then t f of 8 columns
+#pragma unroll
+      for (int i = 0; i < 16; ++i) cs[i] = 0.f;
+#pragma unroll
+      for (int tj = 0; tj < 4; ++tj) {
+        const int drow = own0 + tj * 32 + lr - crow;     // the diagonal element sits at 8 g + q == drow
+        uint32_t pf[4];
+#pragma unroll
+        for (int gi = 0; gi < 2; ++gi) {
+          const int g = 2 * j + gi;
+          float t2[4], f[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) t2[q] = fmaf(acc_read(acc[ti][tj][4 * g + q]), ck[4 * gi + q], -cdk[4 * gi + q]);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) f[q] = __builtin_amdgcn_exp2f(t2[q]);
+          if (MASK) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) f[q] = (drow == 8 * g + q) ? 0.f : f[q];
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            cs[4 * gi + q] += f[q];
+            cs[8 + 4 * gi + q] = fmaf(t2[q], f[q], cs[8 + 4 * gi + q]);
+          }
+          pf[2 * gi] = pack_bf16x2(f[0], f[1]);
+          pf[2 * gi + 1] = pack_bf16x2(f[2], f[3]);
+          FC_PIN();
+        }
+        const u32x4 wf = {pf[0], pf[1], pf[2], pf[3]};
+        *(u32x4*)(fragF0 + tj * row_bytesF + (2 * ti + j) * 1024 + lane * 16) = wf;
+        FC_PIN();
+      }
+      // divide the second quantity by log2(e)/tau_j while each lane still knows its columns, then sum over the lanes
+#pragma unroll
+      for (int i = 0; i < 8; ++i) cs[8 + i] = ck[i] > 0.f ? cs[8 + i] * __builtin_amdgcn_rcpf(ck[i]) : 0.f;
+      lanes32_sum(cs, lane);
+      if ((lr & 1) == 0) {
+        const int v = lr >> 1, gi = (v >> 2) & 1, q = v & 3;     // value v = 8 quantity + 4 gi + q
+        sredc[v >> 3][cl + 8 * gi + q] = cs[0];
+      }
+      FC_PIN();
+    }
+  }
+}
+
+template <int MODE>
 __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
+  constexpr bool REMOTE = MODE == 1, SQUARE = MODE == 2;
   __shared__ __attribute__((aligned(1024))) char ring[kSRing];
   __shared__ __attribute__((aligned(256))) float sk[2][256];      // log2(e)/tau per anchor of the tile, double buffered
   __shared__ __attribute__((aligned(256))) float sdiag[2][256];   // s_pp per anchor of the tile
   __shared__ float sred[4][2][256];
-  __shared__ __attribute__((aligned(256))) float scol[REMOTE ? 2 : 1][REMOTE ? 4 : 1][256];   // column parameters
+  __shared__ __attribute__((aligned(256))) float scol[MODE ? 2 : 1][REMOTE ? 4 : (SQUARE ? 2 : 1)][256];   // column parameters
+  __shared__ float sredc[SQUARE ? 2 : 1][2][SQUARE ? 256 : 1];   // column sums of the two anchor halves of a tile
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wr = wave >> 1, wc = wave & 1, lr = lane & 31, hk = lane >> 5;
@@ -278,7 +373,8 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   // The barrier of stream stage g waits for the loads of stage g + 1; nothing is issued after them except, at a tile
   // change, the 16 fragment stores and 1 sum store of the finished tile and the scalar load of the new one
   // (kind 1: 18 per wave), or, for the first tile, the scalar load alone (kind 2).  S >= 2 keeps these episodes apart.
-  // REMOTE: 32 fragment stores and 3 scalar loads, i.e. 36 and 3.
+  // MODE 1: 32 fragment stores and 3 scalar loads, i.e. 36 and 3.  MODE 2: 32 fragment stores, 2 sum stores and 2
+  // scalar loads, i.e. 36 and 2.
   int pend_kind = 2;
   const bool early = wave < 4;
   bool late_pending = false;
@@ -293,6 +389,10 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
       const float* cp = a.colp + ((int64_t)strip * a.nCT + ct) * 1024;
       dma4(cp + wave * 64, lane * 4, lds_addr(&scol[buf][0][0] + wave * 64));
       dma4(cp + (wave + 8) * 64, lane * 4, lds_addr(&scol[buf][0][0] + (wave + 8) * 64));
+    }
+    if constexpr (SQUARE) {   // the text anchors of the tile's columns (off == 0: anchor index == global row): log2(e)/tau2, s_jj
+      if (wave < 4) dma4(a.kscale[1] + c_tile + wave * 64, lane * 4, lds_addr(&scol[buf][0][wave * 64]));
+      else dma4(a.diag + c_tile + (wave - 4) * 64, lane * 4, lds_addr(&scol[buf][1][(wave - 4) * 64]));
     }
     f32x16 acc[2][4];
     zero_acc24(acc);
@@ -321,8 +421,8 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
       // stage g + 1 has landed for this wave; the barrier (which every wave reaches with its LDS reads complete)
       // makes that true for all waves and retires the current slot: nobody reads it after this point
       if (pend_kind == 0) FC_WAIT_VMCNT0();
-      else if (pend_kind == 1) { if (REMOTE) FC_WAIT_VMCNT36(); else FC_WAIT_VMCNT18(); }
-      else { if (REMOTE) FC_WAIT_VMCNT3(); else FC_WAIT_VMCNT1(); }
+      else if (pend_kind == 1) { if (MODE) FC_WAIT_VMCNT36(); else FC_WAIT_VMCNT18(); }
+      else { if (REMOTE) FC_WAIT_VMCNT3(); else if (SQUARE) FC_WAIT_VMCNT2(); else FC_WAIT_VMCNT1(); }
       pend_kind = 0;
       __syncthreads();
       FC_PIN();
@@ -349,7 +449,17 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
     const int64_t row_bytes = a.nCB * 1024;
     const int own0 = (int)a.off + a_first + wc * 128;
     const bool diagonal = (c_first < own0 + 128) && (c_first + 64 > own0);
-    if (REMOTE) {
+    if constexpr (SQUARE) {
+      if (diagonal) half_epilogue<true>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+      else half_epilogue<false>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+      char* fragF0 = (char*)a.F[0] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
+      const int64_t row_bytesF = a.nCBF * 1024;
+      const int cl0 = wr * 64 + 4 * (lane >> 5);
+      if (diagonal)
+        half_epilogue_cols<true>(acc, scol[buf][0], scol[buf][1], sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
+      else
+        half_epilogue_cols<false>(acc, scol[buf][0], scol[buf][1], sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
+    } else if (REMOTE) {
       char* fragF0 = (char*)a.F[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
       const int64_t row_bytesF = a.nCBF * 1024;
       const int cl0 = wr * 64 + 4 * (lane >> 5);
@@ -382,6 +492,15 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
       const int q = tid >> 8, m = tid & 255;
       a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a_first + m] =
           (sred[0][q][m] + sred[1][q][m]) + (sred[2][q][m] + sred[3][q][m]);
+      // the text anchors' sums (quantities 2, 3): partial number = the anchor tile, position = the column
+      if constexpr (SQUARE) a.sums[((size_t)(2 + q) * a.nparts + at) * a.bstride + c_tile + m] = sredc[0][q][m] + sredc[1][q][m];
+    }
+    if constexpr (SQUARE) {
+      // the first operands of the next tile (read during the last step above) are read again here, so that their
+      // registers are free during this mode's larger epilogue; their slot is retired only by the next barrier
+      x0[0] = FC_LDS16(ring + (bx ^ cs)); x0[1] = FC_LDS16(ring + (bx ^ cs) + 4096);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + (ba ^ cs) + j * 4096);
     }
     pend_kind = 1;
     t = next_interior(t + G);
@@ -392,8 +511,9 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
 
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s) {
   const int grid = a.ntiles < 256 ? a.ntiles : 256;
-  if (a.colp) hipLaunchKernelGGL(k_strips_bf16<true>, dim3((unsigned)grid), dim3(512), 0, s, a);
-  else hipLaunchKernelGGL(k_strips_bf16<false>, dim3((unsigned)grid), dim3(512), 0, s, a);
+  if (a.square) hipLaunchKernelGGL(k_strips_bf16<2>, dim3((unsigned)grid), dim3(512), 0, s, a);
+  else if (a.colp) hipLaunchKernelGGL(k_strips_bf16<1>, dim3((unsigned)grid), dim3(512), 0, s, a);
+  else hipLaunchKernelGGL(k_strips_bf16<0>, dim3((unsigned)grid), dim3(512), 0, s, a);
 }
 
 }  // namespace fc

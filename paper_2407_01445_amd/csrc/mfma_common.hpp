@@ -108,6 +108,9 @@ struct StripArgs {
                                 // c_j (0 where column j takes no part), unused
   bf16_t* F[2];                 // second stored strip c_j l(j, p_r), fragment order, nCBF column blocks per anchor block
   int64_t nCBF;
+  // the whole batch is local and every tile is whole: only strip 0 is formed, l2(j, p) of the text anchors goes to
+  // F[0] and their sums are taken down the columns
+  int square;
 };
 
 // Whole 256 x 256 tiles go to the persistent kernel, tiles with a ragged edge to the guarded one.

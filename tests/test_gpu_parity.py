@@ -112,6 +112,11 @@ BF16_SMALL = [
     (768, 512, 256, 128),
     (1024, 300, 512, 256),
     (900, 512, 388, 96),
+    # the whole batch local and only whole tiles
+    (512, 512, 0, 128),
+    (768, 768, 0, 192),
+    # ... and more tiles than compute units: the similarity matrix is formed once, sums down the columns
+    (3072, 3072, 0, 128),
 ]
 
 
@@ -359,7 +364,8 @@ def test_gradients_through_normalisation(dtype, tol, shape, version):
     compare(g.outputs(), want, version, tol, "normalised %s %s v%d" % (dtype, shape, version))
 
 
-@pytest.mark.parametrize("dtype,tol,B,d", [("f32", TOL_F32, 64, 32), ("bf16", TOL_BF16, 520, 64)])
+@pytest.mark.parametrize("dtype,tol,B,d", [("f32", TOL_F32, 64, 32), ("bf16", TOL_BF16, 520, 64),
+                                          ("bf16", TOL_BF16, 512, 128)])
 def test_mini_batch_contrastive_loss_is_a_special_case(dtype, tol, B, d):
     """The OpenCLIP-style mini-batch contrastive loss needs no code of its own: with zero state (u = g), V1 and
     eps = 1/M the step's gradient is that of tau (CE_rows(S/tau) + CE_cols(S/tau)) (softmax cross-entropy with the
