@@ -174,32 +174,55 @@ def main():
 
     # ---- the state-update kernel alone on many indices: the HBM-bound part of the method
     if not args.no_state_bench:
-        n_idx = min(1 << 24, N)          # distinct indices: at most N of them
-        big_idx = torch.randperm(N, device=dev)[:n_idx].contiguous()
-        s1 = torch.rand(n_idx, **f32) * 100 + 1
-        s2 = torch.rand(n_idx, **f32) * 100 + 1
-        o1, o2 = torch.empty(n_idx, **f32), torch.empty(n_idx, **f32)
-        for _ in range(2):
-            fc.fastclip_state_update(big_idx, n_idx, N, 0.5, float(B - 1), s1, s2, u_img, u_txt, o1, o2)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 10
-        e0.record()
-        for _ in range(reps):
-            fc.fastclip_state_update(big_idx, n_idx, N, 0.5, float(B - 1), s1, s2, u_img, u_txt, o1, o2)
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / reps
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+
+        def timed(fn, reps=10):
+            for _ in range(2):
+                fn()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        # what a plain streaming copy reaches on this machine (1 GiB read + 1 GiB written): the practical HBM ceiling
+        src = torch.empty(1 << 28, **f32)
+        dst = torch.empty_like(src)
+        copy_ms = timed(lambda: dst.copy_(src), reps=5)
+        copy_gbps = 2.0 * src.numel() * 4 / (copy_ms * 1e-3) / 1e9
+        del src, dst
+        n_max = min(1 << 24, N)          # distinct indices: at most N of them
+        perm = torch.randperm(N, device=dev)[:n_max].contiguous()
+        s1 = torch.rand(n_max, **f32) * 100 + 1
+        s2 = torch.rand(n_max, **f32) * 100 + 1
+        o1, o2 = torch.empty(n_max, **f32), torch.empty(n_max, **f32)
+        sweep = []
+        for n_idx in sorted({min(b, n_max), min(1 << 15, n_max), min(1 << 20, n_max), n_max}):
+            ms = timed(lambda: fc.fastclip_state_update(perm, n_idx, N, 0.5, float(B - 1), s1, s2, u_img, u_txt, o1, o2))
+            sweep.append({"n_idx": n_idx, "ms": round(ms, 5), "algorithmic_GBps": round(40.0 * n_idx / (ms * 1e-3) / 1e9, 1)})
+        n_idx, ms = sweep[-1]["n_idx"], sweep[-1]["ms"]
         alg_bytes = 40.0 * n_idx     # idx 8 + u read 2x4 + u write 2x4 + sums 2x4 + u_new 2x4
         out["state_update"] = {"kernel": "k_state_flat", "n_idx": n_idx, "N": N, "ms": round(ms, 4),
                                "bound": "hbm", "achieved": round(alg_bytes / (ms * 1e-3) / 1e9, 1),
                                "peak": PEAK_HBM_BYTES / 1e9, "unit": "GB/s",
                                "frac": round(alg_bytes / (ms * 1e-3) / PEAK_HBM_BYTES, 4),
-                               "algorithmic_bytes_per_index": 40}
+                               "algorithmic_bytes_per_index": 40, "sweep": sweep,
+                               "copy_ceiling_GBps": round(copy_gbps, 1)}
         tr = MEASURED_TRAFFIC.get((name, "state_flat_2^24")) if n_idx == 1 << 24 else None
         if tr is not None:      # what the memory system moves for these random 4-byte accesses (rocprofv3 counters)
             out["state_update"]["traffic"] = tr
             out["state_update"]["traffic_frac_of_peak"] = round(tr / (ms * 1e-3) / PEAK_HBM_BYTES, 4)
-        del big_idx, s1, s2, o1, o2
+            out["state_update"]["traffic_frac_of_copy_ceiling"] = round(tr / (ms * 1e-3) / 1e9 / copy_gbps, 4)
+        # the same update with u_1, u_2 as the two fields of one record per sample (state_stride = 2): one memory
+        # line per sample instead of two
+        rec = torch.zeros(N, 2, **f32)
+        ms_rec = timed(lambda: fc.fastclip_state_update_strided(perm, n_max, N, 2, 0.5, float(B - 1), s1, s2,
+                                                                rec[:, 0], rec[:, 1], o1, o2))
+        out["state_update"]["records_stride_2"] = {"n_idx": n_max, "ms": round(ms_rec, 4),
+                                                   "algorithmic_GBps": round(40.0 * n_max / (ms_rec * 1e-3) / 1e9, 1)}
+        del perm, s1, s2, o1, o2, rec
 
     # ---- the CPU oracle on the same workload (one full step), host cores
     if not args.no_cpu_baseline:

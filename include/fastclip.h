@@ -33,7 +33,7 @@ extern "C" {
 typedef enum {
   FASTCLIP_OK = 0,
   FASTCLIP_ERR_NULL = 1,        /* a required pointer is NULL */
-  FASTCLIP_ERR_SHAPE = 2,       /* B<2, b<1, off<0, off+b>B, d<1, ld<d, N<1, b>N, bad struct_size, unknown flag */
+  FASTCLIP_ERR_SHAPE = 2,       /* B<2, b<1, off<0, off+b>B, d<1, ld<d, N<1, b>N, state_stride outside [1,64], bad struct_size, unknown flag */
   FASTCLIP_ERR_VALUE = 3,       /* gamma not in (0,1], eps<0, NaN scalar, unknown version or dtype */
   FASTCLIP_ERR_WORKSPACE = 4,   /* workspace_bytes smaller than fastclip_workspace_bytes() */
   FASTCLIP_ERR_UNSUPPORTED = 5, /* bf16 path: d or a row stride not a multiple of 8, a matrix base not
@@ -73,7 +73,13 @@ typedef struct {
   int32_t  flags;            /* 0, or FASTCLIP_GATHERED_STATE; any other bit is an error */
   int64_t  B, b, off, d;     /* global rows, local anchors, first local row, embedding width */
   int64_t  ld_img, ld_txt;   /* row strides of img_glob / txt_glob in elements, >= d */
-  int64_t  N;                /* length of the state arrays */
+  int64_t  N;                /* samples in the state arrays */
+  int64_t  state_stride;     /* elements between the entries of consecutive samples in EVERY per-sample state array
+                                (u_img, u_txt, tau_img, tau_txt; with fastclip_step_update_tau also the temperatures'
+                                moments).  1: dense arrays of N floats.  S > 1: the arrays are fields of N records of
+                                S floats each (pass the address of the field in record 0), so that everything the
+                                method keeps for a sample lies in one memory line and one line is moved per
+                                sample instead of one per array.  1 <= S <= 64 */
   float    gamma;            /* inner learning rate of Eq. 1, in (0, 1] */
   float    eps;              /* the small constant inside log(eps + g) */
   float    rho;              /* RGCL / RGCL-g hyper-parameter (V2, V3) */
@@ -167,7 +173,8 @@ typedef struct {             /* host scalars */
   float    lr, beta1, beta2, eps;
   float    tau_min;
   float    lr_drop_below, lr_drop_factor;
-  float    reserved;         /* must be 0 */
+  int32_t  state_stride;     /* V2: elements between consecutive samples in the [N] arrays of fastclip_tau_state
+                                (see fastclip_config.state_stride); 0 or 1 = dense */
 } fastclip_tau_update;
 
 typedef struct {             /* DEVICE memory owned by the caller, updated in place */
@@ -208,6 +215,13 @@ fastclip_status fastclip_state_update(const int64_t* idx, int64_t n, int64_t N, 
                                       const float* sum_img, const float* sum_txt,
                                       float* u_img, float* u_txt,
                                       float* u_new_img, float* u_new_txt, void* stream);
+/* The same with u_img / u_txt as fields of N records of state_stride floats (fastclip_config.state_stride):
+ * sample i is u_img[i * state_stride], u_txt[i * state_stride].  With both fields in one record a sample costs one
+ * memory line instead of two. */
+fastclip_status fastclip_state_update_strided(const int64_t* idx, int64_t n, int64_t N, int64_t state_stride,
+                                              float gamma, float M, const float* sum_img, const float* sum_txt,
+                                              float* u_img, float* u_txt, float* u_new_img, float* u_new_txt,
+                                              void* stream);
 
 /* Debug aid: checks on the device that idx[0..b) are distinct and inside [0, N).
  * Needs fastclip_check_indices_workspace_bytes(b) bytes of workspace.  SYNCHRONISES the

@@ -23,7 +23,7 @@ class fastclip_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("version", C.c_int32), ("emb_dtype", C.c_int32),
                 ("flags", C.c_int32),
                 ("B", C.c_int64), ("b", C.c_int64), ("off", C.c_int64), ("d", C.c_int64),
-                ("ld_img", C.c_int64), ("ld_txt", C.c_int64), ("N", C.c_int64),
+                ("ld_img", C.c_int64), ("ld_txt", C.c_int64), ("N", C.c_int64), ("state_stride", C.c_int64),
                 ("gamma", C.c_float), ("eps", C.c_float), ("rho", C.c_float), ("tau_grad_scale", C.c_float)]
 
 
@@ -43,7 +43,7 @@ class fastclip_tau_update(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("optimizer", C.c_int32), ("step", C.c_int64),
                 ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
                 ("tau_min", C.c_float), ("lr_drop_below", C.c_float), ("lr_drop_factor", C.c_float),
-                ("reserved", C.c_float)]
+                ("state_stride", C.c_int32)]
 
 
 _TAU_STATE_FIELDS = ["tau", "m", "v", "tau_img", "tau_txt", "m_img", "v_img", "m_txt", "v_txt"]
@@ -83,6 +83,9 @@ def load(build_if_missing: bool = True):
     lib.fastclip_phase_name.argtypes = [C.c_int]
     lib.fastclip_state_update.restype = C.c_int
     lib.fastclip_state_update.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_float, C.c_float] + [C.c_void_p] * 7
+    lib.fastclip_state_update_strided.restype = C.c_int
+    lib.fastclip_state_update_strided.argtypes = ([C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_float, C.c_float] +
+                                                  [C.c_void_p] * 7)
     lib.fastclip_check_indices_workspace_bytes.restype = C.c_size_t
     lib.fastclip_check_indices_workspace_bytes.argtypes = [C.c_int64]
     lib.fastclip_check_indices.restype = C.c_int
@@ -113,10 +116,10 @@ class FastclipError(RuntimeError):
 
 
 def make_config(*, version, emb_dtype, B, b, off, d, N, gamma, eps, rho=0.0, tau_grad_scale=1.0,
-                ld_img=None, ld_txt=None, flags=0) -> fastclip_config:
+                ld_img=None, ld_txt=None, flags=0, state_stride=1) -> fastclip_config:
     return fastclip_config(C.sizeof(fastclip_config), int(version), int(emb_dtype), int(flags), int(B), int(b), int(off),
                            int(d), int(d if ld_img is None else ld_img), int(d if ld_txt is None else ld_txt),
-                           int(N), float(gamma), float(eps), float(rho), float(tau_grad_scale))
+                           int(N), int(state_stride), float(gamma), float(eps), float(rho), float(tau_grad_scale))
 
 
 def _ptr(t):
@@ -138,9 +141,10 @@ def make_buffers(**tensors) -> fastclip_buffers:
 
 
 def make_tau_update(*, optimizer, step, lr, beta1, beta2, eps=1e-8, tau_min=0.0, lr_drop_below=0.0,
-                    lr_drop_factor=1.0) -> fastclip_tau_update:
+                    lr_drop_factor=1.0, state_stride=0) -> fastclip_tau_update:
     return fastclip_tau_update(C.sizeof(fastclip_tau_update), int(optimizer), int(step), float(lr), float(beta1),
-                               float(beta2), float(eps), float(tau_min), float(lr_drop_below), float(lr_drop_factor), 0.0)
+                               float(beta2), float(eps), float(tau_min), float(lr_drop_below), float(lr_drop_factor),
+                               int(state_stride))
 
 
 def make_tau_state(**tensors) -> fastclip_tau_state:
@@ -216,6 +220,16 @@ def fastclip_state_update(idx, n, N, gamma, M, sum_img, sum_txt, u_img, u_txt, u
     st = int(load().fastclip_state_update(_ptr(idx), int(n), int(N), float(gamma), float(M), _ptr(sum_img),
                                           _ptr(sum_txt), _ptr(u_img), _ptr(u_txt), _ptr(u_new_img),
                                           _ptr(u_new_txt), _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+def fastclip_state_update_strided(idx, n, N, state_stride, gamma, M, sum_img, sum_txt, u_img, u_txt, u_new_img,
+                                  u_new_txt, stream=None, check=True) -> int:
+    st = int(load().fastclip_state_update_strided(_ptr(idx), int(n), int(N), int(state_stride), float(gamma), float(M),
+                                                  _ptr(sum_img), _ptr(sum_txt), _ptr(u_img), _ptr(u_txt),
+                                                  _ptr(u_new_img), _ptr(u_new_txt), _stream(stream)))
     if check and st != OK:
         raise FastclipError(st)
     return st

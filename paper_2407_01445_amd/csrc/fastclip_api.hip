@@ -27,7 +27,8 @@ fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* buf
   if (!cfg) return FASTCLIP_ERR_NULL;
   if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~FASTCLIP_GATHERED_STATE)) return FASTCLIP_ERR_SHAPE;
   if (cfg->B < 2 || cfg->b < 1 || cfg->off < 0 || cfg->off + cfg->b > cfg->B || cfg->d < 1 ||
-      cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1 || cfg->b > cfg->N)
+      cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1 || cfg->b > cfg->N || cfg->state_stride < 1 ||
+      cfg->state_stride > 64)
     return FASTCLIP_ERR_SHAPE;
   if (cfg->version < FASTCLIP_V0 || cfg->version > FASTCLIP_V3) return FASTCLIP_ERR_VALUE;
   if (cfg->emb_dtype != FASTCLIP_F32 && cfg->emb_dtype != FASTCLIP_BF16) return FASTCLIP_ERR_VALUE;
@@ -70,7 +71,8 @@ fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* buf
 
 fastclip_status validate_tau_update(int32_t version, const fastclip_tau_update* upd, const fastclip_tau_state* st) {
   if (!upd || !st) return FASTCLIP_ERR_NULL;
-  if (upd->struct_size != sizeof(fastclip_tau_update) || upd->reserved != 0.0f) return FASTCLIP_ERR_SHAPE;
+  if (upd->struct_size != sizeof(fastclip_tau_update) || upd->state_stride < 0 || upd->state_stride > 64)
+    return FASTCLIP_ERR_SHAPE;
   if (version < FASTCLIP_V0 || version > FASTCLIP_V3) return FASTCLIP_ERR_VALUE;
   if (upd->optimizer < FASTCLIP_TAU_SGDM || upd->optimizer > FASTCLIP_TAU_ADAMW) return FASTCLIP_ERR_VALUE;
   const float f[7] = {upd->lr, upd->beta1, upd->beta2, upd->eps, upd->tau_min, upd->lr_drop_below, upd->lr_drop_factor};
@@ -97,6 +99,7 @@ TauUpd make_tau_upd(const fastclip_tau_update& upd) {
   u.corr1 = (float)(1.0 / (1.0 - pow((double)upd.beta1, (double)upd.step)));
   u.corr2 = (float)(1.0 / (1.0 - pow((double)upd.beta2, (double)upd.step)));
   u.tau_min = upd.tau_min; u.drop_below = upd.lr_drop_below; u.drop_factor = upd.lr_drop_factor;
+  u.stride = upd.state_stride > 1 ? upd.state_stride : 1;
   return u;
 }
 
@@ -191,6 +194,8 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
     if (cfg->version == FASTCLIP_V2 ? (tst->tau_img != bufs->tau_img || tst->tau_txt != bufs->tau_txt)
                                     : (cfg->version != FASTCLIP_V1 && tst->tau != bufs->tau))
       return FASTCLIP_ERR_VALUE;
+    // ... laid out as the step's own state arrays are
+    if ((upd->state_stride > 1 ? upd->state_stride : 1) != cfg->state_stride) return FASTCLIP_ERR_VALUE;
     if (cfg->version != FASTCLIP_V1) { c.tau_upd = make_tau_upd(*upd); c.tau_st = *tst; }
   }
   make_layout(*cfg, &c.L);
@@ -309,14 +314,23 @@ const char* fastclip_phase_name(int phase) {
 fastclip_status fastclip_state_update(const int64_t* idx, int64_t n, int64_t N, float gamma, float M,
                                       const float* sum_img, const float* sum_txt, float* u_img, float* u_txt,
                                       float* u_new_img, float* u_new_txt, void* stream) {
+  return fastclip_state_update_strided(idx, n, N, 1, gamma, M, sum_img, sum_txt, u_img, u_txt, u_new_img, u_new_txt,
+                                       stream);
+}
+
+fastclip_status fastclip_state_update_strided(const int64_t* idx, int64_t n, int64_t N, int64_t state_stride,
+                                              float gamma, float M, const float* sum_img, const float* sum_txt,
+                                              float* u_img, float* u_txt, float* u_new_img, float* u_new_txt,
+                                              void* stream) {
   if (!idx || !sum_img || !sum_txt || !u_img || !u_txt || !u_new_img || !u_new_txt) return FASTCLIP_ERR_NULL;
   // the indices are distinct values in [0, N), so there cannot be more than N of them
-  if (n < 0 || N < 1 || n > N || n > ((int64_t)1 << 31) - 1024) return FASTCLIP_ERR_SHAPE;
+  if (n < 0 || N < 1 || n > N || n > ((int64_t)1 << 31) - 1024 || state_stride < 1 || state_stride > 64)
+    return FASTCLIP_ERR_SHAPE;
   if (fc::bad_float(gamma) || fc::bad_float(M) || !(gamma > 0.0f && gamma <= 1.0f) || !(M > 0.0f))
     return FASTCLIP_ERR_VALUE;
   if (n == 0) return FASTCLIP_OK;
   (void)hipGetLastError();
-  fc::launch_state_flat(idx, n, N, gamma, M, sum_img, sum_txt, u_img, u_txt, u_new_img, u_new_txt,
+  fc::launch_state_flat(idx, n, state_stride, gamma, M, sum_img, sum_txt, u_img, u_txt, u_new_img, u_new_txt,
                         (hipStream_t)stream);
   return fc::launch_status();
 }

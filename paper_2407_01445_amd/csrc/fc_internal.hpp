@@ -55,6 +55,7 @@ void make_layout(const fastclip_config& cfg, Layout* L);
 struct TauUpd {
   int optimizer;      // 0: no update
   float lr, beta1, beta2, eps, corr1, corr2, tau_min, drop_below, drop_factor;
+  int64_t stride;     // elements between consecutive samples in the per-sample arrays
 };
 fastclip_status validate_tau_update(int32_t version, const fastclip_tau_update* upd, const fastclip_tau_state* st);
 TauUpd make_tau_upd(const fastclip_tau_update& upd);
@@ -79,7 +80,7 @@ void launch_fold_bf16(const StepCtx& c);       // MFMA path: local contrast-side
 void launch_contract_bf16(const StepCtx& c);   // MFMA path: strips x X contractions
 void launch_finalize_bf16(const StepCtx& c);   // MFMA path: combine + scalars
 
-void launch_state_flat(const int64_t* idx, int64_t n, int64_t N, float gamma, float M,
+void launch_state_flat(const int64_t* idx, int64_t n, int64_t stride, float gamma, float M,
                        const float* sum_img, const float* sum_txt, float* u_img, float* u_txt,
                        float* u_new_img, float* u_new_txt, hipStream_t s);
 void launch_check_indices(const int64_t* idx, int64_t b, int64_t N, void* ws, hipStream_t s);

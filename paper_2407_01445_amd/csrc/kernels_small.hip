@@ -52,7 +52,8 @@ __global__ void __launch_bounds__(256) k_prep(const T* __restrict__ img, const T
                                               int64_t ld_txt, int64_t off, int64_t b, int64_t d,
                                               const int64_t* __restrict__ idx, const float* __restrict__ tau,
                                               const float* __restrict__ tau_img, const float* __restrict__ tau_txt,
-                                              int version, float* __restrict__ diag, float* __restrict__ tau1,
+                                              int64_t stride, int version, float* __restrict__ diag,
+                                              float* __restrict__ tau1,
                                               float* __restrict__ tau2, float* __restrict__ k1, float* __restrict__ k2) {
   const int lane = threadIdx.x & 63;
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -60,7 +61,7 @@ __global__ void __launch_bounds__(256) k_prep(const T* __restrict__ img, const T
   float t1 = 0.f, t2 = 0.f;
   if (lane == 0) {        // issue the temperature gather before the dot product so that the latencies overlap
     if (version == FASTCLIP_V2) {
-      const int64_t n = idx[r];
+      const int64_t n = idx[r] * stride;
       t1 = tau_img[n];
       t2 = tau_txt[n];
     } else {
@@ -88,11 +89,11 @@ void launch_prep(const StepCtx& c) {
   if (L.bf16)
     hipLaunchKernelGGL(k_prep<bf16_t>, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
                        c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, c.buf.idx, c.buf.tau, c.buf.tau_img,
-                       c.buf.tau_txt, c.cfg.version, diag, tau1, tau2, k1, k2);
+                       c.buf.tau_txt, c.cfg.state_stride, c.cfg.version, diag, tau1, tau2, k1, k2);
   else
     hipLaunchKernelGGL(k_prep<float>, grid, block, 0, c.s, (const float*)c.buf.img_glob, (const float*)c.buf.txt_glob,
                        c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, c.buf.idx, c.buf.tau, c.buf.tau_img,
-                       c.buf.tau_txt, c.cfg.version, diag, tau1, tau2, k1, k2);
+                       c.buf.tau_txt, c.cfg.state_stride, c.cfg.version, diag, tau1, tau2, k1, k2);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -260,7 +261,7 @@ __global__ void __launch_bounds__(256) k_tau_sparse(TauUpd u, const int64_t* __r
                                                     float* m_txt, float* v_txt) {
   const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (r >= b) return;
-  const int64_t n = idx[r];
+  const int64_t n = idx[r] * u.stride;
   tau_step(u, tau_img + n, m_img + n, v_img ? v_img + n : nullptr, g_img[r]);
   tau_step(u, tau_txt + n, m_txt + n, v_txt ? v_txt + n : nullptr, g_txt[r]);
 }
@@ -286,6 +287,7 @@ struct StateArgs {
   const float* sums;   // [4][nparts][bstride]
   int nparts;
   int64_t bstride, b;
+  int64_t stride;      // elements between consecutive samples in u_img / u_txt (and the temperature arrays)
   float M, gamma, eps, rho, tau_scale;
   int version;
   float *c1, *c2, *dcoef, *red;
@@ -329,7 +331,7 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
       for (int q = 0; q < 4; ++q) s[q] = (part[q][0][al] + part[q][1][al]) + (part[q][2][al] + part[q][3][al]);
       const float invM = 1.0f / a.M;
       const float g1 = s[0] * invM, h1 = s[1] * invM, g2 = s[2] * invM, h2 = s[3] * invM;
-      const int64_t n = a.idx[r];
+      const int64_t n = a.idx[r] * a.stride;
       const float u1 = ema_update(a.u_img[n], g1, a.gamma);
       const float u2 = ema_update(a.u_txt[n], g2, a.gamma);
       a.u_img[n] = u1;
@@ -380,6 +382,7 @@ void launch_state(const StepCtx& c) {
   a.idx = c.buf.idx; a.u_img = c.buf.u_img; a.u_txt = c.buf.u_txt;
   a.tau1 = (const float*)(c.ws + L.tau1); a.tau2 = (const float*)(c.ws + L.tau2);
   a.sums = (const float*)(c.ws + L.sums); a.nparts = L.nparts; a.bstride = L.bstride; a.b = L.b;
+  a.stride = c.cfg.state_stride;
   a.M = (float)(L.B - 1); a.gamma = c.cfg.gamma; a.eps = c.cfg.eps; a.rho = c.cfg.rho;
   a.tau_scale = c.cfg.tau_grad_scale; a.version = c.cfg.version;
   a.c1 = (float*)(c.ws + L.c1); a.c2 = (float*)(c.ws + L.c2); a.dcoef = (float*)(c.ws + L.dcoef);
@@ -394,13 +397,14 @@ void launch_state(const StepCtx& c) {
 }
 
 // Eq. 1 alone, one thread per anchor (the same update as in k_state).
-__global__ void __launch_bounds__(256) k_state_flat(const int64_t* __restrict__ idx, int64_t n, float gamma, float invM,
+__global__ void __launch_bounds__(256) k_state_flat(const int64_t* __restrict__ idx, int64_t n, int64_t stride,
+                                                    float gamma, float invM,
                                                     const float* __restrict__ s1, const float* __restrict__ s2,
                                                     float* __restrict__ u_img, float* __restrict__ u_txt,
                                                     float* __restrict__ o1, float* __restrict__ o2) {
   const int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x;
   if (r >= n) return;
-  const int64_t i = idx[r];
+  const int64_t i = idx[r] * stride;
   const float u1 = ema_update(u_img[i], s1[r] * invM, gamma);
   const float u2 = ema_update(u_txt[i], s2[r] * invM, gamma);
   u_img[i] = u1;
@@ -409,11 +413,10 @@ __global__ void __launch_bounds__(256) k_state_flat(const int64_t* __restrict__ 
   o2[r] = u2;
 }
 
-void launch_state_flat(const int64_t* idx, int64_t n, int64_t N, float gamma, float M, const float* sum_img,
+void launch_state_flat(const int64_t* idx, int64_t n, int64_t stride, float gamma, float M, const float* sum_img,
                        const float* sum_txt, float* u_img, float* u_txt, float* u_new_img, float* u_new_txt,
                        hipStream_t s) {
-  (void)N;
-  hipLaunchKernelGGL(k_state_flat, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, idx, n, gamma, 1.0f / M, sum_img,
+  hipLaunchKernelGGL(k_state_flat, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, idx, n, stride, gamma, 1.0f / M, sum_img,
                      sum_txt, u_img, u_txt, u_new_img, u_new_txt);
 }
 

@@ -10,6 +10,7 @@ import torch
 from paper_2407_01445_amd import binding as fc
 
 DEV = "cuda:0"
+RECORD_FILL = 7.5      # what the unused fields of a state record hold
 
 
 def to_dev_matrix(x32: np.ndarray, dtype: str, ld: int | None = None) -> torch.Tensor:
@@ -29,7 +30,7 @@ class GpuStep:
 
     def __init__(self, *, B, b, off, d, N, dtype, version, eps, rho=0.0, tau=0.07, tau_grad_scale=1.0,
                  ld_img=None, ld_txt=None, u_img0=None, u_txt0=None, tau_img0=None, tau_txt0=None, gathered=None,
-                 norms=None):
+                 norms=None, state_stride=1):
         """gathered: None, or dict(u_img=[B], u_txt=[B], tau_img=[B] or None, tau_txt=[B] or None) = the state
         gathered from all workers (the step then runs with FASTCLIP_GATHERED_STATE)."""
         self.B, self.b, self.off, self.d, self.N = B, b, off, d, N
@@ -44,6 +45,16 @@ class GpuStep:
         if version == fc.V2:
             self.tau_img = torch.full((N,), tau, **f32) if tau_img0 is None else torch.from_numpy(np.asarray(tau_img0, np.float32)).to(DEV)
             self.tau_txt = torch.full((N,), tau, **f32) if tau_txt0 is None else torch.from_numpy(np.asarray(tau_txt0, np.float32)).to(DEV)
+        self.state_stride = state_stride
+        self.records = None
+        if state_stride > 1:
+            assert state_stride >= 4
+            self.records = torch.full((N, state_stride), RECORD_FILL, **f32)
+            self.records[:, 0], self.records[:, 1] = self.u_img, self.u_txt
+            self.u_img, self.u_txt = self.records[:, 0], self.records[:, 1]
+            if version == fc.V2:
+                self.records[:, 2], self.records[:, 3] = self.tau_img, self.tau_txt
+                self.tau_img, self.tau_txt = self.records[:, 2], self.records[:, 3]
         nan = float("nan")
         self.d_img = torch.full((b, d), nan, **f32)
         self.d_txt = torch.full((b, d), nan, **f32)
@@ -73,7 +84,7 @@ class GpuStep:
         return fc.make_config(version=self.version, emb_dtype=fc.BF16 if self.dtype == "bf16" else fc.F32,
                               B=self.B, b=self.b, off=self.off, d=self.d, N=self.N, gamma=gamma, eps=self.eps,
                               rho=self.rho, tau_grad_scale=self.scale, ld_img=self.ld_img, ld_txt=self.ld_txt,
-                              flags=self.flags)
+                              flags=self.flags, state_stride=self.state_stride)
 
     def set_inputs(self, img32, txt32, idx):
         self.img = to_dev_matrix(img32, self.dtype, self.ld_img)

@@ -39,7 +39,7 @@ def test_library_exports_every_declared_function():
 
 
 def test_struct_sizes_match_header_layout():
-    assert C.sizeof(fc.fastclip_config) == 16 + 7 * 8 + 4 * 4
+    assert C.sizeof(fc.fastclip_config) == 16 + 8 * 8 + 4 * 4
     assert C.sizeof(fc.fastclip_buffers) == 24 * 8
 
 
@@ -57,7 +57,8 @@ def test_valid_config_and_workspace_size():
 @pytest.mark.parametrize("over,status", [
     (dict(B=1), fc.ERR_SHAPE), (dict(b=0), fc.ERR_SHAPE), (dict(off=-1), fc.ERR_SHAPE),
     (dict(off=900), fc.ERR_SHAPE), (dict(d=0), fc.ERR_SHAPE), (dict(ld_img=100), fc.ERR_SHAPE),
-    (dict(ld_txt=511), fc.ERR_SHAPE), (dict(N=0), fc.ERR_SHAPE),
+    (dict(ld_txt=511), fc.ERR_SHAPE), (dict(N=0), fc.ERR_SHAPE), (dict(N=100), fc.ERR_SHAPE),   # b > N
+    (dict(state_stride=0), fc.ERR_SHAPE), (dict(state_stride=65), fc.ERR_SHAPE),
     (dict(gamma=0.0), fc.ERR_VALUE), (dict(gamma=1.5), fc.ERR_VALUE), (dict(gamma=float("nan")), fc.ERR_VALUE),
     (dict(eps=-1e-3), fc.ERR_VALUE), (dict(rho=float("inf")), fc.ERR_VALUE), (dict(version=7), fc.ERR_VALUE),
     (dict(emb_dtype=3), fc.ERR_VALUE), (dict(tau_grad_scale=float("nan")), fc.ERR_VALUE),
@@ -147,6 +148,9 @@ def test_state_update_and_check_indices_argument_errors():
     assert lib.fastclip_state_update(1, 4, 10, 0.0, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_VALUE
     assert lib.fastclip_state_update(1, 4, 10, 0.5, 0.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_VALUE
     assert lib.fastclip_state_update(1, 0, 10, 0.5, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.OK      # empty batch
+    assert lib.fastclip_state_update_strided(1, 4, 10, 0, 0.5, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_SHAPE
+    assert lib.fastclip_state_update_strided(1, 4, 10, 65, 0.5, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.ERR_SHAPE
+    assert lib.fastclip_state_update_strided(1, 0, 10, 4, 0.5, 3.0, 1, 1, 1, 1, 1, 1, None) == fc.OK
     need = fc.fastclip_check_indices_workspace_bytes(100)
     assert need >= 256 + 200 * 8
     assert lib.fastclip_check_indices(None, 100, 10, 0x1000, need, None) == fc.ERR_NULL
@@ -182,6 +186,9 @@ def test_temperature_update_argument_errors():
     assert call(fc.V2, upd, st3) == fc.ERR_NULL                             # V2 needs the per-sample arrays
     assert call(fc.V2, upd, st2, idx=None) == fc.ERR_NULL
     assert call(fc.V2, upd, st2, b=-1) == fc.ERR_SHAPE
+    assert call(fc.V2, upd, st2, b=11) == fc.ERR_SHAPE                      # more indices than the 10 entries
+    assert call(fc.V2, fc.make_tau_update(state_stride=-1, **good), st2) == fc.ERR_SHAPE
+    assert call(fc.V2, fc.make_tau_update(state_stride=65, **good), st2) == fc.ERR_SHAPE
     assert call(fc.V2, upd, st2, b=0) == fc.OK
     assert call(7, upd, st3) == fc.ERR_VALUE
     for bad in (dict(optimizer=0), dict(optimizer=5), dict(step=0), dict(lr=-1.0), dict(beta1=1.0), dict(beta2=-0.1),
@@ -198,4 +205,9 @@ def test_temperature_update_argument_errors():
     bufs = fake_bufs(cfg)
     assert fc.fastclip_step_update_tau(cfg, bufs, sg, fc.make_tau_state(tau=0x999, m=0x2000), 0x1000, 1 << 40,
                                        stream=0, check=False) == fc.ERR_VALUE
+    # ... and that both describe the same layout of the per-sample arrays
+    cfg2 = good_cfg(version=fc.V2, state_stride=4)
+    bufs2 = fake_bufs(cfg2)
+    st_same = fc.make_tau_state(tau_img=bufs2.tau_img, tau_txt=bufs2.tau_txt, m_img=0x3000, m_txt=0x5000)
+    assert fc.fastclip_step_update_tau(cfg2, bufs2, sg, st_same, 0x1000, 1 << 40, stream=0, check=False) == fc.ERR_VALUE
     assert fc.fastclip_step_update_tau(cfg, bufs, None, None, 0x1000, 1 << 40, stream=0, check=False) == fc.ERR_NULL

@@ -13,7 +13,7 @@ from oracle import (ADAMW, LAMB, LION, SGDM, V0, V1, V2, V3, ema_update, fcco_st
 from paper_2407_01445_amd import binding as fc
 from paper_2407_01445_amd.workloads import WORKLOADS, draw_indices, make_embeddings, step_seed
 
-from gpu_harness import DEV, GpuStep, compare, rel_each, rel_inf, rel_l2
+from gpu_harness import DEV, RECORD_FILL, GpuStep, compare, rel_each, rel_inf, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -238,9 +238,11 @@ OPTIMIZERS = [(SGDM, dict(lr=1e-3, beta1=0.9, beta2=0.0)), (LAMB, dict(lr=1e-2, 
               (LION, dict(lr=1e-3, beta1=0.9, beta2=0.99)), (ADAMW, dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8))]
 
 
+@pytest.mark.parametrize("stride", [0, 6])
 @pytest.mark.parametrize("opt,hp", OPTIMIZERS)
-def test_temperature_update_alone(opt, hp):
-    """Proc. temperature_update from given gradients: per-sample (V2) and global (V3) temperatures."""
+def test_temperature_update_alone(opt, hp, stride):
+    """Proc. temperature_update from given gradients: per-sample (V2) and global (V3) temperatures; stride 6: the six
+    per-sample arrays as the fields of one record per sample."""
     N, b, step = 5000, 300, 7
     rng = np.random.default_rng(100 + opt)
     idx = draw_indices(55, b, N)
@@ -249,8 +251,12 @@ def test_temperature_update_alone(opt, hp):
                 v_img=f32(0.01, 2, N), v_txt=f32(0.01, 2, N))
     g_img, g_txt = f32(-3, 3, b), f32(-3, 3, b)
     extra = dict(tau_min=0.025, lr_drop_below=0.03, lr_drop_factor=1.0 / 3.0)
-    dev = {k: torch.from_numpy(v).to(DEV) for k, v in host.items()}
-    upd = fc.make_tau_update(optimizer=opt, step=step, **hp, **extra)
+    if stride:
+        rec = torch.from_numpy(np.stack([host[k] for k in host], axis=1)).to(DEV)
+        dev = {k: rec[:, i] for i, k in enumerate(host)}
+    else:
+        dev = {k: torch.from_numpy(v).to(DEV) for k, v in host.items()}
+    upd = fc.make_tau_update(optimizer=opt, step=step, state_stride=stride, **hp, **extra)
     fc.fastclip_temperature_update(V2, upd, fc.make_tau_state(**dev), torch.from_numpy(idx).to(DEV), b, N, None,
                                    torch.from_numpy(g_img).to(DEV), torch.from_numpy(g_txt).to(DEV))
     torch.cuda.synchronize()
@@ -285,9 +291,10 @@ def test_temperature_update_alone(opt, hp):
             assert v.item() == pytest.approx(wv, rel=1e-5)
 
 
+@pytest.mark.parametrize("stride", [1, 8])
 @pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (64, 64, 0, 32)), ("bf16", TOL_BF16, (700, 300, 133, 72))])
 @pytest.mark.parametrize("version", [V2, V3, V0])
-def test_step_with_temperature_update_three_iterations(dtype, tol, shape, version):
+def test_step_with_temperature_update_three_iterations(dtype, tol, shape, version, stride):
     """fastclip_step_update_tau: step + temperature update per iteration, temperatures and moments carried on the
     device, against the oracle's step followed by Proc. temperature_update."""
     B, b, off, d = shape
@@ -298,9 +305,13 @@ def test_step_with_temperature_update_three_iterations(dtype, tol, shape, versio
     t_img0 = rng.uniform(0.05, 0.1, N).astype(np.float32)
     t_txt0 = rng.uniform(0.05, 0.1, N).astype(np.float32)
     g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
-                tau_grad_scale=1.0, tau_img0=t_img0, tau_txt0=t_txt0)
+                tau_grad_scale=1.0, tau_img0=t_img0, tau_txt0=t_txt0, state_stride=stride)
     z = lambda n: torch.zeros(n, dtype=torch.float32, device=DEV)
-    if version == V2:
+    if version == V2 and stride > 1:       # the moments are fields 4..7 of the same records
+        g.records[:, 4:] = 0.0
+        st_dev = dict(tau_img=g.tau_img, tau_txt=g.tau_txt, m_img=g.records[:, 4], v_img=g.records[:, 5],
+                      m_txt=g.records[:, 6], v_txt=g.records[:, 7])
+    elif version == V2:
         st_dev = dict(tau_img=g.tau_img, tau_txt=g.tau_txt, m_img=z(N), v_img=z(N), m_txt=z(N), v_txt=z(N))
     else:
         st_dev = dict(tau=g.tau, m=z(1), v=z(1))
@@ -313,7 +324,7 @@ def test_step_with_temperature_update_three_iterations(dtype, tol, shape, versio
         img, txt = make_embeddings(300 + it, B, d, 0.5, dtype)
         idx = draw_indices(400 + it, b, N)
         g.set_inputs(img, txt, idx)
-        g.step_update_tau(0.7, fc.make_tau_update(optimizer=ADAMW, step=it + 1, **hp, **extra), state)
+        g.step_update_tau(0.7, fc.make_tau_update(optimizer=ADAMW, step=it + 1, state_stride=stride, **hp, **extra), state)
         want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, u_img, u_txt, version=version,
                          gamma=0.7, eps=g.eps, rho=g.rho, tau=w["tau"], tau_img=w["tau_img"], tau_txt=w["tau_txt"],
                          tau_grad_scale=1.0)
@@ -385,6 +396,37 @@ def test_mini_batch_contrastive_loss_is_a_special_case(dtype, tol, B, d):
     assert rel_inf(g.d_txt.cpu().numpy(), T.grad.numpy()) <= tol and rel_l2(g.d_txt.cpu().numpy(), T.grad.numpy()) <= tol
     # loss: tau/B sum [log(eps + g1) + log(eps + g2)] = tau (CE - 2 log M)
     assert g.loss.item() == pytest.approx(tau * (ce.item() - 2.0 * np.log(B - 1)), rel=tol, abs=tol * tau)
+
+
+# ------------------------------------------------------------------------------- state kept as records
+@pytest.mark.parametrize("dtype,shape", [("f32", (64, 64, 0, 32)), ("bf16", (700, 300, 133, 72))])
+@pytest.mark.parametrize("version", [V2, V3])
+def test_record_state_layout_is_the_dense_step(dtype, shape, version):
+    """state_stride = 6: u_1, u_2, tau_1, tau_2 as fields of one record per sample.  Only addresses change, so every
+    output and every state entry must equal the dense run bit for bit, and the other fields stay untouched."""
+    B, b, off, d = shape
+    N = 3000
+    rng = np.random.default_rng(31 + version)
+    img, txt = make_embeddings(17, B, d, 0.5, dtype)
+    idx = draw_indices(18, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img, t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32), rng.uniform(0.05, 0.1, N).astype(np.float32)
+    runs = []
+    for stride in (1, 6):
+        g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
+                    tau_grad_scale=1.0 / N, u_img0=u0i, u_txt0=u0t, tau_img0=t_img, tau_txt0=t_txt, state_stride=stride)
+        g.set_inputs(img, txt, idx)
+        g.step(0.6)
+        runs.append(g)
+    dense, rec = runs
+    for k, v in dense.outputs().items():
+        assert np.array_equal(np.asarray(v), np.asarray(rec.outputs()[k]), equal_nan=True), k
+    assert torch.equal(dense.u_img, rec.u_img.contiguous()) and torch.equal(dense.u_txt, rec.u_txt.contiguous())
+    first_free = 4 if version == V2 else 2
+    assert (rec.records[:, first_free:] == RECORD_FILL).all()
+    if version == V2:
+        assert torch.equal(rec.tau_img.contiguous(), dense.tau_img) and torch.equal(rec.tau_txt.contiguous(), dense.tau_txt)
 
 
 # ------------------------------------------------------------------------------- full-size workloads
@@ -474,6 +516,27 @@ def test_check_indices_on_device():
             oob = idx.copy()
             oob[-1] = bad
             assert fc.fastclip_check_indices(torch.from_numpy(oob).to(DEV), b, N, ws) == fc.ERR_INDEX
+
+
+def test_state_update_alone_on_records():
+    """fastclip_state_update_strided on records {u_1, u_2, free}: bit for bit the dense call."""
+    N, n = 200_000, 50_000
+    rng = np.random.default_rng(5)
+    idx = torch.from_numpy(draw_indices(6, n, N)).to(DEV)
+    u0 = torch.from_numpy(np.where(rng.random((N, 2)) < 0.5, 0.0, rng.uniform(0.05, 2.0, (N, 2))).astype(np.float32)).to(DEV)
+    s1 = torch.from_numpy(rng.uniform(1.0, 900.0, n).astype(np.float32)).to(DEV)
+    s2 = torch.from_numpy(rng.uniform(1.0, 900.0, n).astype(np.float32)).to(DEV)
+    ui, ut = u0[:, 0].contiguous(), u0[:, 1].contiguous()
+    o = [torch.empty(n, device=DEV) for _ in range(4)]
+    fc.fastclip_state_update(idx, n, N, 0.4, 1023.0, s1, s2, ui, ut, o[0], o[1])
+    rec = torch.full((N, 3), RECORD_FILL, dtype=torch.float32, device=DEV)
+    rec[:, :2] = u0
+    fc.fastclip_state_update_strided(idx, n, N, 3, 0.4, 1023.0, s1, s2, rec[:, 0], rec[:, 1], o[2], o[3])
+    torch.cuda.synchronize()
+    assert torch.equal(o[0], o[2]) and torch.equal(o[1], o[3])
+    assert torch.equal(rec[:, 0].contiguous(), ui) and torch.equal(rec[:, 1].contiguous(), ut)
+    assert (rec[:, 2] == RECORD_FILL).all()
+    assert fc.fastclip_state_update_strided(idx, n, N, 0, 0.4, 1023.0, s1, s2, ui, ut, o[0], o[1], check=False) == fc.ERR_SHAPE
 
 
 @pytest.mark.parametrize("n", [1, 1000, 1 << 18])
