@@ -123,7 +123,8 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
     L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
     // Split of the contraction over its column range.  A workgroup owns one 256 x 256 output tile of one side and
     // `slice` stages; the 256 compute units take the workgroups in rounds.  Cost model in units of one stage time:
-    // rounds x (slice + 12 for writing the partial tile) + 2.3 per split for the finalize pass that adds them up.
+    // rounds x (slice + 12 for writing the partial tile) + 0.05 per split and output tile for the finalize pass that
+    // adds the partial results up.
     const int64_t stages = L->ldE / 32;
     const int64_t tiles = ((cfg.b + 255) / 256) * ((cfg.d + 255) / 256) * 2;
     int64_t max_split = stages / 8;
@@ -135,7 +136,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
       const int64_t slice = (stages + ns - 1) / ns;
       const int64_t used = (stages + slice - 1) / slice;          // splits that really get stages
       const int64_t rounds = (tiles * used + 255) / 256;
-      const double cost = (double)rounds * (double)(slice + 12) + 2.3 * (double)used;
+      const double cost = (double)rounds * (double)(slice + 12) + 0.05 * (double)tiles * (double)used;
       if (ns == 1 || cost < best_cost) { best = ns; best_cost = cost; }
     }
     L->kslice = (stages + best - 1) / best;
