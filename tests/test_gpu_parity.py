@@ -565,6 +565,41 @@ def test_state_update_alone(n):
     assert np.array_equal(got_t[mask].view(np.uint32), u0t[mask].view(np.uint32))
 
 
+@pytest.mark.parametrize("shape,version", [((768, 512, 256, 128), V2), ((700, 300, 133, 72), V3)])
+def test_step_replayed_from_a_hip_graph_equals_the_eager_step(shape, version):
+    """The step allocates nothing and records no memset, so a caller may capture it in a HIP graph: every replay, on
+    new inputs copied into the captured buffers and with eager work in between, equals the eager step bit for bit
+    (state carried from replay to replay on both sides)."""
+    B, b, off, d = shape
+    N = 4000
+    mk = lambda: GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=version, eps=1e-6, rho=6.5, tau=0.07,
+                         tau_grad_scale=1.0 / N)
+    eager, cap = mk(), mk()
+    inputs = [(make_embeddings(70 + i, B, d, 0.5, "bf16"), draw_indices(80 + i, b, N)) for i in range(4)]
+    (img, txt), idx = inputs[0]
+    cap.set_inputs(img, txt, idx)               # the captured buffers; later inputs are copied into them
+    cfg = cap.config(0.7)
+    ws = torch.empty(fc.fastclip_workspace_bytes(cfg), dtype=torch.uint8, device=DEV)
+    bufs = cap.buffers()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        fc.fastclip_step(cfg, bufs, ws)
+    for (img, txt), idx in inputs:
+        eager.set_inputs(img, txt, idx)
+        eager.step(0.7)
+        fresh = mk()
+        fresh.set_inputs(img, txt, idx)
+        cap.img.copy_(fresh.img)
+        cap.txt.copy_(fresh.txt)
+        cap.idx.copy_(fresh.idx)
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in ("d_img", "d_txt", "loss", "u_new_img", "u_new_txt", "u_img", "u_txt", "d_tau", "d_tau_img"):
+            x, y = getattr(eager, k), getattr(cap, k)
+            assert torch.equal(x.view(torch.int32), y.view(torch.int32)), k
+
+
 def test_step_timed_reports_phases_and_same_result():
     B, b, off, d, N = 700, 300, 133, 72, 5000
     img, txt = make_embeddings(3, B, d, 0.5, "bf16")
