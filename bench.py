@@ -38,12 +38,13 @@ def algorithmic_flops(B, b, d, gathered=False):
     """Flop the method needs per step and phase (recomputation and padding not counted): one
     'unit' = 2 b B d.  Full batch (b == B): similarity once, then W T and W^T I.  Local share:
     two strips, two anchor-side contractions, and the local contrast-side block (4 b^2 d); with
-    gathered state the contrast side runs over all B anchors instead (2 more units)."""
+    gathered state the contrast side runs over all B anchors, whose weights share the rows of the
+    anchor-side sum (one weight matrix per side: still two contractions)."""
     unit = 2.0 * b * B * d
     if b == B:
         return {"strips": unit, "contract": 2 * unit}
     if gathered:
-        return {"strips": 2 * unit, "contract": 4 * unit}
+        return {"strips": 2 * unit, "contract": 2 * unit}
     return {"strips": 2 * unit, "contract": 2 * unit + 4.0 * b * b * d}
 
 

@@ -168,8 +168,6 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
     if (L->bf16) {
       const size_t rows = round_up((size_t)cfg.b, 256);
       for (int s = 0; s < 2; ++s) L->F[s] = take(esz * rows * (size_t)L->ldE);
-      for (int s = 0; s < 2; ++s)
-        L->OpartF[s] = take(sizeof(float) * (size_t)L->nsplit * (size_t)cfg.b * (size_t)cfg.d);
     } else {
       for (int s = 0; s < 2; ++s) L->F[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
     }

@@ -40,9 +40,8 @@ struct Layout {
   // [s][tile][4][256]: log2(e)/tau_j, s_jj log2(e)/tau_j, c_j (0 for local rows and beyond B), unused.
   // Side 0 describes the text anchors j (l2(j, .), weights of d_img), side 1 the image anchors (l1(j, .), d_txt).
   size_t colp;
-  size_t F[2];                       // gathered: the second stored strip c_j l(j, p_r), same form as E without
-                                     // the local-anchor columns
-  size_t OpartF[2];                  // float [nsplit][b][d]   (MFMA path, gathered)
+  size_t F[2];                       // gathered: the second stored strip c_j l(j, p_r), same form as E, folded into E
+                                     // after the state phase (MFMA path) or summed directly (fp32 path)
   size_t total;
 };
 

@@ -570,9 +570,47 @@ __global__ void __launch_bounds__(256) k_fold_square_bf16(bf16_t* __restrict__ E
   fold_store(E1, nCB, q0, r0, b, 64, t1);
 }
 
+// Gathered state: the weights c_j l(j, p_r) of the remote anchors (strip F, stored by the strip kernel in the layout of
+// E) multiply the same rows of X as l(r, j) does, so E[r][j] += F[r][j] / c_own[r] lets one contraction per side
+// produce both sums (its result is multiplied by c_own[r] afterwards).  F is 0 at the local rows' columns, which
+// k_fold_bf16 handles, so the two folds touch E independently.  One 16-byte fragment chunk per thread.
+__global__ void __launch_bounds__(256) k_fold_remote_bf16(bf16_t* __restrict__ E0, const bf16_t* __restrict__ F0,
+                                                          bf16_t* __restrict__ E1, const bf16_t* __restrict__ F1,
+                                                          const float* __restrict__ c1, const float* __restrict__ c2,
+                                                          int64_t chunks_per_row_block, int64_t b) {
+  const int side = blockIdx.y;
+  bf16_t* __restrict__ E = side == 0 ? E0 : E1;
+  const bf16_t* __restrict__ F = side == 0 ? F0 : F1;
+  const float* __restrict__ c_own = side == 0 ? c1 : c2;
+  const int64_t chunk = (int64_t)blockIdx.x * 256 + threadIdx.x;      // (anchor block, column block, lane)
+  const int64_t ab = chunk / chunks_per_row_block;
+  const int64_t r = ab * 32 + (chunk & 31);
+  if (r >= b) return;
+  const float inv = 1.0f / c_own[r];
+  const uint4 e = *(const uint4*)(E + chunk * 8), f = *(const uint4*)(F + chunk * 8);
+  const uint32_t ew[4] = {e.x, e.y, e.z, e.w}, fw[4] = {f.x, f.y, f.z, f.w};
+  uint32_t o[4];
+#pragma unroll
+  for (int w = 0; w < 4; ++w) {
+    const float lo = fmaf(__uint_as_float(fw[w] << 16), inv, __uint_as_float(ew[w] << 16));
+    const float hi = fmaf(__uint_as_float(fw[w] & 0xffff0000u), inv, __uint_as_float(ew[w] & 0xffff0000u));
+    o[w] = pack_bf16x2(lo, hi);
+  }
+  const u32x4 ov = {o[0], o[1], o[2], o[3]};
+  *(u32x4*)(E + chunk * 8) = ov;
+}
+
 void launch_fold_bf16(const StepCtx& c) {
   const Layout& L = c.L;
   const unsigned nb = (unsigned)((L.b + 63) / 64);
+  if (L.gathered) {
+    const int64_t per_block = (L.ldE / 16) * 64;                       // chunks per block of 32 anchors
+    const int64_t chunks = (int64_t)((L.b + 31) / 32) * per_block;
+    hipLaunchKernelGGL(k_fold_remote_bf16, dim3((unsigned)((chunks + 255) / 256), 2), dim3(256), 0, c.s,
+                       (bf16_t*)(c.ws + L.E[0]), (const bf16_t*)(c.ws + L.F[0]), (bf16_t*)(c.ws + L.E[1]),
+                       (const bf16_t*)(c.ws + L.F[1]), (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
+                       per_block, L.b);
+  }
   if (L.square) {
     hipLaunchKernelGGL(k_fold_square_bf16, dim3(nb, nb), dim3(256), 0, c.s, (bf16_t*)(c.ws + L.E[0]),
                        (const bf16_t*)(c.ws + L.F[0]), (bf16_t*)(c.ws + L.E[1]), L.ldE / 16,
@@ -585,8 +623,7 @@ void launch_fold_bf16(const StepCtx& c) {
 
 // ----------------------------------------------------------------------------------------------------------------
 struct ContractJob {
-  const bf16_t* E;    // fragment-ordered strip: l of the local anchors (+ local operand columns), or the gathered-state
-                      // strip of remote anchors' weights
+  const bf16_t* E;    // fragment-ordered strip: l of the local anchors with the contrast-side weights folded in
   const bf16_t* X;    // the matrix whose rows the strip weights: texts for strip 0, images for strip 1
   float* C;           // [nsplit][M][ldc]
   int64_t ldx, ldc;
@@ -596,7 +633,7 @@ struct ContractJob {
   int all_rows_valid; // no zero rows inside the column range (B == ldE)
 };
 struct ContractArgs {
-  ContractJob job[4];   // 0, 1: the two strips; 2, 3: their gathered-state strips (njobs == 4)
+  ContractJob job[2];   // the two strips
   int64_t M, N, B;
   int nsplit, tiles_m, tiles_n;
 };
@@ -651,15 +688,14 @@ __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
 void launch_contract_bf16(const StepCtx& c) {
   const Layout& L = c.L;
   ContractArgs g;
-  const int njobs = L.gathered ? 4 : 2;
+  const int njobs = 2;
   for (int j = 0; j < njobs; ++j) {
     const int s = j & 1;
-    const bool rem = j >= 2;
     ContractJob& J = g.job[j];
-    J.E = (const bf16_t*)(c.ws + (rem ? L.F[s] : L.E[s]));
+    J.E = (const bf16_t*)(c.ws + L.E[s]);
     J.X = (const bf16_t*)(s == 0 ? c.buf.txt_glob : c.buf.img_glob);
     J.ldx = s == 0 ? c.cfg.ld_txt : c.cfg.ld_img;
-    J.C = (float*)(c.ws + (rem ? L.OpartF[s] : L.Opart[s]));
+    J.C = (float*)(c.ws + L.Opart[s]);
     J.ldc = L.d;
     J.split_stride = (size_t)L.b * (size_t)L.d;
     J.nCB = L.ldE / 16;
@@ -667,7 +703,6 @@ void launch_contract_bf16(const StepCtx& c) {
     J.slice = (int)L.kslice;
     J.all_rows_valid = L.B == L.ldE;
   }
-  for (int j = njobs; j < 4; ++j) g.job[j] = g.job[0];
   g.M = L.b; g.N = L.d; g.B = L.B;
   g.nsplit = L.nsplit;
   g.tiles_m = (int)((L.b + 255) / 256);

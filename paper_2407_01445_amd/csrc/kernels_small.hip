@@ -523,7 +523,7 @@ void launch_grad_f32(const StepCtx& c) {
 
 // ------------------------------------------------------------------------------------------
 // MFMA path, last phase.  d_img[r] = c1_r * (sum over splits of the contraction)[r] - dcoef_r txt_p, and the mirror
-// image (the contraction already carries the local contrast-side term divided by c_r); block (0,0) also writes the
+// image (the contraction already carries the contrast-side terms divided by c_r); block (0,0) also writes the
 // scalars.
 __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict__ img, const bf16_t* __restrict__ txt,
                                                        int64_t ld_img, int64_t ld_txt, int64_t off, int64_t b, int64_t d,
@@ -533,15 +533,13 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
                                                        float* __restrict__ d_img, float* __restrict__ d_txt,
                                                        const float* __restrict__ red, int nblocks, int version,
                                                        const float* __restrict__ tau, float rho, float* __restrict__ loss,
-                                                       float* __restrict__ d_tau, const float* __restrict__ OF1,
-                                                       const float* __restrict__ OF2, const float* __restrict__ norm_img,
+                                                       float* __restrict__ d_tau, const float* __restrict__ norm_img,
                                                        const float* __restrict__ norm_txt) {
   const int64_t r = blockIdx.x;
   const int side = blockIdx.y;
   const int64_t p = off + r;
   const bf16_t* xp = side == 0 ? txt + p * ld_txt : img + p * ld_img;
   const float* O = (side == 0 ? O1 : O2) + r * d;
-  const float* OF = OF1 ? (side == 0 ? OF1 : OF2) + r * d : nullptr;   // gathered: remote anchors' contraction
   const float cown = side == 0 ? c1[r] : c2[r];
   const float dc = dcoef[r];
   float* out = (side == 0 ? d_img : d_txt) + r * d;
@@ -552,20 +550,14 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
       const float4 v = *(const float4*)(O + (size_t)s * split_stride + c0);
       acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
     }
-    float4 rem = make_float4(0.f, 0.f, 0.f, 0.f);
-    if (OF)
-      for (int s = 0; s < nsplit; ++s) {
-        const float4 v = *(const float4*)(OF + (size_t)s * split_stride + c0);
-        rem.x += v.x; rem.y += v.y; rem.z += v.z; rem.w += v.w;
-      }
     const uint2 xr = *(const uint2*)(xp + c0);
     const float x0 = __uint_as_float(xr.x << 16), x1 = __uint_as_float(xr.x & 0xffff0000u);
     const float x2 = __uint_as_float(xr.y << 16), x3 = __uint_as_float(xr.y & 0xffff0000u);
     float4 o;
-    o.x = fmaf(cown, acc.x, rem.x) - dc * x0;
-    o.y = fmaf(cown, acc.y, rem.y) - dc * x1;
-    o.z = fmaf(cown, acc.z, rem.z) - dc * x2;
-    o.w = fmaf(cown, acc.w, rem.w) - dc * x3;
+    o.x = cown * acc.x - dc * x0;
+    o.y = cown * acc.y - dc * x1;
+    o.z = cown * acc.z - dc * x2;
+    o.w = cown * acc.w - dc * x3;
     *(float4*)(out + c0) = o;
   }
   if (norm_img) {
@@ -608,9 +600,8 @@ void launch_finalize_bf16(const StepCtx& c) {
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, (const float*)(c.ws + L.Opart[0]),
                      (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
-                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau,
-                     L.gathered ? (const float*)(c.ws + L.OpartF[0]) : nullptr,
-                     L.gathered ? (const float*)(c.ws + L.OpartF[1]) : nullptr, c.buf.norm_img, c.buf.norm_txt);
+                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau, c.buf.norm_img,
+                     c.buf.norm_txt);
 }
 
 // ------------------------------------------------------------------------------------------
