@@ -612,3 +612,26 @@ def test_gradients_through_normalisation_match_finite_differences(version, B, b,
     np.testing.assert_allclose(out["d_txt"], fd_rows(loss, raw_t, rows), rtol=5e-6, atol=1e-9)
     # a gradient through the normalisation has no component along the row itself
     assert np.max(np.abs(np.einsum("rk,rk->r", out["d_img"], raw_i[rows]))) < 1e-12
+
+
+# ------------------------------------------------------------------------------- stored digest of the oracle
+def test_oracle_digest_on_the_small_workload_is_unchanged():
+    """tests/golden/cfg0_oracle_digest.txt is written by tests/golden/make_golden.py from the oracle alone (the paper
+    prints no numeric example to store instead).  It is no pin - the pins are above - but a guard: a change of the
+    oracle's arithmetic has to be deliberate (and re-run the script)."""
+    import importlib.util
+    import os
+    here = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden")
+    spec = importlib.util.spec_from_file_location("make_golden", os.path.join(here, "make_golden.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    stored = {}
+    for line in open(os.path.join(here, "cfg0_oracle_digest.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, v = line.split()
+        stored[k] = float(v)
+    now = mod.digest()
+    assert list(now) == list(stored)
+    for k, v in now.items():
+        assert v == pytest.approx(stored[k], rel=1e-11, abs=1e-13), k
