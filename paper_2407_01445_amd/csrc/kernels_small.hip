@@ -102,7 +102,7 @@ void launch_prep(const StepCtx& c) {
 // gradient, with l2(j, p) = exp((s_pj - s_jj) / tau2_j), l1(j, p) = exp((s_jp - s_jj) / tau1_j) and
 // c_j = kappa_j / (|B_k| |B_j-| (eps + u_j^{t+1})): the strips already form s_pj and s_jp, so all they need per
 // column j is log2(e)/tau_j, s_jj log2(e)/tau_j and c_j.  Local rows get c = 0 (their u^{t+1} is only known after
-// the state phase; they go through the local operand columns), and so do the padding columns beyond B.
+// the state phase; the fold after the state phase handles them), and so do the padding columns beyond B.
 template <typename T>
 __global__ void __launch_bounds__(256) k_prep_cols(const T* __restrict__ img, const T* __restrict__ txt, int64_t ld_img,
                                                    int64_t ld_txt, int64_t B, int64_t ncol, int64_t off, int64_t b,

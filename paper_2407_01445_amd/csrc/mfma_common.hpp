@@ -23,7 +23,6 @@ constexpr int kRingBytes = 5 * kStageBytes;  // 160 KiB: all of the LDS of a com
 #define FC_WAIT_VMCNT16() __builtin_amdgcn_s_waitcnt(0x4f70)
 #define FC_WAIT_VMCNT20() __builtin_amdgcn_s_waitcnt(0x4f74)
 #define FC_WAIT_VMCNT24() __builtin_amdgcn_s_waitcnt(0x4f78)
-#define FC_WAIT_VMCNT34() __builtin_amdgcn_s_waitcnt(0x8f72)   // vmcnt = 34 = 0b100010: low bits 2, high bits 2
 
 __device__ __forceinline__ uint32_t lds_addr(const void* p) {
   return (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const void*)p;
