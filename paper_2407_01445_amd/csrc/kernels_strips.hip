@@ -509,11 +509,219 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   FC_WAIT_VMCNT0();   // the trailing re-requests write LDS: they must land before the workgroup gives it back
 }
 
+// ----------------------------------------------------------------------------------------------------------------
+// k_strips5_bf16: the plain mode of the kernel above on a ring of FIVE operand panels (a panel = 256 rows x 64 of k =
+// 32 KiB of either the contrast rows X or the anchor rows A; 160 KiB, all of the LDS).  During stage g the ring holds
+// X_g A_g X_g+1 A_g+1 X_g+2: the contrast panel, which is new to the L2 for the first workgroup that touches it and
+// then comes from HBM, is requested two stage times before it is needed; the anchor panel (the same 256 rows for
+// every tile of a workgroup, L2 hits) one.  With two whole-stage slots both had one stage time, less than an HBM
+// access takes under load, and a fifth of the loop went into waiting for data.  The barrier three quarters into
+// stage g retires X_g and A_g; A_g+2 is requested into the first, X_g+3 into the second (A before X, so that "A_g+1
+// has landed" is vmcnt(8): only the eight younger X loads may still fly).  Nothing else has LDS of its own: at the end
+// of a tile the panel that waits for X_g+3 is free, and the tile's per-anchor scalars and the cross-wave sums use it.
+//
+// Who requests.  A SIMD runs waves w and w + 4, and its matrix core serves the older wave first: with the requests
+// shared evenly, waves 0 .. 3 reached every barrier about 700 cycles before waves 4 .. 7 and idled there (a wave
+// that issues a direct-to-LDS load is held for about 60 cycles).  So waves 0 .. 3 issue ALL requests, their own rows
+// and those of their SIMD's other wave (16 wave loads per stage), and waves 4 .. 7 none: 2970 -> 2620 cycles per
+// 64-deep stage (2048 being the MFMA time).
+constexpr int kPart = kSOp;               // 32 KiB
+constexpr int kRing5 = 5 * kPart;         // 160 KiB
+#define FC_WAIT_VMCNT25() __builtin_amdgcn_s_waitcnt(0x4f79)   // vmcnt = 25 = 0b011001: low bits 9, high bits 1
+
+__global__ void __launch_bounds__(512, 2) k_strips5_bf16(StripArgs a) {
+  __shared__ __attribute__((aligned(1024))) char ring[kRing5];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wr = wave >> 1, wc = wave & 1, lr = lane & 31, hk = lane >> 5;
+  const uint32_t ring_addr = lds_addr(ring);
+  const int S = (int)(a.d / kSK);   // >= 2
+  const int G = gridDim.x;
+  const int vid = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
+  const int per_strip = a.nAT * a.nCT;
+  auto next_interior = [&](int tt) {
+    while (tt < a.ntiles &&
+           !strip_tile_is_interior(a, (int64_t)(tt % a.nAT) * 256, (int64_t)((tt / a.nAT) % a.nCT) * 256))
+      tt += G;
+    return tt;
+  };
+
+  // ---- the two request streams (waves 0 .. 3 only): wave w requests rows 32 w .. 32 w + 31 and 128 + 32 w .. of a
+  // panel, 8 wave loads of 8 rows x 128 bytes; lane l of a wave load fetches chunk (l & 7) ^ swz of row (l >> 3) (rows
+  // 128 apart share their swizzle, so loads 4 .. 7 use the lane offsets of loads 0 .. 3 on a base 128 rows on).  The X
+  // stream runs one stage ahead of the A stream, so near a tile change the two are in different tiles.
+  uint32_t ox[4], oa[4];
+  const bf16_t *qx, *qa;
+  int x_left, x_tile, a_left, a_tile;
+  int64_t ldx = 0, lda = 0;
+  auto open_x = [&](int tt) {
+    const int strip = tt / per_strip, ct = (tt / a.nAT) % a.nCT;
+    const int64_t ld = a.ld_contrast[strip];
+    qx = a.contrasts[strip] + (int64_t)ct * 256 * ld;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 8 * (4 * wave + i) + (lane >> 3);
+      ox[i] = (uint32_t)(row * (int)ld + ((((lane & 7) ^ st_swz(row))) << 3)) * 2u;
+    }
+    x_left = S; x_tile = tt; ldx = ld;
+  };
+  auto open_a = [&](int tt) {
+    const int strip = tt / per_strip, at = tt % a.nAT;
+    const int64_t ld = a.ld_anchor[strip];
+    qa = a.anchors[strip] + (int64_t)at * 256 * ld;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int row = 8 * (4 * wave + i) + (lane >> 3);
+      oa[i] = (uint32_t)(row * (int)ld + ((((lane & 7) ^ st_swz(row))) << 3)) * 2u;
+    }
+    a_left = S; a_tile = tt; lda = ld;
+  };
+  auto advance_x = [&]() {
+    if (x_tile >= a.ntiles) return;          // past the end: keep re-requesting the last stage
+    if (--x_left > 0) { qx += kSK; return; }
+    const int tn = next_interior(x_tile + G);
+    if (tn < a.ntiles) open_x(tn); else x_tile = tn;
+  };
+  auto advance_a = [&]() {
+    if (a_tile >= a.ntiles) return;
+    if (--a_left > 0) { qa += kSK; return; }
+    const int tn = next_interior(a_tile + G);
+    if (tn < a.ntiles) open_a(tn); else a_tile = tn;
+  };
+  const uint32_t my = ring_addr + (uint32_t)wave * 4096u;   // this wave's rows inside a panel
+#define FC5_X(i, part) \
+  dma16i<((i) & 3) * 1024>(qx + ((i) >> 2) * 128 * ldx, ox[(i) & 3], my + (part) + (uint32_t)((i) >> 2) * 16384u)
+#define FC5_A(i, part) \
+  dma16i<((i) & 3) * 1024>(qa + ((i) >> 2) * 128 * lda, oa[(i) & 3], my + (part) + (uint32_t)((i) >> 2) * 16384u)
+#define FC5_X8(p) FC5_X(0, p); FC5_X(1, p); FC5_X(2, p); FC5_X(3, p); FC5_X(4, p); FC5_X(5, p); FC5_X(6, p); FC5_X(7, p)
+#define FC5_A8(p) FC5_A(0, p); FC5_A(1, p); FC5_A(2, p); FC5_A(3, p); FC5_A(4, p); FC5_A(5, p); FC5_A(6, p); FC5_A(7, p)
+
+  int t = next_interior(vid);
+  if (t >= a.ntiles) return;
+  // ring positions (byte offsets) of X_g A_g X_g+1 A_g+1 X_g+2; every stage moves on by two
+  uint32_t P0 = 0u, P1 = (uint32_t)kPart, P2 = 2u * kPart, P3 = 3u * kPart, P4 = 4u * kPart;
+  const bool requester = wave < 4;
+  open_x(t);
+  open_a(t);
+  if (requester) {
+    FC5_X8(P0); advance_x();
+    FC5_A8(P1); advance_a();
+    FC5_X8(P2); advance_x();
+    FC5_A8(P3); advance_a();
+    FC5_X8(P4); advance_x();
+  }
+
+  // operand reads: the lane's address inside a panel for the 16-deep step 0 (step j: bits 5..6 XORed by j)
+  const uint32_t bx = (uint32_t)((wr * 64 + lr) * 128 + ((hk ^ st_swz(wr * 64 + lr)) << 4));
+  const uint32_t ba = (uint32_t)((wc * 128 + lr) * 128 + ((hk ^ st_swz(wc * 128 + lr)) << 4));
+
+  FC_WAIT_VMCNT0();
+  __syncthreads();
+  bf16x8 x0[2], a0[4], x1[2], a1[4];
+  x0[0] = FC_LDS16(ring + P0 + bx); x0[1] = FC_LDS16(ring + P0 + bx + 4096);
+#pragma unroll
+  for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + P1 + ba + j * 4096);
+
+  bool pend_x = false;   // X_g+2 is still to be requested (always during the first step after a barrier's last step)
+  bool after_epilogue = false;
+  while (t < a.ntiles) {
+    const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
+    const int a_first = at * 256, c_tile = ct * 256;
+    f32x16 acc[2][4];
+    zero_acc24(acc);
+#pragma unroll 1
+    for (int s = 0; s < S; ++s) {
+      const bool last = s + 1 == S;
+      {
+        const char* px = ring + ((bx ^ 32u) + P0);
+        const char* pa = ring + ((ba ^ 32u) + P1);
+        // X_g+2 into the panel that A_g-1 left (now called P4); at the start of a tile this comes after the
+        // epilogue, which used that panel
+        FC_STEP(x0, a0, x1, a1, px, pa, if (pend_x) FC5_X(0, P4), if (pend_x) FC5_X(1, P4), if (pend_x) FC5_X(2, P4),
+                if (pend_x) FC5_X(3, P4), if (pend_x) FC5_X(4, P4), if (pend_x) FC5_X(5, P4), if (pend_x) FC5_X(6, P4),
+                if (pend_x) FC5_X(7, P4));
+        if (pend_x) advance_x();
+        pend_x = false;
+      }
+      {
+        const char* px = ring + ((bx ^ 64u) + P0);
+        const char* pa = ring + ((ba ^ 64u) + P1);
+        FC_STEP_PLAIN(x1, a1, x0, a0, px, pa);
+      }
+      {
+        const char* px = ring + ((bx ^ 96u) + P0);
+        const char* pa = ring + ((ba ^ 96u) + P1);
+        FC_STEP_PLAIN(x0, a0, x1, a1, px, pa);
+      }
+      // A_g+1 has landed (X_g+1 long before): younger are only the eight loads of X_g+2, and once after an epilogue
+      // its 16 fragment stores and its sum store as well.  The barrier publishes it to the waves that request
+      // nothing and retires X_g and A_g.
+      if (requester) { if (after_epilogue) FC_WAIT_VMCNT25(); else FC_WAIT_VMCNT8(); }
+      after_epilogue = false;
+      __syncthreads();
+      FC_PIN();
+      if (last) {   // the tile's per-anchor scalars go into the panel A_g has just left (free until X_g+3 is requested)
+        if (wave < 4) dma4(a.kscale[strip] + a_first + wave * 64, lane * 4, ring_addr + P1 + (uint32_t)wave * 256u);
+        else dma4(a.diag + a_first + (wave - 4) * 64, lane * 4, ring_addr + P1 + 1024u + (uint32_t)(wave - 4) * 256u);
+      }
+      {
+        // last step; meanwhile read the first step's operands of stage g + 1 and request A_g+2 into X_g's panel
+        // (X_g+3 follows during the next step, into A_g's)
+        const char* px = ring + (bx + P2);
+        const char* pa = ring + (ba + P3);
+        FC_STEP(x1, a1, x0, a0, px, pa, if (requester) FC5_A(0, P0), if (requester) FC5_A(1, P0),
+                if (requester) FC5_A(2, P0), if (requester) FC5_A(3, P0), if (requester) FC5_A(4, P0),
+                if (requester) FC5_A(5, P0), if (requester) FC5_A(6, P0), if (requester) FC5_A(7, P0));
+        if (requester) advance_a();
+        pend_x = requester;
+      }
+      const uint32_t n0 = P2, n1 = P3, n2 = P4, n3 = P0, n4 = P1;
+      P0 = n0; P1 = n1; P2 = n2; P3 = n3; P4 = n4;
+    }
+    // the scalars have landed (for the requesting waves the eight loads of A_g+2 are younger); the free panel is now
+    // called P4
+    if (requester) FC_WAIT_VMCNT8(); else FC_WAIT_VMCNT0();
+    __syncthreads();
+    const float* sk = (const float*)(ring + P4);
+    const float* sdiag = sk + 256;
+    float (*sred)[2][256] = (float (*)[2][256])(ring + P4 + 2048u);
+    float sg[4] = {0.f, 0.f, 0.f, 0.f}, st[4] = {0.f, 0.f, 0.f, 0.f};
+    const int c_first = c_tile + wr * 64;
+    char* frag0 = (char*)a.E[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCB + (c_first >> 4)) * 1024;
+    const int64_t row_bytes = a.nCB * 1024;
+    const int own0 = (int)a.off + a_first + wc * 128;
+    const bool diagonal = (c_first < own0 + 128) && (c_first + 64 > own0);
+    if (diagonal) half_epilogue<true>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+    else half_epilogue<false>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+#pragma unroll
+    for (int tj = 0; tj < 4; ++tj) {
+      const int al = wc * 128 + tj * 32 + lr;
+      const float kk = sk[al];
+      const float g2 = sg[tj] + __shfl_xor(sg[tj], 32);
+      const float t2 = st[tj] + __shfl_xor(st[tj], 32);
+      if (hk == 0) {
+        sred[wr][0][al] = g2;
+        sred[wr][1][al] = kk > 0.f ? t2 * __builtin_amdgcn_rcpf(kk) : 0.f;   // sum of (s - s_pp) l
+      }
+    }
+    __syncthreads();
+    {
+      const int q = tid >> 8, m = tid & 255;
+      a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a_first + m] =
+          (sred[0][q][m] + sred[1][q][m]) + (sred[2][q][m] + sred[3][q][m]);
+    }
+    __syncthreads();     // the panel is given back: X_g+3 is requested into it during the next step
+    after_epilogue = true;
+    t = next_interior(t + G);
+  }
+  FC_WAIT_VMCNT0();   // the trailing re-requests write LDS: they must land before the workgroup gives it back
+}
+
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s) {
   const int grid = a.ntiles < 256 ? a.ntiles : 256;
   if (a.square) hipLaunchKernelGGL(k_strips_bf16<2>, dim3((unsigned)grid), dim3(512), 0, s, a);
   else if (a.colp) hipLaunchKernelGGL(k_strips_bf16<1>, dim3((unsigned)grid), dim3(512), 0, s, a);
-  else hipLaunchKernelGGL(k_strips_bf16<0>, dim3((unsigned)grid), dim3(512), 0, s, a);
+  else hipLaunchKernelGGL(k_strips5_bf16, dim3((unsigned)grid), dim3(512), 0, s, a);
 }
 
 }  // namespace fc
