@@ -10,13 +10,24 @@
 // instruction stream when one waits for LDS data.
 //
 // Data movement.  Operands go global -> LDS with direct-to-LDS loads, 64 deep in k per stage: every row contributes
-// one whole 128-byte line per stage (half-line requests reach only about 60 % of the load path's rate), 64 KiB per
-// stage, two slots.  The requests form one continuous stream over stages and tiles: three quarters into stage g all
-// waves have read slot g % 2 for the last time (one barrier, which also publishes stage g + 1), and stage g + 2 is
-// requested into it, so the epilogue of a tile runs with the next tile's first two stages already requested.  Past
-// the last tile the stream keeps re-requesting its last stage (nobody reads it), which keeps every s_waitcnt
-// immediate constant.  Vector memory operations complete in order, so "stage g + 1 has landed" is
-// s_waitcnt vmcnt(n) with n = the number of operations issued after that stage's loads.
+// one whole 128-byte line per stage (half-line requests reach only about 60 % of the load path's rate).  A panel is
+// 256 rows x 64 of k = 32 KiB of either the contrast rows X or the anchor rows A, and the LDS is a ring of FIVE
+// panels (160 KiB, all of it).  During stage g the ring holds X_g A_g X_g+1 A_g+1 X_g+2: the contrast panel, which is
+// new to the L2 for the first workgroup that touches it and then comes from HBM, is requested two stage times
+// before it is needed; the anchor panel (the same 256 rows for every tile of a workgroup, L2 hits) one.  (With two
+// whole-stage slots both had one stage time, less than an HBM access takes under load, and a fifth of the loop went
+// into waiting for data.)  The barrier three quarters into stage g retires X_g and A_g; A_g+2 is requested into the
+// first, X_g+3 into the second, A before X, so that "A_g+1 has landed" is vmcnt(8): vector memory operations
+// complete in order, and only the eight younger X loads may still fly.  The requests form one continuous stream over
+// stages and tiles; past the last tile the stream keeps re-requesting its last stage (nobody reads it), which keeps
+// every s_waitcnt immediate constant.  Nothing else has LDS of its own: at the end of a tile the panel that waits
+// for X_g+3 is free, and the tile's per-anchor scalars, column parameters and cross-wave sums use it.
+//
+// Who requests.  A SIMD runs waves w and w + 4, and its matrix core serves the older wave first: with the requests
+// shared evenly, waves 0 .. 3 reached every barrier about 700 cycles before waves 4 .. 7 and idled there (a wave
+// that issues a direct-to-LDS load is held for about 60 cycles).  So waves 0 .. 3 issue ALL requests, their own rows
+// and those of their SIMD's other wave (16 wave loads per stage), and waves 4 .. 7 none: 2970 -> 2620 cycles per
+// 64-deep stage (2048 being the MFMA time).
 //
 // MODE 1 (gathered state): every element additionally yields the weight of Eqs. 3 / 5 / 7 with which its contrast
 // column, taken as an anchor of another worker, moves the local row; it goes to a second strip of the same form.
@@ -30,18 +41,12 @@ namespace fc {
 
 constexpr int kSK = 64;                         // contraction depth of a stage: 128 bytes per row
 constexpr int kSOp = 256 * kSK * 2;             // one operand of a stage: 32 KiB
-constexpr int kSStage = 2 * kSOp;               // 64 KiB
-constexpr int kSRing = 2 * kSStage;             // 128 KiB
 
 // LDS image of an operand of a stage (256 rows x 128 bytes): 16-byte chunk c of row r sits at chunk position
 // c ^ ((r >> 1) & 7), so that the 16 consecutive rows one operand read touches per cycle cover all 16 chunk slots
 // of a 256-byte bank window.
 __device__ __forceinline__ int st_swz(int row) { return (row >> 1) & 7; }
 
-// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt and lgkmcnt left open)
-#define FC_WAIT_VMCNT1() __builtin_amdgcn_s_waitcnt(0x0f71)
-#define FC_WAIT_VMCNT2() __builtin_amdgcn_s_waitcnt(0x0f72)
-#define FC_WAIT_VMCNT18() __builtin_amdgcn_s_waitcnt(0x4f72)
 
 // 16 bytes per lane from uniform_base + lane_byte_off into LDS at (lds_uniform + IMM) + 16 * lane.
 template <int IMM>
@@ -273,88 +278,6 @@ __device__ __forceinline__ void half_epilogue_cols(f32x16 (&acc)[2][4], const fl
   }
 }
 
-template <int MODE>
-__global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
-  constexpr bool REMOTE = MODE == 1, SQUARE = MODE == 2;
-  __shared__ __attribute__((aligned(1024))) char ring[kSRing];
-  __shared__ __attribute__((aligned(256))) float sk[2][256];      // log2(e)/tau per anchor of the tile, double buffered
-  __shared__ __attribute__((aligned(256))) float sdiag[2][256];   // s_pp per anchor of the tile
-  __shared__ float sred[4][2][256];
-  __shared__ __attribute__((aligned(256))) float scol[MODE ? 2 : 1][REMOTE ? 4 : (SQUARE ? 2 : 1)][256];   // column parameters
-  __shared__ float sredc[SQUARE ? 2 : 1][2][SQUARE ? 256 : 1];   // column sums of the two anchor halves of a tile
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wr = wave >> 1, wc = wave & 1, lr = lane & 31, hk = lane >> 5;
-  const uint32_t ring_addr = lds_addr(ring);
-  const int S = (int)(a.d / kSK);   // >= 2
-  // ids that share an XCD (id mod 8 under round-robin dispatch) take neighbouring tiles, and neighbouring tiles are
-  // the anchor tiles of one contrast tile, so a contrast tile is fetched once per L2
-  const int G = gridDim.x;
-  const int vid = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
-  const int per_strip = a.nAT * a.nCT;
-  auto next_interior = [&](int tt) {
-    while (tt < a.ntiles &&
-           !strip_tile_is_interior(a, (int64_t)(tt % a.nAT) * 256, (int64_t)((tt / a.nAT) % a.nCT) * 256))
-      tt += G;
-    return tt;
-  };
-
-  // ---- the request stream --------------------------------------------------------------------------------------
-  // wave w requests rows 32 w .. 32 w + 31 of both operands: 4 + 4 wave loads of 8 rows x 128 bytes; lane l of a
-  // wave load fetches chunk (l & 7) ^ swz of row (l >> 3), i.e. 8 consecutive lanes cover one whole line.
-  const uint32_t mX = ring_addr + (uint32_t)(4 * wave) * 1024u;              // LDS targets inside slot 0
-  const uint32_t mA = mX + (uint32_t)kSOp;
-  uint32_t ox[4], oa[4];   // per-lane byte offsets of the wave loads within a stage
-  const bf16_t *qx, *qa;   // wave-uniform: operands of the next stage to request
-  int q_left, q_tile;
-  auto request_tile = [&](int tt) {
-    const int strip = tt / per_strip, at = tt % a.nAT, ct = (tt / a.nAT) % a.nCT;
-    const int64_t ldx = a.ld_contrast[strip], lda = a.ld_anchor[strip];
-    qx = a.contrasts[strip] + (int64_t)ct * 256 * ldx;
-    qa = a.anchors[strip] + (int64_t)at * 256 * lda;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int row = 8 * (4 * wave + i) + (lane >> 3);
-      const int chunk = (lane & 7) ^ st_swz(row);
-      ox[i] = (uint32_t)(row * (int)ldx + (chunk << 3)) * 2u;
-      oa[i] = (uint32_t)(row * (int)lda + (chunk << 3)) * 2u;
-    }
-    q_left = S; q_tile = tt;
-  };
-  // after the 8 wave loads of a stage: step the stream
-  auto request_advance = [&]() {
-    if (q_tile >= a.ntiles) return;          // past the end: keep re-requesting the last stage
-    if (--q_left > 0) { qx += kSK; qa += kSK; return; }
-    const int tn = next_interior(q_tile + G);
-    if (tn < a.ntiles) request_tile(tn); else q_tile = tn;
-  };
-#define FC_REQ_X(i, slot) dma16i<(i) * 1024>(qx, ox[i], mX + (slot))
-#define FC_REQ_A(i, slot) dma16i<(i) * 1024>(qa, oa[i], mA + (slot))
-#define FC_REQ_ALL(slot)                                                          \
-  FC_REQ_X(0, slot); FC_REQ_A(0, slot); FC_REQ_X(1, slot); FC_REQ_A(1, slot);     \
-  FC_REQ_X(2, slot); FC_REQ_A(2, slot); FC_REQ_X(3, slot); FC_REQ_A(3, slot)
-
-  int t = next_interior(vid);
-  if (t >= a.ntiles) return;
-  request_tile(t);
-  FC_REQ_ALL(0u);
-  request_advance();
-  FC_REQ_ALL((uint32_t)kSStage);
-  request_advance();
-
-  // ---- operand reads.  Chunk 2 j + hk of a row for the 16-deep step j sits at position ((hk ^ swz) ^ 2 j): the
-  // address for step j is the address for step 0 with bits 5..6 XORed by j; bit 16 selects the slot.
-  const uint32_t bx = (uint32_t)((wr * 64 + lr) * 128 + ((hk ^ st_swz(wr * 64 + lr)) << 4));
-  const uint32_t ba = (uint32_t)kSOp + (uint32_t)((wc * 128 + lr) * 128 + ((hk ^ st_swz(wc * 128 + lr)) << 4));
-
-  uint32_t cs = 0u, ns = (uint32_t)kSStage;   // slots of stages g, g + 1 (bit 16)
-  FC_WAIT_VMCNT8();   // stage 0 of the stream has landed (stage 1 may be in flight)
-  __syncthreads();
-  bf16x8 x0[2], a0[4], x1[2], a1[4];
-  x0[0] = FC_LDS16(ring + bx); x0[1] = FC_LDS16(ring + bx + 4096);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + ba + j * 4096);
-
 // One 16-deep step: 8 MFMAs on operand set P while operand set Q is read for the following step from px / pa;
 // D0 .. D7 are statements (requests or nothing) placed one per MFMA.
 #define FC_NONE (void)0
@@ -370,166 +293,19 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
 #define FC_STEP_PLAIN(XP, AP, XQ, AQ, px, pa) \
   FC_STEP(XP, AP, XQ, AQ, px, pa, FC_NONE, FC_NONE, FC_NONE, FC_NONE, FC_NONE, FC_NONE, FC_NONE, FC_NONE)
 
-  // The barrier of stream stage g waits for the loads of stage g + 1; nothing is issued after them except, at a tile
-  // change, the 16 fragment stores and 1 sum store of the finished tile and the scalar load of the new one
-  // (kind 1: 18 per wave), or, for the first tile, the scalar load alone (kind 2).  S >= 2 keeps these episodes apart.
-  // MODE 1: 32 fragment stores and 3 scalar loads, i.e. 36 and 3.  MODE 2: 32 fragment stores, 2 sum stores and 2
-  // scalar loads, i.e. 36 and 2.
-  int pend_kind = 2;
-  const bool early = wave < 4;
-  bool late_pending = false;
-  int buf = 0;
-  while (t < a.ntiles) {
-    const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
-    const int a_first = at * 256, c_tile = ct * 256;
-    // per-anchor scalars of this tile: covered by the wait of the tile's second stage
-    if (wave < 4) dma4(a.kscale[strip] + a_first + wave * 64, lane * 4, lds_addr(&sk[buf][wave * 64]));
-    else dma4(a.diag + a_first + (wave - 4) * 64, lane * 4, lds_addr(&sdiag[buf][(wave - 4) * 64]));
-    if (REMOTE) {   // the tile's column parameters, 4 KiB: two 256-byte pieces per wave
-      const float* cp = a.colp + ((int64_t)strip * a.nCT + ct) * 1024;
-      dma4(cp + wave * 64, lane * 4, lds_addr(&scol[buf][0][0] + wave * 64));
-      dma4(cp + (wave + 8) * 64, lane * 4, lds_addr(&scol[buf][0][0] + (wave + 8) * 64));
-    }
-    if constexpr (SQUARE) {   // the text anchors of the tile's columns (off == 0: anchor index == global row): log2(e)/tau2, s_jj
-      if (wave < 4) dma4(a.kscale[1] + c_tile + wave * 64, lane * 4, lds_addr(&scol[buf][0][wave * 64]));
-      else dma4(a.diag + c_tile + (wave - 4) * 64, lane * 4, lds_addr(&scol[buf][1][(wave - 4) * 64]));
-    }
-    f32x16 acc[2][4];
-    zero_acc24(acc);
-#pragma unroll 1
-    for (int s = 0; s < S; ++s) {
-      {
-        const char* px = ring + ((bx ^ 32u) ^ cs);
-        const char* pa = ring + ((ba ^ 32u) ^ cs);
-        // waves 4 .. 7 request their part of stage g + 1 here (into the other slot, retired by the previous barrier)
-        FC_STEP(x0, a0, x1, a1, px, pa, if (late_pending) FC_REQ_X(0, ns), if (late_pending) FC_REQ_A(0, ns),
-                if (late_pending) FC_REQ_X(1, ns), if (late_pending) FC_REQ_A(1, ns), if (late_pending) FC_REQ_X(2, ns),
-                if (late_pending) FC_REQ_A(2, ns), if (late_pending) FC_REQ_X(3, ns), if (late_pending) FC_REQ_A(3, ns));
-        if (late_pending) request_advance();
-        late_pending = false;
-      }
-      {
-        const char* px = ring + ((bx ^ 64u) ^ cs);
-        const char* pa = ring + ((ba ^ 64u) ^ cs);
-        FC_STEP_PLAIN(x1, a1, x0, a0, px, pa);
-      }
-      {
-        const char* px = ring + ((bx ^ 96u) ^ cs);
-        const char* pa = ring + ((ba ^ 96u) ^ cs);
-        FC_STEP_PLAIN(x0, a0, x1, a1, px, pa);
-      }
-      // stage g + 1 has landed for this wave; the barrier (which every wave reaches with its LDS reads complete)
-      // makes that true for all waves and retires the current slot: nobody reads it after this point
-      if (pend_kind == 0) FC_WAIT_VMCNT0();
-      else if (pend_kind == 1) { if (MODE) FC_WAIT_VMCNT36(); else FC_WAIT_VMCNT18(); }
-      else { if (REMOTE) FC_WAIT_VMCNT3(); else if (SQUARE) FC_WAIT_VMCNT2(); else FC_WAIT_VMCNT1(); }
-      pend_kind = 0;
-      __syncthreads();
-      FC_PIN();
-      {
-        // last step; meanwhile read the first step's operands of stage g + 1 and request stage g + 2 into the slot
-        // just retired.  The two waves of a SIMD take turns: waves 0 .. 3 request now, waves 4 .. 7 during the next
-        // step, so a wave that queues behind the load unit always leaves its neighbour free to issue MFMAs - except
-        // before an epilogue, whose stores must stay behind the requests.
-        const char* px = ring + (bx ^ ns);
-        const char* pa = ring + (ba ^ ns);
-        const bool now = early || (s + 1 == S);
-        FC_STEP(x1, a1, x0, a0, px, pa, if (now) FC_REQ_X(0, cs), if (now) FC_REQ_A(0, cs), if (now) FC_REQ_X(1, cs),
-                if (now) FC_REQ_A(1, cs), if (now) FC_REQ_X(2, cs), if (now) FC_REQ_A(2, cs), if (now) FC_REQ_X(3, cs),
-                if (now) FC_REQ_A(3, cs));
-        if (now) request_advance();
-        late_pending = !now;
-      }
-      const uint32_t tmp = cs; cs = ns; ns = tmp;
-    }
-    // exponentials, sums and fragment stores of this tile (16 stores per lane)
-    float sg[4] = {0.f, 0.f, 0.f, 0.f}, st[4] = {0.f, 0.f, 0.f, 0.f};
-    const int c_first = c_tile + wr * 64;
-    char* frag0 = (char*)a.E[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCB + (c_first >> 4)) * 1024;
-    const int64_t row_bytes = a.nCB * 1024;
-    const int own0 = (int)a.off + a_first + wc * 128;
-    const bool diagonal = (c_first < own0 + 128) && (c_first + 64 > own0);
-    if constexpr (SQUARE) {
-      if (diagonal) half_epilogue<true>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
-      else half_epilogue<false>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
-      char* fragF0 = (char*)a.F[0] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
-      const int64_t row_bytesF = a.nCBF * 1024;
-      const int cl0 = wr * 64 + 4 * (lane >> 5);
-      if (diagonal)
-        half_epilogue_cols<true>(acc, scol[buf][0], scol[buf][1], sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
-      else
-        half_epilogue_cols<false>(acc, scol[buf][0], scol[buf][1], sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
-    } else if (REMOTE) {
-      char* fragF0 = (char*)a.F[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
-      const int64_t row_bytesF = a.nCBF * 1024;
-      const int cl0 = wr * 64 + 4 * (lane >> 5);
-      if (diagonal)
-        half_epilogue_remote<true>(acc, sk[buf], sdiag[buf], &scol[REMOTE ? buf : 0][0][0], sg, st, frag0, row_bytes,
-                                   fragF0, row_bytesF, c_first, own0, wc * 128, cl0, lane);
-      else
-        half_epilogue_remote<false>(acc, sk[buf], sdiag[buf], &scol[REMOTE ? buf : 0][0][0], sg, st, frag0, row_bytes,
-                                    fragF0, row_bytesF, c_first, own0, wc * 128, cl0, lane);
-    } else if (diagonal) {
-      half_epilogue<true>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
-    } else {
-      half_epilogue<false>(acc, sk[buf], sdiag[buf], sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
-    }
-    // per-anchor sums of the tile: lanes hk = 0 / 1 hold the two halves of each 8-row group, waves wr = 0 .. 3 the
-    // four 64-row blocks
-#pragma unroll
-    for (int tj = 0; tj < 4; ++tj) {
-      const int al = wc * 128 + tj * 32 + lr;
-      const float kk = sk[buf][al];
-      const float g2 = sg[tj] + __shfl_xor(sg[tj], 32);
-      const float t2 = st[tj] + __shfl_xor(st[tj], 32);
-      if (hk == 0) {
-        sred[wr][0][al] = g2;
-        sred[wr][1][al] = kk > 0.f ? t2 * __builtin_amdgcn_rcpf(kk) : 0.f;   // sum of (s - s_pp) l
-      }
-    }
-    __syncthreads();
-    {
-      const int q = tid >> 8, m = tid & 255;
-      a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a_first + m] =
-          (sred[0][q][m] + sred[1][q][m]) + (sred[2][q][m] + sred[3][q][m]);
-      // the text anchors' sums (quantities 2, 3): partial number = the anchor tile, position = the column
-      if constexpr (SQUARE) a.sums[((size_t)(2 + q) * a.nparts + at) * a.bstride + c_tile + m] = sredc[0][q][m] + sredc[1][q][m];
-    }
-    if constexpr (SQUARE) {
-      // the first operands of the next tile (read during the last step above) are read again here, so that their
-      // registers are free during this mode's larger epilogue; their slot is retired only by the next barrier
-      x0[0] = FC_LDS16(ring + (bx ^ cs)); x0[1] = FC_LDS16(ring + (bx ^ cs) + 4096);
-#pragma unroll
-      for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + (ba ^ cs) + j * 4096);
-    }
-    pend_kind = 1;
-    t = next_interior(t + G);
-    buf ^= 1;
-  }
-  FC_WAIT_VMCNT0();   // the trailing re-requests write LDS: they must land before the workgroup gives it back
-}
 
-// ----------------------------------------------------------------------------------------------------------------
-// k_strips5_bf16: the plain mode of the kernel above on a ring of FIVE operand panels (a panel = 256 rows x 64 of k =
-// 32 KiB of either the contrast rows X or the anchor rows A; 160 KiB, all of the LDS).  During stage g the ring holds
-// X_g A_g X_g+1 A_g+1 X_g+2: the contrast panel, which is new to the L2 for the first workgroup that touches it and
-// then comes from HBM, is requested two stage times before it is needed; the anchor panel (the same 256 rows for
-// every tile of a workgroup, L2 hits) one.  With two whole-stage slots both had one stage time, less than an HBM
-// access takes under load, and a fifth of the loop went into waiting for data.  The barrier three quarters into
-// stage g retires X_g and A_g; A_g+2 is requested into the first, X_g+3 into the second (A before X, so that "A_g+1
-// has landed" is vmcnt(8): only the eight younger X loads may still fly).  Nothing else has LDS of its own: at the end
-// of a tile the panel that waits for X_g+3 is free, and the tile's per-anchor scalars and the cross-wave sums use it.
-//
-// Who requests.  A SIMD runs waves w and w + 4, and its matrix core serves the older wave first: with the requests
-// shared evenly, waves 0 .. 3 reached every barrier about 700 cycles before waves 4 .. 7 and idled there (a wave
-// that issues a direct-to-LDS load is held for about 60 cycles).  So waves 0 .. 3 issue ALL requests, their own rows
-// and those of their SIMD's other wave (16 wave loads per stage), and waves 4 .. 7 none: 2970 -> 2620 cycles per
-// 64-deep stage (2048 being the MFMA time).
 constexpr int kPart = kSOp;               // 32 KiB
 constexpr int kRing5 = 5 * kPart;         // 160 KiB
-#define FC_WAIT_VMCNT25() __builtin_amdgcn_s_waitcnt(0x4f79)   // vmcnt = 25 = 0b011001: low bits 9, high bits 1
+// what the free panel holds during an epilogue, after the per-anchor scalars sk[256], sdiag[256] (byte offsets)
+constexpr uint32_t kScolOff = 2048u, kSredOff = 6144u, kSredcOff = 14336u;
+// s_waitcnt immediates (gfx9 encoding: vmcnt[3:0] in bits 3:0, vmcnt[5:4] in bits 15:14; expcnt and lgkmcnt left open)
+#define FC_WAIT_VMCNT25() __builtin_amdgcn_s_waitcnt(0x4f79)   // 25 = 0b011001
+#define FC_WAIT_VMCNT41() __builtin_amdgcn_s_waitcnt(0x8f79)   // 41 = 0b101001
+#define FC_WAIT_VMCNT42() __builtin_amdgcn_s_waitcnt(0x8f7a)   // 42 = 0b101010
 
-__global__ void __launch_bounds__(512, 2) k_strips5_bf16(StripArgs a) {
+template <int MODE>
+__global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
+  constexpr bool REMOTE = MODE == 1, SQUARE = MODE == 2;
   __shared__ __attribute__((aligned(1024))) char ring[kRing5];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -654,15 +430,29 @@ __global__ void __launch_bounds__(512, 2) k_strips5_bf16(StripArgs a) {
         FC_STEP_PLAIN(x0, a0, x1, a1, px, pa);
       }
       // A_g+1 has landed (X_g+1 long before): younger are only the eight loads of X_g+2, and once after an epilogue
-      // its 16 fragment stores and its sum store as well.  The barrier publishes it to the waves that request
-      // nothing and retires X_g and A_g.
-      if (requester) { if (after_epilogue) FC_WAIT_VMCNT25(); else FC_WAIT_VMCNT8(); }
+      // its fragment stores (16; with a second strip 32) and its sum stores (1; MODE 2: 2) as well.  The barrier
+      // publishes it to the waves that request nothing and retires X_g and A_g.
+      if (requester) {
+        if (!after_epilogue) FC_WAIT_VMCNT8();
+        else if (REMOTE) FC_WAIT_VMCNT41();
+        else if (SQUARE) FC_WAIT_VMCNT42();
+        else FC_WAIT_VMCNT25();
+      }
       after_epilogue = false;
       __syncthreads();
       FC_PIN();
       if (last) {   // the tile's per-anchor scalars go into the panel A_g has just left (free until X_g+3 is requested)
         if (wave < 4) dma4(a.kscale[strip] + a_first + wave * 64, lane * 4, ring_addr + P1 + (uint32_t)wave * 256u);
         else dma4(a.diag + a_first + (wave - 4) * 64, lane * 4, ring_addr + P1 + 1024u + (uint32_t)(wave - 4) * 256u);
+        if constexpr (REMOTE) {   // the tile's column parameters [4][256], two 256-byte pieces per wave
+          const float* cp = a.colp + ((int64_t)strip * a.nCT + ct) * 1024;
+          dma4(cp + wave * 64, lane * 4, ring_addr + P1 + kScolOff + (uint32_t)wave * 256u);
+          dma4(cp + (wave + 8) * 64, lane * 4, ring_addr + P1 + kScolOff + (uint32_t)(wave + 8) * 256u);
+        }
+        if constexpr (SQUARE) {   // the text anchors of the tile's columns (off == 0: anchor index == global row)
+          if (wave < 4) dma4(a.kscale[1] + c_tile + wave * 64, lane * 4, ring_addr + P1 + kScolOff + (uint32_t)wave * 256u);
+          else dma4(a.diag + c_tile + (wave - 4) * 64, lane * 4, ring_addr + P1 + kScolOff + 1024u + (uint32_t)(wave - 4) * 256u);
+        }
       }
       {
         // last step; meanwhile read the first step's operands of stage g + 1 and request A_g+2 into X_g's panel
@@ -684,15 +474,36 @@ __global__ void __launch_bounds__(512, 2) k_strips5_bf16(StripArgs a) {
     __syncthreads();
     const float* sk = (const float*)(ring + P4);
     const float* sdiag = sk + 256;
-    float (*sred)[2][256] = (float (*)[2][256])(ring + P4 + 2048u);
+    const float* scol = (const float*)(ring + P4 + kScolOff);                    // MODE 1: [4][256]; MODE 2: [2][256]
+    float (*sred)[2][256] = (float (*)[2][256])(ring + P4 + kSredOff);           // [4 contrast quarters][2][256]
+    float (*sredc)[2][256] = (float (*)[2][256])(ring + P4 + kSredcOff);         // MODE 2: [2 anchor halves][2][256]
     float sg[4] = {0.f, 0.f, 0.f, 0.f}, st[4] = {0.f, 0.f, 0.f, 0.f};
     const int c_first = c_tile + wr * 64;
     char* frag0 = (char*)a.E[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCB + (c_first >> 4)) * 1024;
     const int64_t row_bytes = a.nCB * 1024;
     const int own0 = (int)a.off + a_first + wc * 128;
     const bool diagonal = (c_first < own0 + 128) && (c_first + 64 > own0);
-    if (diagonal) half_epilogue<true>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
-    else half_epilogue<false>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+    if constexpr (REMOTE) {
+      char* fragF0 = (char*)a.F[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
+      const int64_t row_bytesF = a.nCBF * 1024;
+      const int cl0 = wr * 64 + 4 * (lane >> 5);
+      if (diagonal)
+        half_epilogue_remote<true>(acc, sk, sdiag, scol, sg, st, frag0, row_bytes, fragF0, row_bytesF, c_first, own0,
+                                   wc * 128, cl0, lane);
+      else
+        half_epilogue_remote<false>(acc, sk, sdiag, scol, sg, st, frag0, row_bytes, fragF0, row_bytesF, c_first, own0,
+                                    wc * 128, cl0, lane);
+    } else {
+      if (diagonal) half_epilogue<true>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+      else half_epilogue<false>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+    }
+    if constexpr (SQUARE) {
+      char* fragF0 = (char*)a.F[0] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
+      const int64_t row_bytesF = a.nCBF * 1024;
+      const int cl0 = wr * 64 + 4 * (lane >> 5);
+      if (diagonal) half_epilogue_cols<true>(acc, scol, scol + 256, sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
+      else half_epilogue_cols<false>(acc, scol, scol + 256, sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
+    }
 #pragma unroll
     for (int tj = 0; tj < 4; ++tj) {
       const int al = wc * 128 + tj * 32 + lr;
@@ -709,8 +520,17 @@ __global__ void __launch_bounds__(512, 2) k_strips5_bf16(StripArgs a) {
       const int q = tid >> 8, m = tid & 255;
       a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a_first + m] =
           (sred[0][q][m] + sred[1][q][m]) + (sred[2][q][m] + sred[3][q][m]);
+      // the text anchors' sums (quantities 2, 3): partial number = the anchor tile, position = the column
+      if constexpr (SQUARE) a.sums[((size_t)(2 + q) * a.nparts + at) * a.bstride + c_tile + m] = sredc[0][q][m] + sredc[1][q][m];
     }
     __syncthreads();     // the panel is given back: X_g+3 is requested into it during the next step
+    if constexpr (MODE != 0) {
+      // the first operands of the next tile (read during the last step above) are read again here, so that their
+      // registers are free during these modes' larger epilogues; their panels are retired only by the next barrier
+      x0[0] = FC_LDS16(ring + P0 + bx); x0[1] = FC_LDS16(ring + P0 + bx + 4096);
+#pragma unroll
+      for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + P1 + ba + j * 4096);
+    }
     after_epilogue = true;
     t = next_interior(t + G);
   }
@@ -721,7 +541,7 @@ void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s) {
   const int grid = a.ntiles < 256 ? a.ntiles : 256;
   if (a.square) hipLaunchKernelGGL(k_strips_bf16<2>, dim3((unsigned)grid), dim3(512), 0, s, a);
   else if (a.colp) hipLaunchKernelGGL(k_strips_bf16<1>, dim3((unsigned)grid), dim3(512), 0, s, a);
-  else hipLaunchKernelGGL(k_strips5_bf16, dim3((unsigned)grid), dim3(512), 0, s, a);
+  else hipLaunchKernelGGL(k_strips_bf16<0>, dim3((unsigned)grid), dim3(512), 0, s, a);
 }
 
 }  // namespace fc

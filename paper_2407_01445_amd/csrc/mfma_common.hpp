@@ -118,7 +118,5 @@ __host__ __device__ __forceinline__ bool strip_tile_is_interior(const StripArgs&
 }
 
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s);   // kernels_strips.hip
-#define FC_WAIT_VMCNT3() __builtin_amdgcn_s_waitcnt(0x0f73)
-#define FC_WAIT_VMCNT36() __builtin_amdgcn_s_waitcnt(0x8f74)   // vmcnt = 36 = 0b100100: low bits 4, high bits 2
 
 }  // namespace fc
