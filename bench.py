@@ -143,6 +143,17 @@ def main():
     anchors_per_s = b * K / (t1 - t0)
     assert torch.isfinite(loss).all() and torch.isfinite(d_img).all()
 
+    # ---- spread of single steps: HIP events around each of K more steps (torch's current stream is the launch stream)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
+    for i in range(K):
+        t = W + (i % K)
+        evs[i][0].record()
+        fc.fastclip_step(cfgs[t], bufs[t], ws)
+        evs[i][1].record()
+    torch.cuda.synchronize()
+    per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
+    step_ms = {"mean": round(sum(per_step) / K, 5), "min": round(per_step[0], 5), "p50": round(per_step[K // 2], 5)}
+
     # ---- per-kernel durations: the library records HIP events around every kernel on its launch stream
     phase_ms = {}
     for t in range(W + K, W + 2 * K):
@@ -170,7 +181,7 @@ def main():
                                   "FastCLIP-v%d%s" % (name, b, B, d, w["dtype"], N, version,
                                                       ", gathered state of all workers" if args.gathered else ""),
                       "B": B, "b": b, "off": off, "d": d, "N": N, "version": version},
-           "roofline": roofline, "gemm_phases": gemm_phases,
+           "step_ms_hip_events": step_ms, "roofline": roofline, "gemm_phases": gemm_phases,
            "phase_ms": {k: round(v, 5) for k, v in phase_ms.items()}}
 
     # ---- the state-update kernel alone on many indices: the HBM-bound part of the method

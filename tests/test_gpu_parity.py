@@ -142,6 +142,21 @@ def test_bf16_small_shapes(B, b, off, d, version):
     check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
 
 
+def test_bf16_large_ragged_global_batch():
+    """One worker's 256 anchors against 40003 global pairs: two strips of 156 whole contrast tiles plus a ragged last
+    one, 1251 contraction stages split over the column range."""
+    B, b, off, d, N = 40_003, 256, 20_096, 128, 50_000
+    img, txt = make_embeddings(91, B, d, 0.5, "bf16")
+    idx = draw_indices(92, b, N)
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=V3, eps=1e-14, rho=8.5, tau=0.07)
+    g.set_inputs(img, txt, idx)
+    g.step(0.9)
+    u_img, u_txt = np.zeros(N), np.zeros(N)
+    want = oracle_step(g, img, txt, idx, u_img, u_txt, 0.9, tau=float(np.float32(0.07)))
+    compare(g.outputs(), want, V3, TOL_BF16, "bf16 large B")
+    check_state(g, np.zeros(N, np.float32), np.zeros(N, np.float32), idx, u_img, u_txt, TOL_BF16)
+
+
 def test_bf16_repeatable_bit_for_bit():
     B, b, off, d, N = 700, 300, 133, 72, 5000
     img, txt = make_embeddings(3, B, d, 0.5, "bf16")
