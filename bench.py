@@ -57,6 +57,9 @@ def main():
     ap.add_argument("--gathered", action="store_true",
                     help="time the step with FASTCLIP_GATHERED_STATE (contrast side over every global anchor); "
                          "not the headline workload")
+    ap.add_argument("--update-tau", action="store_true",
+                    help="time fastclip_step_update_tau (the step with the temperature update fused in, AdamW) instead of "
+                         "fastclip_step; not the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-state-bench", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -130,13 +133,24 @@ def main():
     cfgs = [cfg_at(t) for t in range(n_sets)]
     bufs = [bufs_at(t) for t in range(n_sets)]
 
+    step = lambda t: fc.fastclip_step(cfgs[t], bufs[t], ws)
+    if args.update_tau:      # Alg. 1 line 12 fused into the step: temperatures and their AdamW moments stepped in place
+        if version == fc.V2:
+            tst = fc.make_tau_state(tau_img=tau_img, tau_txt=tau_txt, m_img=torch.zeros(N, **f32), v_img=torch.zeros(N, **f32),
+                                    m_txt=torch.zeros(N, **f32), v_txt=torch.zeros(N, **f32))
+        else:
+            tst = fc.make_tau_state(tau=tau, m=torch.zeros(1, **f32), v=torch.zeros(1, **f32))
+        upd = lambda t: fc.make_tau_update(optimizer=fc.TAU_ADAMW, step=t + 1, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8,
+                                           tau_min=0.01)
+        step = lambda t: fc.fastclip_step_update_tau(cfgs[t], bufs[t], upd(t), tst, ws)
+
     # ---- warm-up, then exactly K timed steps bracketed by synchronisation
     for t in range(W):
-        fc.fastclip_step(cfgs[t], bufs[t], ws)
+        step(t)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(W, W + K):
-        fc.fastclip_step(cfgs[t], bufs[t], ws)
+        step(t)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / K
@@ -179,7 +193,8 @@ def main():
            "scaling": "weak", "vs_baseline": None, "dtype": w["dtype"], "data": "synthetic",
            "config": {"workload": "%s: b=%d local anchors x B=%d global pairs, d=%d %s, N=%d state entries, "
                                   "FastCLIP-v%d%s" % (name, b, B, d, w["dtype"], N, version,
-                                                      ", gathered state of all workers" if args.gathered else ""),
+                                                      (", gathered state of all workers" if args.gathered else "") +
+                                                      (", temperature update fused in" if args.update_tau else "")),
                       "B": B, "b": b, "off": off, "d": d, "N": N, "version": version},
            "step_ms_hip_events": step_ms, "roofline": roofline, "gemm_phases": gemm_phases,
            "phase_ms": {k: round(v, 5) for k, v in phase_ms.items()}}
