@@ -107,7 +107,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   memset(L, 0, sizeof(*L));
   L->B = cfg.B; L->b = cfg.b; L->off = cfg.off; L->d = cfg.d; L->N = cfg.N;
   L->bf16 = cfg.emb_dtype == FASTCLIP_BF16;
-  L->bstride = (int64_t)round_up((size_t)cfg.b, 64);
+  L->bstride = (int64_t)round_up((size_t)cfg.b, kTileContrasts);   // whole anchor tiles: the strip kernel works on 256 rows
   L->gathered = (cfg.flags & FASTCLIP_GATHERED_STATE) && cfg.b < cfg.B;
   L->ncol = (int64_t)round_up((size_t)cfg.B, kTileContrasts);
   // forming the similarity matrix once halves the MFMA work of the strip phase but doubles the epilogue of every

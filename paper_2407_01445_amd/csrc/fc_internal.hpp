@@ -21,7 +21,7 @@ struct Layout {
   int64_t B, b, off, d, N;
   int bf16;          // 1: MFMA path, 0: fp32 accuracy path
   int nparts;        // partial row sums per anchor and quantity written by the strip phase
-  int64_t bstride;   // anchors padded to a multiple of 64 (stride of the per-anchor arrays)
+  int64_t bstride;   // anchors padded to whole tiles of 256 (stride of the per-anchor arrays)
   int64_t ldE;       // contrast columns of the stored exp strips (MFMA path: multiple of 64; fp32 path: B)
   int nsplit;        // split of the contraction over its column range
   int64_t kslice;    // 32-deep stages per split

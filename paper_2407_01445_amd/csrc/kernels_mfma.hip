@@ -431,8 +431,9 @@ void launch_strips_bf16(const StepCtx& c) {
   a.F[0] = (L.gathered || L.square) ? (bf16_t*)(c.ws + L.F[0]) : nullptr;
   a.F[1] = L.gathered ? (bf16_t*)(c.ws + L.F[1]) : nullptr;
   a.nCBF = L.ldE / 16;
-  const bool any_interior = L.b >= 256 && L.B >= 256 && L.d % 64 == 0 && L.d >= 128;
-  const bool any_edge = (L.b % 256) || (L.B % 256) || !any_interior;
+  const bool d_ok = L.d % 64 == 0 && L.d >= 128;
+  const bool any_interior = d_ok && L.off + 256 <= L.B;              // anchor tile 0 against contrast tile 0
+  const bool any_edge = !d_ok || (L.B % 256) || L.off + (int64_t)a.nAT * 256 > L.B;
   if (any_interior) launch_strips_interior_bf16(a, c.s);
   if (any_edge) hipLaunchKernelGGL(k_strips_edge_bf16, dim3((unsigned)a.ntiles), dim3(256), 0, c.s, a);
 }

@@ -112,9 +112,13 @@ struct StripArgs {
   int square;
 };
 
-// Whole 256 x 256 tiles go to the persistent kernel, tiles with a ragged edge to the guarded one.
+// Which tiles go to the persistent kernel (unguarded direct-to-LDS loads), which to the guarded one.  The persistent
+// kernel needs 256 rows of each operand to EXIST, not to be wanted: a last anchor tile with fewer than 256 local
+// anchors is computed on the global rows that follow the local ones (off + a0 + 256 <= B) and what it produces for
+// them lands in padding (strip rows and per-anchor slots beyond b) that nothing reads.  Only a tile whose rows would
+// run past the end of the global batch, or a width that is not whole 64-deep stages, needs the guarded kernel.
 __host__ __device__ __forceinline__ bool strip_tile_is_interior(const StripArgs& a, int64_t a0, int64_t c0) {
-  return (a0 + 256 <= a.b) && (c0 + 256 <= a.B) && (a.d % 64 == 0) && (a.d >= 128);
+  return (a.off + a0 + 256 <= a.B) && (c0 + 256 <= a.B) && (a.d % 64 == 0) && (a.d >= 128);
 }
 
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s);   // kernels_strips.hip
