@@ -382,7 +382,7 @@ __global__ void __launch_bounds__(256) k_strips_edge_bf16(StripArgs a) {
   const int t = blockIdx.x;
   const int per_strip = a.nAT * a.nCT;
   const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
-  const int64_t a0 = (int64_t)at * 256, c0 = (int64_t)ct * 256;
+  const int64_t a0 = strip_anchor_first(a, at), c0 = (int64_t)ct * 256;
   if (strip_tile_is_interior(a, a0, c0)) return;
   const int S = (int)((a.d + BK - 1) / BK);
   {
@@ -432,8 +432,12 @@ void launch_strips_bf16(const StepCtx& c) {
   a.F[1] = L.gathered ? (bf16_t*)(c.ws + L.F[1]) : nullptr;
   a.nCBF = L.ldE / 16;
   const bool d_ok = L.d % 64 == 0 && L.d >= 128;
-  const bool any_interior = d_ok && L.off + 256 <= L.B;              // anchor tile 0 against contrast tile 0
-  const bool any_edge = !d_ok || (L.B % 256) || L.off + (int64_t)a.nAT * 256 > L.B;
+  bool any_interior = false, any_edge = !d_ok || (L.B % 256);
+  for (int at = 0; at < a.nAT; ++at) {
+    const bool in = strip_tile_is_interior(a, strip_anchor_first(a, at), 0);
+    any_interior |= in && L.B >= 256;
+    any_edge |= !in;
+  }
   if (any_interior) launch_strips_interior_bf16(a, c.s);
   if (any_edge) hipLaunchKernelGGL(k_strips_edge_bf16, dim3((unsigned)a.ntiles), dim3(256), 0, c.s, a);
 }

@@ -317,7 +317,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   const int per_strip = a.nAT * a.nCT;
   auto next_interior = [&](int tt) {
     while (tt < a.ntiles &&
-           !strip_tile_is_interior(a, (int64_t)(tt % a.nAT) * 256, (int64_t)((tt / a.nAT) % a.nCT) * 256))
+           !strip_tile_is_interior(a, strip_anchor_first(a, tt % a.nAT), (int64_t)((tt / a.nAT) % a.nCT) * 256))
       tt += G;
     return tt;
   };
@@ -344,7 +344,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   auto open_a = [&](int tt) {
     const int strip = tt / per_strip, at = tt % a.nAT;
     const int64_t ld = a.ld_anchor[strip];
-    qa = a.anchors[strip] + (int64_t)at * 256 * ld;
+    qa = a.anchors[strip] + strip_anchor_first(a, at) * ld;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = 8 * (4 * wave + i) + (lane >> 3);
@@ -402,7 +402,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   bool after_epilogue = false;
   while (t < a.ntiles) {
     const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
-    const int a_first = at * 256, c_tile = ct * 256;
+    const int a_first = (int)strip_anchor_first(a, at), c_tile = ct * 256;
     f32x16 acc[2][4];
     zero_acc24(acc);
 #pragma unroll 1

@@ -117,6 +117,14 @@ struct StripArgs {
 // anchors is computed on the global rows that follow the local ones (off + a0 + 256 <= B) and what it produces for
 // them lands in padding (strip rows and per-anchor slots beyond b) that nothing reads.  Only a tile whose rows would
 // run past the end of the global batch, or a width that is not whole 64-deep stages, needs the guarded kernel.
+// First local anchor of anchor tile `at`.  Tiles start every 256 anchors, except that a last tile with fewer than 256
+// anchors left is moved back to end exactly at b when the 32-anchor blocks of the stored strips allow it (b >= 256,
+// b % 32 == 0): it then recomputes some anchors of the tile before it - to the same bits, every anchor's values and
+// sums depend on its row and on the contrast tile only - and is a whole tile on every worker, also the last one.
+__host__ __device__ __forceinline__ int64_t strip_anchor_first(const StripArgs& a, int at) {
+  const int64_t a0 = (int64_t)at * 256;
+  return (a0 + 256 > a.b && a.b >= 256 && a.b % 32 == 0) ? a.b - 256 : a0;
+}
 __host__ __device__ __forceinline__ bool strip_tile_is_interior(const StripArgs& a, int64_t a0, int64_t c0) {
   return (a.off + a0 + 256 <= a.B) && (c0 + 256 <= a.B) && (a.d % 64 == 0) && (a.d >= 128);
 }

@@ -116,6 +116,9 @@ BF16_SMALL = [
     # (its results for those land in padding); a last anchor tile that would run past the global batch is guarded
     (768, 100, 300, 128),
     (1024, 300, 724, 256),
+    # ... and 320 anchors at the very end of the global batch: the last tile is moved back to end at b and recomputes
+    # 192 anchors of the first one
+    (1024, 320, 704, 128),
     # the whole batch local and only whole tiles
     (512, 512, 0, 128),
     (768, 768, 0, 192),
@@ -231,7 +234,8 @@ def test_f32_gathered_state(version):
 
 
 @pytest.mark.parametrize("B,b,off,d", [(700, 300, 133, 72), (1000, 64, 936, 136), (768, 256, 256, 128),
-                                       (1024, 300, 512, 256), (1536, 512, 512, 192), (1024, 300, 724, 256)])
+                                       (1024, 300, 512, 256), (1536, 512, 512, 192), (1024, 300, 724, 256),
+                                       (1024, 320, 704, 128)])
 @pytest.mark.parametrize("version", [V0, V1, V2, V3])
 def test_bf16_gathered_state(B, b, off, d, version):
     run_gathered(B, b, off, d, version, "bf16", TOL_BF16, ld_pad=8)
