@@ -312,6 +312,8 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   const int wr = wave >> 1, wc = wave & 1, lr = lane & 31, hk = lane >> 5;
   const uint32_t ring_addr = lds_addr(ring);
   const int S = (int)(a.d / kSK);   // >= 2
+  // ids that share an XCD (id mod 8 under round-robin dispatch) take neighbouring tiles, and neighbouring tiles are
+  // the anchor tiles of one contrast tile, so a contrast tile is fetched once per L2
   const int G = gridDim.x;
   const int vid = (G % 8 == 0) ? (int)(blockIdx.x % 8) * (G / 8) + (int)(blockIdx.x / 8) : (int)blockIdx.x;
   const int per_strip = a.nAT * a.nCT;
