@@ -48,6 +48,54 @@ def algorithmic_flops(B, b, d, gathered=False):
     return {"strips": 2 * unit, "contract": 2 * unit + 4.0 * b * b * d}
 
 
+def stock_ops_step(torch, img, txt, idx, u_img, u_txt, tau1, tau2, *, off, b, gamma, eps, rho, version, scale):
+    """The same step (local-anchor mode) written with stock PyTorch-ROCm tensor ops on the GPU: bf16 matmuls for the
+    two similarity strips and the two gradient contractions, fp32 element-wise ops, index_select / index_copy_ for the
+    state (Eq. 1, Eqs. 2-10).  Context for the timing only: the product never calls it, nothing is checked to the
+    parity bar against it.  tau1, tau2: [b] temperatures of the anchors (a global temperature repeated)."""
+    B = img.shape[0]
+    M = float(B - 1)
+    Il, Tl = img[off:off + b], txt[off:off + b]
+    ar = torch.arange(b, device=img.device)
+    diag = (Il.float() * Tl.float()).sum(1)
+
+    def side(A, X, tau_a, u):
+        Z = (A @ X.T).float() - diag[:, None]
+        E = torch.exp(Z / tau_a[:, None])
+        E[ar, off + ar] = 0.0
+        g, h = E.sum(1) / M, (Z * E).sum(1) / M
+        u_old = u.index_select(0, idx)
+        u_new = torch.where(u_old == 0, g, (1.0 - gamma) * u_old + gamma * g)
+        u.index_copy_(0, idx, u_new)
+        c = 1.0 / (b * M * (eps + u_new))
+        if version == 0:
+            c = c / tau_a
+        return E, g, h, u_new, c
+
+    E1, g1, h1, u1, c1 = side(Il, txt, tau1, u_img)
+    E2, g2, h2, u2, c2 = side(Tl, img, tau2, u_txt)
+    W1, W2 = c1[:, None] * E1, c2[:, None] * E2
+    loc1 = W1[:, off:off + b].clone()
+    W1[:, off:off + b] += W2[:, off:off + b].T          # contrast side of the local text anchors (Eqs. 3 / 5 / 7)
+    W2[:, off:off + b] += loc1.T
+    dd = (M * (c1 * g1 + c2 * g2))[:, None]
+    d_img = (W1.to(img.dtype) @ txt).float() - dd * Tl.float()
+    d_txt = (W2.to(img.dtype) @ img).float() - dd * Il.float()
+    l1, l2 = torch.log(eps + u1), torch.log(eps + u2)
+    if version == 2:
+        loss = (tau1 * (l1 + rho) + tau2 * (l2 + rho)).sum() / b
+        d_tau = (scale * (l1 + rho - h1 / (tau1 * (eps + u1))), scale * (l2 + rho - h2 / (tau2 * (eps + u2))))
+    else:
+        t = tau1[0]
+        hs = (h1 / (eps + u1) + h2 / (eps + u2)).sum()
+        if version == 0:
+            loss, d_tau = (l1 + l2).sum() / b, -hs / (b * t * t)
+        else:
+            loss = t * (l1 + l2).sum() / b + (2.0 * rho * t if version == 3 else 0.0)
+            d_tau = (l1 + l2).sum() / b + 2.0 * rho - hs / (b * t)
+    return loss, d_img, d_txt, d_tau
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,6 +110,7 @@ def main():
                          "fastclip_step; not the headline workload")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-state-bench", action="store_true")
+    ap.add_argument("--no-stock-ops", action="store_true", help="skip timing the step written with stock PyTorch ops")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a device-to-device copy of 1 GiB a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -250,6 +299,40 @@ def main():
         out["state_update"]["records_stride_2"] = {"n_idx": n_max, "ms": round(ms_rec, 4),
                                                    "algorithmic_GBps": round(40.0 * n_max / (ms_rec * 1e-3) / 1e9, 1)}
         del perm, s1, s2, o1, o2, rec
+
+    # ---- context: the same step with stock PyTorch-ROCm ops on this GPU (what framework tensor ops give)
+    if not (args.no_stock_ops or args.gathered or args.update_tau):
+        us1, us2 = torch.zeros(N, **f32), torch.zeros(N, **f32)
+        tau_of = lambda t, arr: arr.index_select(0, idx_sets[t % n_sets]) if version == fc.V2 else tau.expand(b)
+        run = lambda t: stock_ops_step(torch, img, txt, idx_sets[t % n_sets], us1, us2, tau_of(t, tau_img), tau_of(t, tau_txt), off=off,
+                                       b=b, gamma=gamma_at(t), eps=w["eps"], rho=w["rho"], version=version, scale=1.0 / N)
+        # one step of each from the same fresh state: the two must tell the same story (a sanity check, not parity)
+        uc1, uc2 = torch.zeros(N, **f32), torch.zeros(N, **f32)
+        fc.fastclip_step(cfgs[0], fc.make_buffers(img_glob=img, txt_glob=txt, idx=idx_sets[0], u_img=uc1, u_txt=uc2, tau=tau,
+                                                  tau_img=tau_img, tau_txt=tau_txt, d_img=d_img, d_txt=d_txt, loss=loss,
+                                                  d_tau=d_tau, d_tau_img=d_tau_img, d_tau_txt=d_tau_txt), ws)
+        s_loss, s_dimg, _, _ = run(0)
+        torch.cuda.synchronize()
+        loss_diff = abs(float(s_loss) - float(loss)) / abs(float(loss))
+        grad_diff = float((s_dimg - d_img).abs().max() / d_img.abs().max())
+        del uc1, uc2
+        Ks = min(K, 20)
+        for t in range(1, 3):
+            run(t)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for t in range(3, 3 + Ks):
+            run(t)
+        e1.record()
+        torch.cuda.synchronize()
+        stock_ms = e0.elapsed_time(e1) / Ks
+        out["stock_ops_baseline"] = {"value": round(b / (stock_ms * 1e-3), 1), "unit": "anchors/s",
+                                     "ms_per_step": round(stock_ms, 4), "steps": Ks,
+                                     "kind": "the same step with stock PyTorch-ROCm ops on the same GPU: bf16 matmul, "
+                                             "fp32 element-wise, index_select / index_copy_; context, not the product",
+                                     "speedup_of_this_library": round(stock_ms / ms_per_step, 2),
+                                     "loss_rel_diff": float("%.3g" % loss_diff), "d_img_rel_inf_diff": float("%.3g" % grad_diff)}
+        del us1, us2
 
     # ---- the CPU oracle on the same workload (one full step), host cores
     if not args.no_cpu_baseline:
