@@ -5,8 +5,9 @@ A "step" is one fastclip_step call: similarity strips, exp sums, state update of
 gradient contractions, temperature gradient, over one batch of synthetic embeddings that already sit
 in HBM.  Prints ONE JSON line: anchors/s for the whole step, the roofline of the dominant kernel
 (per-kernel durations from HIP events recorded by the library on its launch stream), the per-phase
-times, the state-update kernel on 2^24 indices against the HBM roofline, and the CPU oracle timed on
-the host cores.
+times, the step replayed from a HIP graph, the state-update kernel on 2^24 indices against the HBM
+roofline, the same step written with stock PyTorch-ROCm ops on the same GPU (context), and the CPU oracle
+timed on the host cores.
 """
 from __future__ import annotations
 
@@ -217,6 +218,22 @@ def main():
     per_step = sorted(e0.elapsed_time(e1) for e0, e1 in evs)
     step_ms = {"mean": round(sum(per_step) / K, 5), "min": round(per_step[0], 5), "p50": round(per_step[K // 2], 5)}
 
+    # ---- the step replayed from a HIP graph (it allocates nothing and records no memset): what a training loop that
+    # captures its iteration sees; same index set every replay, the state keeps evolving
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):
+        step(W)
+    for _ in range(W):
+        graph.replay()
+    torch.cuda.synchronize()
+    g0 = time.perf_counter()
+    for _ in range(K):
+        graph.replay()
+    torch.cuda.synchronize()
+    graph_ms = (time.perf_counter() - g0) * 1e3 / K
+    del graph
+
     # ---- per-kernel durations: the library records HIP events around every kernel on its launch stream
     phase_ms = {}
     for t in range(W + K, W + 2 * K):
@@ -245,7 +262,7 @@ def main():
                                                       (", gathered state of all workers" if args.gathered else "") +
                                                       (", temperature update fused in" if args.update_tau else "")),
                       "B": B, "b": b, "off": off, "d": d, "N": N, "version": version},
-           "step_ms_hip_events": step_ms, "roofline": roofline, "gemm_phases": gemm_phases,
+           "step_ms_hip_events": step_ms, "step_ms_hip_graph_replay": round(graph_ms, 5), "roofline": roofline, "gemm_phases": gemm_phases,
            "phase_ms": {k: round(v, 5) for k, v in phase_ms.items()}}
 
     # ---- the state-update kernel alone on many indices: the HBM-bound part of the method
