@@ -167,7 +167,7 @@ void launch_prep_cols(const StepCtx& c) {
 // side 0: image anchor vs texts (l1), side 1: text anchor vs images (l2).  One wavefront per
 // contrast row, fp64 accumulation; stores l as fp32 and the two row sums.
 __global__ void __launch_bounds__(256) k_strips_f32(const float* __restrict__ img, const float* __restrict__ txt,
-                                                    int64_t ld_img, int64_t ld_txt, int64_t off, int64_t b, int64_t B,
+                                                    int64_t ld_img, int64_t ld_txt, int64_t off, int64_t B,
                                                     int64_t d, const float* __restrict__ diag,
                                                     const float* __restrict__ tau1, const float* __restrict__ tau2,
                                                     float* __restrict__ E1, float* __restrict__ E2, int64_t ldE,
@@ -216,7 +216,7 @@ void launch_strips_f32(const StepCtx& c) {
   const Layout& L = c.L;
   dim3 grid((unsigned)L.b, 2), block(256);
   hipLaunchKernelGGL(k_strips_f32, grid, block, 0, c.s, (const float*)c.buf.img_glob, (const float*)c.buf.txt_glob,
-                     c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.B, L.d, (const float*)(c.ws + L.diag),
+                     c.cfg.ld_img, c.cfg.ld_txt, L.off, L.B, L.d, (const float*)(c.ws + L.diag),
                      (const float*)(c.ws + L.tau1), (const float*)(c.ws + L.tau2), (float*)(c.ws + L.E[0]),
                      (float*)(c.ws + L.E[1]), L.ldE, (float*)(c.ws + L.sums), L.bstride,
                      L.gathered ? (const float*)(c.ws + L.colp) : nullptr, L.ncol,
