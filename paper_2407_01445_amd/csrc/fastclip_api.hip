@@ -158,7 +158,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
     const size_t rows = round_up((size_t)cfg.b, 256);
     for (int s = 0; s < 2; ++s) L->E[s] = take(esz * rows * (size_t)L->ldE);
     for (int s = 0; s < 2; ++s)
-      L->Opart[s] = take(sizeof(float) * (size_t)L->nsplit * (size_t)cfg.b * (size_t)cfg.d);
+      L->Opart[s] = take(sizeof(float) * (size_t)L->nsplit * partial_split_floats(cfg.b, cfg.d));
   } else {
     for (int s = 0; s < 2; ++s) L->E[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
   }

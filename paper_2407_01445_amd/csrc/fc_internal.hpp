@@ -16,6 +16,14 @@ constexpr int kStateAnchors = 8;     // anchors per block of the state kernel
 
 static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
+// One split's partial result of the contraction is kept as whole 256 x 256 tiles, each laid out as
+// [64 groups of 4 rows][256 columns][4 rows] (tile = (n / 256) * tiles_m + m / 256): floats per tile, and per split
+// for b rows of width d.
+constexpr size_t kPartialTileFloats = 256 * 256;
+__host__ __device__ static inline size_t partial_split_floats(int64_t b, int64_t d) {
+  return (size_t)((b + 255) / 256) * (size_t)((d + 255) / 256) * kPartialTileFloats;
+}
+
 // Where everything lives inside the caller's workspace (byte offsets, 256-byte aligned).
 struct Layout {
   int64_t B, b, off, d, N;
@@ -35,7 +43,7 @@ struct Layout {
   size_t c1, c2, dcoef;              // float[bstride]
   size_t red;                        // float[nstate_blocks][2]
   size_t E[2];                       // fp32 path: float [b][ldE]; MFMA path: fragment-ordered bf16 strips
-  size_t Opart[2];                   // float [nsplit][b][d]   (MFMA path)
+  size_t Opart[2];                   // float [nsplit][partial_split_floats(b, d)]   (MFMA path)
   // gathered: per global row j (= contrast column of the strips) and side s, in tiles of 256 columns
   // [s][tile][4][256]: log2(e)/tau_j, s_jj log2(e)/tau_j, c_j (0 for local rows and beyond B), unused.
   // Side 0 describes the text anchors j (l2(j, .), weights of d_img), side 1 the image anchors (l1(j, .), d_txt).

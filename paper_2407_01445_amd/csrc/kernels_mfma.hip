@@ -630,8 +630,8 @@ void launch_fold_bf16(const StepCtx& c) {
 struct ContractJob {
   const bf16_t* E;    // fragment-ordered strip: l of the local anchors with the contrast-side weights folded in
   const bf16_t* X;    // the matrix whose rows the strip weights: texts for strip 0, images for strip 1
-  float* C;           // [nsplit][M][ldc]
-  int64_t ldx, ldc;
+  float* C;           // [nsplit][tile][64 groups of 4 rows][256 columns][4 rows]: whole 256 x 256 tiles
+  int64_t ldx;
   size_t split_stride;
   int64_t nCB;        // column blocks (of 16) per anchor block of E
   int stages, slice;  // 32-deep stages in all; stages per split
@@ -670,24 +670,22 @@ __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
       guarded_mainloop(acc, T, ring, s0, S, tid);
     }
   }
-  // C[m][n]: m = m0 + wm 128 + ti 32 + 8 q + 4 hk + t, n = n0 + wn 128 + tj 32 + lr.  Everything but (hk, lr) is
-  // wave-uniform, so each store is a uniform base plus a small per-lane offset.
-  float* __restrict__ C = J.C + (size_t)split * J.split_stride;
+  // The partial result leaves as whole tiles of [64 groups of 4 rows][256 columns][4 rows]: a lane holds C[m][n] for
+  // n = n0 + wn 128 + tj 32 + lr and the rows m = m0 + wm 128 + ti 32 + 8 q + 4 hk + t, t = 0..3, so its four values of one
+  // q are one 16-byte word of that layout and a wave store covers two runs of 512 consecutive bytes.  The buffer holds
+  // whole tiles, so nothing is guarded here; k_finalize_bf16 reads four rows at a time in the same order.
   const int lr = lane & 31, hk = lane >> 5;
-  const int64_t lane_off = (int64_t)(4 * hk) * J.ldc + lr;
-  const bool full = (m0 + 256 <= g.M) && (n0 + 256 <= g.N);
+  float* __restrict__ C = J.C + (size_t)split * J.split_stride + (size_t)tile * kPartialTileFloats +
+                          ((wm * 32 + hk) * 256 + wn * 128 + lr) * 4;
 #pragma unroll
   for (int ti = 0; ti < 4; ++ti)
 #pragma unroll
-    for (int tj = 0; tj < 4; ++tj) {
-      const int64_t nb = n0 + wn * 128 + tj * 32;
+    for (int tj = 0; tj < 4; ++tj)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int64_t mb = m0 + wm * 128 + ti * 32 + 8 * (v >> 2) + (v & 3);
-        float* rowp = C + mb * J.ldc + nb;
-        if (full || (mb + 4 * hk < g.M && nb + lr < g.N)) rowp[lane_off] = acc[ti][tj][v];
+      for (int q = 0; q < 4; ++q) {
+        const f32x4 v = {acc[ti][tj][4 * q], acc[ti][tj][4 * q + 1], acc[ti][tj][4 * q + 2], acc[ti][tj][4 * q + 3]};
+        *(f32x4*)(C + ((ti * 8 + q * 2) * 256 + tj * 32) * 4) = v;
       }
-    }
 }
 
 void launch_contract_bf16(const StepCtx& c) {
@@ -701,8 +699,7 @@ void launch_contract_bf16(const StepCtx& c) {
     J.X = (const bf16_t*)(s == 0 ? c.buf.txt_glob : c.buf.img_glob);
     J.ldx = s == 0 ? c.cfg.ld_txt : c.cfg.ld_img;
     J.C = (float*)(c.ws + L.Opart[s]);
-    J.ldc = L.d;
-    J.split_stride = (size_t)L.b * (size_t)L.d;
+    J.split_stride = partial_split_floats(L.b, L.d);
     J.nCB = L.ldE / 16;
     J.stages = (int)(L.ldE / BK);
     J.slice = (int)L.kslice;

@@ -523,8 +523,10 @@ void launch_grad_f32(const StepCtx& c) {
 
 // ------------------------------------------------------------------------------------------
 // MFMA path, last phase.  d_img[r] = c1_r * (sum over splits of the contraction)[r] - dcoef_r txt_p, and the mirror
-// image (the contraction already carries the contrast-side terms divided by c_r); block (0,0) also writes the
-// scalars.
+// image (the contraction already carries the contrast-side terms divided by c_r); block (0,0,0) also writes the
+// scalars.  The split partials are whole 256 x 256 tiles of [64 groups of 4 rows][256 columns][4 rows] (the order in
+// which k_contract_bf16's accumulators leave in 16-byte words), so a wavefront takes four rows and the 256 columns of
+// one tile, 4 KiB of consecutive addresses per split, a thread four columns, and a block sixteen rows.
 __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict__ img, const bf16_t* __restrict__ txt,
                                                        int64_t ld_img, int64_t ld_txt, int64_t off, int64_t b, int64_t d,
                                                        const float* __restrict__ O1, const float* __restrict__ O2,
@@ -533,75 +535,87 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
                                                        float* __restrict__ d_img, float* __restrict__ d_txt,
                                                        const float* __restrict__ red, int nblocks, int version,
                                                        const float* __restrict__ tau, float rho, float* __restrict__ loss,
-                                                       float* __restrict__ d_tau, const float* __restrict__ norm_img,
-                                                       const float* __restrict__ norm_txt) {
+                                                       float* __restrict__ d_tau) {
+  const int64_t r0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4;          // rows r0 .. r0 + 3 (those below b)
+  const int64_t n0 = (int64_t)blockIdx.z * 256 + (int64_t)(threadIdx.x & 63) * 4;   // columns n0 .. n0 + 3 (d % 8 == 0)
+  const int side = blockIdx.y;
+  if (r0 < b && n0 < d) {
+    const int nr = (int)(b - r0 < 4 ? b - r0 : 4);
+    const bf16_t* X = side == 0 ? txt : img;        // the diagonal term takes the other side's row
+    const int64_t ldx = side == 0 ? ld_txt : ld_img;
+    const float* O = side == 0 ? O1 : O2;
+    float* out = (side == 0 ? d_img : d_txt) + r0 * d + n0;
+    const size_t split_stride = partial_split_floats(b, d);
+    const int64_t tiles_m = (b + 255) / 256;
+    const size_t at = (size_t)((n0 >> 8) * tiles_m + (r0 >> 8)) * kPartialTileFloats +
+                      (size_t)((((r0 & 255) >> 2) * 256 + (n0 & 255)) * 4);
+    float cown[4], dc[4];                           // requested ahead of the partial sums: one memory latency, not two
+    uint2 xr[4];
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const int64_t r = r0 + (t < nr ? t : 0);
+      cown[t] = (side == 0 ? c1 : c2)[r];
+      dc[t] = dcoef[r];
+      xr[t] = *(const uint2*)(X + (off + r) * ldx + n0);
+    }
+    float acc[4][4] = {};                           // [column][row]
+#pragma unroll 4
+    for (int s = 0; s < nsplit; ++s) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float4 v = *(const float4*)(O + (size_t)s * split_stride + at + 4 * j);
+        acc[j][0] += v.x; acc[j][1] += v.y; acc[j][2] += v.z; acc[j][3] += v.w;
+      }
+    }
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      if (t >= nr) break;
+      float4 o;
+      o.x = cown[t] * acc[0][t] - dc[t] * __uint_as_float(xr[t].x << 16);
+      o.y = cown[t] * acc[1][t] - dc[t] * __uint_as_float(xr[t].x & 0xffff0000u);
+      o.z = cown[t] * acc[2][t] - dc[t] * __uint_as_float(xr[t].y << 16);
+      o.w = cown[t] * acc[3][t] - dc[t] * __uint_as_float(xr[t].y & 0xffff0000u);
+      *(float4*)(out + t * d) = o;
+    }
+  }
+  if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < 64)
+    write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
+}
+
+// Gradient through e^ = e / |e| (cosine similarity, Sec. 3) on the MFMA path, after k_finalize_bf16:
+// out := (out - e^ (e^ . out)) / |e|, e^ = the side's own row.  One block per anchor and side.
+__global__ void __launch_bounds__(256) k_norm_backward_bf16(const bf16_t* __restrict__ img, const bf16_t* __restrict__ txt,
+                                                            int64_t ld_img, int64_t ld_txt, int64_t off, int64_t d,
+                                                            float* __restrict__ d_img, float* __restrict__ d_txt,
+                                                            const float* __restrict__ norm_img,
+                                                            const float* __restrict__ norm_txt) {
+  __shared__ float part[4];
   const int64_t r = blockIdx.x;
   const int side = blockIdx.y;
-  const int64_t p = off + r;
-  const bf16_t* xp = side == 0 ? txt + p * ld_txt : img + p * ld_img;
-  const float* O = (side == 0 ? O1 : O2) + r * d;
-  const float cown = side == 0 ? c1[r] : c2[r];
-  const float dc = dcoef[r];
+  const bf16_t* ep = side == 0 ? img + (off + r) * ld_img : txt + (off + r) * ld_txt;
   float* out = (side == 0 ? d_img : d_txt) + r * d;
-  const size_t split_stride = (size_t)b * (size_t)d;
-  for (int64_t c0 = (int64_t)threadIdx.x * 4; c0 < d; c0 += 1024) {   // d % 8 == 0 on this path
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int s = 0; s < nsplit; ++s) {
-      const float4 v = *(const float4*)(O + (size_t)s * split_stride + c0);
-      acc.x += v.x; acc.y += v.y; acc.z += v.z; acc.w += v.w;
-    }
-    const uint2 xr = *(const uint2*)(xp + c0);
-    const float x0 = __uint_as_float(xr.x << 16), x1 = __uint_as_float(xr.x & 0xffff0000u);
-    const float x2 = __uint_as_float(xr.y << 16), x3 = __uint_as_float(xr.y & 0xffff0000u);
-    float4 o;
-    o.x = cown * acc.x - dc * x0;
-    o.y = cown * acc.y - dc * x1;
-    o.z = cown * acc.z - dc * x2;
-    o.w = cown * acc.w - dc * x3;
-    *(float4*)(out + c0) = o;
-  }
-  if (norm_img) {
-    // gradient through e^ = e / |e| (cosine similarity, Sec. 3): out := (out - e^ (e^ . out)) / |e|, e^ = this side's own row
-    __shared__ float part[4];
-    const bf16_t* ep = side == 0 ? img + p * ld_img : txt + p * ld_txt;
-    __syncthreads();                       // the block's own writes of out[] are visible to it from here on
-    float dot = 0.f;
-    for (int64_t c0 = (int64_t)threadIdx.x * 4; c0 < d; c0 += 1024) {
-      const float4 o = *(const float4*)(out + c0);
-      const uint2 er = *(const uint2*)(ep + c0);
-      dot = fmaf(o.x, __uint_as_float(er.x << 16), dot);
-      dot = fmaf(o.y, __uint_as_float(er.x & 0xffff0000u), dot);
-      dot = fmaf(o.z, __uint_as_float(er.y << 16), dot);
-      dot = fmaf(o.w, __uint_as_float(er.y & 0xffff0000u), dot);
-    }
-    dot = wave_sum(dot);
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = dot;
-    __syncthreads();
-    dot = (part[0] + part[1]) + (part[2] + part[3]);
-    const float inv = 1.0f / (side == 0 ? norm_img[r] : norm_txt[r]);
-    for (int64_t c0 = (int64_t)threadIdx.x * 4; c0 < d; c0 += 1024) {
-      float4 o = *(const float4*)(out + c0);
-      const uint2 er = *(const uint2*)(ep + c0);
-      o.x = (o.x - dot * __uint_as_float(er.x << 16)) * inv;
-      o.y = (o.y - dot * __uint_as_float(er.x & 0xffff0000u)) * inv;
-      o.z = (o.z - dot * __uint_as_float(er.y << 16)) * inv;
-      o.w = (o.w - dot * __uint_as_float(er.y & 0xffff0000u)) * inv;
-      *(float4*)(out + c0) = o;
-    }
-  }
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 64)
-    write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
+  float dot = 0.f;
+  for (int64_t n = threadIdx.x; n < d; n += 256) dot = fmaf(out[n], load_elem(ep + n), dot);
+  dot = wave_sum(dot);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = dot;
+  __syncthreads();
+  dot = (part[0] + part[1]) + (part[2] + part[3]);
+  const float inv = 1.0f / (side == 0 ? norm_img : norm_txt)[r];
+  for (int64_t n = threadIdx.x; n < d; n += 256) out[n] = (out[n] - dot * load_elem(ep + n)) * inv;
 }
 
 void launch_finalize_bf16(const StepCtx& c) {
   const Layout& L = c.L;
-  dim3 grid((unsigned)L.b, 2), block(256);
+  dim3 grid((unsigned)((L.b + 15) / 16), 2, (unsigned)((L.d + 255) / 256)), block(256);
   hipLaunchKernelGGL(k_finalize_bf16, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, (const float*)(c.ws + L.Opart[0]),
                      (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
-                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau, c.buf.norm_img,
-                     c.buf.norm_txt);
+                     L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau);
+  if (c.buf.norm_img)
+    hipLaunchKernelGGL(k_norm_backward_bf16, dim3((unsigned)L.b, 2), block, 0, c.s, (const bf16_t*)c.buf.img_glob,
+                       (const bf16_t*)c.buf.txt_glob, c.cfg.ld_img, c.cfg.ld_txt, L.off, L.d, c.buf.d_img, c.buf.d_txt,
+                       c.buf.norm_img, c.buf.norm_txt);
 }
 
 // ------------------------------------------------------------------------------------------
