@@ -149,6 +149,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   }
   L->nstate_blocks = (int)((cfg.b + kStateAnchors - 1) / kStateAnchors);
   L->diag = take(fb); L->tau1 = take(fb); L->tau2 = take(fb); L->k1 = take(fb); L->k2 = take(fb);
+  L->uold1 = take(fb); L->uold2 = take(fb);
   L->sums = take(fb * 4 * (size_t)L->nparts);
   L->c1 = take(fb); L->c2 = take(fb); L->dcoef = take(fb);
   L->red = take(sizeof(float) * 2 * (size_t)L->nstate_blocks);

@@ -39,6 +39,7 @@ struct Layout {
                      //    l2(j, p) in the layout of E[0] until the fold transposes it into E[1])
   int64_t ncol;      // gathered: entries per column-parameter array (B rounded up to whole 256-column tiles)
   size_t diag, tau1, tau2, k1, k2;   // float[bstride]
+  size_t uold1, uold2;               // float[bstride]: u^t of the batch's samples (gathered with the temperatures)
   size_t sums;                       // float[4][nparts][bstride]: sum e1, sum x1 e1, sum e2, sum x2 e2
   size_t c1, c2, dcoef;              // float[bstride]
   size_t red;                        // float[nstate_blocks][2]

@@ -52,16 +52,20 @@ __global__ void __launch_bounds__(256) k_prep(const T* __restrict__ img, const T
                                               int64_t ld_txt, int64_t off, int64_t b, int64_t d,
                                               const int64_t* __restrict__ idx, const float* __restrict__ tau,
                                               const float* __restrict__ tau_img, const float* __restrict__ tau_txt,
+                                              const float* __restrict__ u_img, const float* __restrict__ u_txt,
                                               int64_t stride, int version, float* __restrict__ diag,
                                               float* __restrict__ tau1,
-                                              float* __restrict__ tau2, float* __restrict__ k1, float* __restrict__ k2) {
+                                              float* __restrict__ tau2, float* __restrict__ k1, float* __restrict__ k2,
+                                              float* __restrict__ uold1, float* __restrict__ uold2) {
   const int lane = threadIdx.x & 63;
   const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   if (r >= b) return;
-  float t1 = 0.f, t2 = 0.f;
-  if (lane == 0) {        // issue the temperature gather before the dot product so that the latencies overlap
+  float t1 = 0.f, t2 = 0.f, u1 = 0.f, u2 = 0.f;
+  if (lane == 0) {        // issue the gathers by dataset index before the dot product so that the latencies overlap:
+    const int64_t n = idx[r] * stride;   // the temperatures, and u^t of Eq. 1 for the state phase (nothing writes u
+    u1 = u_img[n];                       // before that phase)
+    u2 = u_txt[n];
     if (version == FASTCLIP_V2) {
-      const int64_t n = idx[r] * stride;
       t1 = tau_img[n];
       t2 = tau_txt[n];
     } else {
@@ -75,6 +79,8 @@ __global__ void __launch_bounds__(256) k_prep(const T* __restrict__ img, const T
     tau2[r] = t2;
     k1[r] = kLog2e / t1;
     k2[r] = kLog2e / t2;
+    uold1[r] = u1;
+    uold2[r] = u2;
   }
 }
 
@@ -85,15 +91,19 @@ void launch_prep(const StepCtx& c) {
   float* tau2 = (float*)(c.ws + L.tau2);
   float* k1 = (float*)(c.ws + L.k1);
   float* k2 = (float*)(c.ws + L.k2);
+  float* uold1 = (float*)(c.ws + L.uold1);
+  float* uold2 = (float*)(c.ws + L.uold2);
   dim3 grid((unsigned)((L.b + 3) / 4)), block(256);
   if (L.bf16)
     hipLaunchKernelGGL(k_prep<bf16_t>, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
                        c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, c.buf.idx, c.buf.tau, c.buf.tau_img,
-                       c.buf.tau_txt, c.cfg.state_stride, c.cfg.version, diag, tau1, tau2, k1, k2);
+                       c.buf.tau_txt, c.buf.u_img, c.buf.u_txt, c.cfg.state_stride, c.cfg.version, diag, tau1, tau2, k1, k2,
+                       uold1, uold2);
   else
     hipLaunchKernelGGL(k_prep<float>, grid, block, 0, c.s, (const float*)c.buf.img_glob, (const float*)c.buf.txt_glob,
                        c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, c.buf.idx, c.buf.tau, c.buf.tau_img,
-                       c.buf.tau_txt, c.cfg.state_stride, c.cfg.version, diag, tau1, tau2, k1, k2);
+                       c.buf.tau_txt, c.buf.u_img, c.buf.u_txt, c.cfg.state_stride, c.cfg.version, diag, tau1, tau2, k1, k2,
+                       uold1, uold2);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -284,6 +294,7 @@ struct StateArgs {
   const int64_t* idx;
   float *u_img, *u_txt;
   const float *tau1, *tau2;
+  const float *uold1, *uold2;   // u^t at the batch positions, gathered by the prep kernel
   const float* sums;   // [4][nparts][bstride]
   int nparts;
   int64_t bstride, b;
@@ -309,6 +320,13 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
   const int al = threadIdx.x & 7, pl = threadIdx.x >> 3, wave = threadIdx.x >> 6;
   const int64_t r = (int64_t)blockIdx.x * kStateAnchors + al;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  int64_t n = 0;
+  float uo1 = 0.f, uo2 = 0.f, t1 = 0.f, t2 = 0.f;
+  if (threadIdx.x < 8 && r < a.b) {    // the per-anchor inputs of the threads that finish the anchors, requested first
+    n = a.idx[r] * a.stride;
+    uo1 = a.uold1[r]; uo2 = a.uold2[r];
+    t1 = a.tau1[r]; t2 = a.tau2[r];
+  }
   if (r < a.b) {
     for (int pt = pl; pt < a.nparts; pt += 32) {
 #pragma unroll
@@ -331,12 +349,10 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
       for (int q = 0; q < 4; ++q) s[q] = (part[q][0][al] + part[q][1][al]) + (part[q][2][al] + part[q][3][al]);
       const float invM = 1.0f / a.M;
       const float g1 = s[0] * invM, h1 = s[1] * invM, g2 = s[2] * invM, h2 = s[3] * invM;
-      const int64_t n = a.idx[r] * a.stride;
-      const float u1 = ema_update(a.u_img[n], g1, a.gamma);
-      const float u2 = ema_update(a.u_txt[n], g2, a.gamma);
+      const float u1 = ema_update(uo1, g1, a.gamma);
+      const float u2 = ema_update(uo2, g2, a.gamma);
       a.u_img[n] = u1;
       a.u_txt[n] = u2;
-      const float t1 = a.tau1[r], t2 = a.tau2[r];
       const float e1 = a.eps + u1, e2 = a.eps + u2;
       const float bm = (float)a.b * a.M;
       float c1 = 1.0f / (bm * e1), c2 = 1.0f / (bm * e2);
@@ -381,6 +397,7 @@ void launch_state(const StepCtx& c) {
   StateArgs a;
   a.idx = c.buf.idx; a.u_img = c.buf.u_img; a.u_txt = c.buf.u_txt;
   a.tau1 = (const float*)(c.ws + L.tau1); a.tau2 = (const float*)(c.ws + L.tau2);
+  a.uold1 = (const float*)(c.ws + L.uold1); a.uold2 = (const float*)(c.ws + L.uold2);
   a.sums = (const float*)(c.ws + L.sums); a.nparts = L.nparts; a.bstride = L.bstride; a.b = L.b;
   a.stride = c.cfg.state_stride;
   a.M = (float)(L.B - 1); a.gamma = c.cfg.gamma; a.eps = c.cfg.eps; a.rho = c.cfg.rho;
