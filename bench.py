@@ -187,11 +187,14 @@ def main():
 
     step = lambda t: fc.fastclip_step(cfgs[t], bufs[t], ws)
     if args.update_tau:      # Alg. 1 line 12 fused into the step: temperatures and their AdamW moments stepped in place
+        # the moment arrays stay referenced here for the whole run: the library is handed their addresses only
         if version == fc.V2:
-            tst = fc.make_tau_state(tau_img=tau_img, tau_txt=tau_txt, m_img=torch.zeros(N, **f32), v_img=torch.zeros(N, **f32),
-                                    m_txt=torch.zeros(N, **f32), v_txt=torch.zeros(N, **f32))
+            moments = [torch.zeros(N, **f32) for _ in range(4)]
+            tst = fc.make_tau_state(tau_img=tau_img, tau_txt=tau_txt, m_img=moments[0], v_img=moments[1],
+                                    m_txt=moments[2], v_txt=moments[3])
         else:
-            tst = fc.make_tau_state(tau=tau, m=torch.zeros(1, **f32), v=torch.zeros(1, **f32))
+            moments = [torch.zeros(1, **f32) for _ in range(2)]
+            tst = fc.make_tau_state(tau=tau, m=moments[0], v=moments[1])
         upd = lambda t: fc.make_tau_update(optimizer=fc.TAU_ADAMW, step=t + 1, lr=1e-4, beta1=0.9, beta2=0.999, eps=1e-8,
                                            tau_min=0.01)
         step = lambda t: fc.fastclip_step_update_tau(cfgs[t], bufs[t], upd(t), tst, ws)

@@ -133,11 +133,14 @@ def _ptr(t):
 
 
 def make_buffers(**tensors) -> fastclip_buffers:
-    """Field name -> CUDA tensor (or raw device address, or None)."""
+    """Field name -> CUDA tensor (or raw device address, or None).  The struct holds plain addresses; the returned
+    object also keeps the tensors referenced, so that a tensor passed as a temporary lives as long as the struct."""
     unknown = set(tensors) - set(_BUF_FIELDS)
     if unknown:
         raise TypeError("unknown buffer(s): %s" % sorted(unknown))
-    return fastclip_buffers(*[_ptr(tensors.get(n)) for n in _BUF_FIELDS])
+    out = fastclip_buffers(*[_ptr(tensors.get(n)) for n in _BUF_FIELDS])
+    out._keepalive = tuple(tensors.values())
+    return out
 
 
 def make_tau_update(*, optimizer, step, lr, beta1, beta2, eps=1e-8, tau_min=0.0, lr_drop_below=0.0,
@@ -148,11 +151,13 @@ def make_tau_update(*, optimizer, step, lr, beta1, beta2, eps=1e-8, tau_min=0.0,
 
 
 def make_tau_state(**tensors) -> fastclip_tau_state:
-    """Field name -> CUDA tensor (or raw device address, or None)."""
+    """Field name -> CUDA tensor (or raw device address, or None); keeps the tensors referenced like make_buffers."""
     unknown = set(tensors) - set(_TAU_STATE_FIELDS)
     if unknown:
         raise TypeError("unknown temperature state field(s): %s" % sorted(unknown))
-    return fastclip_tau_state(*[_ptr(tensors.get(n)) for n in _TAU_STATE_FIELDS])
+    out = fastclip_tau_state(*[_ptr(tensors.get(n)) for n in _TAU_STATE_FIELDS])
+    out._keepalive = tuple(tensors.values())
+    return out
 
 
 def _stream(stream):

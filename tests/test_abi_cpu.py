@@ -211,3 +211,30 @@ def test_temperature_update_argument_errors():
     st_same = fc.make_tau_state(tau_img=bufs2.tau_img, tau_txt=bufs2.tau_txt, m_img=0x3000, m_txt=0x5000)
     assert fc.fastclip_step_update_tau(cfg2, bufs2, sg, st_same, 0x1000, 1 << 40, stream=0, check=False) == fc.ERR_VALUE
     assert fc.fastclip_step_update_tau(cfg, bufs, None, None, 0x1000, 1 << 40, stream=0, check=False) == fc.ERR_NULL
+
+
+def test_structs_keep_their_tensors_alive():
+    """The structs carry plain addresses; a tensor handed to make_buffers / make_tau_state as a temporary must not be
+    freed while the struct is in use (a freed moment array under a later kernel is a wild write)."""
+    import gc
+    import weakref
+
+    class FakeTensor:            # what the binding asks of a tensor
+        is_cuda = True
+
+        def __init__(self, addr):
+            self.addr = addr
+
+        def data_ptr(self):
+            return self.addr
+
+    for make, field in ((fc.make_tau_state, "m_img"), (fc.make_buffers, "idx")):
+        t = FakeTensor(0x4000)
+        alive = weakref.ref(t)
+        st = make(**{field: t})
+        del t
+        gc.collect()
+        assert alive() is not None and getattr(st, field) == 0x4000
+        del st
+        gc.collect()
+        assert alive() is None
