@@ -542,8 +542,12 @@ void launch_grad_f32(const StepCtx& c) {
 // MFMA path, last phase.  d_img[r] = c1_r * (sum over splits of the contraction)[r] - dcoef_r txt_p, and the mirror
 // image (the contraction already carries the contrast-side terms divided by c_r); block (0,0,0) also writes the
 // scalars.  The split partials are whole 256 x 256 tiles of [64 groups of 4 rows][256 columns][4 rows] (the order in
-// which k_contract_bf16's accumulators leave in 16-byte words), so a wavefront takes four rows and the 256 columns of
-// one tile, 4 KiB of consecutive addresses per split, a thread four columns, and a block sixteen rows.
+// which k_contract_bf16's accumulators leave in 16-byte words), so a block of one wavefront takes four rows and the 256
+// columns of one tile, 4 KiB of consecutive addresses per split, and a thread four columns.  A block is four
+// wavefronts: four groups of rows (SHARE_SPLITS false), or, when that would leave most of the chip idle, one group
+// of rows whose splits the four wavefronts share (wave w sums the splits w, w + 4, ..; the four sums meet in LDS and
+// are added in the order of the waves).
+template <bool SHARE_SPLITS>
 __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict__ img, const bf16_t* __restrict__ txt,
                                                        int64_t ld_img, int64_t ld_txt, int64_t off, int64_t b, int64_t d,
                                                        const float* __restrict__ O1, const float* __restrict__ O2,
@@ -553,37 +557,59 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
                                                        const float* __restrict__ red, int nblocks, int version,
                                                        const float* __restrict__ tau, float rho, float* __restrict__ loss,
                                                        float* __restrict__ d_tau) {
-  const int64_t r0 = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * 4;          // rows r0 .. r0 + 3 (those below b)
-  const int64_t n0 = (int64_t)blockIdx.z * 256 + (int64_t)(threadIdx.x & 63) * 4;   // columns n0 .. n0 + 3 (d % 8 == 0)
+  __shared__ float4 meet[SHARE_SPLITS ? 3 : 1][4][64];     // [wave - 1][column of the thread][lane]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int64_t r0 = ((int64_t)blockIdx.x * (SHARE_SPLITS ? 1 : 4) + (SHARE_SPLITS ? 0 : wave)) * 4;   // rows r0 .. r0 + 3
+  const int64_t n0 = (int64_t)blockIdx.z * 256 + (int64_t)lane * 4;     // columns n0 .. n0 + 3 (d % 8 == 0)
   const int side = blockIdx.y;
-  if (r0 < b && n0 < d) {
-    const int nr = (int)(b - r0 < 4 ? b - r0 : 4);
-    const bf16_t* X = side == 0 ? txt : img;        // the diagonal term takes the other side's row
-    const int64_t ldx = side == 0 ? ld_txt : ld_img;
+  const bool live = r0 < b && n0 < d;
+  const int nr = (int)(b - r0 < 4 ? b - r0 : 4);
+  const bf16_t* X = side == 0 ? txt : img;          // the diagonal term takes the other side's row
+  const int64_t ldx = side == 0 ? ld_txt : ld_img;
+  float cown[4], dc[4];                             // requested ahead of the partial sums: one memory latency, not two
+  uint2 xr[4];
+  float acc[4][4] = {};                             // [column][row]
+  if (live) {
+    if (!SHARE_SPLITS || wave == 0) {
+#pragma unroll
+      for (int t = 0; t < 4; ++t) {
+        const int64_t r = r0 + (t < nr ? t : 0);
+        cown[t] = (side == 0 ? c1 : c2)[r];
+        dc[t] = dcoef[r];
+        xr[t] = *(const uint2*)(X + (off + r) * ldx + n0);
+      }
+    }
     const float* O = side == 0 ? O1 : O2;
-    float* out = (side == 0 ? d_img : d_txt) + r0 * d + n0;
     const size_t split_stride = partial_split_floats(b, d);
     const int64_t tiles_m = (b + 255) / 256;
     const size_t at = (size_t)((n0 >> 8) * tiles_m + (r0 >> 8)) * kPartialTileFloats +
                       (size_t)((((r0 & 255) >> 2) * 256 + (n0 & 255)) * 4);
-    float cown[4], dc[4];                           // requested ahead of the partial sums: one memory latency, not two
-    uint2 xr[4];
-#pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int64_t r = r0 + (t < nr ? t : 0);
-      cown[t] = (side == 0 ? c1 : c2)[r];
-      dc[t] = dcoef[r];
-      xr[t] = *(const uint2*)(X + (off + r) * ldx + n0);
-    }
-    float acc[4][4] = {};                           // [column][row]
 #pragma unroll 4
-    for (int s = 0; s < nsplit; ++s) {
+    for (int s = SHARE_SPLITS ? wave : 0; s < nsplit; s += SHARE_SPLITS ? 4 : 1) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const float4 v = *(const float4*)(O + (size_t)s * split_stride + at + 4 * j);
         acc[j][0] += v.x; acc[j][1] += v.y; acc[j][2] += v.z; acc[j][3] += v.w;
       }
     }
+  }
+  if (SHARE_SPLITS) {
+    if (wave > 0) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) meet[wave - 1][j][lane] = make_float4(acc[j][0], acc[j][1], acc[j][2], acc[j][3]);
+    }
+    __syncthreads();
+    if (wave > 0) return;
+#pragma unroll
+    for (int w = 0; w < 3; ++w)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float4 v = meet[w][j][lane];
+        acc[j][0] += v.x; acc[j][1] += v.y; acc[j][2] += v.z; acc[j][3] += v.w;
+      }
+  }
+  if (live) {
+    float* out = (side == 0 ? d_img : d_txt) + r0 * d + n0;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
       if (t >= nr) break;
@@ -623,8 +649,13 @@ __global__ void __launch_bounds__(256) k_norm_backward_bf16(const bf16_t* __rest
 
 void launch_finalize_bf16(const StepCtx& c) {
   const Layout& L = c.L;
-  dim3 grid((unsigned)((L.b + 15) / 16), 2, (unsigned)((L.d + 255) / 256)), block(256);
-  hipLaunchKernelGGL(k_finalize_bf16, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
+  const dim3 block(256);
+  const unsigned col_tiles = (unsigned)((L.d + 255) / 256);
+  // four row groups per block unless that makes fewer than two blocks per compute unit: then one, its splits shared
+  const bool share = (uint64_t)((L.b + 15) / 16) * 2 * col_tiles < 512 && L.nsplit >= 4;
+  const dim3 grid((unsigned)(share ? (L.b + 3) / 4 : (L.b + 15) / 16), 2, col_tiles);
+  auto* kernel = share ? k_finalize_bf16<true> : k_finalize_bf16<false>;
+  hipLaunchKernelGGL(kernel, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, (const float*)(c.ws + L.Opart[0]),
                      (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
