@@ -119,6 +119,9 @@ BF16_SMALL = [
     # ... and 320 anchors at the very end of the global batch: the last tile is moved back to end at b and recomputes
     # 192 anchors of the first one
     (1024, 320, 704, 128),
+    # enough contrast columns for a split contraction and an anchor count that is no multiple of 4: the last group of
+    # four rows of the split partial sums is ragged where the wavefronts of a block share the splits
+    (1100, 203, 50, 136),
     # the whole batch local and only whole tiles
     (512, 512, 0, 128),
     (768, 768, 0, 192),
