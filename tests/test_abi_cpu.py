@@ -4,6 +4,7 @@ sizes its workspace, and its gamma schedule agrees with the oracle's."""
 import ctypes as C
 import os
 import re
+import sys
 
 import pytest
 
@@ -238,3 +239,13 @@ def test_structs_keep_their_tensors_alive():
         del st
         gc.collect()
         assert alive() is None
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """This build runs on one GPU only: bench.py --gpus N with N > 1 exits with a message, before touching a GPU."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr
