@@ -259,6 +259,64 @@ def test_gathered_state_with_whole_batch_is_the_plain_step():
         assert torch.equal(x, y)
 
 
+# ------------------------------------------------------------------------------- seeded random shapes
+def random_case(rs, dtype):
+    """A valid shape: sizes around the 256-tile edges, tiny ones, whole batches, local shares of every offset."""
+    if dtype == "f32":
+        B = int(rs.integers(2, 160))
+        d = int(rs.integers(1, 70))
+    else:
+        kind = rs.integers(0, 6)
+        B = int(rs.choice([255, 256, 257, 511, 512, 513, 767, 768, 769, 1023, 1024, 1025, 2047, 2048, 2049])) if kind == 0 \
+            else int(rs.integers(2, 300)) if kind == 1 else int(rs.integers(300, 2500))
+        d = int(rs.choice([8, 16, 24, 40, 64, 72, 96, 128, 136, 192, 200, 256, 264, 320]))
+    mode = rs.integers(0, 5)
+    b = B if mode == 0 else int(rs.integers(1, min(B, 40) + 1)) if mode == 1 else \
+        int(min(B, 32 * rs.integers(1, 40))) if mode == 2 else int(rs.integers(1, B + 1))
+    off = 0 if b == B else int(rs.choice([0, B - b, int(rs.integers(0, B - b + 1))]))
+    return B, b, off, d
+
+
+@pytest.mark.parametrize("dtype,tol,cases", [("bf16", TOL_BF16, 60), ("f32", TOL_F32, 40)])
+def test_random_shapes(dtype, tol, cases):
+    """Seeded draws of shape, version, gathered state, record stride, gamma and row strides against the oracle."""
+    rs = np.random.default_rng(20240701)
+    for case in range(cases):
+        B, b, off, d = random_case(rs, dtype)
+        version = int(rs.choice([V0, V1, V2, V3]))
+        gathered = bool(rs.integers(0, 3) == 0) and b < B
+        stride = int(rs.choice([1, 1, 4, 8]))
+        gamma = float(rs.choice([0.6, 1.0, 0.25]))
+        N = int(rs.integers(b, 4 * b + 100))
+        pad = int(rs.choice([0, 8, 24]))
+        print("[random %s %d] B=%d b=%d off=%d d=%d v%d gathered=%d stride=%d gamma=%.2f N=%d pad=%d"
+              % (dtype, case, B, b, off, d, version, gathered, stride, gamma, N, pad), flush=True)
+        rng = np.random.default_rng(case)
+        img, txt = make_embeddings(case + 7, B, d, 0.5, dtype)
+        idx = draw_indices(case + 3, b, N)
+        u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+        u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+        t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+        t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+        f64 = lambda a: None if a is None else a.astype(np.float64)
+        gath, extra = None, {}
+        if gathered:
+            ug1, ug2, tg1, tg2 = gathered_inputs(rng, B, version)
+            gath = dict(u_img=ug1, u_txt=ug2, tau_img=tg1, tau_txt=tg2)
+            extra = dict(u_glob_img=f64(ug1), u_glob_txt=f64(ug2), tau_glob_img=f64(tg1), tau_glob_txt=f64(tg2))
+        g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
+                    tau_grad_scale=1.0 / N, ld_img=d + pad, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img,
+                    tau_txt0=t_txt, gathered=gath, state_stride=stride)
+        g.set_inputs(img, txt, idx)
+        g.step(gamma)
+        u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+        want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, u_img, u_txt, version=version,
+                         gamma=gamma, eps=g.eps, rho=g.rho, tau=float(np.float32(0.07)), tau_img=f64(t_img),
+                         tau_txt=f64(t_txt), tau_grad_scale=g.scale, **extra)
+        compare(g.outputs(), want, version, tol, "random %s %d" % (dtype, case))
+        check_state(g, u0i, u0t, idx, u_img, u_txt, tol)
+
+
 # ------------------------------------------------------------------------------- temperature update (Alg. 1 line 12)
 OPTIMIZERS = [(SGDM, dict(lr=1e-3, beta1=0.9, beta2=0.0)), (LAMB, dict(lr=1e-2, beta1=0.9, beta2=0.98, eps=1e-6)),
               (LION, dict(lr=1e-3, beta1=0.9, beta2=0.99)), (ADAMW, dict(lr=1e-2, beta1=0.9, beta2=0.999, eps=1e-8))]
