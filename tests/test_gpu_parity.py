@@ -289,8 +289,9 @@ def test_random_shapes(dtype, tol, cases):
         gamma = float(rs.choice([0.6, 1.0, 0.25]))
         N = int(rs.integers(b, 4 * b + 100))
         pad = int(rs.choice([0, 8, 24]))
-        print("[random %s %d] B=%d b=%d off=%d d=%d v%d gathered=%d stride=%d gamma=%.2f N=%d pad=%d"
-              % (dtype, case, B, b, off, d, version, gathered, stride, gamma, N, pad), flush=True)
+        normed = bool(rs.integers(0, 3) == 0)       # gradients with respect to rows that were normalised outside
+        print("[random %s %d] B=%d b=%d off=%d d=%d v%d gathered=%d stride=%d gamma=%.2f N=%d pad=%d normed=%d"
+              % (dtype, case, B, b, off, d, version, gathered, stride, gamma, N, pad, normed), flush=True)
         rng = np.random.default_rng(case)
         img, txt = make_embeddings(case + 7, B, d, 0.5, dtype)
         idx = draw_indices(case + 3, b, N)
@@ -304,9 +305,13 @@ def test_random_shapes(dtype, tol, cases):
             ug1, ug2, tg1, tg2 = gathered_inputs(rng, B, version)
             gath = dict(u_img=ug1, u_txt=ug2, tau_img=tg1, tau_txt=tg2)
             extra = dict(u_glob_img=f64(ug1), u_glob_txt=f64(ug2), tau_glob_img=f64(tg1), tau_glob_txt=f64(tg2))
+        norms = None
+        if normed:
+            norms = (rng.uniform(0.3, 20.0, b).astype(np.float32), rng.uniform(0.3, 20.0, b).astype(np.float32))
+            extra.update(norm_img=f64(norms[0]), norm_txt=f64(norms[1]))
         g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
                     tau_grad_scale=1.0 / N, ld_img=d + pad, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img,
-                    tau_txt0=t_txt, gathered=gath, state_stride=stride)
+                    tau_txt0=t_txt, gathered=gath, state_stride=stride, norms=norms)
         g.set_inputs(img, txt, idx)
         g.step(gamma)
         u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
