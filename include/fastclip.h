@@ -144,8 +144,8 @@ fastclip_status fastclip_step(const fastclip_config* cfg, const fastclip_buffers
 #define FASTCLIP_N_PHASES 8
 #define FASTCLIP_PHASE_PREP 0      /* s_ii and temperature gather */
 #define FASTCLIP_PHASE_STRIPS 1    /* similarity strips + exp + row sums (Proc. 1) */
-#define FASTCLIP_PHASE_STATE 2     /* Eq. 1 gather / update / scatter, coefficients, scalars */
-#define FASTCLIP_PHASE_LOCAL 3     /* contrast-side weights of Eqs. 3/5/7 folded into the stored strips */
+#define FASTCLIP_PHASE_STATE 2     /* Eq. 1 update / scatter, coefficients, scalars (0 where the bf16 path runs it inside the next phase) */
+#define FASTCLIP_PHASE_LOCAL 3     /* bf16 path: contrast-side weights of Eqs. 3/5/7 folded into the stored strips (+ the state phase for small batches) */
 #define FASTCLIP_PHASE_CONTRACT 4  /* gradient contractions of Eqs. 2-7 */
 #define FASTCLIP_PHASE_FINALIZE 5  /* split sums, scaling, diagonal terms, loss and tau gradient */
 fastclip_status fastclip_step_timed(const fastclip_config* cfg, const fastclip_buffers* bufs,

@@ -147,7 +147,12 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
     L->nsplit = 0;
     L->kslice = 0;
   }
-  L->nstate_blocks = (int)((cfg.b + kStateAnchors - 1) / kStateAnchors);
+  // Every 64 x 64 block of the fold needs the coefficients of 128 anchor sides.  Forming them inside the fold saves a
+  // launch, but every block then sums those anchors' partial sums again (b^2 / 32 anchor sides x nparts floats in
+  // all, against 2 b x nparts once): worth it only while that stays small.
+  L->fused_state = L->bf16 && L->nparts <= 64 &&
+                   (double)cfg.b * (double)cfg.b / 32.0 * (double)L->nparts * 4.0 <= 2.0 * 1024 * 1024;
+  L->nstate_blocks = L->fused_state ? (int)((cfg.b + 63) / 64) : (int)((cfg.b + kStateAnchors - 1) / kStateAnchors);
   L->diag = take(fb); L->tau1 = take(fb); L->tau2 = take(fb); L->k1 = take(fb); L->k2 = take(fb);
   L->uold1 = take(fb); L->uold2 = take(fb);
   L->sums = take(fb * 4 * (size_t)L->nparts);
@@ -219,8 +224,8 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
   mark(FASTCLIP_PHASE_PREP);
   if (c.L.bf16) {
     launch_strips_bf16(c);                mark(FASTCLIP_PHASE_STRIPS);
-    launch_state(c);                      mark(FASTCLIP_PHASE_STATE);
-    launch_fold_bf16(c);                  mark(FASTCLIP_PHASE_LOCAL);
+    if (!c.L.fused_state) { launch_state(c); mark(FASTCLIP_PHASE_STATE); }
+    launch_fold_bf16(c);                  mark(FASTCLIP_PHASE_LOCAL);   // with fused_state: the state phase as well
     launch_contract_bf16(c);              mark(FASTCLIP_PHASE_CONTRACT);
     launch_finalize_bf16(c);
   } else {

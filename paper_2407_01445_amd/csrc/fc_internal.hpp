@@ -33,7 +33,8 @@ struct Layout {
   int64_t ldE;       // contrast columns of the stored exp strips (MFMA path: multiple of 64; fp32 path: B)
   int nsplit;        // split of the contraction over its column range
   int64_t kslice;    // 32-deep stages per split
-  int nstate_blocks; // blocks of the state kernel (one scalar partial each)
+  int nstate_blocks; // scalar partials: one per block of the state kernel, or per diagonal block of the fused fold
+  int fused_state;   // 1: MFMA path, few anchors and few partial sums: the fold kernel runs the state phase itself
   int gathered;      // 1: contrast-side estimator over every global anchor (FASTCLIP_GATHERED_STATE and b < B)
   int square;        // 1: MFMA path, b == B and only whole tiles: the similarity matrix is formed once (F[0] holds
                      //    l2(j, p) in the layout of E[0] until the fold transposes it into E[1])

@@ -25,6 +25,7 @@
 // the next 16-deep step are issued between the MFMAs of the current one.  Tiles that touch a ragged edge use guarded
 // register loads into the same LDS images, one stage at a time.
 #include "mfma_common.hpp"
+#include "state_common.hpp"
 
 namespace fc {
 
@@ -498,22 +499,81 @@ __device__ __forceinline__ void fold_store(bf16_t* __restrict__ E, int64_t nCB, 
   }
 }
 
+// The state phase inside the fold kernels (Layout::fused_state; otherwise k_state has run and the coefficients are
+// read).  A block needs the coefficients c1 of its 64 rows r0 .. and c2 of its 64 rows q0 ..: it sums the strip phase's partial sums of those anchors (4 threads per anchor and side, then LDS, always
+// in the same order, so every block that forms an anchor's coefficient gets the same bits) and applies Eq. 1 to the
+// u^t that the prep kernel gathered.  Blocks on the diagonal (r0 == q0) have both sides of their anchors and finish
+// them: scatter of u^{t+1}, coefficients and diagonal factor for the later phases, Eq. 9, the scalars' partial sums.
+// sc: c1_r, c2_q, 1 / c1_r, 1 / c2_q; rows at or beyond b get 1.
+struct FoldState {
+  float part[4][4][64];   // [quantity][part lane][anchor]
+  float scal[2][64];
+};
+__device__ __forceinline__ void fold_coefficients(const StateArgs& a, int64_t r0, int64_t q0, float (*sc)[64], FoldState& fs) {
+  const int al = threadIdx.x & 63, pl = threadIdx.x >> 6;
+  const bool diag = r0 == q0;
+  const int side = threadIdx.x >> 6;                       // threads 0..63: side 0 of row r0 + al, 64..127: side 1 of q0 + al
+  const int64_t m = (side == 0 ? r0 : q0) + al;
+  if (!a.fused) {                                          // the state kernel has left the coefficients
+    if (threadIdx.x < 128) {
+      const float c = m < a.b ? (side == 0 ? a.c1 : a.c2)[m] : 1.0f;
+      sc[side][al] = c;
+      sc[2 + side][al] = 1.0f / c;
+    }
+    return;
+  }
+  // per-anchor inputs of the threads that form the coefficients below, requested before the sums
+  float uo = 0.f, tt = 0.07f, uo_other = 0.f, tt_other = 0.07f;
+  if (threadIdx.x < 128 && m < a.b) {
+    uo = (side == 0 ? a.uold1 : a.uold2)[m];
+    tt = (side == 0 ? a.tau1 : a.tau2)[m];
+    if (diag && side == 0) { uo_other = a.uold2[m]; tt_other = a.tau2[m]; }
+  }
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int pt = pl; pt < a.nparts; pt += 4) {              // rows up to bstride exist (whole 256-anchor tiles)
+    acc[0] += a.sums[((size_t)0 * a.nparts + pt) * a.bstride + r0 + al];
+    acc[2] += a.sums[((size_t)2 * a.nparts + pt) * a.bstride + q0 + al];
+    if (diag) {
+      acc[1] += a.sums[((size_t)1 * a.nparts + pt) * a.bstride + r0 + al];
+      acc[3] += a.sums[((size_t)3 * a.nparts + pt) * a.bstride + q0 + al];
+    }
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) fs.part[q][pl][al] = acc[q];
+  __syncthreads();
+  auto total = [&](int q) { return (fs.part[q][0][al] + fs.part[q][1][al]) + (fs.part[q][2][al] + fs.part[q][3][al]); };
+  if (diag) {
+    if (threadIdx.x < 64) {
+      float c1 = 1.0f, c2 = 1.0f, lsum = 0.f, hsum = 0.f;
+      if (m < a.b) {
+        const float s4[4] = {total(0), total(1), total(2), total(3)};
+        state_finish_anchor(a, m, s4, uo, uo_other, tt, tt_other, &c1, &c2, &lsum, &hsum);
+      }
+      sc[0][al] = c1; sc[1][al] = c2; sc[2][al] = 1.0f / c1; sc[3][al] = 1.0f / c2;
+      // the 64 anchors' terms of the loss and of the h sums (Eqs. 8 / 10): one pair per diagonal block
+      const double x = wave_sum_f64((double)lsum), y = wave_sum_f64((double)hsum);
+      if (threadIdx.x == 0) { a.red[2 * blockIdx.x + 0] = (float)x; a.red[2 * blockIdx.x + 1] = (float)y; }
+    }
+  } else if (threadIdx.x < 128) {
+    float c = 1.0f, u_new;
+    if (m < a.b) c = anchor_coefficient(a, total(side == 0 ? 0 : 2), uo, tt, &u_new);
+    sc[side][al] = c;
+    sc[2 + side][al] = 1.0f / c;
+  }
+}
+
 __global__ void __launch_bounds__(256) k_fold_bf16(bf16_t* __restrict__ E0, bf16_t* __restrict__ E1, int64_t nCB,
-                                                   const float* __restrict__ c1, const float* __restrict__ c2,
-                                                   int64_t off, int64_t b) {
+                                                   StateArgs a, int64_t off) {
   __shared__ float t0[64][65];   // [r][q]: l1(r, off + q), then w / c1_r
   __shared__ float t1[64][65];   // [q][r]: l2(q, off + r), then w / c2_q
   __shared__ float sc[4][64];    // c1_r, c2_q, 1 / c1_r, 1 / c2_q of the block's rows
+  __shared__ FoldState fs;
+  const int64_t b = a.b;
   const int64_t r0 = (int64_t)blockIdx.x * 64, q0 = (int64_t)blockIdx.y * 64;
-  if (threadIdx.x < 128) {
-    const int side = threadIdx.x >> 6, l = threadIdx.x & 63;
-    const int64_t m = (side == 0 ? r0 : q0) + l;
-    const float c = m < b ? (side == 0 ? c1 : c2)[m] : 1.0f;
-    sc[side][l] = c;
-    sc[2 + side][l] = 1.0f / c;
-  }
-  fold_load(E0, nCB, r0, off + q0, b, t0);
+  if (!a.fused) fold_coefficients(a, r0, q0, sc, fs);   // two loads per thread, requested first
+  fold_load(E0, nCB, r0, off + q0, b, t0);      // independent of the coefficients: in flight while they are formed
   fold_load(E1, nCB, q0, off + r0, b, t1);
+  if (a.fused) fold_coefficients(a, r0, q0, sc, fs);
   __syncthreads();
   const int nr = (int)(b - r0 < 64 ? b - r0 : 64), nq = (int)(b - q0 < 64 ? b - q0 : 64);
   {
@@ -536,21 +596,17 @@ __global__ void __launch_bounds__(256) k_fold_bf16(bf16_t* __restrict__ E0, bf16
 // layout of E0 (off == 0), so w = c1_r E0[r][q] + c2_q F0[r][q]; w / c1_r goes back to E0[r][q] and w / c2_q, transposed,
 // to E1[q][r], which nothing has written before.  b is a multiple of 256 here.
 __global__ void __launch_bounds__(256) k_fold_square_bf16(bf16_t* __restrict__ E0, const bf16_t* __restrict__ F0,
-                                                          bf16_t* __restrict__ E1, int64_t nCB,
-                                                          const float* __restrict__ c1, const float* __restrict__ c2,
-                                                          int64_t b) {
+                                                          bf16_t* __restrict__ E1, int64_t nCB, StateArgs a) {
   __shared__ float t0[64][65];   // [r][q]: l1(r, q), then w / c1_r
   __shared__ float t1[64][65];   // [r][q]: l2(q, r); then [q][r]: w / c2_q
   __shared__ float sc[4][64];
+  __shared__ FoldState fs;
+  const int64_t b = a.b;
   const int64_t r0 = (int64_t)blockIdx.x * 64, q0 = (int64_t)blockIdx.y * 64;
-  if (threadIdx.x < 128) {
-    const int side = threadIdx.x >> 6, l = threadIdx.x & 63;
-    const float c = (side == 0 ? c1 : c2)[(side == 0 ? r0 : q0) + l];
-    sc[side][l] = c;
-    sc[2 + side][l] = 1.0f / c;
-  }
+  if (!a.fused) fold_coefficients(a, r0, q0, sc, fs);
   fold_load(E0, nCB, r0, q0, b, t0);
   fold_load(F0, nCB, r0, q0, b, t1);
+  if (a.fused) fold_coefficients(a, r0, q0, sc, fs);
   __syncthreads();
   float keep[16];
   {
@@ -608,7 +664,14 @@ __global__ void __launch_bounds__(256) k_fold_remote_bf16(bf16_t* __restrict__ E
 void launch_fold_bf16(const StepCtx& c) {
   const Layout& L = c.L;
   const unsigned nb = (unsigned)((L.b + 63) / 64);
-  if (L.gathered) {
+  const StateArgs st = make_state_args(c);
+  if (L.square)
+    hipLaunchKernelGGL(k_fold_square_bf16, dim3(nb, nb), dim3(256), 0, c.s, (bf16_t*)(c.ws + L.E[0]),
+                       (const bf16_t*)(c.ws + L.F[0]), (bf16_t*)(c.ws + L.E[1]), L.ldE / 16, st);
+  else
+    hipLaunchKernelGGL(k_fold_bf16, dim3(nb, nb), dim3(256), 0, c.s, (bf16_t*)(c.ws + L.E[0]), (bf16_t*)(c.ws + L.E[1]),
+                       L.ldE / 16, st, L.off);
+  if (L.gathered) {   // after the kernel above: it leaves the coefficients of all local rows
     const int64_t per_block = (L.ldE / 16) * 64;                       // chunks per block of 32 anchors
     const int64_t chunks = (int64_t)((L.b + 31) / 32) * per_block;
     hipLaunchKernelGGL(k_fold_remote_bf16, dim3((unsigned)((chunks + 255) / 256), 2), dim3(256), 0, c.s,
@@ -616,14 +679,6 @@ void launch_fold_bf16(const StepCtx& c) {
                        (const bf16_t*)(c.ws + L.F[1]), (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
                        per_block, L.b);
   }
-  if (L.square) {
-    hipLaunchKernelGGL(k_fold_square_bf16, dim3(nb, nb), dim3(256), 0, c.s, (bf16_t*)(c.ws + L.E[0]),
-                       (const bf16_t*)(c.ws + L.F[0]), (bf16_t*)(c.ws + L.E[1]), L.ldE / 16,
-                       (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.b);
-    return;
-  }
-  hipLaunchKernelGGL(k_fold_bf16, dim3(nb, nb), dim3(256), 0, c.s, (bf16_t*)(c.ws + L.E[0]), (bf16_t*)(c.ws + L.E[1]),
-                     L.ldE / 16, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2), L.off, L.b);
 }
 
 // ----------------------------------------------------------------------------------------------------------------

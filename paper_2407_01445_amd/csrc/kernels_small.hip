@@ -2,6 +2,7 @@
 // the per-anchor coefficients, the fp32-storage accuracy path (strips and gradients in
 // plain loops with fp64 accumulation), the scalar outputs, and the index checker.
 #include "fc_internal.hpp"
+#include "state_common.hpp"
 
 namespace fc {
 
@@ -233,31 +234,6 @@ void launch_strips_f32(const StepCtx& c) {
                      L.gathered ? (float*)(c.ws + L.F[0]) : nullptr, L.gathered ? (float*)(c.ws + L.F[1]) : nullptr);
 }
 
-// ------------------------------------------------------------------------------------------
-// Proc. "parameter_update" for one temperature with weight decay 0, then the projection onto tau >= tau_0.
-// g: gradient estimator (Eqs. 8-10).  m, v: the optimizer's state (v only for AdamW / LAMB, pv may be NULL otherwise).
-__device__ inline void tau_step(const TauUpd& u, float* ptau, float* pm, float* pv, float g) {
-  const float tau = *ptau;
-  float m = *pm;
-  const float lr = tau < u.drop_below ? u.lr * u.drop_factor : u.lr;
-  float next;
-  if (u.optimizer == FASTCLIP_TAU_SGDM) {
-    m = fmaf(u.beta1, m, g);
-    next = tau - lr * m;
-  } else if (u.optimizer == FASTCLIP_TAU_LION) {
-    const float c = fmaf(u.beta1, m, (1.0f - u.beta1) * g);
-    m = fmaf(u.beta2, m, (1.0f - u.beta2) * g);
-    next = tau - lr * (c > 0.f ? 1.f : (c < 0.f ? -1.f : 0.f));
-  } else {                                             // AdamW; LAMB with layer factor 1
-    float v = *pv;
-    m = fmaf(u.beta1, m, (1.0f - u.beta1) * g);
-    v = fmaf(u.beta2, v, (1.0f - u.beta2) * g * g);
-    *pv = v;
-    next = tau - lr * ((m * u.corr1) / (sqrtf(v * u.corr2) + u.eps));
-  }
-  *pm = m;
-  *ptau = fmaxf(next, u.tau_min);
-}
 
 // Global temperature (V0, V3): one thread.
 __global__ void k_tau_scalar(TauUpd u, float* tau, float* m, float* v, const float* d_tau) {
@@ -287,31 +263,7 @@ void launch_tau_sparse(const TauUpd& u, const fastclip_tau_state& st, const int6
 }
 
 // ------------------------------------------------------------------------------------------
-// State phase.  Eq. 1 at the batch positions (first visit: stored 0 -> g), the coefficient
-// 1/(|B_k| |B_i-| (eps+u)) of Eqs. 2-7 (with the extra 1/tau of Eqs. 4-5 for V0), Eq. 9 per anchor,
-// and per-block partial sums of the two scalars that Eqs. 8 and 10 and the loss need.
-struct StateArgs {
-  const int64_t* idx;
-  float *u_img, *u_txt;
-  const float *tau1, *tau2;
-  const float *uold1, *uold2;   // u^t at the batch positions, gathered by the prep kernel
-  const float* sums;   // [4][nparts][bstride]
-  int nparts;
-  int64_t bstride, b;
-  int64_t stride;      // elements between consecutive samples in u_img / u_txt (and the temperature arrays)
-  float M, gamma, eps, rho, tau_scale;
-  int version;
-  float *c1, *c2, *dcoef, *red;
-  float *d_tau_img, *d_tau_txt, *g_img, *g_txt, *u_new_img, *u_new_txt;
-  // V2 with the temperature update in the same pass (optimizer != 0): the temperatures and their moments at idx
-  TauUpd tau_upd;
-  float *tau_img, *tau_txt, *m_img, *v_img, *m_txt, *v_txt;
-};
-
-__device__ inline float ema_update(float u_old, float g, float gamma) {
-  return u_old == 0.0f ? g : fmaf(gamma, g, (1.0f - gamma) * u_old);
-}
-
+// State phase of the fp32 path (the MFMA path runs it inside its fold kernels).
 // 256 threads = 8 anchors x 32 lanes over the partial sums (thread = 8 * lane + anchor); threads 0..7 then do the
 // per-anchor work.  kStateAnchors anchors and one pair of scalar partials per block.
 __global__ void __launch_bounds__(256) k_state(StateArgs a) {
@@ -320,10 +272,8 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
   const int al = threadIdx.x & 7, pl = threadIdx.x >> 3, wave = threadIdx.x >> 6;
   const int64_t r = (int64_t)blockIdx.x * kStateAnchors + al;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  int64_t n = 0;
   float uo1 = 0.f, uo2 = 0.f, t1 = 0.f, t2 = 0.f;
   if (threadIdx.x < 8 && r < a.b) {    // the per-anchor inputs of the threads that finish the anchors, requested first
-    n = a.idx[r] * a.stride;
     uo1 = a.uold1[r]; uo2 = a.uold2[r];
     t1 = a.tau1[r]; t2 = a.tau2[r];
   }
@@ -347,38 +297,8 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
       float s[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) s[q] = (part[q][0][al] + part[q][1][al]) + (part[q][2][al] + part[q][3][al]);
-      const float invM = 1.0f / a.M;
-      const float g1 = s[0] * invM, h1 = s[1] * invM, g2 = s[2] * invM, h2 = s[3] * invM;
-      const float u1 = ema_update(uo1, g1, a.gamma);
-      const float u2 = ema_update(uo2, g2, a.gamma);
-      a.u_img[n] = u1;
-      a.u_txt[n] = u2;
-      const float e1 = a.eps + u1, e2 = a.eps + u2;
-      const float bm = (float)a.b * a.M;
-      float c1 = 1.0f / (bm * e1), c2 = 1.0f / (bm * e2);
-      if (a.version == FASTCLIP_V0) { c1 /= t1; c2 /= t2; }
-      a.c1[r] = c1;
-      a.c2[r] = c2;
-      a.dcoef[r] = c1 * s[0] + c2 * s[2];          // c1 M g1 + c2 M g2
-      const float l1 = logf(e1), l2 = logf(e2);
-      if (a.version == FASTCLIP_V2) {
-        const float gt1 = a.tau_scale * (l1 + a.rho - h1 / (t1 * e1));
-        const float gt2 = a.tau_scale * (l2 + a.rho - h2 / (t2 * e2));
-        a.d_tau_img[r] = gt1;
-        a.d_tau_txt[r] = gt2;
-        lsum = t1 * (l1 + a.rho) + t2 * (l2 + a.rho);
-        if (a.tau_upd.optimizer) {   // Proc. "temperature_update" for sample n, same gather/scatter as u
-          tau_step(a.tau_upd, a.tau_img + n, a.m_img + n, a.v_img ? a.v_img + n : nullptr, gt1);
-          tau_step(a.tau_upd, a.tau_txt + n, a.m_txt + n, a.v_txt ? a.v_txt + n : nullptr, gt2);
-        }
-      } else {
-        lsum = l1 + l2;
-      }
-      hsum = h1 / e1 + h2 / e2;
-      if (a.g_img) a.g_img[r] = g1;
-      if (a.g_txt) a.g_txt[r] = g2;
-      if (a.u_new_img) a.u_new_img[r] = u1;
-      if (a.u_new_txt) a.u_new_txt[r] = u2;
+      float c1, c2;
+      state_finish_anchor(a, r, s, uo1, uo2, t1, t2, &c1, &c2, &lsum, &hsum);
     }
     scal[0][al] = lsum;
     scal[1][al] = hsum;
@@ -392,13 +312,14 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
   }
 }
 
-void launch_state(const StepCtx& c) {
+StateArgs make_state_args(const StepCtx& c) {
   const Layout& L = c.L;
   StateArgs a;
   a.idx = c.buf.idx; a.u_img = c.buf.u_img; a.u_txt = c.buf.u_txt;
   a.tau1 = (const float*)(c.ws + L.tau1); a.tau2 = (const float*)(c.ws + L.tau2);
   a.uold1 = (const float*)(c.ws + L.uold1); a.uold2 = (const float*)(c.ws + L.uold2);
   a.sums = (const float*)(c.ws + L.sums); a.nparts = L.nparts; a.bstride = L.bstride; a.b = L.b;
+  a.fused = L.fused_state;
   a.stride = c.cfg.state_stride;
   a.M = (float)(L.B - 1); a.gamma = c.cfg.gamma; a.eps = c.cfg.eps; a.rho = c.cfg.rho;
   a.tau_scale = c.cfg.tau_grad_scale; a.version = c.cfg.version;
@@ -410,7 +331,11 @@ void launch_state(const StepCtx& c) {
   if (c.cfg.version != FASTCLIP_V2) a.tau_upd.optimizer = 0;
   a.tau_img = c.tau_st.tau_img; a.tau_txt = c.tau_st.tau_txt;
   a.m_img = c.tau_st.m_img; a.v_img = c.tau_st.v_img; a.m_txt = c.tau_st.m_txt; a.v_txt = c.tau_st.v_txt;
-  hipLaunchKernelGGL(k_state, dim3((unsigned)L.nstate_blocks), dim3(256), 0, c.s, a);
+  return a;
+}
+
+void launch_state(const StepCtx& c) {
+  hipLaunchKernelGGL(k_state, dim3((unsigned)c.L.nstate_blocks), dim3(256), 0, c.s, make_state_args(c));
 }
 
 // Eq. 1 alone, one thread per anchor (the same update as in k_state).

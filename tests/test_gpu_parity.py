@@ -700,6 +700,6 @@ def test_step_timed_reports_phases_and_same_result():
         ms = g.step(0.7, timed=timed)
         outs.append((g.d_img.cpu(), g.u_img.cpu(), g.d_tau.cpu()))
     assert set(ms) == {"prep", "strips", "state", "local", "contract", "finalize"}
-    assert all(v > 0 for v in ms.values())
+    assert all(v > 0 for k, v in ms.items() if k != "state") and ms["state"] >= 0     # few anchors: state runs inside "local"
     for x, y in zip(*outs):
         assert torch.equal(x, y)
