@@ -28,9 +28,9 @@ PEAK_HBM_BYTES = 8.0e12      # MI355X HBM3E
 # dispatch, FETCH_SIZE x 2.000 and WRITE_SIZE x 1.000 after calibration against a 1 GiB device copy;
 # the summaries are kept under profiles/), keyed by (workload, phase); absent = not measured.
 MEASURED_TRAFFIC = {
-    ("cfg4", "strips"): (98609.9 * 2.0 + 133120.0) * 1024,
-    ("cfg4", "contract"): (131184.4 * 2.0 + 65536.0) * 1024,
-    ("cfg4", "state_flat_2^24"): (2225824.2 * 2.0 + 1180160.5) * 1024,
+    ("cfg4", "strips"): (98597.6 * 2.0 + 133120.0) * 1024,
+    ("cfg4", "contract"): (131191.5 * 2.0 + 65536.0) * 1024,
+    ("cfg4", "state_flat_2^24"): (2225825.5 * 2.0 + 1180160.6) * 1024,
 }
 
 
