@@ -500,16 +500,17 @@ __device__ __forceinline__ void fold_store(bf16_t* __restrict__ E, int64_t nCB, 
 }
 
 // The state phase inside the fold kernels (Layout::fused_state; otherwise k_state has run and the coefficients are
-// read).  A block needs the coefficients c1 of its 64 rows r0 .. and c2 of its 64 rows q0 ..: it sums the strip phase's partial sums of those anchors (4 threads per anchor and side, then LDS, always
-// in the same order, so every block that forms an anchor's coefficient gets the same bits) and applies Eq. 1 to the
-// u^t that the prep kernel gathered.  Blocks on the diagonal (r0 == q0) have both sides of their anchors and finish
-// them: scatter of u^{t+1}, coefficients and diagonal factor for the later phases, Eq. 9, the scalars' partial sums.
+// read).  A block needs the coefficients c1 of its 64 rows r0 .. and c2 of its 64 rows q0 ..: it sums the strip
+// phase's partial sums of those anchors (4 threads per anchor and side, then LDS, always in the same order, so every
+// block that forms an anchor's coefficient gets the same bits) and applies Eq. 1 to the u^t that the prep kernel
+// gathered.  Blocks on the diagonal (r0 == q0) have both sides of their anchors and finish them: scatter of u^{t+1},
+// coefficients and diagonal factor for the later phases, Eq. 9, the scalars' partial sums.
 // sc: c1_r, c2_q, 1 / c1_r, 1 / c2_q; rows at or beyond b get 1.
 struct FoldState {
   float part[4][4][64];   // [quantity][part lane][anchor]
-  float scal[2][64];
 };
-__device__ __forceinline__ void fold_coefficients(const StateArgs& a, int64_t r0, int64_t q0, float (*sc)[64], FoldState& fs) {
+__device__ __forceinline__ void fold_coefficients(const StateArgs& a, int64_t r0, int64_t q0, float (*sc)[64],
+                                                  FoldState& fs) {
   const int al = threadIdx.x & 63, pl = threadIdx.x >> 6;
   const bool diag = r0 == q0;
   const int side = threadIdx.x >> 6;                       // threads 0..63: side 0 of row r0 + al, 64..127: side 1 of q0 + al
