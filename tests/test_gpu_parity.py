@@ -381,13 +381,15 @@ def test_temperature_update_alone(opt, hp, stride):
 
 
 @pytest.mark.parametrize("stride", [1, 8])
-@pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (64, 64, 0, 32)), ("bf16", TOL_BF16, (700, 300, 133, 72))])
+@pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (64, 64, 0, 32)), ("bf16", TOL_BF16, (700, 300, 133, 72)),
+                                             # enough anchors that the state phase is a kernel of its own on the MFMA path
+                                             ("bf16", TOL_BF16, (2048, 1536, 256, 64))])
 @pytest.mark.parametrize("version", [V2, V3, V0])
 def test_step_with_temperature_update_three_iterations(dtype, tol, shape, version, stride):
     """fastclip_step_update_tau: step + temperature update per iteration, temperatures and moments carried on the
     device, against the oracle's step followed by Proc. temperature_update."""
     B, b, off, d = shape
-    N = 2000
+    N = max(2000, 2 * b)
     rng = np.random.default_rng(9 + version)
     hp = dict(lr=2e-3, beta1=0.9, beta2=0.98, eps=1e-6)
     extra = dict(tau_min=0.01, lr_drop_below=0.03, lr_drop_factor=1.0 / 3.0)
