@@ -122,6 +122,9 @@ BF16_SMALL = [
     # enough contrast columns for a split contraction and an anchor count that is no multiple of 4: the last group of
     # four rows of the split partial sums is ragged where the wavefronts of a block share the splits
     (1100, 203, 50, 136),
+    # wide embeddings: many 64-deep stages per tile, a width of whole stages and one with a ragged last stage
+    (700, 300, 133, 2048),
+    (300, 300, 0, 4104),
     # the whole batch local and only whole tiles
     (512, 512, 0, 128),
     (768, 768, 0, 192),
