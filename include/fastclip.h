@@ -50,7 +50,9 @@ typedef enum {
  *   V3  RGCL-g, learnable global tau                           (Eqs. 2, 3, 10)          */
 typedef enum { FASTCLIP_V0 = 0, FASTCLIP_V1 = 1, FASTCLIP_V2 = 2, FASTCLIP_V3 = 3 } fastclip_version_t;
 
-/* Embedding storage type.  F32: accuracy path (fp32 rows, sums carried in fp64).
+/* Embedding storage type.  F32: accuracy path (fp32 rows; dot products, the sums over the contrasts, the gradient
+ * sums, the logarithms and the sums behind loss and d_tau are carried in fp64; what is stored between the phases
+ * - exponentials, row sums, u, coefficients - and every output is fp32).
  * BF16: MFMA path (bf16 rows, fp32 accumulation; exp values are rounded to bf16 only
  * where they are operands of the gradient contractions). */
 typedef enum { FASTCLIP_F32 = 0, FASTCLIP_BF16 = 1 } fastclip_dtype;

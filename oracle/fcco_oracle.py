@@ -103,7 +103,7 @@ def ema_update(u_arr, idx, g, gamma):
 def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0.0,
               tau=None, tau_img=None, tau_txt=None, tau_grad_scale=1.0,
               u_glob_img=None, u_glob_txt=None, tau_glob_img=None, tau_glob_txt=None,
-              norm_img=None, norm_txt=None):
+              norm_img=None, norm_txt=None, contrast_side=True):
     """One FCCO step of worker k.  Updates u_img / u_txt IN PLACE at idx.
 
     img, txt   [B, d] global image / text embeddings (any float dtype; used as float64)
@@ -123,6 +123,8 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
     norm_img/txt  optional [b]: the rows of img / txt are the L2-normalised encoder outputs (cosine
                similarity, Sec. 3) and these are the norms the local rows had before; d_img / d_txt
                are then gradients with respect to the rows BEFORE normalisation.
+    contrast_side  False leaves the estimator of Eq. 3 / 5 / 7 out (only Eq. 2 / 4 / 6 remains).  Not a mode
+               of the method: tests use it to learn how large that term is in a given gradient.
     Returns a dict with g_img, g_txt, h_img, h_txt, u_new_img, u_new_txt, d_img,
     d_txt ([b, d]), loss, and d_tau (v0, v3) or d_tau_img, d_tau_txt ([b], v2).
     """
@@ -179,7 +181,9 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
     # d l2(i,j)/d e_{1,i} = -l2 e_{2,i} / tau, and the mirror images for e_{2,i}.
     d_img = c1[:, None] * (E1 @ txt - (M * g1)[:, None] * T_loc) - (c2 * M * g2)[:, None] * T_loc
     d_txt = c2[:, None] * (E2 @ img - (M * g2)[:, None] * I_loc) - (c1 * M * g1)[:, None] * I_loc
-    if u_glob_img is None and u_glob_txt is None:
+    if not contrast_side:
+        pass
+    elif u_glob_img is None and u_glob_txt is None:
         # Eq. 3 / 5 / 7 restricted to local anchors i: local row p is a contrast of the
         # other local anchors r'.  l2(r', p) = exp((s_{p p'} - s_{p'p'}) / tau2_{r'}) moves image
         # row p, l1(r', p) = exp((s_{p'p} - s_{p'p'}) / tau1_{r'}) moves text row p.
@@ -232,22 +236,46 @@ def fcco_step(img, txt, off, b, idx, u_img, u_txt, *, version, gamma, eps, rho=0
     out = dict(g_img=g1, g_txt=g2, h_img=h1, h_txt=h2, u_new_img=u1, u_new_txt=u2,
                d_img=d_img, d_txt=d_txt)
     log1, log2 = np.log(eps + u1), np.log(eps + u2)
+    # loss_abs / d_tau_abs: the same sums with every term replaced by its absolute value.  They are no
+    # outputs of the method but the scale against which an error of the scalar is judged: the scalars are
+    # sums of terms of both signs (logarithms of values around 1, tau log against 2 rho tau) and can
+    # cancel to nearly nothing, and then an error relative to the scalar itself says nothing about the
+    # arithmetic that produced it.
+    mean_abs_log = np.mean(np.abs(log1) + np.abs(log2))
+    mean_abs_h = np.mean(np.abs(h1) / (eps + u1) + np.abs(h2) / (eps + u2))
     if version == V1:
         out["loss"] = float(tau) * np.mean(log1 + log2)
+        out["loss_abs"] = abs(float(tau)) * mean_abs_log
     elif version == V0:                          # Eq. 8
         out["loss"] = np.mean(log1 + log2)
+        out["loss_abs"] = mean_abs_log
         out["d_tau"] = -np.mean(h1 / (eps + u1) + h2 / (eps + u2)) / float(tau) ** 2
+        out["d_tau_abs"] = mean_abs_h / float(tau) ** 2
     elif version == V3:                          # Eq. 10
         out["loss"] = float(tau) * np.mean(log1 + log2) + 2.0 * rho * float(tau)
+        out["loss_abs"] = abs(float(tau)) * mean_abs_log + abs(2.0 * rho * float(tau))
         out["d_tau"] = (np.mean(log1 + log2) + 2.0 * rho
                         - np.mean(h1 / (eps + u1) + h2 / (eps + u2)) / float(tau))
+        out["d_tau_abs"] = mean_abs_log + abs(2.0 * rho) + mean_abs_h / abs(float(tau))
     elif version == V2:                          # Eq. 9
         out["loss"] = np.mean(tau1 * (log1 + rho) + tau2 * (log2 + rho))
+        out["loss_abs"] = np.mean(np.abs(tau1) * (np.abs(log1) + abs(rho)) + np.abs(tau2) * (np.abs(log2) + abs(rho)))
         out["d_tau_img"] = tau_grad_scale * (log1 + rho - h1 / (tau1 * (eps + u1)))
         out["d_tau_txt"] = tau_grad_scale * (log2 + rho - h2 / (tau2 * (eps + u2)))
     else:
         raise ValueError("unknown version")
     return out
+
+
+def normalize_rows(raw):
+    """Cosine similarity of Sec. 3 at the boundary: the unit rows e / |e| that fcco_step takes, and the norms |e|.
+
+    raw: [b, d] encoder outputs (any float dtype; used as float64), no row all zero.
+    Returns (unit [b, d], norm [b]) in float64.
+    """
+    raw = np.asarray(raw, dtype=np.float64)
+    norm = np.sqrt(np.einsum("rk,rk->r", raw, raw))
+    return raw / norm[:, None], norm
 
 
 # ----------------------------------------------------------------------------------------------

@@ -57,7 +57,7 @@ fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* buf
       if ((cfg->version == FASTCLIP_V0 || cfg->version == FASTCLIP_V3) && !bufs->d_tau) return FASTCLIP_ERR_NULL;
     }
     if ((bufs->norm_img == nullptr) != (bufs->norm_txt == nullptr)) return FASTCLIP_ERR_NULL;
-    if (cfg->flags & FASTCLIP_GATHERED_STATE) {
+    if ((cfg->flags & FASTCLIP_GATHERED_STATE) && cfg->b < cfg->B) {   // b == B: no remote anchors, arrays not read
       if (!bufs->u_glob_img || !bufs->u_glob_txt) return FASTCLIP_ERR_NULL;
       if (cfg->version == FASTCLIP_V2 && (!bufs->tau_glob_img || !bufs->tau_glob_txt)) return FASTCLIP_ERR_NULL;
     }
@@ -157,7 +157,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   L->uold1 = take(fb); L->uold2 = take(fb);
   L->sums = take(fb * 4 * (size_t)L->nparts);
   L->c1 = take(fb); L->c2 = take(fb); L->dcoef = take(fb);
-  L->red = take(sizeof(float) * 2 * (size_t)L->nstate_blocks);
+  L->red = take(sizeof(double) * 2 * (size_t)L->nstate_blocks);
   const size_t esz = L->bf16 ? sizeof(bf16_t) : sizeof(float);
   if (L->bf16) {
     // fragment-ordered strips: anchors padded to whole 256-row tiles
@@ -200,7 +200,8 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
                                     : (cfg->version != FASTCLIP_V1 && tst->tau != bufs->tau))
       return FASTCLIP_ERR_VALUE;
     // ... laid out as the step's own state arrays are
-    if ((upd->state_stride > 1 ? upd->state_stride : 1) != cfg->state_stride) return FASTCLIP_ERR_VALUE;
+    if (cfg->version == FASTCLIP_V2 && (upd->state_stride > 1 ? upd->state_stride : 1) != cfg->state_stride)
+      return FASTCLIP_ERR_VALUE;
     if (cfg->version != FASTCLIP_V1) { c.tau_upd = make_tau_upd(*upd); c.tau_st = *tst; }
   }
   make_layout(*cfg, &c.L);

@@ -43,7 +43,7 @@ struct Layout {
   size_t uold1, uold2;               // float[bstride]: u^t of the batch's samples (gathered with the temperatures)
   size_t sums;                       // float[4][nparts][bstride]: sum e1, sum x1 e1, sum e2, sum x2 e2
   size_t c1, c2, dcoef;              // float[bstride]
-  size_t red;                        // float[nstate_blocks][2]
+  size_t red;                        // double[nstate_blocks][2]
   size_t E[2];                       // fp32 path: float [b][ldE]; MFMA path: fragment-ordered bf16 strips
   size_t Opart[2];                   // float [nsplit][partial_split_floats(b, d)]   (MFMA path)
   // gathered: per global row j (= contrast column of the strips) and side s, in tiles of 256 columns

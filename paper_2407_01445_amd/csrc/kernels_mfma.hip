@@ -545,15 +545,16 @@ __device__ __forceinline__ void fold_coefficients(const StateArgs& a, int64_t r0
   auto total = [&](int q) { return (fs.part[q][0][al] + fs.part[q][1][al]) + (fs.part[q][2][al] + fs.part[q][3][al]); };
   if (diag) {
     if (threadIdx.x < 64) {
-      float c1 = 1.0f, c2 = 1.0f, lsum = 0.f, hsum = 0.f;
+      float c1 = 1.0f, c2 = 1.0f;
+      double lsum = 0.0, hsum = 0.0;
       if (m < a.b) {
         const float s4[4] = {total(0), total(1), total(2), total(3)};
-        state_finish_anchor(a, m, s4, uo, uo_other, tt, tt_other, &c1, &c2, &lsum, &hsum);
+        state_finish_anchor<false>(a, m, s4, uo, uo_other, tt, tt_other, &c1, &c2, &lsum, &hsum);
       }
       sc[0][al] = c1; sc[1][al] = c2; sc[2][al] = 1.0f / c1; sc[3][al] = 1.0f / c2;
       // the 64 anchors' terms of the loss and of the h sums (Eqs. 8 / 10): one pair per diagonal block
-      const double x = wave_sum_f64((double)lsum), y = wave_sum_f64((double)hsum);
-      if (threadIdx.x == 0) { a.red[2 * blockIdx.x + 0] = (float)x; a.red[2 * blockIdx.x + 1] = (float)y; }
+      const double x = wave_sum_f64(lsum), y = wave_sum_f64(hsum);
+      if (threadIdx.x == 0) { a.red[2 * blockIdx.x + 0] = x; a.red[2 * blockIdx.x + 1] = y; }
     }
   } else if (threadIdx.x < 128) {
     float c = 1.0f, u_new;

@@ -266,9 +266,10 @@ void launch_tau_sparse(const TauUpd& u, const fastclip_tau_state& st, const int6
 // State phase of the fp32 path (the MFMA path runs it inside its fold kernels).
 // 256 threads = 8 anchors x 32 lanes over the partial sums (thread = 8 * lane + anchor); threads 0..7 then do the
 // per-anchor work.  kStateAnchors anchors and one pair of scalar partials per block.
+template <bool PRECISE>
 __global__ void __launch_bounds__(256) k_state(StateArgs a) {
   __shared__ float part[4][4][8];
-  __shared__ float scal[2][8];
+  __shared__ double scal[2][8];
   const int al = threadIdx.x & 7, pl = threadIdx.x >> 3, wave = threadIdx.x >> 6;
   const int64_t r = (int64_t)blockIdx.x * kStateAnchors + al;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};
@@ -292,13 +293,13 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
   }
   __syncthreads();
   if (threadIdx.x < 8) {
-    float lsum = 0.f, hsum = 0.f;
+    double lsum = 0.0, hsum = 0.0;
     if (r < a.b) {
       float s[4];
 #pragma unroll
       for (int q = 0; q < 4; ++q) s[q] = (part[q][0][al] + part[q][1][al]) + (part[q][2][al] + part[q][3][al]);
       float c1, c2;
-      state_finish_anchor(a, r, s, uo1, uo2, t1, t2, &c1, &c2, &lsum, &hsum);
+      state_finish_anchor<PRECISE>(a, r, s, uo1, uo2, t1, t2, &c1, &c2, &lsum, &hsum);
     }
     scal[0][al] = lsum;
     scal[1][al] = hsum;
@@ -306,9 +307,9 @@ __global__ void __launch_bounds__(256) k_state(StateArgs a) {
   __syncthreads();
   if (threadIdx.x == 0) {
     double x = 0.0, y = 0.0;
-    for (int i = 0; i < 8; ++i) { x += (double)scal[0][i]; y += (double)scal[1][i]; }
-    a.red[2 * blockIdx.x + 0] = (float)x;
-    a.red[2 * blockIdx.x + 1] = (float)y;
+    for (int i = 0; i < 8; ++i) { x += scal[0][i]; y += scal[1][i]; }
+    a.red[2 * blockIdx.x + 0] = x;
+    a.red[2 * blockIdx.x + 1] = y;
   }
 }
 
@@ -324,7 +325,7 @@ StateArgs make_state_args(const StepCtx& c) {
   a.M = (float)(L.B - 1); a.gamma = c.cfg.gamma; a.eps = c.cfg.eps; a.rho = c.cfg.rho;
   a.tau_scale = c.cfg.tau_grad_scale; a.version = c.cfg.version;
   a.c1 = (float*)(c.ws + L.c1); a.c2 = (float*)(c.ws + L.c2); a.dcoef = (float*)(c.ws + L.dcoef);
-  a.red = (float*)(c.ws + L.red);
+  a.red = (double*)(c.ws + L.red);
   a.d_tau_img = c.buf.d_tau_img; a.d_tau_txt = c.buf.d_tau_txt; a.g_img = c.buf.g_img; a.g_txt = c.buf.g_txt;
   a.u_new_img = c.buf.u_new_img; a.u_new_txt = c.buf.u_new_txt;
   a.tau_upd = c.tau_upd;
@@ -335,7 +336,8 @@ StateArgs make_state_args(const StepCtx& c) {
 }
 
 void launch_state(const StepCtx& c) {
-  hipLaunchKernelGGL(k_state, dim3((unsigned)c.L.nstate_blocks), dim3(256), 0, c.s, make_state_args(c));
+  auto* kernel = c.L.bf16 ? k_state<false> : k_state<true>;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)c.L.nstate_blocks), dim3(256), 0, c.s, make_state_args(c));
 }
 
 // Eq. 1 alone, one thread per anchor (the same update as in k_state).
@@ -364,11 +366,11 @@ void launch_state_flat(const int64_t* idx, int64_t n, int64_t stride, float gamm
 
 // ------------------------------------------------------------------------------------------
 // Scalars (called by one whole wavefront): loss of the local batch with g replaced by u^{t+1}; Eq. 8 (V0), Eq. 10 (V3).
-__device__ void write_scalars(const float* red, int nblocks, int64_t b, int version, const float* tau, float rho,
+__device__ void write_scalars(const double* red, int nblocks, int64_t b, int version, const float* tau, float rho,
                               float* loss, float* d_tau) {
   const int lane = threadIdx.x & 63;
   double A = 0.0, H = 0.0;
-  for (int i = lane; i < nblocks; i += 64) { A += (double)red[2 * i]; H += (double)red[2 * i + 1]; }
+  for (int i = lane; i < nblocks; i += 64) { A += red[2 * i]; H += red[2 * i + 1]; }
   A = wave_sum(A) / (double)b;
   H = wave_sum(H) / (double)b;
   if (lane != 0) return;
@@ -390,7 +392,7 @@ __global__ void __launch_bounds__(256) k_grad_f32(const float* __restrict__ img,
                                                   int64_t d, const float* __restrict__ E1, const float* __restrict__ E2,
                                                   int64_t ldE, const float* __restrict__ c1, const float* __restrict__ c2,
                                                   const float* __restrict__ dcoef, float* __restrict__ d_img,
-                                                  float* __restrict__ d_txt, const float* __restrict__ red, int nblocks,
+                                                  float* __restrict__ d_txt, const double* __restrict__ red, int nblocks,
                                                   int version, const float* __restrict__ tau, float rho,
                                                   float* __restrict__ loss, float* __restrict__ d_tau,
                                                   const float* __restrict__ F1, const float* __restrict__ F2,
@@ -457,7 +459,7 @@ void launch_grad_f32(const StepCtx& c) {
   hipLaunchKernelGGL(k_grad_f32, grid, block, 0, c.s, (const float*)c.buf.img_glob, (const float*)c.buf.txt_glob,
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.B, L.d, (const float*)(c.ws + L.E[0]),
                      (const float*)(c.ws + L.E[1]), L.ldE, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
-                     (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
+                     (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const double*)(c.ws + L.red),
                      L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau,
                      L.gathered ? (const float*)(c.ws + L.F[0]) : nullptr,
                      L.gathered ? (const float*)(c.ws + L.F[1]) : nullptr, c.buf.norm_img, c.buf.norm_txt);
@@ -479,7 +481,7 @@ __global__ void __launch_bounds__(256) k_finalize_bf16(const bf16_t* __restrict_
                                                        int nsplit, const float* __restrict__ c1,
                                                        const float* __restrict__ c2, const float* __restrict__ dcoef,
                                                        float* __restrict__ d_img, float* __restrict__ d_txt,
-                                                       const float* __restrict__ red, int nblocks, int version,
+                                                       const double* __restrict__ red, int nblocks, int version,
                                                        const float* __restrict__ tau, float rho, float* __restrict__ loss,
                                                        float* __restrict__ d_tau) {
   __shared__ float4 meet[SHARE_SPLITS ? 3 : 1][4][64];     // [wave - 1][column of the thread][lane]
@@ -583,7 +585,7 @@ void launch_finalize_bf16(const StepCtx& c) {
   hipLaunchKernelGGL(kernel, grid, block, 0, c.s, (const bf16_t*)c.buf.img_glob, (const bf16_t*)c.buf.txt_glob,
                      c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, (const float*)(c.ws + L.Opart[0]),
                      (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
-                     (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const float*)(c.ws + L.red),
+                     (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const double*)(c.ws + L.red),
                      L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau);
   if (c.buf.norm_img)
     hipLaunchKernelGGL(k_norm_backward_bf16, dim3((unsigned)L.b, 2), block, 0, c.s, (const bf16_t*)c.buf.img_glob,

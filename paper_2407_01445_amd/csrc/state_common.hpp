@@ -45,7 +45,8 @@ struct StateArgs {
   int64_t stride;      // elements between consecutive samples in u_img / u_txt (and the temperature arrays)
   float M, gamma, eps, rho, tau_scale;
   int version;
-  float *c1, *c2, *dcoef, *red;
+  float *c1, *c2, *dcoef;
+  double* red;        // [blocks][2]: per-block sums of the anchors' loss terms and h terms
   float *d_tau_img, *d_tau_txt, *g_img, *g_txt, *u_new_img, *u_new_txt;
   // V2 with the temperature update in the same pass (optimizer != 0): the temperatures and their moments at idx
   TauUpd tau_upd;
@@ -75,36 +76,59 @@ __device__ inline float anchor_coefficient(const StateArgs& a, float sum_e, floa
 
 // Everything the state phase does for local anchor r once its four sums s = (sum e1, sum x1 e1, sum e2, sum x2 e2)
 // are known: scatter of u^{t+1}, coefficients, Eq. 9 (and the temperature step if asked for), optional outputs.
-// Returns the anchor's terms of the loss and of the h sums of Eqs. 8 / 10.
+// Returns the anchor's terms of the loss and of the h sums of Eqs. 8 / 10, as doubles: the scalars are sums of terms
+// of both signs and are accumulated in fp64 on every path.  PRECISE (fp32-storage accuracy path): the logarithms, the
+// h terms and Eq. 9 are evaluated in fp64 as well, so that the only fp32 roundings behind the scalars are those of the
+// stored sums and of u^{t+1} itself; the MFMA path keeps them in fp32.
+template <bool PRECISE>
 __device__ inline void state_finish_anchor(const StateArgs& a, int64_t r, const float (&s)[4], float uo1, float uo2,
-                                           float t1, float t2, float* c1_out, float* c2_out, float* lsum, float* hsum) {
+                                           float t1, float t2, float* c1_out, float* c2_out, double* lsum,
+                                           double* hsum) {
   const float invM = 1.0f / a.M;
-  const float g1 = s[0] * invM, h1 = s[1] * invM, g2 = s[2] * invM, h2 = s[3] * invM;
+  const float g1 = s[0] * invM, g2 = s[2] * invM;
   const int64_t n = a.idx[r] * a.stride;
   float u1, u2;
   const float c1 = anchor_coefficient(a, s[0], uo1, t1, &u1);
   const float c2 = anchor_coefficient(a, s[2], uo2, t2, &u2);
   a.u_img[n] = u1;
   a.u_txt[n] = u2;
-  const float e1 = a.eps + u1, e2 = a.eps + u2;
   a.c1[r] = c1;
   a.c2[r] = c2;
   a.dcoef[r] = c1 * s[0] + c2 * s[2];          // c1 M g1 + c2 M g2
-  const float l1 = logf(e1), l2 = logf(e2);
+  float gt1, gt2;
+  if (PRECISE) {
+    const double e1 = (double)a.eps + (double)u1, e2 = (double)a.eps + (double)u2;
+    const double h1 = (double)s[1] / (double)a.M, h2 = (double)s[3] / (double)a.M;
+    const double l1 = log(e1), l2 = log(e2);
+    if (a.version == FASTCLIP_V2) {
+      gt1 = (float)((double)a.tau_scale * (l1 + (double)a.rho - h1 / ((double)t1 * e1)));
+      gt2 = (float)((double)a.tau_scale * (l2 + (double)a.rho - h2 / ((double)t2 * e2)));
+      *lsum = (double)t1 * (l1 + (double)a.rho) + (double)t2 * (l2 + (double)a.rho);
+    } else {
+      *lsum = l1 + l2;
+    }
+    *hsum = h1 / e1 + h2 / e2;
+  } else {
+    const float e1 = a.eps + u1, e2 = a.eps + u2;
+    const float h1 = s[1] * invM, h2 = s[3] * invM;
+    const float l1 = logf(e1), l2 = logf(e2);
+    if (a.version == FASTCLIP_V2) {
+      gt1 = a.tau_scale * (l1 + a.rho - h1 / (t1 * e1));
+      gt2 = a.tau_scale * (l2 + a.rho - h2 / (t2 * e2));
+      *lsum = (double)(t1 * (l1 + a.rho)) + (double)(t2 * (l2 + a.rho));
+    } else {
+      *lsum = (double)l1 + (double)l2;
+    }
+    *hsum = (double)(h1 / e1) + (double)(h2 / e2);
+  }
   if (a.version == FASTCLIP_V2) {
-    const float gt1 = a.tau_scale * (l1 + a.rho - h1 / (t1 * e1));
-    const float gt2 = a.tau_scale * (l2 + a.rho - h2 / (t2 * e2));
     a.d_tau_img[r] = gt1;
     a.d_tau_txt[r] = gt2;
-    *lsum = t1 * (l1 + a.rho) + t2 * (l2 + a.rho);
     if (a.tau_upd.optimizer) {   // Proc. "temperature_update" for sample n, same gather/scatter as u
       tau_step(a.tau_upd, a.tau_img + n, a.m_img + n, a.v_img ? a.v_img + n : nullptr, gt1);
       tau_step(a.tau_upd, a.tau_txt + n, a.m_txt + n, a.v_txt ? a.v_txt + n : nullptr, gt2);
     }
-  } else {
-    *lsum = l1 + l2;
   }
-  *hsum = h1 / e1 + h2 / e2;
   if (a.g_img) a.g_img[r] = g1;
   if (a.g_txt) a.g_txt[r] = g2;
   if (a.u_new_img) a.u_new_img[r] = u1;

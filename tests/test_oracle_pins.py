@@ -635,3 +635,67 @@ def test_oracle_digest_on_the_small_workload_is_unchanged():
     assert list(now) == list(stored)
     for k, v in now.items():
         assert v == pytest.approx(stored[k], rel=1e-11, abs=1e-13), k
+
+
+# ------------------------------------------------------------------------------- conditioning scales, row normalisation
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_scalar_scales_bound_the_scalars_and_equal_them_where_nothing_cancels(version):
+    """loss_abs / d_tau_abs are the scalars with every term replaced by its magnitude: never below |scalar|, and equal
+    to it when all terms share a sign (u < 1 - eps makes every logarithm negative; rho = 0 removes the positive
+    terms)."""
+    img, txt = rand_problem(5, 12, 6)
+    N, b = 40, 12
+    idx = np.arange(b) * 3
+    t = np.full(N, 0.3)
+    out = fcco_step(img, txt, 0, b, idx, np.zeros(N), np.zeros(N), version=version, gamma=1.0, eps=1e-9, rho=6.5,
+                    tau=0.3, tau_img=t, tau_txt=t)
+    assert out["loss_abs"] >= abs(out["loss"])
+    if version in (V0, V3):
+        assert out["d_tau_abs"] >= abs(out["d_tau"])
+    # a tiny temperature on orthogonal-ish rows: every l is far below 1, so u = g < 1 and all logarithms are negative
+    out = fcco_step(img, txt, 0, b, idx, np.zeros(N), np.zeros(N), version=version, gamma=1.0, eps=1e-9, rho=0.0,
+                    tau=0.05, tau_img=np.full(N, 0.05), tau_txt=np.full(N, 0.05))
+    if (out["u_new_img"] < 1).all() and (out["u_new_txt"] < 1).all():
+        assert out["loss_abs"] == pytest.approx(abs(out["loss"]), rel=1e-14)
+
+
+def test_normalize_rows():
+    from oracle import normalize_rows
+    unit, norm = normalize_rows(np.array([[3.0, 4.0, 0.0], [0.0, -2.0, 0.0], [1.0, 1.0, 1.0]]))
+    np.testing.assert_allclose(norm, [5.0, 2.0, np.sqrt(3.0)], rtol=1e-15)
+    np.testing.assert_allclose(unit[0], [0.6, 0.8, 0.0], rtol=1e-15)
+    np.testing.assert_allclose(unit[1], [0.0, -1.0, 0.0], rtol=1e-15)
+    rng = np.random.default_rng(3)
+    raw = rng.standard_normal((7, 33)) * rng.uniform(0.01, 50.0, (7, 1))
+    unit, norm = normalize_rows(raw)
+    np.testing.assert_allclose((unit * unit).sum(axis=1), 1.0, rtol=1e-14)
+    np.testing.assert_allclose(unit * norm[:, None], raw, rtol=1e-14)
+    unit2, norm2 = normalize_rows(-3.0 * raw)                  # direction flips, length scales
+    np.testing.assert_allclose(unit2, -unit, rtol=1e-14)
+    np.testing.assert_allclose(norm2, 3.0 * norm, rtol=1e-14)
+
+
+@pytest.mark.parametrize("version", [V0, V2, V3])
+def test_without_contrast_side_only_each_anchors_own_term_moves_its_rows(version):
+    """contrast_side=False leaves Eq. 2 / 4 / 6 alone: row p then moves only through anchor p's own term of the frozen-u
+    surrogate, (1/b) kappa_p [g1_p / (eps + u1_p) + g2_p / (eps + u2_p)], differentiated here by central differences."""
+    B, b, off, d, N, eps = 9, 4, 3, 3, 20, 1e-3
+    img, txt = rand_problem(21, B, d)
+    rng = np.random.default_rng(8)
+    idx = rng.choice(N, b, replace=False)
+    tau_img, tau_txt = rng.uniform(0.08, 0.2, N), rng.uniform(0.08, 0.2, N)
+    out = fcco_step(img, txt, off, b, idx, rng.uniform(0.2, 3.0, N), rng.uniform(0.2, 3.0, N), version=version,
+                    gamma=0.4, eps=eps, rho=7.0, tau=0.13, tau_img=tau_img, tau_txt=tau_txt, contrast_side=False)
+    full = fcco_step(img, txt, off, b, idx, np.zeros(N), np.zeros(N), version=version, gamma=1.0, eps=eps, rho=7.0,
+                     tau=0.13, tau_img=tau_img, tau_txt=tau_txt)
+    assert not np.allclose(full["d_img"], out["d_img"])
+    for r in range(b):
+        p = off + r
+
+        def own_term():
+            return direct_loss(img, txt, p, 1, version, eps, 7.0, tau=0.13, tau1=tau_img[idx[r:r + 1]],
+                               tau2=tau_txt[idx[r:r + 1]],
+                               frozen_u=(out["u_new_img"][r:r + 1], out["u_new_txt"][r:r + 1])) / b
+
+        np.testing.assert_allclose(out["d_img"][r], fd_rows(own_term, img, [p])[0], rtol=2e-6, atol=1e-9)
+        np.testing.assert_allclose(out["d_txt"][r], fd_rows(own_term, txt, [p])[0], rtol=2e-6, atol=1e-9)
