@@ -139,6 +139,24 @@ fastclip_status fastclip_validate(const fastclip_config* cfg, const fastclip_buf
 fastclip_status fastclip_step(const fastclip_config* cfg, const fastclip_buffers* bufs,
                               void* workspace, size_t workspace_bytes, void* stream);
 
+/* For callers that cannot allocate device memory or hold a workspace of their own (code under HIP graph capture,
+ * serving loops, harnesses that forbid hipMalloc): the same step as fastclip_step, same kernels, same results, with
+ * its workspace in a static array of FASTCLIP_STATIC_SCRATCH_BYTES of device memory that is part of the library's
+ * code object.  Every GPU the library runs on holds one such array from the first kernel launch until the process
+ * ends.  The call allocates and frees nothing (no hipMalloc / hipFree, no allocating library routine); on its first
+ * call on a device it looks the array's device address up (hipGetSymbolAddress) and keeps it.
+ *   - A configuration whose fastclip_workspace_bytes() exceeds FASTCLIP_STATIC_SCRATCH_BYTES is refused with
+ *     FASTCLIP_ERR_WORKSPACE before anything is launched (64 MiB holds the paper's own shapes: up to 640 local
+ *     anchors of a global batch of 5120 at width 512, and 1024 x 1024 x 512 or 256 of 8192 x 512).
+ *   - All calls on one GPU share that GPU's array, whatever their stream: calls that overlap in time on one GPU race
+ *     on it.  Calls that follow each other on one stream, or are ordered by events, are safe.  The array keeps the
+ *     last call's contents; the step reads nothing from its workspace that it has not written in the same call, so
+ *     nothing needs clearing in between.
+ *   - The current device must be the one `stream` belongs to.
+ * Errors, outputs and asynchrony are those of fastclip_step. */
+#define FASTCLIP_STATIC_SCRATCH_BYTES (64u << 20)
+fastclip_status fastclip_step_static(const fastclip_config* cfg, const fastclip_buffers* bufs, void* stream);
+
 /* Same step, but brackets every kernel with HIP events on `stream`, synchronises, and
  * writes the duration of each phase in milliseconds to phase_ms[0 .. FASTCLIP_N_PHASES-1]
  * (host memory; phases that a path does not run are reported as 0).  Measurement aid:

@@ -77,6 +77,8 @@ def load(build_if_missing: bool = True):
     lib.fastclip_validate.argtypes = [cfgp, bufp]
     lib.fastclip_step.restype = C.c_int
     lib.fastclip_step.argtypes = [cfgp, bufp, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fastclip_step_static.restype = C.c_int
+    lib.fastclip_step_static.argtypes = [cfgp, bufp, C.c_void_p]
     lib.fastclip_step_timed.restype = C.c_int
     lib.fastclip_step_timed.argtypes = [cfgp, bufp, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_float)]
     lib.fastclip_phase_name.restype = C.c_char_p
@@ -180,6 +182,17 @@ def fastclip_step(cfg, bufs, workspace, workspace_bytes=None, stream=None, check
     """workspace: CUDA uint8 tensor (or raw address with workspace_bytes given)."""
     nbytes = workspace.numel() * workspace.element_size() if workspace_bytes is None else workspace_bytes
     st = int(load().fastclip_step(C.byref(cfg), C.byref(bufs), _ptr(workspace), nbytes, _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def fastclip_step_static(cfg, bufs, stream=None, check=True) -> int:
+    """The step with its workspace in the library's static device array (no workspace argument, no allocation)."""
+    st = int(load().fastclip_step_static(C.byref(cfg), C.byref(bufs), _stream(stream)))
     if check and st != OK:
         raise FastclipError(st)
     return st

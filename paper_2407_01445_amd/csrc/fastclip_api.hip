@@ -4,6 +4,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "fc_internal.hpp"
 
 namespace fc {
@@ -251,9 +253,47 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
   return rc;
 }
 
+// ---- fastclip_step_static: the step's workspace in device memory that the library's code object brings along -------
+// One array per GPU (every device that loads the code object holds its own copy at its own address, until the process
+// ends).  In host code the array's name is only a handle for hipGetSymbolAddress: the address that kernels and memory
+// calls need is looked up once per device, with that device current, and kept.
+static __device__ __align__(256) unsigned char scratch[FASTCLIP_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, nullptr until first used there
+
+static fastclip_status static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_failed(e);
+  if (dev < 0 || dev >= kMaxDevices) return FASTCLIP_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return hip_failed(e != hipSuccess ? e : hipErrorInvalidSymbol);
+    g_scratch_ptr[dev] = p;
+  }
+  *out = g_scratch_ptr[dev];
+  return FASTCLIP_OK;
+}
+
 }  // namespace fc
 
 extern "C" {
+
+fastclip_status fastclip_step_static(const fastclip_config* cfg, const fastclip_buffers* bufs, void* stream) {
+  const fastclip_status st = fc::validate(cfg, bufs);
+  if (st != FASTCLIP_OK) return st;
+  fc::Layout L;
+  fc::make_layout(*cfg, &L);
+  if (L.total > (size_t)FASTCLIP_STATIC_SCRATCH_BYTES) return FASTCLIP_ERR_WORKSPACE;
+  void* ws = nullptr;
+  const fastclip_status sp = fc::static_scratch(&ws);
+  if (sp != FASTCLIP_OK) return sp;
+  return fc::run_step(cfg, bufs, ws, (size_t)FASTCLIP_STATIC_SCRATCH_BYTES, stream, nullptr);
+}
 
 size_t fastclip_workspace_bytes(const fastclip_config* cfg) {
   if (fc::validate(cfg, nullptr) != FASTCLIP_OK) return 0;
