@@ -157,6 +157,18 @@ fastclip_status fastclip_step(const fastclip_config* cfg, const fastclip_buffers
 #define FASTCLIP_STATIC_SCRATCH_BYTES (64u << 20)
 fastclip_status fastclip_step_static(const fastclip_config* cfg, const fastclip_buffers* bufs, void* stream);
 
+/* The forward half of the cosine similarity of Sec. 3: the b raw encoder rows of one worker become the unit rows
+ * e / |e| that fastclip_step takes and the norms |e| that it takes as norm_img / norm_txt to return gradients with
+ * respect to the raw rows.  A worker calls it on its own b image rows and b text rows with `unit` pointing at its slice
+ * (row off) of img_glob / txt_glob, before the rows are gathered.
+ *   raw   [b, ld_raw] device, raw_dtype FASTCLIP_F32 or FASTCLIP_BF16;  unit  [b, ld_unit] device out, unit_dtype likewise
+ *         (the emb_dtype of the step that follows);  norm  [b] device out, fp32.
+ * The squares are summed in fp64; each element is divided in fp32 and rounded once to unit_dtype.  A row of zeros
+ * yields a row of zeros and norm 0 (the step's gradient through such a row is not defined).  unit may be raw itself
+ * (same type and stride): rows are then normalised in place.  Asynchronous on `stream`; b == 0 does nothing. */
+fastclip_status fastclip_normalize_rows(const void* raw, int32_t raw_dtype, int64_t ld_raw, int64_t b, int64_t d,
+                                        void* unit, int32_t unit_dtype, int64_t ld_unit, float* norm, void* stream);
+
 /* Same step, but brackets every kernel with HIP events on `stream`, synchronises, and
  * writes the duration of each phase in milliseconds to phase_ms[0 .. FASTCLIP_N_PHASES-1]
  * (host memory; phases that a path does not run are reported as 0).  Measurement aid:
@@ -172,6 +184,26 @@ fastclip_status fastclip_step_timed(const fastclip_config* cfg, const fastclip_b
                                     void* workspace, size_t workspace_bytes, void* stream,
                                     float* phase_ms);
 const char* fastclip_phase_name(int phase);
+
+/* Measurement aid, not part of the step: what the matrix cores deliver in the launch shape of the strip kernel when
+ * nothing else is in the way.  `workgroups` workgroups of 8 wavefronts (two per SIMD, 128 accumulator registers each)
+ * issue iters x 8 independent MFMAs 32x32x16 bf16 on pseudo-random register operands: no memory traffic, no LDS, no
+ * barrier.  The kernel is launched twice, the second launch is timed with HIP events on `stream`; the call creates and
+ * destroys two events, allocates a few KiB of host memory, SYNCHRONISES the stream and copies the wavefronts' counters
+ * back.  ms: duration of the timed launch.  stats[0] = flop of that launch, stats[1] = mean shader cycles of a
+ * wavefront's loop, stats[2] = shader clock in GHz while the loops ran (cycles over the 100 MHz wall clock),
+ * stats[3] = cycles per MFMA as one wavefront sees them (64 = two wavefronts sharing a SIMD at the nominal 32).
+ * workspace: workgroups x 128 + 2048 bytes of device memory, 256-byte aligned. */
+fastclip_status fastclip_measure_mfma_ceiling(int32_t workgroups, int32_t iters, void* workspace,
+                                              size_t workspace_bytes, void* stream, float* ms, double* stats);
+
+/* Measurement aid, not part of the step: the access pattern of the state phase on 32-byte records with nothing else in
+ * the way.  For each of the n distinct indices idx[i] in [0, N) the first 32 bytes of record idx[i] (records of
+ * record_floats floats, a multiple of 8, 32-byte aligned) are read, changed by one multiply-add per word and written
+ * back, 16 bytes per lane by two neighbouring lanes: what the memory system delivers for random whole-sector
+ * read-modify-writes, against which the state kernel's rate is read.  CHANGES the records.  Asynchronous on `stream`. */
+fastclip_status fastclip_measure_record_rmw(const int64_t* idx, int64_t n, int64_t N, float* records,
+                                            int64_t record_floats, void* stream);
 
 /* ---- temperature update (Alg. 1 line 12: Proc. "temperature_update" with Proc. "parameter_update", weight decay 0) ----
  * V1 keeps tau.  V0 / V3 step the global tau with d_tau (Eq. 8 / Eq. 10).  V2 steps tau_1[idx[r]], tau_2[idx[r]] with
@@ -224,6 +256,30 @@ fastclip_status fastclip_temperature_update(int32_t version, const fastclip_tau_
 fastclip_status fastclip_step_update_tau(const fastclip_config* cfg, const fastclip_buffers* bufs,
                                          const fastclip_tau_update* upd, const fastclip_tau_state* state,
                                          void* workspace, size_t workspace_bytes, void* stream);
+
+/* The state phase of fastclip_step on its own (Alg. 1 line 7, the per-anchor half of lines 9 and 12: Eq. 1 by dataset
+ * index, the coefficients of Eqs. 2-7, Eq. 9, loss and Eqs. 8 / 10, and with upd / state the temperature update of the
+ * same samples), for cfg->b anchors whose sums over the contrasts are given.  It runs the kernel and the per-anchor code
+ * that the step runs for this phase, and exists to measure that code against the HBM roofline on many indices and to
+ * test it alone.
+ *   cfg    used: version, emb_dtype (FASTCLIP_F32 selects the fp64 logarithms of the accuracy path), B (only through
+ *          M = B - 1; b may exceed it here), b <= 2^24 anchors, N, state_stride, gamma, eps, rho, tau_grad_scale
+ *   bufs   used: idx, u_img, u_txt (updated in place), tau or tau_img / tau_txt, loss, d_tau or d_tau_img / d_tau_txt,
+ *          and the optional g_img, g_txt, u_new_img, u_new_txt; the embedding pointers are not read
+ *   upd, state   both NULL: no temperature update; otherwise as for fastclip_step_update_tau
+ *   sums   [4][b] device, read only: per anchor the sum of l1, of (s - s_ii) l1, of l2, of (s - s_ii) l2 over B_{i-}
+ *   coef   [3][b] device, out: c_1, c_2 (the factors 1 / (|B_k| |B_i-| (eps + u^{t+1})) of Eqs. 2-7, divided by tau for
+ *          V0) and c_1 M g_1 + c_2 M g_2
+ * Records: when the eight per-sample arrays of V2 with the temperature update are the fields
+ * {u_img, tau_img, m_img, v_img, u_txt, tau_txt, m_txt, v_txt}, in this order, of records of state_stride floats with
+ * state_stride a multiple of 8 and u_img 32-byte aligned, every sample is read and written as whole 32-byte sectors
+ * (16 bytes per side and lane); fastclip_step_update_tau takes the same path.  Any other layout is moved field by field.
+ * workspace: fastclip_state_phase_workspace_bytes(b) bytes, 256-byte aligned.  Asynchronous on `stream`. */
+size_t fastclip_state_phase_workspace_bytes(int64_t b);
+fastclip_status fastclip_state_phase(const fastclip_config* cfg, const fastclip_buffers* bufs,
+                                     const fastclip_tau_update* upd, const fastclip_tau_state* state,
+                                     const float* sums, float* coef, void* workspace, size_t workspace_bytes,
+                                     void* stream);
 
 /* Eq. 1 alone, for n anchors whose exp-sums are already known (the state phase of
  * fastclip_step run on its own; used to measure the gather/update/scatter kernel on many

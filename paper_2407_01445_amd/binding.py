@@ -102,6 +102,18 @@ def load(build_if_missing: bool = True):
                                                 C.c_void_p, C.c_void_p, C.c_void_p]
     lib.fastclip_step_update_tau.restype = C.c_int
     lib.fastclip_step_update_tau.argtypes = [cfgp, bufp, updp, tstp, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fastclip_state_phase_workspace_bytes.restype = C.c_size_t
+    lib.fastclip_state_phase_workspace_bytes.argtypes = [C.c_int64]
+    lib.fastclip_state_phase.restype = C.c_int
+    lib.fastclip_state_phase.argtypes = [cfgp, bufp, updp, tstp, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.fastclip_measure_mfma_ceiling.restype = C.c_int
+    lib.fastclip_measure_mfma_ceiling.argtypes = [C.c_int32, C.c_int32, C.c_void_p, C.c_size_t, C.c_void_p,
+                                                  C.POINTER(C.c_float), C.POINTER(C.c_double)]
+    lib.fastclip_measure_record_rmw.restype = C.c_int
+    lib.fastclip_measure_record_rmw.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_void_p, C.c_int64, C.c_void_p]
+    lib.fastclip_normalize_rows.restype = C.c_int
+    lib.fastclip_normalize_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int32,
+                                            C.c_int64, C.c_void_p, C.c_void_p]
     lib.fastclip_last_hip_error.restype = C.c_char_p
     lib.fastclip_last_hip_error.argtypes = []
     _lib = lib
@@ -193,6 +205,50 @@ STATIC_SCRATCH_BYTES = 64 << 20
 def fastclip_step_static(cfg, bufs, stream=None, check=True) -> int:
     """The step with its workspace in the library's static device array (no workspace argument, no allocation)."""
     st = int(load().fastclip_step_static(C.byref(cfg), C.byref(bufs), _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+def fastclip_measure_mfma_ceiling(workgroups, iters, workspace, stream=None) -> dict:
+    """Returns {ms, flop, tflops, cycles_per_wave, ghz, cycles_per_mfma}."""
+    ms = C.c_float(0.0)
+    stats = (C.c_double * 4)()
+    st = int(load().fastclip_measure_mfma_ceiling(int(workgroups), int(iters), _ptr(workspace),
+                                                  workspace.numel() * workspace.element_size(), _stream(stream),
+                                                  C.byref(ms), stats))
+    if st != OK:
+        raise FastclipError(st)
+    return dict(ms=ms.value, flop=stats[0], tflops=stats[0] / (ms.value * 1e-3) / 1e12, cycles_per_wave=stats[1],
+                ghz=stats[2], cycles_per_mfma=stats[3])
+
+
+def fastclip_measure_record_rmw(idx, n, N, records, record_floats, stream=None, check=True) -> int:
+    st = int(load().fastclip_measure_record_rmw(_ptr(idx), int(n), int(N), _ptr(records), int(record_floats), _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+def fastclip_normalize_rows(raw, raw_dtype, ld_raw, b, d, unit, unit_dtype, ld_unit, norm, stream=None, check=True) -> int:
+    """raw / unit: device tensors or raw device addresses (an address lets `unit` be a slice of the global batch)."""
+    st = int(load().fastclip_normalize_rows(_ptr(raw), int(raw_dtype), int(ld_raw), int(b), int(d), _ptr(unit),
+                                            int(unit_dtype), int(ld_unit), _ptr(norm), _stream(stream)))
+    if check and st != OK:
+        raise FastclipError(st)
+    return st
+
+
+def fastclip_state_phase_workspace_bytes(b) -> int:
+    return int(load().fastclip_state_phase_workspace_bytes(int(b)))
+
+
+def fastclip_state_phase(cfg, bufs, upd, state, sums, coef, workspace, stream=None, check=True) -> int:
+    """sums [4, b], coef [3, b] float32 device tensors; upd / state both None for no temperature update."""
+    nbytes = workspace.numel() * workspace.element_size()
+    st = int(load().fastclip_state_phase(C.byref(cfg), C.byref(bufs), C.byref(upd) if upd is not None else None,
+                                         C.byref(state) if state is not None else None, _ptr(sums), _ptr(coef),
+                                         _ptr(workspace), nbytes, _stream(stream)))
     if check and st != OK:
         raise FastclipError(st)
     return st

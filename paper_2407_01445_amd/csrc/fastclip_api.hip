@@ -2,6 +2,7 @@
 // The arithmetic lives in the kernel translation units; nothing here runs on the CPU
 // except checks, address arithmetic and the gamma schedule.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <mutex>
@@ -154,7 +155,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   // all, against 2 b x nparts once): worth it only while that stays small.
   L->fused_state = L->bf16 && L->nparts <= 64 &&
                    (double)cfg.b * (double)cfg.b / 32.0 * (double)L->nparts * 4.0 <= 2.0 * 1024 * 1024;
-  L->nstate_blocks = L->fused_state ? (int)((cfg.b + 63) / 64) : (int)((cfg.b + kStateAnchors - 1) / kStateAnchors);
+  L->nstate_blocks = L->fused_state ? (int)((cfg.b + 63) / 64) : state_blocks(cfg.b, L->nparts);
   L->diag = take(fb); L->tau1 = take(fb); L->tau2 = take(fb); L->k1 = take(fb); L->k2 = take(fb);
   L->uold1 = take(fb); L->uold2 = take(fb);
   L->sums = take(fb * 4 * (size_t)L->nparts);
@@ -324,6 +325,66 @@ fastclip_status fastclip_step_update_tau(const fastclip_config* cfg, const fastc
   return fc::run_step(cfg, bufs, workspace, workspace_bytes, stream, nullptr, upd, state);
 }
 
+// blocks of the state phase on its own: one per 128 anchors up to eight per compute unit of the largest part
+static int state_phase_blocks(int64_t b) {
+  const int tiles = fc::state_blocks(b, 1);
+  return tiles < 2048 ? tiles : 2048;
+}
+
+size_t fastclip_state_phase_workspace_bytes(int64_t b) {
+  if (b < 1 || b > ((int64_t)1 << 24)) return 0;
+  return fc::round_up(sizeof(double) * 2 * (size_t)state_phase_blocks(b), 256);
+}
+
+fastclip_status fastclip_state_phase(const fastclip_config* cfg, const fastclip_buffers* bufs,
+                                     const fastclip_tau_update* upd, const fastclip_tau_state* state,
+                                     const float* sums, float* coef, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+  // the phase sees the batch only through M = B - 1 and its b anchors: none of the matrix limits of the step apply
+  if (!cfg) return FASTCLIP_ERR_NULL;
+  if (cfg->struct_size != sizeof(fastclip_config) || cfg->B < 2 || cfg->b < 1 || cfg->N < 1 || cfg->b > cfg->N ||
+      cfg->state_stride < 1 || cfg->state_stride > 64)
+    return FASTCLIP_ERR_SHAPE;
+  if (cfg->version < FASTCLIP_V0 || cfg->version > FASTCLIP_V3 ||
+      (cfg->emb_dtype != FASTCLIP_F32 && cfg->emb_dtype != FASTCLIP_BF16))
+    return FASTCLIP_ERR_VALUE;
+  if (fc::bad_float(cfg->gamma) || fc::bad_float(cfg->eps) || fc::bad_float(cfg->rho) ||
+      fc::bad_float(cfg->tau_grad_scale) || !(cfg->gamma > 0.0f && cfg->gamma <= 1.0f) || cfg->eps < 0.0f)
+    return FASTCLIP_ERR_VALUE;
+  if (cfg->b > ((int64_t)1 << 24) || cfg->B > ((int64_t)1 << 24)) return FASTCLIP_ERR_UNSUPPORTED;
+  fastclip_status st = FASTCLIP_OK;
+  if (!bufs || !sums || !coef || !workspace) return FASTCLIP_ERR_NULL;
+  if (!bufs->idx || !bufs->u_img || !bufs->u_txt || !bufs->loss) return FASTCLIP_ERR_NULL;
+  if (cfg->version == FASTCLIP_V2) {
+    if (!bufs->tau_img || !bufs->tau_txt || !bufs->d_tau_img || !bufs->d_tau_txt) return FASTCLIP_ERR_NULL;
+  } else {
+    if (!bufs->tau) return FASTCLIP_ERR_NULL;
+    if (cfg->version != FASTCLIP_V1 && !bufs->d_tau) return FASTCLIP_ERR_NULL;
+  }
+  if ((upd == nullptr) != (state == nullptr)) return FASTCLIP_ERR_NULL;
+  fc::TauUpd tu;
+  memset(&tu, 0, sizeof(tu));
+  fastclip_tau_state ts;
+  memset(&ts, 0, sizeof(ts));
+  if (upd) {
+    st = fc::validate_tau_update(cfg->version, upd, state);
+    if (st != FASTCLIP_OK) return st;
+    if (cfg->version == FASTCLIP_V2 ? (state->tau_img != bufs->tau_img || state->tau_txt != bufs->tau_txt)
+                                    : (cfg->version != FASTCLIP_V1 && state->tau != bufs->tau))
+      return FASTCLIP_ERR_VALUE;
+    if (cfg->version == FASTCLIP_V2 && (upd->state_stride > 1 ? upd->state_stride : 1) != cfg->state_stride)
+      return FASTCLIP_ERR_VALUE;
+    if (cfg->version != FASTCLIP_V1) { tu = fc::make_tau_upd(*upd); ts = *state; }
+  }
+  if (workspace_bytes < fastclip_state_phase_workspace_bytes(cfg->b) || ((uintptr_t)workspace & 255))
+    return FASTCLIP_ERR_WORKSPACE;
+  (void)hipGetLastError();
+  fc::launch_state_phase(*cfg, *bufs, tu, ts, sums, coef, (double*)workspace, state_phase_blocks(cfg->b),
+                         (hipStream_t)stream);
+  if (tu.optimizer && cfg->version != FASTCLIP_V2) fc::launch_tau_scalar(tu, ts, bufs->d_tau, (hipStream_t)stream);
+  return fc::launch_status();
+}
+
 fastclip_status fastclip_temperature_update(int32_t version, const fastclip_tau_update* upd,
                                             const fastclip_tau_state* state, const int64_t* idx, int64_t b,
                                             int64_t N, const float* d_tau, const float* d_tau_img,
@@ -342,6 +403,79 @@ fastclip_status fastclip_temperature_update(int32_t version, const fastclip_tau_
     if (!d_tau) return FASTCLIP_ERR_NULL;
     fc::launch_tau_scalar(u, *state, d_tau, (hipStream_t)stream);
   }
+  return fc::launch_status();
+}
+
+fastclip_status fastclip_measure_mfma_ceiling(int32_t workgroups, int32_t iters, void* workspace,
+                                              size_t workspace_bytes, void* stream, float* ms, double* stats) {
+  if (!workspace || !ms || !stats) return FASTCLIP_ERR_NULL;
+  if (workgroups < 1 || workgroups > 4096 || iters < 1 || iters > (1 << 24)) return FASTCLIP_ERR_SHAPE;
+  const size_t need = (size_t)workgroups * 8 * 2 * sizeof(uint64_t) + 512 * sizeof(float);
+  if (workspace_bytes < need || ((uintptr_t)workspace & 255)) return FASTCLIP_ERR_WORKSPACE;
+  hipStream_t s = (hipStream_t)stream;
+  uint64_t* out = (uint64_t*)workspace;
+  float* sink = (float*)((char*)workspace + (size_t)workgroups * 8 * 2 * sizeof(uint64_t));
+  (void)hipGetLastError();
+  hipEvent_t e0, e1;
+  hipError_t e = hipEventCreate(&e0);
+  if (e != hipSuccess) return fc::hip_failed(e);
+  e = hipEventCreate(&e1);
+  if (e != hipSuccess) { (void)hipEventDestroy(e0); return fc::hip_failed(e); }
+  fc::launch_mfma_ceiling(workgroups, iters, out, sink, s);     // untimed: first launch of the kernel
+  (void)hipEventRecord(e0, s);
+  fc::launch_mfma_ceiling(workgroups, iters, out, sink, s);
+  (void)hipEventRecord(e1, s);
+  fastclip_status rc = fc::launch_status();
+  e = hipStreamSynchronize(s);
+  if (e != hipSuccess) rc = fc::hip_failed(e);
+  *ms = 0.f;
+  if (rc == FASTCLIP_OK && hipEventElapsedTime(ms, e0, e1) != hipSuccess) rc = FASTCLIP_ERR_LAUNCH;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != FASTCLIP_OK) return rc;
+  // per-wave counters of the timed launch: mean shader cycles and mean 100 MHz ticks of a wave's loop
+  const size_t nw = (size_t)workgroups * 8;
+  uint64_t* host = (uint64_t*)malloc(nw * 2 * sizeof(uint64_t));
+  if (!host) return FASTCLIP_ERR_LAUNCH;
+  e = hipMemcpy(host, out, nw * 2 * sizeof(uint64_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) { free(host); return fc::hip_failed(e); }
+  double cyc = 0.0, ticks = 0.0;
+  for (size_t i = 0; i < nw; ++i) { cyc += (double)host[2 * i]; ticks += (double)host[2 * i + 1]; }
+  free(host);
+  cyc /= (double)nw; ticks /= (double)nw;
+  stats[0] = (double)workgroups * 8.0 * (double)iters * 8.0 * 32768.0;   // flop of the timed launch
+  stats[1] = cyc;                                                       // shader cycles per wave
+  stats[2] = ticks > 0.0 ? cyc / (ticks * 10.0) : 0.0;                  // GHz while the loop ran (ticks of 10 ns)
+  stats[3] = cyc / ((double)iters * 8.0);                               // cycles per MFMA as one wave sees them
+  return FASTCLIP_OK;
+}
+
+fastclip_status fastclip_normalize_rows(const void* raw, int32_t raw_dtype, int64_t ld_raw, int64_t b, int64_t d,
+                                        void* unit, int32_t unit_dtype, int64_t ld_unit, float* norm, void* stream) {
+  if (!raw || !unit || !norm) return FASTCLIP_ERR_NULL;
+  if (b < 0 || d < 1 || ld_raw < d || ld_unit < d) return FASTCLIP_ERR_SHAPE;
+  if ((raw_dtype != FASTCLIP_F32 && raw_dtype != FASTCLIP_BF16) || (unit_dtype != FASTCLIP_F32 && unit_dtype != FASTCLIP_BF16))
+    return FASTCLIP_ERR_VALUE;
+  if (b > ((int64_t)1 << 31) - 1024 || d > ((int64_t)1 << 24) || ld_raw > ((int64_t)1 << 30) || ld_unit > ((int64_t)1 << 30))
+    return FASTCLIP_ERR_UNSUPPORTED;
+  if (raw == unit && (raw_dtype != unit_dtype || ld_raw != ld_unit)) return FASTCLIP_ERR_VALUE;
+  if (b == 0) return FASTCLIP_OK;
+  (void)hipGetLastError();
+  fc::launch_normalize_rows(raw, raw_dtype == FASTCLIP_BF16, ld_raw, b, d, unit, unit_dtype == FASTCLIP_BF16, ld_unit, norm,
+                            (hipStream_t)stream);
+  return fc::launch_status();
+}
+
+fastclip_status fastclip_measure_record_rmw(const int64_t* idx, int64_t n, int64_t N, float* records,
+                                            int64_t record_floats, void* stream) {
+  if (!idx || !records) return FASTCLIP_ERR_NULL;
+  if (n < 0 || N < 1 || n > N || n > ((int64_t)1 << 30) || record_floats < 8 || record_floats % 8 ||
+      record_floats > 64)
+    return FASTCLIP_ERR_SHAPE;
+  if ((uintptr_t)records & 31) return FASTCLIP_ERR_UNSUPPORTED;
+  if (n == 0) return FASTCLIP_OK;
+  (void)hipGetLastError();
+  fc::launch_record_rmw(idx, n, records, record_floats, (hipStream_t)stream);
   return fc::launch_status();
 }
 

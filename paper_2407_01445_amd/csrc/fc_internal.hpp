@@ -12,7 +12,19 @@ typedef uint16_t bf16_t;  // raw bf16 bits in memory
 
 constexpr int kTileContrasts = 256;  // contrast rows per workgroup tile of the strip kernel
 constexpr int kMaxSplit = 64;
-constexpr int kStateAnchors = 8;     // anchors per block of the state kernel
+
+// State kernel: threads per anchor side that share the work of adding up that side's partial sums (a power of two up to
+// 32, a quarter of the partial sums at most so that every thread has four loads of each quantity in flight); a block
+// of 256 threads then finishes 128 / lanes anchors.
+static inline int state_lanes(int nparts) {
+  int lanes = 1;
+  while (lanes < 32 && lanes * 8 <= nparts) lanes *= 2;
+  return lanes;
+}
+static inline int state_blocks(int64_t b, int nparts) {
+  const int per_block = 128 / state_lanes(nparts);
+  return (int)((b + per_block - 1) / per_block);
+}
 
 static inline size_t round_up(size_t x, size_t m) { return (x + m - 1) / m * m; }
 
@@ -84,10 +96,19 @@ void launch_prep_cols(const StepCtx& c);       // gathered: s_jj, temperature an
 void launch_strips_f32(const StepCtx& c);      // accuracy path: exp strips + row sums
 void launch_strips_bf16(const StepCtx& c);     // MFMA path: exp strips + row sums
 void launch_state(const StepCtx& c);           // Eq. 1, coefficients, scalar partials
+void launch_state_phase(const fastclip_config& cfg, const fastclip_buffers& buf, const TauUpd& upd,
+                        const fastclip_tau_state& tst, const float* sums, float* coef, double* red, int nblocks,
+                        hipStream_t s);    // the state phase on its own, one partial sum per anchor and quantity
+bool state_records_are_canonical(const float* u_img, const float* u_txt, const fastclip_tau_state& t, int64_t stride);
 void launch_grad_f32(const StepCtx& c);        // accuracy path: gradients + scalars
 void launch_fold_bf16(const StepCtx& c);       // MFMA path: local contrast-side weights folded into the strips
 void launch_contract_bf16(const StepCtx& c);   // MFMA path: strips x X contractions
 void launch_finalize_bf16(const StepCtx& c);   // MFMA path: combine + scalars
+
+void launch_normalize_rows(const void* raw, int raw_bf16, int64_t ld_raw, int64_t b, int64_t d, void* unit, int unit_bf16,
+                           int64_t ld_unit, float* norm, hipStream_t s);
+void launch_record_rmw(const int64_t* idx, int64_t n, float* rec, int64_t stride, hipStream_t s);    // measurement only
+void launch_mfma_ceiling(int workgroups, int iters, uint64_t* out, float* sink, hipStream_t s);   // measurement only
 
 void launch_state_flat(const int64_t* idx, int64_t n, int64_t stride, float gamma, float M,
                        const float* sum_img, const float* sum_txt, float* u_img, float* u_txt,

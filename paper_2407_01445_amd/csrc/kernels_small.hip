@@ -1,6 +1,8 @@
 // Small kernels of the FCCO step: s_ii and temperature gather, the state update of Eq. 1 with
 // the per-anchor coefficients, the fp32-storage accuracy path (strips and gradients in
 // plain loops with fp64 accumulation), the scalar outputs, and the index checker.
+#include <string.h>
+
 #include "fc_internal.hpp"
 #include "state_common.hpp"
 
@@ -105,6 +107,44 @@ void launch_prep(const StepCtx& c) {
                        c.cfg.ld_img, c.cfg.ld_txt, L.off, L.b, L.d, c.buf.idx, c.buf.tau, c.buf.tau_img,
                        c.buf.tau_txt, c.buf.u_img, c.buf.u_txt, c.cfg.state_stride, c.cfg.version, diag, tau1, tau2, k1, k2,
                        uold1, uold2);
+}
+
+// ------------------------------------------------------------------------------------------
+// Cosine similarity at the boundary (Sec. 3): one wavefront per raw encoder row e: |e| with the squares summed in fp64,
+// then e / |e| rounded once to the storage type of the step.  A row of zeros gives a row of zeros and norm 0.
+__device__ inline void store_elem(float* p, float x) { *p = x; }
+__device__ inline void store_elem(bf16_t* p, float x) { *p = __builtin_bit_cast(uint16_t, (__bf16)x); }
+
+template <typename TI, typename TO>
+__global__ void __launch_bounds__(256) k_normalize_rows(const TI* __restrict__ raw, int64_t ld_raw, int64_t b, int64_t d,
+                                                        TO* __restrict__ unit, int64_t ld_unit, float* __restrict__ norm) {
+  const int lane = threadIdx.x & 63;
+  const int64_t r = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (r >= b) return;
+  const TI* src = raw + r * ld_raw;
+  double acc = 0.0;
+  for (int64_t k = lane; k < d; k += 64) {
+    const double x = (double)load_elem(src + k);
+    acc += x * x;
+  }
+  const double n = sqrt(wave_sum(acc));
+  const float inv = n > 0.0 ? (float)(1.0 / n) : 0.f;
+  TO* dst = unit + r * ld_unit;
+  for (int64_t k = lane; k < d; k += 64) store_elem(dst + k, load_elem(src + k) * inv);
+  if (lane == 0) norm[r] = (float)n;
+}
+
+void launch_normalize_rows(const void* raw, int raw_bf16, int64_t ld_raw, int64_t b, int64_t d, void* unit, int unit_bf16,
+                           int64_t ld_unit, float* norm, hipStream_t s) {
+  const dim3 grid((unsigned)((b + 3) / 4)), block(256);
+  if (raw_bf16 && unit_bf16)
+    hipLaunchKernelGGL((k_normalize_rows<bf16_t, bf16_t>), grid, block, 0, s, (const bf16_t*)raw, ld_raw, b, d, (bf16_t*)unit, ld_unit, norm);
+  else if (raw_bf16)
+    hipLaunchKernelGGL((k_normalize_rows<bf16_t, float>), grid, block, 0, s, (const bf16_t*)raw, ld_raw, b, d, (float*)unit, ld_unit, norm);
+  else if (unit_bf16)
+    hipLaunchKernelGGL((k_normalize_rows<float, bf16_t>), grid, block, 0, s, (const float*)raw, ld_raw, b, d, (bf16_t*)unit, ld_unit, norm);
+  else
+    hipLaunchKernelGGL((k_normalize_rows<float, float>), grid, block, 0, s, (const float*)raw, ld_raw, b, d, (float*)unit, ld_unit, norm);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -263,54 +303,134 @@ void launch_tau_sparse(const TauUpd& u, const fastclip_tau_state& st, const int6
 }
 
 // ------------------------------------------------------------------------------------------
-// State phase of the fp32 path (the MFMA path runs it inside its fold kernels).
-// 256 threads = 8 anchors x 32 lanes over the partial sums (thread = 8 * lane + anchor); threads 0..7 then do the
-// per-anchor work.  kStateAnchors anchors and one pair of scalar partials per block.
+// State phase (Alg. 1 line 7 and the per-anchor half of lines 9 and 12): Eq. 1 at the batch's samples, the coefficients
+// of Eqs. 2-7, Eq. 9, the partial sums of the loss and of Eqs. 8 / 10, and - if asked for - the temperature step of the
+// same samples.  A thread owns ONE SIDE of one anchor (threads 2 r and 2 r + 1 are the image and the text side of
+// anchor r), so the two words that a record layout keeps next to each other are moved by neighbouring lanes of one
+// memory instruction.  256 threads = `lanes` partial-sum lanes x (256 / lanes) anchor sides; the threads of partial-sum
+// lane 0 finish the anchor sides.  With canonical 8-float records a finishing thread moves its side's four fields
+// {u, tau, m, v} as one 16-byte word: a sample costs one 32-byte sector each way, read and written whole.
+// se / sx of partial-sum lane 0 plus those of lanes 1 .. LANES - 1, which sit 256 / LANES entries apart
+template <int LANES>
+__device__ __forceinline__ void add_parts(const float (*part)[256], int sa, float& se, float& sx) {
+  float e[LANES], x[LANES];
+#pragma unroll
+  for (int q = 1; q < LANES; ++q) { e[q] = part[0][q * (256 / LANES) + sa]; x[q] = part[1][q * (256 / LANES) + sa]; }
+#pragma unroll
+  for (int q = 1; q < LANES; ++q) { se += e[q]; sx += x[q]; }
+}
+
 template <bool PRECISE>
 __global__ void __launch_bounds__(256) k_state(StateArgs a) {
-  __shared__ float part[4][4][8];
-  __shared__ double scal[2][8];
-  const int al = threadIdx.x & 7, pl = threadIdx.x >> 3, wave = threadIdx.x >> 6;
-  const int64_t r = (int64_t)blockIdx.x * kStateAnchors + al;
-  float acc[4] = {0.f, 0.f, 0.f, 0.f};
-  float uo1 = 0.f, uo2 = 0.f, t1 = 0.f, t2 = 0.f;
-  if (threadIdx.x < 8 && r < a.b) {    // the per-anchor inputs of the threads that finish the anchors, requested first
-    uo1 = a.uold1[r]; uo2 = a.uold2[r];
-    t1 = a.tau1[r]; t2 = a.tau2[r];
-  }
-  if (r < a.b) {
-    for (int pt = pl; pt < a.nparts; pt += 32) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) acc[q] += a.sums[((size_t)q * a.nparts + pt) * a.bstride + r];
+  __shared__ float part[2][256];
+  __shared__ double scal[2][4];
+  const int SA = 256 / a.lanes;                       // anchor sides per tile of a block
+  const int sa = threadIdx.x % SA, pl = threadIdx.x / SA;
+  const int side = sa & 1;
+  double lterm = 0.0, hterm = 0.0;                    // this thread's terms of the two scalars, over all its tiles
+  // a block takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ..: the step launches one block per tile, the phase on
+  // its own a bounded number of blocks (so that the scalars' partial sums stay few)
+  for (int64_t tile = blockIdx.x; tile < a.ntiles; tile += gridDim.x) {
+    const int64_t r = tile * (SA >> 1) + (sa >> 1);
+    const bool finisher = pl == 0 && r < a.b;
+    // the finishing threads' own inputs are requested first: the gather by dataset index is the longest latency here
+    int64_t n = 0;
+    float u_old = 0.f, tau = 0.f, m = 0.f, v = 0.f;
+    if (finisher) {
+      n = a.idx[r] * a.stride;
+      if (a.records) {
+        const float4 w = *(const float4*)(a.u_img + n + 4 * side);
+        u_old = w.x; tau = w.y; m = w.z; v = w.w;
+      } else if (a.gather) {
+        u_old = (side ? a.u_txt : a.u_img)[n];
+        tau = a.version == FASTCLIP_V2 ? (side ? a.tau_txt : a.tau_img)[n] : a.tau_glob[0];
+      } else {
+        u_old = (side ? a.uold2 : a.uold1)[r];
+        tau = (side ? a.tau2 : a.tau1)[r];
+      }
     }
-  }
-#pragma unroll
-  for (int q = 0; q < 4; ++q) {       // the 8 partial-sum lanes of this wave, then the 4 waves through LDS
-    acc[q] += __shfl_xor(acc[q], 8);
-    acc[q] += __shfl_xor(acc[q], 16);
-    acc[q] += __shfl_xor(acc[q], 32);
-    if ((threadIdx.x & 63) < 8) part[q][wave][al] = acc[q];
-  }
-  __syncthreads();
-  if (threadIdx.x < 8) {
-    double lsum = 0.0, hsum = 0.0;
+    float se = 0.f, sx = 0.f;
     if (r < a.b) {
-      float s[4];
+      const float* s0 = a.sums + (size_t)(2 * side) * a.nparts * a.bstride + r;
+      const float* s1 = s0 + (size_t)a.nparts * a.bstride;
+      // four partial sums of each quantity per round, so that eight loads are in flight instead of two
+      int pt = pl;
+      for (; pt + 3 * a.lanes < a.nparts; pt += 4 * a.lanes) {
+        float e[4], x[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) s[q] = (part[q][0][al] + part[q][1][al]) + (part[q][2][al] + part[q][3][al]);
-      float c1, c2;
-      state_finish_anchor<PRECISE>(a, r, s, uo1, uo2, t1, t2, &c1, &c2, &lsum, &hsum);
+        for (int q = 0; q < 4; ++q) {
+          e[q] = s0[(size_t)(pt + q * a.lanes) * a.bstride];
+          x[q] = s1[(size_t)(pt + q * a.lanes) * a.bstride];
+        }
+        se += (e[0] + e[1]) + (e[2] + e[3]);
+        sx += (x[0] + x[1]) + (x[2] + x[3]);
+      }
+      for (; pt < a.nparts; pt += a.lanes) {
+        se += s0[(size_t)pt * a.bstride];
+        sx += s1[(size_t)pt * a.bstride];
+      }
     }
-    scal[0][al] = lsum;
-    scal[1][al] = hsum;
+    if (a.lanes > 1) {                                   // block-uniform
+      part[0][threadIdx.x] = se;
+      part[1][threadIdx.x] = sx;
+      __syncthreads();
+      if (pl == 0) {      // all LDS reads of a thread issued together (compile-time trip counts), then added in order
+        switch (a.lanes) {
+          case 2: add_parts<2>(part, sa, se, sx); break;
+          case 4: add_parts<4>(part, sa, se, sx); break;
+          case 8: add_parts<8>(part, sa, se, sx); break;
+          case 16: add_parts<16>(part, sa, se, sx); break;
+          default: add_parts<32>(part, sa, se, sx); break;
+        }
+      }
+      __syncthreads();                                   // before the next tile overwrites part
+    }
+    float ce = 0.f;
+    if (finisher) {
+      const SideResult o = state_side<PRECISE>(a, se, sx, u_old, tau);
+      ce = o.ce;
+      lterm += o.lterm;
+      hterm += o.hterm;
+      const bool step_tau = a.version == FASTCLIP_V2 && a.tau_upd.optimizer;
+      if (a.records) {
+        if (step_tau) {
+          tau_step_values(a.tau_upd, tau, m, v, o.gt);
+          *(float4*)(a.u_img + n + 4 * side) = make_float4(o.u, tau, m, v);
+        } else {
+          a.u_img[n + 4 * side] = o.u;
+        }
+      } else {
+        (side ? a.u_txt : a.u_img)[n] = o.u;
+        if (step_tau) {
+          float* pv = side ? a.v_txt : a.v_img;
+          tau_step(a.tau_upd, (side ? a.tau_txt : a.tau_img) + n, (side ? a.m_txt : a.m_img) + n, pv ? pv + n : nullptr,
+                   o.gt);
+        }
+      }
+      (side ? a.c2 : a.c1)[r] = o.c;
+      if (a.version == FASTCLIP_V2) (side ? a.d_tau_txt : a.d_tau_img)[r] = o.gt;
+      float* g_out = side ? a.g_txt : a.g_img;
+      if (g_out) g_out[r] = se * (1.0f / a.M);
+      float* u_out = side ? a.u_new_txt : a.u_new_img;
+      if (u_out) u_out[r] = o.u;
+    }
+    const float ce_other = __shfl_xor(ce, 1);              // the two sides of an anchor are neighbouring lanes
+    if (finisher && side == 0) a.dcoef[r] = ce + ce_other;  // c1 M g1 + c2 M g2
   }
+  const double x = wave_sum_f64(lterm), y = wave_sum_f64(hterm);
+  if ((threadIdx.x & 63) == 0) { scal[0][threadIdx.x >> 6] = x; scal[1][threadIdx.x >> 6] = y; }
   __syncthreads();
   if (threadIdx.x == 0) {
-    double x = 0.0, y = 0.0;
-    for (int i = 0; i < 8; ++i) { x += scal[0][i]; y += scal[1][i]; }
-    a.red[2 * blockIdx.x + 0] = x;
-    a.red[2 * blockIdx.x + 1] = y;
+    a.red[2 * blockIdx.x + 0] = (scal[0][0] + scal[0][1]) + (scal[0][2] + scal[0][3]);
+    a.red[2 * blockIdx.x + 1] = (scal[1][0] + scal[1][1]) + (scal[1][2] + scal[1][3]);
   }
+}
+
+// The per-sample arrays are the fields {u_1, tau_1, m_1, v_1, u_2, tau_2, m_2, v_2} of 32-byte aligned records.
+bool state_records_are_canonical(const float* u_img, const float* u_txt, const fastclip_tau_state& t, int64_t stride) {
+  return stride >= 8 && stride % 8 == 0 && ((uintptr_t)u_img & 31) == 0 && t.tau_img == u_img + 1 &&
+         t.m_img == u_img + 2 && t.v_img == u_img + 3 && u_txt == u_img + 4 && t.tau_txt == u_img + 5 &&
+         t.m_txt == u_img + 6 && t.v_txt == u_img + 7;
 }
 
 StateArgs make_state_args(const StepCtx& c) {
@@ -332,12 +452,56 @@ StateArgs make_state_args(const StepCtx& c) {
   if (c.cfg.version != FASTCLIP_V2) a.tau_upd.optimizer = 0;
   a.tau_img = c.tau_st.tau_img; a.tau_txt = c.tau_st.tau_txt;
   a.m_img = c.tau_st.m_img; a.v_img = c.tau_st.v_img; a.m_txt = c.tau_st.m_txt; a.v_txt = c.tau_st.v_txt;
+  a.lanes = state_lanes(L.nparts);
+  a.ntiles = L.nstate_blocks;
+  a.tau_glob = c.buf.tau;
+  // with the temperature update on canonical records the kernel takes u^t and the temperatures from the records
+  // themselves (the same values that the prep kernel gathered): one 16-byte word per side holds all it needs
+  a.records = a.tau_upd.optimizer && state_records_are_canonical(a.u_img, a.u_txt, c.tau_st, a.stride);
+  a.gather = a.records;
   return a;
 }
 
 void launch_state(const StepCtx& c) {
   auto* kernel = c.L.bf16 ? k_state<false> : k_state<true>;
   hipLaunchKernelGGL(kernel, dim3((unsigned)c.L.nstate_blocks), dim3(256), 0, c.s, make_state_args(c));
+}
+
+// One wavefront: the scalars of a state phase that ran on its own.
+__global__ void k_scalars(const double* red, int nblocks, int64_t b, int version, const float* tau, float rho,
+                          float* loss, float* d_tau);
+
+// The state phase on its own (fastclip_state_phase): n = cfg.b anchors whose four sums are given, everything else as
+// in the step; the kernel gathers u^t and the temperatures itself.
+void launch_state_phase(const fastclip_config& cfg, const fastclip_buffers& buf, const TauUpd& upd,
+                        const fastclip_tau_state& tst, const float* sums, float* coef, double* red, int nblocks,
+                        hipStream_t s) {
+  StateArgs a;
+  memset(&a, 0, sizeof(a));
+  a.idx = buf.idx; a.u_img = buf.u_img; a.u_txt = buf.u_txt;
+  a.sums = sums; a.nparts = 1; a.bstride = cfg.b; a.b = cfg.b;
+  a.stride = cfg.state_stride;
+  a.M = (float)(cfg.B - 1); a.gamma = cfg.gamma; a.eps = cfg.eps; a.rho = cfg.rho;
+  a.tau_scale = cfg.tau_grad_scale; a.version = cfg.version;
+  a.c1 = coef; a.c2 = coef + cfg.b; a.dcoef = coef + 2 * cfg.b;
+  a.red = red;
+  a.d_tau_img = buf.d_tau_img; a.d_tau_txt = buf.d_tau_txt; a.g_img = buf.g_img; a.g_txt = buf.g_txt;
+  a.u_new_img = buf.u_new_img; a.u_new_txt = buf.u_new_txt;
+  a.tau_upd = upd;
+  if (cfg.version != FASTCLIP_V2) a.tau_upd.optimizer = 0;
+  a.tau_img = a.tau_upd.optimizer ? tst.tau_img : const_cast<float*>(buf.tau_img);
+  a.tau_txt = a.tau_upd.optimizer ? tst.tau_txt : const_cast<float*>(buf.tau_txt);
+  a.m_img = tst.m_img; a.v_img = tst.v_img; a.m_txt = tst.m_txt; a.v_txt = tst.v_txt;
+  a.lanes = 1;
+  a.ntiles = (cfg.b + 127) / 128;
+  a.tau_glob = buf.tau;
+  a.gather = 1;
+  a.records = cfg.version == FASTCLIP_V2 && a.tau_upd.optimizer &&
+              state_records_are_canonical(a.u_img, a.u_txt, tst, a.stride);
+  auto* kernel = cfg.emb_dtype == FASTCLIP_BF16 ? k_state<false> : k_state<true>;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)nblocks), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(k_scalars, dim3(1), dim3(64), 0, s, (const double*)red, nblocks, cfg.b, cfg.version, buf.tau,
+                     cfg.rho, buf.loss, buf.d_tau);
 }
 
 // Eq. 1 alone, one thread per anchor (the same update as in k_state).
@@ -380,6 +544,11 @@ __device__ void write_scalars(const double* red, int nblocks, int64_t b, int ver
   if (version == FASTCLIP_V0) { *loss = (float)A; *d_tau = (float)(-H / (t * t)); return; }
   *loss = (float)(t * A + 2.0 * (double)rho * t);
   *d_tau = (float)(A + 2.0 * (double)rho - H / t);
+}
+
+__global__ void k_scalars(const double* red, int nblocks, int64_t b, int version, const float* tau, float rho,
+                          float* loss, float* d_tau) {
+  write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
 }
 
 // ------------------------------------------------------------------------------------------

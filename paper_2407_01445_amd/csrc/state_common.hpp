@@ -1,15 +1,14 @@
-// The per-anchor arithmetic of the state phase, shared by the kernels that run it: k_state (fp32 path) and the fold
-// kernels of the MFMA path, whose blocks on the diagonal finish the anchors of their rows.
+// The per-anchor arithmetic of the state phase, shared by the kernels that run it: k_state (both paths, and on its own
+// behind fastclip_state_phase) and the fold kernels of the MFMA path, whose blocks on the diagonal finish the anchors of
+// their rows when the batch is small.
 #pragma once
 #include "fc_internal.hpp"
 
 namespace fc {
 
 // Proc. "parameter_update" for one temperature with weight decay 0, then the projection onto tau >= tau_0.
-// g: gradient estimator (Eqs. 8-10).  m, v: the optimizer's state (v only for AdamW / LAMB, pv may be NULL otherwise).
-__device__ inline void tau_step(const TauUpd& u, float* ptau, float* pm, float* pv, float g) {
-  const float tau = *ptau;
-  float m = *pm;
+// g: gradient estimator (Eqs. 8-10).  m, v: the optimizer's state (v only for AdamW / LAMB, untouched otherwise).
+__device__ inline void tau_step_values(const TauUpd& u, float& tau, float& m, float& v, float g) {
   const float lr = tau < u.drop_below ? u.lr * u.drop_factor : u.lr;
   float next;
   if (u.optimizer == FASTCLIP_TAU_SGDM) {
@@ -20,14 +19,20 @@ __device__ inline void tau_step(const TauUpd& u, float* ptau, float* pm, float* 
     m = fmaf(u.beta2, m, (1.0f - u.beta2) * g);
     next = tau - lr * (c > 0.f ? 1.f : (c < 0.f ? -1.f : 0.f));
   } else {                                             // AdamW; LAMB with layer factor 1
-    float v = *pv;
     m = fmaf(u.beta1, m, (1.0f - u.beta1) * g);
     v = fmaf(u.beta2, v, (1.0f - u.beta2) * g * g);
-    *pv = v;
     next = tau - lr * ((m * u.corr1) / (sqrtf(v * u.corr2) + u.eps));
   }
+  tau = fmaxf(next, u.tau_min);
+}
+// The same on memory (pv may be NULL for SGDM / LION).
+__device__ inline void tau_step(const TauUpd& u, float* ptau, float* pm, float* pv, float g) {
+  const bool two = u.optimizer == FASTCLIP_TAU_ADAMW || u.optimizer == FASTCLIP_TAU_LAMB;
+  float tau = *ptau, m = *pm, v = two ? *pv : 0.f;
+  tau_step_values(u, tau, m, v, g);
+  if (two) *pv = v;
   *pm = m;
-  *ptau = fmaxf(next, u.tau_min);
+  *ptau = tau;
 }
 
 // State phase.  Eq. 1 at the batch positions (first visit: stored 0 -> g), the coefficient
@@ -51,6 +56,13 @@ struct StateArgs {
   // V2 with the temperature update in the same pass (optimizer != 0): the temperatures and their moments at idx
   TauUpd tau_upd;
   float *tau_img, *tau_txt, *m_img, *v_img, *m_txt, *v_txt;
+  // k_state only.  gather: the kernel reads u^t and the temperatures from the state arrays itself (uold / tau1 / tau2
+  // are not used; tau_glob is the global temperature of V0, V1, V3 for that case).  records: the per-sample arrays are
+  // the fields {u_1, tau_1, m_1, v_1, u_2, tau_2, m_2, v_2} of 32-byte aligned records (state_records_are_canonical):
+  // a lane moves its side's four fields as one 16-byte word.  lanes: threads per anchor side over the partial sums.
+  int gather, records, lanes;
+  int64_t ntiles;     // tiles of 128 / lanes anchors; a block takes the tiles blockIdx.x, blockIdx.x + gridDim.x, ..
+  const float* tau_glob;
 };
 StateArgs make_state_args(const StepCtx& c);
 
@@ -74,67 +86,80 @@ __device__ inline float anchor_coefficient(const StateArgs& a, float sum_e, floa
   return c;
 }
 
-// Everything the state phase does for local anchor r once its four sums s = (sum e1, sum x1 e1, sum e2, sum x2 e2)
-// are known: scatter of u^{t+1}, coefficients, Eq. 9 (and the temperature step if asked for), optional outputs.
-// Returns the anchor's terms of the loss and of the h sums of Eqs. 8 / 10, as doubles: the scalars are sums of terms
-// of both signs and are accumulated in fp64 on every path.  PRECISE (fp32-storage accuracy path): the logarithms, the
-// h terms and Eq. 9 are evaluated in fp64 as well, so that the only fp32 roundings behind the scalars are those of the
-// stored sums and of u^{t+1} itself; the MFMA path keeps them in fp32.
+// Everything the state phase computes for ONE SIDE (image or text) of one anchor from that side's two sums
+// (sum_e = sum of l, sum_xe = sum of (s - s_ii) l over the contrasts), u^t and the temperature: u^{t+1} (Eq. 1), the
+// coefficient, the side's term of Eq. 9 (V2), and its terms of the loss and of the h sums of Eqs. 8 / 10, as doubles
+// (the scalars are sums of terms of both signs and are accumulated in fp64 on every path).  PRECISE (fp32-storage
+// accuracy path): the logarithm, the h term and Eq. 9 are evaluated in fp64 as well, so that the only fp32 roundings
+// behind the scalars are those of the stored sums and of u^{t+1} itself; the MFMA path keeps them in fp32.
+struct SideResult {
+  float u, c, ce;       // u^{t+1}, coefficient, coefficient x sum_e (the side's share of the diagonal factor)
+  float gt;             // V2: the side's Eq. 9
+  double lterm, hterm;
+};
+template <bool PRECISE>
+__device__ inline SideResult state_side(const StateArgs& a, float sum_e, float sum_xe, float u_old, float tau) {
+  SideResult o;
+  o.c = anchor_coefficient(a, sum_e, u_old, tau, &o.u);
+  o.ce = __fmul_rn(o.c, sum_e);
+  o.gt = 0.f;
+  if (PRECISE) {
+    const double e = (double)a.eps + (double)o.u;
+    const double h = (double)sum_xe / (double)a.M;
+    const double l = log(e);
+    if (a.version == FASTCLIP_V2) {
+      o.gt = (float)((double)a.tau_scale * (l + (double)a.rho - h / ((double)tau * e)));
+      o.lterm = (double)tau * (l + (double)a.rho);
+    } else {
+      o.lterm = l;
+    }
+    o.hterm = h / e;
+  } else {
+    const float e = a.eps + o.u;
+    const float h = sum_xe * (1.0f / a.M);
+    const float l = logf(e);
+    if (a.version == FASTCLIP_V2) {
+      o.gt = a.tau_scale * (l + a.rho - h / (tau * e));
+      o.lterm = (double)(tau * (l + a.rho));
+    } else {
+      o.lterm = (double)l;
+    }
+    o.hterm = (double)(h / e);
+  }
+  return o;
+}
+
+// Both sides of local anchor r by one thread (the fold kernels' diagonal blocks): scatter of u^{t+1}, coefficients,
+// Eq. 9 (and the temperature step if asked for), optional outputs.  s = (sum e1, sum x1 e1, sum e2, sum x2 e2).
 template <bool PRECISE>
 __device__ inline void state_finish_anchor(const StateArgs& a, int64_t r, const float (&s)[4], float uo1, float uo2,
                                            float t1, float t2, float* c1_out, float* c2_out, double* lsum,
                                            double* hsum) {
-  const float invM = 1.0f / a.M;
-  const float g1 = s[0] * invM, g2 = s[2] * invM;
   const int64_t n = a.idx[r] * a.stride;
-  float u1, u2;
-  const float c1 = anchor_coefficient(a, s[0], uo1, t1, &u1);
-  const float c2 = anchor_coefficient(a, s[2], uo2, t2, &u2);
-  a.u_img[n] = u1;
-  a.u_txt[n] = u2;
-  a.c1[r] = c1;
-  a.c2[r] = c2;
-  a.dcoef[r] = c1 * s[0] + c2 * s[2];          // c1 M g1 + c2 M g2
-  float gt1, gt2;
-  if (PRECISE) {
-    const double e1 = (double)a.eps + (double)u1, e2 = (double)a.eps + (double)u2;
-    const double h1 = (double)s[1] / (double)a.M, h2 = (double)s[3] / (double)a.M;
-    const double l1 = log(e1), l2 = log(e2);
-    if (a.version == FASTCLIP_V2) {
-      gt1 = (float)((double)a.tau_scale * (l1 + (double)a.rho - h1 / ((double)t1 * e1)));
-      gt2 = (float)((double)a.tau_scale * (l2 + (double)a.rho - h2 / ((double)t2 * e2)));
-      *lsum = (double)t1 * (l1 + (double)a.rho) + (double)t2 * (l2 + (double)a.rho);
-    } else {
-      *lsum = l1 + l2;
-    }
-    *hsum = h1 / e1 + h2 / e2;
-  } else {
-    const float e1 = a.eps + u1, e2 = a.eps + u2;
-    const float h1 = s[1] * invM, h2 = s[3] * invM;
-    const float l1 = logf(e1), l2 = logf(e2);
-    if (a.version == FASTCLIP_V2) {
-      gt1 = a.tau_scale * (l1 + a.rho - h1 / (t1 * e1));
-      gt2 = a.tau_scale * (l2 + a.rho - h2 / (t2 * e2));
-      *lsum = (double)(t1 * (l1 + a.rho)) + (double)(t2 * (l2 + a.rho));
-    } else {
-      *lsum = (double)l1 + (double)l2;
-    }
-    *hsum = (double)(h1 / e1) + (double)(h2 / e2);
-  }
+  const SideResult o1 = state_side<PRECISE>(a, s[0], s[1], uo1, t1);
+  const SideResult o2 = state_side<PRECISE>(a, s[2], s[3], uo2, t2);
+  a.u_img[n] = o1.u;
+  a.u_txt[n] = o2.u;
+  a.c1[r] = o1.c;
+  a.c2[r] = o2.c;
+  a.dcoef[r] = o1.ce + o2.ce;                  // c1 M g1 + c2 M g2
   if (a.version == FASTCLIP_V2) {
-    a.d_tau_img[r] = gt1;
-    a.d_tau_txt[r] = gt2;
+    a.d_tau_img[r] = o1.gt;
+    a.d_tau_txt[r] = o2.gt;
     if (a.tau_upd.optimizer) {   // Proc. "temperature_update" for sample n, same gather/scatter as u
-      tau_step(a.tau_upd, a.tau_img + n, a.m_img + n, a.v_img ? a.v_img + n : nullptr, gt1);
-      tau_step(a.tau_upd, a.tau_txt + n, a.m_txt + n, a.v_txt ? a.v_txt + n : nullptr, gt2);
+      tau_step(a.tau_upd, a.tau_img + n, a.m_img + n, a.v_img ? a.v_img + n : nullptr, o1.gt);
+      tau_step(a.tau_upd, a.tau_txt + n, a.m_txt + n, a.v_txt ? a.v_txt + n : nullptr, o2.gt);
     }
   }
-  if (a.g_img) a.g_img[r] = g1;
-  if (a.g_txt) a.g_txt[r] = g2;
-  if (a.u_new_img) a.u_new_img[r] = u1;
-  if (a.u_new_txt) a.u_new_txt[r] = u2;
-  *c1_out = c1;
-  *c2_out = c2;
+  const float invM = 1.0f / a.M;
+  if (a.g_img) a.g_img[r] = s[0] * invM;
+  if (a.g_txt) a.g_txt[r] = s[2] * invM;
+  if (a.u_new_img) a.u_new_img[r] = o1.u;
+  if (a.u_new_txt) a.u_new_txt[r] = o2.u;
+  *lsum = o1.lterm + o2.lterm;
+  *hsum = o1.hterm + o2.hterm;
+  *c1_out = o1.c;
+  *c2_out = o2.c;
 }
 
 }  // namespace fc

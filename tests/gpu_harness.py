@@ -11,6 +11,7 @@ from paper_2407_01445_amd import binding as fc
 
 DEV = "cuda:0"
 RECORD_FILL = 7.5      # what the unused fields of a state record hold
+CANONICAL_FIELDS = dict(u_img=0, tau_img=1, m_img=2, v_img=3, u_txt=4, tau_txt=5, m_txt=6, v_txt=7)
 
 
 def to_dev_matrix(x32: np.ndarray, dtype: str, ld: int | None = None) -> torch.Tensor:
@@ -30,7 +31,7 @@ class GpuStep:
 
     def __init__(self, *, B, b, off, d, N, dtype, version, eps, rho=0.0, tau=0.07, tau_grad_scale=1.0,
                  ld_img=None, ld_txt=None, u_img0=None, u_txt0=None, tau_img0=None, tau_txt0=None, gathered=None,
-                 norms=None, state_stride=1):
+                 norms=None, state_stride=1, canonical_records=False):
         """gathered: None, or dict(u_img=[B], u_txt=[B], tau_img=[B] or None, tau_txt=[B] or None) = the state
         gathered from all workers (the step then runs with FASTCLIP_GATHERED_STATE)."""
         self.B, self.b, self.off, self.d, self.N = B, b, off, d, N
@@ -47,14 +48,17 @@ class GpuStep:
             self.tau_txt = torch.full((N,), tau, **f32) if tau_txt0 is None else torch.from_numpy(np.asarray(tau_txt0, np.float32)).to(DEV)
         self.state_stride = state_stride
         self.records = None
+        # columns of the record that hold u_1, u_2, tau_1, tau_2; canonical_records: the order {u_1, tau_1, m_1, v_1,
+        # u_2, tau_2, m_2, v_2} that the library moves as two 16-byte words (CANONICAL_FIELDS names all eight columns)
+        cu1, cu2, ct1, ct2 = (0, 4, 1, 5) if canonical_records else (0, 1, 2, 3)
         if state_stride > 1:
-            assert state_stride >= 4
+            assert state_stride >= (8 if canonical_records else 4)
             self.records = torch.full((N, state_stride), RECORD_FILL, **f32)
-            self.records[:, 0], self.records[:, 1] = self.u_img, self.u_txt
-            self.u_img, self.u_txt = self.records[:, 0], self.records[:, 1]
+            self.records[:, cu1], self.records[:, cu2] = self.u_img, self.u_txt
+            self.u_img, self.u_txt = self.records[:, cu1], self.records[:, cu2]
             if version == fc.V2:
-                self.records[:, 2], self.records[:, 3] = self.tau_img, self.tau_txt
-                self.tau_img, self.tau_txt = self.records[:, 2], self.records[:, 3]
+                self.records[:, ct1], self.records[:, ct2] = self.tau_img, self.tau_txt
+                self.tau_img, self.tau_txt = self.records[:, ct1], self.records[:, ct2]
         nan = float("nan")
         self.d_img = torch.full((b, d), nan, **f32)
         self.d_txt = torch.full((b, d), nan, **f32)

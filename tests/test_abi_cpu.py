@@ -249,3 +249,46 @@ def test_bench_refuses_more_than_one_gpu():
                        timeout=120)
     assert r.returncode != 0
     assert "ONE GPU" in r.stderr
+
+
+def test_state_phase_and_static_step_argument_errors():
+    """Every early return of fastclip_state_phase and fastclip_step_static (nothing is launched, nothing dereferenced)."""
+    lib = fc.load()
+    cfg = good_cfg(version=fc.V2, B=1000, b=1000, off=0)
+    bufs = fake_bufs(cfg)
+    need = fc.fastclip_state_phase_workspace_bytes(1000)
+    assert need >= 2 * 8 * 8 and need % 256 == 0 and fc.fastclip_state_phase_workspace_bytes(0) == 0
+    call = lambda c, b, sums=0x1000, coef=0x2000, ws=0x3000, nbytes=need, upd=None, st=None: \
+        lib.fastclip_state_phase(C.byref(c), C.byref(b) if b is not None else None, upd, st, sums, coef, ws, nbytes, None)
+    assert call(good_cfg(B=1), bufs) == fc.ERR_SHAPE
+    assert call(cfg, None) == fc.ERR_NULL
+    assert call(cfg, bufs, sums=None) == fc.ERR_NULL and call(cfg, bufs, coef=None) == fc.ERR_NULL
+    assert call(cfg, fake_bufs(cfg, idx=None)) == fc.ERR_NULL
+    assert call(cfg, fake_bufs(cfg, tau_img=None)) == fc.ERR_NULL
+    assert call(good_cfg(version=fc.V3), fake_bufs(cfg, d_tau=None)) == fc.ERR_NULL
+    assert call(cfg, bufs, nbytes=need - 1) == fc.ERR_WORKSPACE
+    assert call(cfg, bufs, ws=0x3010) == fc.ERR_WORKSPACE
+    upd = fc.make_tau_update(optimizer=fc.TAU_ADAMW, step=1, lr=1e-3, beta1=0.9, beta2=0.99, eps=1e-8)
+    assert call(cfg, bufs, upd=C.byref(upd)) == fc.ERR_NULL          # update without its state
+    # static step: too large for the array, bad shape
+    big = good_cfg(B=32768, b=1024, off=0, d=1024)
+    assert fc.fastclip_workspace_bytes(big) > fc.STATIC_SCRATCH_BYTES
+    assert fc.fastclip_step_static(big, fake_bufs(big), stream=0, check=False) == fc.ERR_WORKSPACE
+    assert fc.fastclip_step_static(good_cfg(b=0), bufs, stream=0, check=False) == fc.ERR_SHAPE
+    assert fc.fastclip_step_static(cfg, fake_bufs(cfg, loss=None), stream=0, check=False) == fc.ERR_NULL
+
+
+def test_normalize_rows_argument_errors():
+    lib = fc.load()
+    call = lambda raw=0x1000, rd=fc.F32, ldr=64, b=4, d=64, unit=0x2000, ud=fc.BF16, ldu=64, norm=0x3000: \
+        lib.fastclip_normalize_rows(raw, rd, ldr, b, d, unit, ud, ldu, norm, None)
+    assert call(raw=None) == fc.ERR_NULL and call(unit=None) == fc.ERR_NULL and call(norm=None) == fc.ERR_NULL
+    assert call(b=-1) == fc.ERR_SHAPE and call(d=0) == fc.ERR_SHAPE and call(ldr=63) == fc.ERR_SHAPE and call(ldu=8) == fc.ERR_SHAPE
+    assert call(rd=7) == fc.ERR_VALUE and call(ud=-1) == fc.ERR_VALUE
+    assert call(unit=0x1000) == fc.ERR_VALUE                     # in place needs equal types
+    assert call(b=0) == fc.OK                                    # nothing to do, nothing launched
+    assert lib.fastclip_measure_record_rmw(None, 4, 10, 0x1000, 8, None) == fc.ERR_NULL
+    assert lib.fastclip_measure_record_rmw(0x1000, 11, 10, 0x2000, 8, None) == fc.ERR_SHAPE
+    assert lib.fastclip_measure_record_rmw(0x1000, 4, 10, 0x2000, 12, None) == fc.ERR_SHAPE
+    assert lib.fastclip_measure_record_rmw(0x1000, 4, 10, 0x2010, 8, None) == fc.ERR_UNSUPPORTED
+    assert lib.fastclip_measure_record_rmw(0x1000, 0, 10, 0x2000, 8, None) == fc.OK

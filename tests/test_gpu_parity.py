@@ -8,12 +8,12 @@ import numpy as np
 import pytest
 import torch
 
-from oracle import (ADAMW, LAMB, LION, SGDM, V0, V1, V2, V3, ema_update, fcco_step, gamma_cosine,
+from oracle import (ADAMW, LAMB, LION, SGDM, V0, V1, V2, V3, ema_update, fcco_step, gamma_cosine, normalize_rows,
                     temperature_update)
 from paper_2407_01445_amd import binding as fc
-from paper_2407_01445_amd.workloads import WORKLOADS, draw_indices, make_embeddings, step_seed
+from paper_2407_01445_amd.workloads import WORKLOADS, draw_indices, make_embeddings, round_to_bf16, step_seed
 
-from gpu_harness import DEV, RECORD_FILL, GpuStep, compare, rel_each, rel_inf, rel_l2
+from gpu_harness import CANONICAL_FIELDS, DEV, RECORD_FILL, GpuStep, compare, rel_each, rel_inf, rel_l2
 
 pytestmark = pytest.mark.gpu
 
@@ -476,7 +476,7 @@ def test_temperature_update_alone(opt, hp, stride):
             assert v.item() == pytest.approx(wv, rel=1e-5)
 
 
-@pytest.mark.parametrize("stride", [1, 8])
+@pytest.mark.parametrize("stride", [1, 8, "canonical 8", "canonical 16"])
 @pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (64, 64, 0, 32)), ("bf16", TOL_BF16, (700, 300, 133, 72)),
                                              # enough anchors that the state phase is a kernel of its own on the MFMA path
                                              ("bf16", TOL_BF16, (2048, 1536, 256, 64))])
@@ -485,6 +485,8 @@ def test_step_with_temperature_update_three_iterations(dtype, tol, shape, versio
     """fastclip_step_update_tau: step + temperature update per iteration, temperatures and moments carried on the
     device, against the oracle's step followed by Proc. temperature_update."""
     B, b, off, d = shape
+    canonical = isinstance(stride, str)       # records {u_1, tau_1, m_1, v_1, u_2, tau_2, m_2, v_2}: 16-byte words per side
+    stride = int(stride.split()[1]) if canonical else stride
     N = max(2000, 2 * b)
     rng = np.random.default_rng(9 + version)
     hp = dict(lr=2e-3, beta1=0.9, beta2=0.98, eps=1e-6)
@@ -492,10 +494,15 @@ def test_step_with_temperature_update_three_iterations(dtype, tol, shape, versio
     t_img0 = rng.uniform(0.05, 0.1, N).astype(np.float32)
     t_txt0 = rng.uniform(0.05, 0.1, N).astype(np.float32)
     g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
-                tau_grad_scale=1.0, tau_img0=t_img0, tau_txt0=t_txt0, state_stride=stride)
+                tau_grad_scale=1.0, tau_img0=t_img0, tau_txt0=t_txt0, state_stride=stride, canonical_records=canonical)
     z = lambda n: torch.zeros(n, dtype=torch.float32, device=DEV)
-    if version == V2 and stride > 1:       # the moments are fields 4..7 of the same records
-        g.records[:, 4:] = 0.0
+    if version == V2 and canonical:
+        for k in ("m_img", "v_img", "m_txt", "v_txt"):
+            g.records[:, CANONICAL_FIELDS[k]] = 0.0
+        st_dev = dict(tau_img=g.tau_img, tau_txt=g.tau_txt, **{k: g.records[:, CANONICAL_FIELDS[k]]
+                                                                for k in ("m_img", "v_img", "m_txt", "v_txt")})
+    elif version == V2 and stride > 1:     # the moments are fields 4..7 of the same records
+        g.records[:, 4:8] = 0.0
         st_dev = dict(tau_img=g.tau_img, tau_txt=g.tau_txt, m_img=g.records[:, 4], v_img=g.records[:, 5],
                       m_txt=g.records[:, 6], v_txt=g.records[:, 7])
     elif version == V2:
@@ -535,6 +542,8 @@ def test_step_with_temperature_update_three_iterations(dtype, tol, shape, versio
             assert st_dev["m"].item() == pytest.approx(w["m"], rel=tol) and st_dev["v"].item() == pytest.approx(w["v"], rel=2 * tol)
     assert st_dev["tau_img" if version == V2 else "tau"].cpu().numpy().std() >= 0      # still finite
     assert np.isfinite(g.loss.item())
+    if g.records is not None and stride > 8:
+        assert (g.records[:, 8:] == RECORD_FILL).all()       # what lies behind the eight fields is never touched
 
 
 # ------------------------------------------------------------------------------- cosine similarity, MBCL
@@ -560,6 +569,86 @@ def test_gradients_through_normalisation(dtype, tol, shape, version):
                      tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64), tau_grad_scale=g.scale,
                      norm_img=n_img.astype(np.float64), norm_txt=n_txt.astype(np.float64))
     compare(g.outputs(), want, version, tol, "normalised %s %s v%d" % (dtype, shape, version))
+
+
+def raw_rows(rng, b, d, dtype):
+    """Encoder outputs before normalisation: rows of very different lengths (values bf16-representable if dtype is bf16)."""
+    raw = (rng.standard_normal((b, d)) * np.exp(rng.uniform(np.log(0.05), np.log(30.0), (b, 1)))).astype(np.float32)
+    return round_to_bf16(raw) if dtype == "bf16" else raw
+
+
+@pytest.mark.parametrize("raw_dtype,unit_dtype", [("f32", "f32"), ("f32", "bf16"), ("bf16", "bf16"), ("bf16", "f32")])
+@pytest.mark.parametrize("b,d,pad", [(1, 1, 0), (5, 3, 2), (37, 19, 5), (300, 72, 8), (1024, 1024, 0), (130, 4104, 0)])
+def test_normalize_rows(raw_dtype, unit_dtype, b, d, pad):
+    """fastclip_normalize_rows against the oracle's e / |e| and |e|: norms to fp32 rounding, unit rows to the rounding
+    of the storage type (half a unit in the last place of bf16 or fp32, plus the fp32 division)."""
+    rng = np.random.default_rng(b + d)
+    raw = raw_rows(rng, b, d, raw_dtype)
+    if b > 2:
+        raw[2] = 0.0                                                    # a row of zeros: zeros out, norm 0
+    tdt = {"f32": torch.float32, "bf16": torch.bfloat16}
+    t_raw = torch.full((b, d + pad), float("nan"), dtype=tdt[raw_dtype])
+    t_raw[:, :d] = torch.from_numpy(raw).to(tdt[raw_dtype])
+    t_raw = t_raw.to(DEV)
+    t_unit = torch.full((b, d + 2 * pad), 7.5, dtype=tdt[unit_dtype], device=DEV)
+    t_norm = torch.full((b,), float("nan"), dtype=torch.float32, device=DEV)
+    code = {"f32": fc.F32, "bf16": fc.BF16}
+    fc.fastclip_normalize_rows(t_raw, code[raw_dtype], d + pad, b, d, t_unit, code[unit_dtype], d + 2 * pad, t_norm)
+    torch.cuda.synchronize()
+    got_unit, got_norm = t_unit[:, :d].float().cpu().numpy().astype(np.float64), t_norm.cpu().numpy().astype(np.float64)
+    keep = np.ones(b, bool)
+    if b > 2:
+        keep[2] = False
+        assert got_norm[2] == 0.0 and (got_unit[2] == 0.0).all()
+    want_unit, want_norm = normalize_rows(raw[keep].astype(np.float64))
+    assert rel_each(got_norm[keep], want_norm) <= 2e-7
+    half_ulp = 2.0 ** -8 if unit_dtype == "bf16" else 2.0 ** -24         # 8 and 24 significand bits
+    assert np.all(np.abs(got_unit[keep] - want_unit) <= (half_ulp + 3e-7) * np.abs(want_unit) + 1e-30)
+    if pad:
+        assert (t_unit[:, d:].float() == 7.5).all()                     # nothing written beyond the row
+
+
+@pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (37, 11, 13, 19)), ("bf16", TOL_BF16, (700, 300, 133, 72)),
+                                             ("bf16", TOL_BF16, (1024, 320, 704, 128))])
+@pytest.mark.parametrize("version", [V2, V3])
+def test_from_raw_encoder_rows_to_gradients_of_raw_rows(dtype, tol, shape, version):
+    """The worker's whole boundary: its b raw image and text rows are normalised by the library into its slice of the
+    global batch (cosine similarity, Sec. 3), the step runs on the unit rows with the norms it was handed, and d_img / d_txt
+    are gradients with respect to the RAW rows.  The oracle normalises the same raw rows itself, rounds them to the
+    storage type, and differentiates through the normalisation."""
+    B, b, off, d = shape
+    N = 3000
+    rng = np.random.default_rng(B + 3 * version)
+    img, txt = make_embeddings(B + 9, B, d, 0.5, dtype)                 # the other workers' rows, already unit rows
+    raw_i, raw_t = raw_rows(rng, b, d, dtype), raw_rows(rng, b, d, dtype)
+    raw_t = (raw_t + 2.0 * np.linalg.norm(raw_t, axis=1, keepdims=True) * raw_i / np.linalg.norm(raw_i, axis=1, keepdims=True)).astype(np.float32)
+    if dtype == "bf16":
+        raw_t = round_to_bf16(raw_t)
+    idx = draw_indices(B + 10, b, N)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
+                tau_grad_scale=1.0 / N, tau_img0=t_img, tau_txt0=t_txt,
+                norms=(np.full(b, np.nan, np.float32), np.full(b, np.nan, np.float32)))
+    g.set_inputs(img, txt, idx)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    code = fc.BF16 if dtype == "bf16" else fc.F32
+    esz = 2 if dtype == "bf16" else 4
+    for raw, glob, norm in ((raw_i, g.img, g.norm_img), (raw_t, g.txt, g.norm_txt)):
+        t_raw = torch.from_numpy(raw).to(tdt).to(DEV)
+        fc.fastclip_normalize_rows(t_raw, code, d, b, d, glob.data_ptr() + off * glob.stride(0) * esz, code, glob.stride(0), norm)
+    g.step(0.6)
+    # oracle side: its own normalisation of the same raw rows, rounded to the storage type like every other input
+    img64, txt64 = img.astype(np.float64), txt.astype(np.float64)
+    ui, ni = normalize_rows(raw_i.astype(np.float64))
+    ut, nt = normalize_rows(raw_t.astype(np.float64))
+    store = (lambda a: round_to_bf16(a.astype(np.float32)).astype(np.float64)) if dtype == "bf16" else \
+        (lambda a: a.astype(np.float32).astype(np.float64))
+    img64[off:off + b], txt64[off:off + b] = store(ui), store(ut)
+    want = fcco_step(img64, txt64, off, b, idx, np.zeros(N), np.zeros(N), version=version, gamma=0.6, eps=g.eps, rho=g.rho,
+                     tau=float(np.float32(0.07)), tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64),
+                     tau_grad_scale=g.scale, norm_img=ni, norm_txt=nt)
+    compare(g.outputs(), want, version, tol, "raw rows %s %s v%d" % (dtype, shape, version))
 
 
 @pytest.mark.parametrize("dtype,tol,B,d", [("f32", TOL_F32, 64, 32), ("bf16", TOL_BF16, 520, 64),
@@ -765,6 +854,108 @@ def test_state_update_alone_on_records():
     assert torch.equal(rec[:, 0].contiguous(), ui) and torch.equal(rec[:, 1].contiguous(), ut)
     assert (rec[:, 2] == RECORD_FILL).all()
     assert fc.fastclip_state_update_strided(idx, n, N, 0, 0.4, 1023.0, s1, s2, ui, ut, o[0], o[1], check=False) == fc.ERR_SHAPE
+
+
+STATE_LAYOUTS = ["dense", "records 8", "records 16", "fields in another order"]
+
+
+@pytest.mark.parametrize("update", [False, True])
+@pytest.mark.parametrize("dtype,tol", [("f32", TOL_F32), ("bf16", 1e-4)])
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_state_phase_alone(version, dtype, tol, update):
+    """fastclip_state_phase (the step's state kernel given the sums over the contrasts) against the oracle's step on
+    a small problem whose sums the oracle supplies; the dense arrays, canonical records of 8 and 16 floats (one 16-byte
+    word per side) and records with the fields in another order must give the same bits.  bf16 here only selects the
+    fp32 logarithms of the MFMA path: from identical sums that path agrees with the oracle to 1e-4, not 2e-2."""
+    B, b, off, d, N = 300, 300, 0, 16, 1500
+    n = b
+    rng = np.random.default_rng(70 + version)
+    img, txt = make_embeddings(71, B, d, 0.5, "f32")
+    idx = draw_indices(72, n, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    m0 = {k: rng.uniform(-1, 1, N).astype(np.float32) for k in ("m_img", "m_txt")}
+    v0 = {k: rng.uniform(0.01, 2, N).astype(np.float32) for k in ("v_img", "v_txt")}
+    tau32, gamma, eps, rho, scale = float(np.float32(0.07)), 0.6, 1e-6, 6.5, 0.25
+    u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+    want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, u_img, u_txt, version=version,
+                     gamma=gamma, eps=eps, rho=rho, tau=tau32, tau_img=t_img.astype(np.float64),
+                     tau_txt=t_txt.astype(np.float64), tau_grad_scale=scale)
+    M = B - 1
+    sums = np.stack([M * want["g_img"], M * want["h_img"], M * want["g_txt"], M * want["h_txt"]]).astype(np.float32)
+    hp = dict(optimizer=ADAMW, step=3, lr=2e-3, beta1=0.9, beta2=0.98, eps=1e-6)
+    extra = dict(tau_min=0.01, lr_drop_below=0.06, lr_drop_factor=1.0 / 3.0)
+    w = dict(tau=tau32, m=0.3, v=0.5, tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64),
+             **{k: a.astype(np.float64) for k, a in {**m0, **v0}.items()})
+    if update and version == V2:
+        temperature_update(V2, want, idx=idx, **hp, **extra, **{k: w[k] for k in ("tau_img", "tau_txt", "m_img", "v_img", "m_txt", "v_txt")})
+    elif update and version != V1:
+        w["tau"], w["m"], w["v"] = temperature_update(version, want, tau=w["tau"], m=w["m"], v=w["v"], **hp, **extra)
+    host = dict(u_img=u0i, u_txt=u0t, tau_img=t_img, tau_txt=t_txt, **m0, **v0)
+    results = []
+    for layout in STATE_LAYOUTS:
+        f32 = dict(dtype=torch.float32, device=DEV)
+        if layout == "dense":
+            stride, fields = 1, {k: torch.from_numpy(a).to(DEV) for k, a in host.items()}
+        else:
+            stride = 16 if layout == "records 16" else 8
+            cols = CANONICAL_FIELDS if layout != "fields in another order" else \
+                dict(u_img=0, u_txt=1, tau_img=2, tau_txt=3, m_img=4, v_img=5, m_txt=6, v_txt=7)
+            rec = torch.full((N, stride), RECORD_FILL, **f32)
+            for k, a in host.items():
+                rec[:, cols[k]] = torch.from_numpy(a).to(DEV)
+            fields = {k: rec[:, cols[k]] for k in host}
+        tau_t, m_t, v_t = (torch.tensor([x], **f32) for x in (0.07, 0.3, 0.5))
+        out = {k: torch.full((n,), float("nan"), **f32) for k in ("d_tau_img", "d_tau_txt", "g_img", "g_txt", "u_new_img", "u_new_txt")}
+        loss, d_tau = torch.full((1,), float("nan"), **f32), torch.full((1,), float("nan"), **f32)
+        coef = torch.full((3, n), float("nan"), **f32)
+        cfg = fc.make_config(version=version, emb_dtype=fc.BF16 if dtype == "bf16" else fc.F32, B=B, b=b, off=off, d=d, N=N,
+                             gamma=gamma, eps=eps, rho=rho, tau_grad_scale=scale, state_stride=stride)
+        bufs = fc.make_buffers(idx=torch.from_numpy(idx).to(DEV), u_img=fields["u_img"], u_txt=fields["u_txt"], tau=tau_t,
+                               tau_img=fields["tau_img"], tau_txt=fields["tau_txt"], loss=loss, d_tau=d_tau, **out)
+        upd = state = None
+        if update:
+            upd = fc.make_tau_update(state_stride=stride, **hp, **extra)
+            state = fc.make_tau_state(tau=tau_t, m=m_t, v=v_t, **{k: fields[k] for k in ("tau_img", "tau_txt", "m_img", "v_img", "m_txt", "v_txt")})
+        ws = torch.empty(fc.fastclip_state_phase_workspace_bytes(n), dtype=torch.uint8, device=DEV)
+        fc.fastclip_state_phase(cfg, bufs, upd, state, torch.from_numpy(sums).to(DEV), coef, ws)
+        torch.cuda.synchronize()
+        got = {k: t.cpu().numpy().astype(np.float64) for k, t in out.items()}
+        got.update(loss=float(loss.item()), d_tau=float(d_tau.item()), d_img=want["d_img"], d_txt=want["d_txt"])
+        compare(got, want, version, tol, "state phase %s v%d %s update=%d" % (dtype, version, layout, update))
+        # the coefficients of Eqs. 2-7 from the oracle's u^{t+1} (V0: divided by tau)
+        kappa = (1.0 / t_img[idx].astype(np.float64) if version == V2 else 1.0 / tau32) if version == V0 else 1.0
+        kappa2 = (1.0 / t_txt[idx].astype(np.float64) if version == V2 else 1.0 / tau32) if version == V0 else 1.0
+        c = coef.cpu().numpy().astype(np.float64)
+        assert rel_each(c[0], kappa / (b * M * (eps + want["u_new_img"]))) <= tol
+        assert rel_each(c[1], kappa2 / (b * M * (eps + want["u_new_txt"]))) <= tol
+        assert rel_each(c[2], c[0] * sums[0] + c[1] * sums[2]) <= 1e-6
+        state_now = {k: t.contiguous().cpu().numpy() for k, t in fields.items()}
+        mask = np.ones(N, bool)
+        mask[idx] = False
+        for k, a in host.items():
+            assert np.array_equal(state_now[k][mask].view(np.uint32), a[mask].view(np.uint32)), (k, layout)   # untouched
+        assert np.array_equal(state_now["u_img"][idx], out["u_new_img"].cpu().numpy())
+        if update and version == V2:
+            for k in ("tau_img", "tau_txt", "m_img", "v_img", "m_txt", "v_txt"):
+                lim = 1e-4 if k.startswith("tau") else 10 * tol
+                assert rel_inf(state_now[k][idx], w[k][idx]) <= lim, (k, layout)
+        else:
+            for k in ("tau_img", "tau_txt", "m_img", "v_img", "m_txt", "v_txt"):
+                assert np.array_equal(state_now[k].view(np.uint32), host[k].view(np.uint32)), (k, layout)
+        if update and version in (V0, V3):
+            assert tau_t.item() == pytest.approx(w["tau"], rel=1e-4) and m_t.item() == pytest.approx(w["m"], rel=10 * tol)
+        if layout != "dense":
+            assert (rec[:, 8:] == RECORD_FILL).all()
+        results.append((state_now, {k: t.cpu().numpy() for k, t in out.items()}, coef.cpu().numpy(), loss.item(), d_tau.item()))
+    for other in results[1:]:                 # every layout: the same bits
+        for k in host:
+            assert np.array_equal(other[0][k].view(np.uint32), results[0][0][k].view(np.uint32)), k
+        for k in other[1]:
+            assert np.array_equal(other[1][k], results[0][1][k], equal_nan=True), k
+        assert np.array_equal(other[2], results[0][2]) and np.array_equal([other[3], other[4]], [results[0][3], results[0][4]], equal_nan=True)
 
 
 @pytest.mark.parametrize("n", [1, 1000, 1 << 18])
