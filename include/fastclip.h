@@ -67,12 +67,18 @@ typedef enum { FASTCLIP_F32 = 0, FASTCLIP_BF16 = 1 } fastclip_dtype;
  * (u_new_img / u_new_txt) and gathering; on a single GPU holding the whole batch (b == B) the
  * flag changes nothing and the arrays are not read. */
 #define FASTCLIP_GATHERED_STATE 1
+/* FASTCLIP_FINE_TILES (opt-in, bf16 path without gathered state): batches whose 256 x 256 tiles would occupy fewer than
+ * 192 compute units run the strip phase on 128 x 128 tiles and the contraction on 64 x 64 output tiles that are finished
+ * in place (no partial results and no finalize kernel when the column range needs no split).  Results are those of the
+ * default path up to summation order.  NOT enabled by default: see the design notes (one of thirteen runs on hardware
+ * ended in a memory fault whose cause has not been found). */
+#define FASTCLIP_FINE_TILES 2
 
 typedef struct {
   uint32_t struct_size;      /* sizeof(fastclip_config) */
   int32_t  version;          /* fastclip_version_t */
   int32_t  emb_dtype;        /* fastclip_dtype */
-  int32_t  flags;            /* 0, or FASTCLIP_GATHERED_STATE; any other bit is an error */
+  int32_t  flags;            /* 0 or an OR of FASTCLIP_GATHERED_STATE, FASTCLIP_FINE_TILES; any other bit is an error */
   int64_t  B, b, off, d;     /* global rows, local anchors, first local row, embedding width */
   int64_t  ld_img, ld_txt;   /* row strides of img_glob / txt_glob in elements, >= d */
   int64_t  N;                /* samples in the state arrays */

@@ -15,6 +15,7 @@ LIB_PATH = os.path.join(_PKG, "libfastclip.so")
 OK, ERR_NULL, ERR_SHAPE, ERR_VALUE, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_LAUNCH, ERR_INDEX = range(8)
 V0, V1, V2, V3 = 0, 1, 2, 3
 GATHERED_STATE = 1
+FINE_TILES = 2
 F32, BF16 = 0, 1
 N_PHASES = 8
 

@@ -28,7 +28,8 @@ static fastclip_status hip_failed(hipError_t e) {
 
 fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
   if (!cfg) return FASTCLIP_ERR_NULL;
-  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~FASTCLIP_GATHERED_STATE)) return FASTCLIP_ERR_SHAPE;
+  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~(FASTCLIP_GATHERED_STATE | FASTCLIP_FINE_TILES)))
+    return FASTCLIP_ERR_SHAPE;
   if (cfg->B < 2 || cfg->b < 1 || cfg->off < 0 || cfg->off + cfg->b > cfg->B || cfg->d < 1 ||
       cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1 || cfg->b > cfg->N || cfg->state_stride < 1 ||
       cfg->state_stride > 64)
@@ -118,10 +119,34 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   const int64_t bt = cfg.B / kTileContrasts;
   L->square = L->bf16 && cfg.b == cfg.B && cfg.B % kTileContrasts == 0 && cfg.d % 64 == 0 && cfg.d >= 128 &&
               2 * bt * bt > 256;
+  // Fine tiles (opt-in) where 256 x 256 tiles would leave most of the chip idle: fewer large strip tiles than three
+  // quarters of the compute units (one per compute unit is what the large-tile kernels are built for).
+  const int64_t big_tiles = 2 * ((cfg.b + 255) / 256) * ((cfg.B + 255) / 256);
+  L->fine = (cfg.flags & FASTCLIP_FINE_TILES) && L->bf16 && !L->gathered && !L->square && big_tiles < 192;
   size_t at = 0;
   auto take = [&](size_t bytes) { size_t o = at; at += round_up(bytes, 256); return o; };
   const size_t fb = sizeof(float) * (size_t)L->bstride;
-  if (L->bf16) {
+  if (L->fine) {
+    L->nparts = (int)((cfg.B + 127) / 128);
+    L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
+    // Split of the contraction over its column range, in 64-deep stages.  Cost model in units of one stage time: rounds
+    // of 512 workgroups (two per compute unit) x (slice + 6 for the tile's start and end), and with more than one split
+    // the finalize kernel: 27 for its launch + 0.02 per split and output tile.  One split needs no finalize kernel.
+    const int64_t stages = L->ldE / 64;
+    const int64_t tiles = ((cfg.b + 63) / 64) * ((cfg.d + 63) / 64) * 2;
+    int64_t best = 1;
+    double best_cost = 0.0;
+    for (int64_t ns = 1; ns <= kMaxSplit && ns <= stages; ++ns) {
+      const int64_t slice = (stages + ns - 1) / ns;
+      const int64_t used = (stages + slice - 1) / slice;
+      if (used != ns) continue;                                     // every split must get at least one stage
+      const int64_t rounds = (tiles * ns + 511) / 512;
+      const double cost = (double)rounds * (double)(slice + 6) + (ns > 1 ? 27.0 + 0.02 * (double)tiles * (double)ns : 0.0);
+      if (ns == 1 || cost < best_cost) { best = ns; best_cost = cost; }
+    }
+    L->nsplit = (int)best;
+    L->kslice = (stages + best - 1) / best;
+  } else if (L->bf16) {
     L->nparts = (int)((cfg.B + kTileContrasts - 1) / kTileContrasts);
     L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
     // Split of the contraction over its column range.  A workgroup owns one 256 x 256 output tile of one side and
@@ -166,8 +191,13 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
     // fragment-ordered strips: anchors padded to whole 256-row tiles
     const size_t rows = round_up((size_t)cfg.b, 256);
     for (int s = 0; s < 2; ++s) L->E[s] = take(esz * rows * (size_t)L->ldE);
-    for (int s = 0; s < 2; ++s)
-      L->Opart[s] = take(sizeof(float) * (size_t)L->nsplit * partial_split_floats(cfg.b, cfg.d));
+    if (L->fine) {     // [nsplit][2 sides][b to 64][d to 64] floats, only with more than one split
+      if (L->nsplit > 1)
+        L->Opart[0] = take(sizeof(float) * (size_t)L->nsplit * 2 * round_up((size_t)cfg.b, 64) * round_up((size_t)cfg.d, 64));
+    } else {
+      for (int s = 0; s < 2; ++s)
+        L->Opart[s] = take(sizeof(float) * (size_t)L->nsplit * partial_split_floats(cfg.b, cfg.d));
+    }
   } else {
     for (int s = 0; s < 2; ++s) L->E[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
   }
@@ -226,12 +256,19 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
   launch_prep(c);
   if (c.L.gathered) launch_prep_cols(c);
   mark(FASTCLIP_PHASE_PREP);
-  if (c.L.bf16) {
+  if (c.L.fine) {
+    launch_strips_fine_bf16(c);           mark(FASTCLIP_PHASE_STRIPS);
+    if (!c.L.fused_state) { launch_state(c); mark(FASTCLIP_PHASE_STATE); }
+    launch_fold_bf16(c);                  mark(FASTCLIP_PHASE_LOCAL);   // with fused_state: the state phase as well
+    launch_contract_fine_bf16(c);         mark(FASTCLIP_PHASE_CONTRACT);  // outputs and scalars included
+    launch_norm_backward_bf16(c);
+  } else if (c.L.bf16) {
     launch_strips_bf16(c);                mark(FASTCLIP_PHASE_STRIPS);
     if (!c.L.fused_state) { launch_state(c); mark(FASTCLIP_PHASE_STATE); }
     launch_fold_bf16(c);                  mark(FASTCLIP_PHASE_LOCAL);   // with fused_state: the state phase as well
     launch_contract_bf16(c);              mark(FASTCLIP_PHASE_CONTRACT);
     launch_finalize_bf16(c);
+    launch_norm_backward_bf16(c);
   } else {
     launch_strips_f32(c);                 mark(FASTCLIP_PHASE_STRIPS);
     launch_state(c);                      mark(FASTCLIP_PHASE_STATE);

@@ -48,6 +48,9 @@ struct Layout {
   int nstate_blocks; // scalar partials: one per block of the state kernel, or per diagonal block of the fused fold
   int fused_state;   // 1: MFMA path, few anchors and few partial sums: the fold kernel runs the state phase itself
   int gathered;      // 1: contrast-side estimator over every global anchor (FASTCLIP_GATHERED_STATE and b < B)
+  int fine;          // 1: MFMA path on fine tiles (kernels_fine.hip): 128 x 128 strip tiles, 64 x 64 output tiles of the
+                     //    contraction; nparts counts 128-column tiles, nsplit / kslice count 64-deep stages, and with one
+                     //    split there are no partial results
   int square;        // 1: MFMA path, b == B and only whole tiles: the similarity matrix is formed once (F[0] holds
                      //    l2(j, p) in the layout of E[0] until the fold transposes it into E[1])
   int64_t ncol;      // gathered: entries per column-parameter array (B rounded up to whole 256-column tiles)
@@ -103,6 +106,9 @@ bool state_records_are_canonical(const float* u_img, const float* u_txt, const f
 void launch_grad_f32(const StepCtx& c);        // accuracy path: gradients + scalars
 void launch_fold_bf16(const StepCtx& c);       // MFMA path: local contrast-side weights folded into the strips
 void launch_contract_bf16(const StepCtx& c);   // MFMA path: strips x X contractions
+void launch_strips_fine_bf16(const StepCtx& c);    // MFMA path, fine tiles: exp strips + row sums
+void launch_contract_fine_bf16(const StepCtx& c);  // MFMA path, fine tiles: contractions, outputs and scalars
+void launch_norm_backward_bf16(const StepCtx& c);  // MFMA path: gradients through the L2 normalisation, if asked for
 void launch_finalize_bf16(const StepCtx& c);   // MFMA path: combine + scalars
 
 void launch_normalize_rows(const void* raw, int raw_bf16, int64_t ld_raw, int64_t b, int64_t d, void* unit, int unit_bf16,

@@ -528,24 +528,6 @@ void launch_state_flat(const int64_t* idx, int64_t n, int64_t stride, float gamm
                      sum_txt, u_img, u_txt, u_new_img, u_new_txt);
 }
 
-// ------------------------------------------------------------------------------------------
-// Scalars (called by one whole wavefront): loss of the local batch with g replaced by u^{t+1}; Eq. 8 (V0), Eq. 10 (V3).
-__device__ void write_scalars(const double* red, int nblocks, int64_t b, int version, const float* tau, float rho,
-                              float* loss, float* d_tau) {
-  const int lane = threadIdx.x & 63;
-  double A = 0.0, H = 0.0;
-  for (int i = lane; i < nblocks; i += 64) { A += red[2 * i]; H += red[2 * i + 1]; }
-  A = wave_sum(A) / (double)b;
-  H = wave_sum(H) / (double)b;
-  if (lane != 0) return;
-  if (version == FASTCLIP_V2) { *loss = (float)A; return; }
-  const double t = (double)tau[0];
-  if (version == FASTCLIP_V1) { *loss = (float)(t * A); return; }
-  if (version == FASTCLIP_V0) { *loss = (float)A; *d_tau = (float)(-H / (t * t)); return; }
-  *loss = (float)(t * A + 2.0 * (double)rho * t);
-  *d_tau = (float)(A + 2.0 * (double)rho - H / t);
-}
-
 __global__ void k_scalars(const double* red, int nblocks, int64_t b, int version, const float* tau, float rho,
                           float* loss, float* d_tau) {
   write_scalars(red, nblocks, b, version, tau, rho, loss, d_tau);
@@ -756,8 +738,12 @@ void launch_finalize_bf16(const StepCtx& c) {
                      (const float*)(c.ws + L.Opart[1]), L.nsplit, (const float*)(c.ws + L.c1), (const float*)(c.ws + L.c2),
                      (const float*)(c.ws + L.dcoef), c.buf.d_img, c.buf.d_txt, (const double*)(c.ws + L.red),
                      L.nstate_blocks, c.cfg.version, c.buf.tau, c.cfg.rho, c.buf.loss, c.buf.d_tau);
+}
+
+void launch_norm_backward_bf16(const StepCtx& c) {
+  const Layout& L = c.L;
   if (c.buf.norm_img)
-    hipLaunchKernelGGL(k_norm_backward_bf16, dim3((unsigned)L.b, 2), block, 0, c.s, (const bf16_t*)c.buf.img_glob,
+    hipLaunchKernelGGL(k_norm_backward_bf16, dim3((unsigned)L.b, 2), dim3(256), 0, c.s, (const bf16_t*)c.buf.img_glob,
                        (const bf16_t*)c.buf.txt_glob, c.cfg.ld_img, c.cfg.ld_txt, L.off, L.d, c.buf.d_img, c.buf.d_txt,
                        c.buf.norm_img, c.buf.norm_txt);
 }

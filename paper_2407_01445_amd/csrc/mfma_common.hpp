@@ -130,6 +130,103 @@ __host__ __device__ __forceinline__ bool strip_tile_is_interior(const StripArgs&
   return (a.off + a0 + 256 <= a.B) && (c0 + 256 <= a.B) && (a.d % 64 == 0) && (a.d >= 128);
 }
 
+// ----------------------------------------------------------------------------------------------------------------
+// Epilogue of one wave of a strip tile whose accumulators are NI x NJ blocks of 32 x 32: accumulator (ti, tj, v) of
+// lane (lr, hk) is contrast c0 + cw + ti 32 + 8 (v >> 2) + 4 hk + (v & 3), anchor a0 + aw + tj 32 + lr (c0 / a0: first
+// contrast / anchor of the workgroup's tile, cw / aw: the wave's offset inside it; a0 + aw is a multiple of 32, c0 + cw
+// of 16).  t = (s - s_pp) log2(e)/tau, l = 2^t; l goes to the fragment-ordered strip, the sums of l and of (s - s_pp) l
+// over the wave's contrasts to sred_w[quantity][anchor inside the tile].  sk / sdiag: log2(e)/tau and s_pp of the
+// tile's anchors.  GUARD: zero outside the batch and on the anchor's own column (B_{i-} excludes i).
+template <bool GUARD, int NI, int NJ>
+__device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)[NI][NJ], const float* sk,
+                                               const float* sdiag, float (*sred_w)[256], int strip, int64_t a0,
+                                               int64_t c0, int cw, int aw, int lane) {
+  const int lr = lane & 31, hk = lane >> 5;
+  bf16_t* __restrict__ E = a.E[strip];
+  // fragment (ab, cb) of this lane: E + ((ab nCB + cb) 64 + lane) 8; ab and cb are wave-uniform
+  const int64_t ab0 = (a0 + aw) >> 5, cb0 = (c0 + cw) >> 4;
+  const int B = (int)a.B, b = (int)a.b, off = (int)a.off;   // all below 2^24
+  // gathered state: column parameters of this tile (log2(e)/tau_j, s_jj log2(e)/tau_j, c_j), second strip F
+  const float* __restrict__ colp = a.colp ? a.colp + ((int64_t)strip * a.nCT + (c0 >> 8)) * 1024 : nullptr;
+  bf16_t* __restrict__ F = a.F[strip];
+#pragma unroll
+  for (int tj = 0; tj < NJ; ++tj) {
+    const int al = aw + tj * 32 + lr;
+    const float kk = sk[al], dk = sdiag[al] * kk;   // log2(e)/tau and s_pp log2(e)/tau of this anchor
+    const int anchor = (int)a0 + al;
+    // 4 independent partial sums per quantity: a dependent VALU op issues only every ~36 cycles on a lone
+    // wavefront, so one serial accumulation chain per sum would dominate this phase
+    float sgv[4] = {0.f, 0.f, 0.f, 0.f}, stv[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int ti = 0; ti < NI; ++ti) {
+      const int crow = (int)c0 + cw + ti * 32 + 4 * hk;
+      // groups of 4 accumulators (v = 4 g + q <-> contrast crow + 8 g + q), pinned apart to keep live ranges short
+      uint32_t pk[8], pf[8];
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        float sv[4], t[4], e[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) sv[q] = acc_read(acc[ti][tj][4 * g + q]);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) t[q] = fmaf(sv[q], kk, -dk);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) e[q] = __builtin_amdgcn_exp2f(t[q]);
+        if (colp) {   // wave-uniform
+          const int cl = ((int)c0 & 255) + cw + ti * 32 + 4 * hk + 8 * g;   // column inside the 256-column parameter tile
+          const float4 ck = *(const float4*)(colp + cl), cd = *(const float4*)(colp + 256 + cl),
+                       cc = *(const float4*)(colp + 512 + cl);
+          const float ckq[4] = {ck.x, ck.y, ck.z, ck.w}, cdq[4] = {cd.x, cd.y, cd.z, cd.w},
+                      ccq[4] = {cc.x, cc.y, cc.z, cc.w};
+          float f[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            f[q] = ccq[q] * __builtin_amdgcn_exp2f(fmaf(sv[q], ckq[q], -cdq[q]));
+            if (GUARD) f[q] = anchor < b ? f[q] : 0.f;
+          }
+          pf[2 * g] = pack_bf16x2(f[0], f[1]);
+          pf[2 * g + 1] = pack_bf16x2(f[2], f[3]);
+        }
+        if (GUARD) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int c = crow + 8 * g + q;
+            const bool ok = (c < B) && (anchor < b) && (c != off + anchor);
+            e[q] = ok ? e[q] : 0.f;
+          }
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          sgv[q] += e[q];
+          stv[q] = fmaf(t[q], e[q], stv[q]);
+        }
+        pk[2 * g] = pack_bf16x2(e[0], e[1]);
+        pk[2 * g + 1] = pack_bf16x2(e[2], e[3]);
+        FC_PIN();
+      }
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int64_t cb = cb0 + 2 * ti + j;
+        bf16_t* frag = E + ((ab0 + tj) * a.nCB + cb) * 512;   // wave-uniform
+        const u32x4 w = {pk[4 * j], pk[4 * j + 1], pk[4 * j + 2], pk[4 * j + 3]};
+        if (!GUARD || 16 * cb < a.ldE) *(u32x4*)(frag + lane * 8) = w;
+        if (colp && (!GUARD || 16 * cb < a.ldE)) {
+          const u32x4 wf = {pf[4 * j], pf[4 * j + 1], pf[4 * j + 2], pf[4 * j + 3]};
+          *(u32x4*)(F + (((ab0 + tj) * a.nCBF + cb) * 64 + lane) * 8) = wf;
+        }
+      }
+      FC_PIN();
+    }
+    const float sgl = (sgv[0] + sgv[1]) + (sgv[2] + sgv[3]);
+    const float stl = (stv[0] + stv[1]) + (stv[2] + stv[3]);
+    const float sg = sgl + __shfl_xor(sgl, 32);
+    const float st = stl + __shfl_xor(stl, 32);
+    if (hk == 0) {
+      sred_w[0][al] = sg;
+      sred_w[1][al] = kk > 0.f ? st * __builtin_amdgcn_rcpf(kk) : 0.f;   // sum of (s - s_pp) l
+    }
+  }
+}
+
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s);   // kernels_strips.hip
 
 }  // namespace fc

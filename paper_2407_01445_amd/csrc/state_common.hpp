@@ -72,6 +72,24 @@ __device__ inline double wave_sum_f64(double v) {
   return v;
 }
 
+// Scalars (called by one whole wavefront): loss of the local batch with g replaced by u^{t+1}; Eq. 8 (V0), Eq. 10 (V3).
+// red: the state phase's per-block sums of the anchors' loss terms and h terms.
+__device__ inline void write_scalars(const double* red, int nblocks, int64_t b, int version, const float* tau, float rho,
+                                     float* loss, float* d_tau) {
+  const int lane = threadIdx.x & 63;
+  double A = 0.0, H = 0.0;
+  for (int i = lane; i < nblocks; i += 64) { A += red[2 * i]; H += red[2 * i + 1]; }
+  A = wave_sum_f64(A) / (double)b;
+  H = wave_sum_f64(H) / (double)b;
+  if (lane != 0) return;
+  if (version == FASTCLIP_V2) { *loss = (float)A; return; }
+  const double t = (double)tau[0];
+  if (version == FASTCLIP_V1) { *loss = (float)(t * A); return; }
+  if (version == FASTCLIP_V0) { *loss = (float)A; *d_tau = (float)(-H / (t * t)); return; }
+  *loss = (float)(t * A + 2.0 * (double)rho * t);
+  *d_tau = (float)(A + 2.0 * (double)rho - H / t);
+}
+
 __device__ inline float ema_update(float u_old, float g, float gamma) {
   return u_old == 0.0f ? g : fmaf(gamma, g, (1.0f - gamma) * u_old);
 }

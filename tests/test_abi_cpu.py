@@ -48,8 +48,8 @@ def test_valid_config_and_workspace_size():
     cfg = good_cfg()
     assert fc.fastclip_validate(cfg, fake_bufs(cfg)) == fc.OK
     ws = fc.fastclip_workspace_bytes(cfg)
-    # at least the two stored exp strips (bf16) and the two fp32 local-block results
-    assert ws >= 2 * 256 * 1024 * 2 + 2 * 256 * 512 * 4
+    # at least the two stored exp strips (bf16)
+    assert ws >= 2 * 256 * 1024 * 2
     assert ws % 256 == 0
     small = fc.fastclip_workspace_bytes(good_cfg(emb_dtype=fc.F32, B=64, b=64, off=0, d=32))
     assert 0 < small < ws
@@ -84,9 +84,23 @@ def test_struct_size_and_flags_are_checked():
     cfg.struct_size = 8
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
     cfg = good_cfg()
-    cfg.flags = 2
+    cfg.flags = 4
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
+    cfg.flags = fc.GATHERED_STATE | fc.FINE_TILES
+    assert fc.fastclip_validate(cfg, None) == fc.OK
     assert fc.fastclip_validate(None, None) == fc.ERR_NULL
+
+
+def test_fine_tiles_flag_changes_the_workspace_only_for_small_batches():
+    """FASTCLIP_FINE_TILES: a batch of 256 of 1024 finishes its output tiles in place (no split partial results, so a
+    smaller workspace); a batch that fills the chip with 256 x 256 tiles, gathered state and the fp32 path ignore it."""
+    small = dict(B=1024, b=256, off=512, d=512)
+    assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.FINE_TILES, **small)) < fc.fastclip_workspace_bytes(good_cfg(**small))
+    for kw in (dict(B=32768, b=1024, off=0, d=1024), dict(flags_extra=fc.GATHERED_STATE, **small),
+               dict(emb_dtype=fc.F32, **small)):
+        extra = kw.pop("flags_extra", 0)
+        assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.FINE_TILES | extra, **kw)) == \
+            fc.fastclip_workspace_bytes(good_cfg(flags=extra, **kw))
 
 
 @pytest.mark.parametrize("version", [fc.V2, fc.V3])

@@ -248,6 +248,37 @@ def test_bf16_small_shapes(B, b, off, d, version):
     check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
 
 
+FINE_TILES_OFF = ("FASTCLIP_FINE_TILES is switched off on the GPU: after twelve steps on this path that agreed with the oracle "
+                  "(four on this very shape), a thirteenth ended in a GPU memory fault; a CPU emulation of every index the two "
+                  "kernels form finds all of them in bounds, no cause has been shown, so the path is not run on the GPU")
+
+
+@pytest.mark.skip(reason=FINE_TILES_OFF)
+@pytest.mark.parametrize("B,b,off,d", BF16_SMALL[:-1] + [(1024, 128, 128, 512), (2560, 320, 320, 512), (5120, 640, 640, 512)])
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_bf16_fine_tiles(B, b, off, d, version):
+    """The opt-in fine-tile path (128 x 128 strip tiles, 64 x 64 output tiles finished in place) on the small shapes
+    and on the paper's own per-GPU shapes, against the oracle."""
+    N = 5000
+    rng = np.random.default_rng(B + version)
+    img, txt = make_embeddings(B + d, B, d, 0.5, "bf16")
+    idx = draw_indices(B + 1, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=version, eps=1e-6, rho=6.5, tau=0.07,
+                tau_grad_scale=1.0 / N, ld_img=d + 8, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img, tau_txt0=t_txt,
+                fine_tiles=True)
+    g.set_inputs(img, txt, idx)
+    g.step(0.6)
+    u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+    want = oracle_step(g, img, txt, idx, u_img, u_txt, 0.6, tau=float(np.float32(0.07)),
+                       tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64))
+    compare(g.outputs(), want, version, TOL_BF16, "bf16 fine tiles %s v%d" % ((B, b, off, d), version))
+    check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
+
+
 def test_bf16_large_ragged_global_batch():
     """One worker's 256 anchors against 40003 global pairs: two strips of 156 whole contrast tiles plus a ragged last
     one, 1251 contraction stages split over the column range."""
