@@ -160,6 +160,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-state-bench", action="store_true")
     ap.add_argument("--no-stock-ops", action="store_true", help="skip timing the step written with stock PyTorch ops")
+    ap.add_argument("--strip-ablations", action="store_true",
+                    help="only run the measurement variants of the strip kernel (parts compiled out, in-kernel cycle "
+                         "counters) on the workload and print their table as JSON")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="only run a device-to-device copy of 1 GiB a few times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -246,6 +249,26 @@ def main():
     bufs = [bufs_at(t) for t in range(W + K + KE)]
     digest = source_digest()
     traffic = profiled_traffic()
+    if args.strip_ablations:
+        mws = torch.empty(fc.fastclip_workspace_bytes(cfgs[0]) + fc.MEASURE_STRIPS_EXTRA_BYTES, dtype=torch.uint8, device=dev)
+        for t in range(args.prewarm):
+            fc.fastclip_step(cfgs[0], bufs[0], ws)
+        names = {0: "complete kernel", 1: "no global->LDS requests", 2: "no LDS operand reads", 3: "no requests, no operand reads",
+                 4: "no epilogue", 7: "MFMAs and barriers only"}
+        rows = []
+        for abl, label in names.items():
+            for _ in range(20):                 # keep the clock where the step holds it
+                fc.fastclip_step(cfgs[0], bufs[0], ws)
+            r = fc.fastclip_measure_strips(cfgs[0], bufs[0], mws, abl, reps=20)
+            stages = r["stages_per_workgroup"]
+            rows.append({"ablation": abl, "what": label, "us_per_launch": round(r["ms"] * 1e3, 2), "ghz": round(r["ghz"], 3),
+                         "cycles_older_wave": round(r["cycles_older_wave"]), "cycles_younger_wave": round(r["cycles_younger_wave"]),
+                         "cycles_between_tiles": round(r["cycles_between_tiles"]),
+                         "cycles_per_stage_in_the_loops": round((r["cycles_older_wave"] - r["cycles_between_tiles"]) / stages, 1),
+                         "stages_per_workgroup": stages, "workgroups": r["workgroups"]})
+        print(json.dumps({"strip_ablations": rows, "workload": name, "sources": digest,
+                          "note": "2048 cycles of matrix-core time per 64-deep stage and SIMD (64 MFMAs of 32 cycles)"}))
+        return
 
     step = lambda t: fc.fastclip_step(cfgs[t], bufs[t], ws)
     if args.update_tau:      # Alg. 1 line 12 fused into the step: temperatures and their AdamW moments stepped in place

@@ -203,6 +203,22 @@ const char* fastclip_phase_name(int phase);
 fastclip_status fastclip_measure_mfma_ceiling(int32_t workgroups, int32_t iters, void* workspace,
                                               size_t workspace_bytes, void* stream, float* ms, double* stats);
 
+/* Measurement aid, not part of the step: the whole-tile strip kernel (plain mode: bf16, every 256 x 256 tile whole, no
+ * gathered state, not the single-pass form of b == B) with parts of it compiled out and per-wavefront cycle counters,
+ * so that what bounds the kernel can be measured again after any change to it.  ablation: 0 the complete kernel;
+ * 1 without the global -> LDS operand requests; 2 without the LDS operand reads of the main loop; 3 without both;
+ * 4 without the epilogue (exponentials, sums, stores); 7 MFMAs and barriers only.  Every variant but 0 computes
+ * nonsense and LEAVES THE WORKSPACE'S STRIPS AND SUMS UNDEFINED.  The call runs the prep kernel, launches the variant
+ * once untimed and `reps` times between two HIP events, SYNCHRONISES the stream and reads the counters back (it creates
+ * and destroys two events and allocates a few KiB of host memory).  workspace: fastclip_workspace_bytes(cfg) + 16 KiB.
+ * ms: mean duration of a launch.  stats[0] / stats[1]: mean cycles from kernel entry to exit of the older / younger
+ * wavefront of a SIMD; stats[2]: of which between a tile's last stage and the next tile (the epilogue and its
+ * barriers); stats[3]: 64-deep stages per workgroup; stats[4]: shader clock in GHz while the kernel ran;
+ * stats[5]: workgroups.  FASTCLIP_ERR_UNSUPPORTED where the layout is not the plain whole-tile one. */
+fastclip_status fastclip_measure_strips(const fastclip_config* cfg, const fastclip_buffers* bufs, void* workspace,
+                                        size_t workspace_bytes, void* stream, int32_t ablation, int32_t reps, float* ms,
+                                        double* stats);
+
 /* Measurement aid, not part of the step: the access pattern of the state phase on 32-byte records with nothing else in
  * the way.  For each of the n distinct indices idx[i] in [0, N) the first 32 bytes of record idx[i] (records of
  * record_floats floats, a multiple of 8, 32-byte aligned) are read, changed by one multiply-add per word and written

@@ -115,6 +115,9 @@ def load(build_if_missing: bool = True):
     lib.fastclip_normalize_rows.restype = C.c_int
     lib.fastclip_normalize_rows.argtypes = [C.c_void_p, C.c_int32, C.c_int64, C.c_int64, C.c_int64, C.c_void_p, C.c_int32,
                                             C.c_int64, C.c_void_p, C.c_void_p]
+    lib.fastclip_measure_strips.restype = C.c_int
+    lib.fastclip_measure_strips.argtypes = [cfgp, bufp, C.c_void_p, C.c_size_t, C.c_void_p, C.c_int32, C.c_int32,
+                                            C.POINTER(C.c_float), C.POINTER(C.c_double)]
     lib.fastclip_last_hip_error.restype = C.c_char_p
     lib.fastclip_last_hip_error.argtypes = []
     _lib = lib
@@ -222,6 +225,22 @@ def fastclip_measure_mfma_ceiling(workgroups, iters, workspace, stream=None) -> 
         raise FastclipError(st)
     return dict(ms=ms.value, flop=stats[0], tflops=stats[0] / (ms.value * 1e-3) / 1e12, cycles_per_wave=stats[1],
                 ghz=stats[2], cycles_per_mfma=stats[3])
+
+
+MEASURE_STRIPS_EXTRA_BYTES = 16 << 10
+
+
+def fastclip_measure_strips(cfg, bufs, workspace, ablation, reps=10, stream=None) -> dict:
+    """workspace: fastclip_workspace_bytes(cfg) + MEASURE_STRIPS_EXTRA_BYTES.  Returns the header's ms and stats by name."""
+    ms = C.c_float(0.0)
+    stats = (C.c_double * 6)()
+    st = int(load().fastclip_measure_strips(C.byref(cfg), C.byref(bufs), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream), int(ablation),
+                                            int(reps), C.byref(ms), stats))
+    if st != OK:
+        raise FastclipError(st)
+    return dict(ms=ms.value, cycles_older_wave=stats[0], cycles_younger_wave=stats[1], cycles_between_tiles=stats[2],
+                stages_per_workgroup=stats[3], ghz=stats[4], workgroups=int(stats[5]))
 
 
 def fastclip_measure_record_rmw(idx, n, N, records, record_floats, stream=None, check=True) -> int:

@@ -487,6 +487,73 @@ fastclip_status fastclip_measure_mfma_ceiling(int32_t workgroups, int32_t iters,
   return FASTCLIP_OK;
 }
 
+fastclip_status fastclip_measure_strips(const fastclip_config* cfg, const fastclip_buffers* bufs, void* workspace,
+                                        size_t workspace_bytes, void* stream, int32_t ablation, int32_t reps, float* ms,
+                                        double* stats) {
+  if (!ms || !stats) return FASTCLIP_ERR_NULL;
+  fastclip_status st = fc::validate(cfg, bufs);
+  if (st != FASTCLIP_OK) return st;
+  if (!bufs || !workspace) return FASTCLIP_ERR_NULL;
+  if (reps < 1 || reps > 1000) return FASTCLIP_ERR_SHAPE;
+  fc::StepCtx c;
+  c.cfg = *cfg;
+  c.buf = *bufs;
+  memset(&c.tau_upd, 0, sizeof(c.tau_upd));
+  memset(&c.tau_st, 0, sizeof(c.tau_st));
+  fc::make_layout(*cfg, &c.L);
+  const size_t ncyc = (size_t)256 * 2 * 4;
+  if (workspace_bytes < c.L.total + ncyc * sizeof(uint64_t) || ((uintptr_t)workspace & 255)) return FASTCLIP_ERR_WORKSPACE;
+  if (!c.L.bf16 || c.L.fine || c.L.square || c.L.gathered) return FASTCLIP_ERR_UNSUPPORTED;
+  c.ws = (char*)workspace;
+  c.s = (hipStream_t)stream;
+  uint64_t* cycles = (uint64_t*)(c.ws + c.L.total);
+  (void)hipGetLastError();
+  hipError_t e = hipMemsetAsync(cycles, 0, ncyc * sizeof(uint64_t), c.s);
+  if (e != hipSuccess) return fc::hip_failed(e);
+  fc::launch_prep(c);                                   // s_ii and the temperatures that the epilogue reads
+  if (!fc::launch_strips_measure(c, ablation, cycles)) return FASTCLIP_ERR_UNSUPPORTED;   // untimed first launch
+  hipEvent_t e0, e1;
+  e = hipEventCreate(&e0);
+  if (e != hipSuccess) return fc::hip_failed(e);
+  e = hipEventCreate(&e1);
+  if (e != hipSuccess) { (void)hipEventDestroy(e0); return fc::hip_failed(e); }
+  (void)hipEventRecord(e0, c.s);
+  for (int i = 0; i < reps; ++i) (void)fc::launch_strips_measure(c, ablation, cycles);
+  (void)hipEventRecord(e1, c.s);
+  fastclip_status rc = fc::launch_status();
+  e = hipStreamSynchronize(c.s);
+  if (e != hipSuccess) rc = fc::hip_failed(e);
+  *ms = 0.f;
+  if (rc == FASTCLIP_OK && hipEventElapsedTime(ms, e0, e1) != hipSuccess) rc = FASTCLIP_ERR_LAUNCH;
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc != FASTCLIP_OK) return rc;
+  *ms /= (float)reps;
+  uint64_t* host = (uint64_t*)malloc(ncyc * sizeof(uint64_t));
+  if (!host) return FASTCLIP_ERR_LAUNCH;
+  e = hipMemcpy(host, cycles, ncyc * sizeof(uint64_t), hipMemcpyDeviceToHost);
+  if (e != hipSuccess) { free(host); return fc::hip_failed(e); }
+  // counters of the last launch: [workgroup][older | younger wave of SIMD 0][total cycles, epilogue cycles, 10 ns ticks, -]
+  double tot[2] = {0.0, 0.0}, epi[2] = {0.0, 0.0}, ticks = 0.0;
+  int used = 0;
+  for (int w = 0; w < 256; ++w) {
+    if (!host[(w * 2) * 4]) continue;
+    ++used;
+    for (int y = 0; y < 2; ++y) { tot[y] += (double)host[(w * 2 + y) * 4]; epi[y] += (double)host[(w * 2 + y) * 4 + 1]; }
+    ticks += (double)host[(w * 2) * 4 + 2];
+  }
+  free(host);
+  if (!used) return FASTCLIP_ERR_LAUNCH;
+  const double tiles_per_wg = 2.0 * (double)((cfg->b + 255) / 256) * (double)((cfg->B + 255) / 256) / (double)used;
+  stats[0] = tot[0] / used;                                 // cycles of the older wave of a SIMD, kernel entry to exit
+  stats[1] = tot[1] / used;                                 // ... of the younger wave
+  stats[2] = epi[0] / used;                                 // of which between the last stage of a tile and the next tile
+  stats[3] = tiles_per_wg * (double)(cfg->d / 64);          // 64-deep stages per workgroup
+  stats[4] = ticks > 0.0 ? tot[0] / (ticks * 10.0) : 0.0;   // shader clock in GHz while the kernel ran
+  stats[5] = (double)used;                                  // workgroups
+  return FASTCLIP_OK;
+}
+
 fastclip_status fastclip_normalize_rows(const void* raw, int32_t raw_dtype, int64_t ld_raw, int64_t b, int64_t d,
                                         void* unit, int32_t unit_dtype, int64_t ld_unit, float* norm, void* stream) {
   if (!raw || !unit || !norm) return FASTCLIP_ERR_NULL;

@@ -114,6 +114,7 @@ void launch_finalize_bf16(const StepCtx& c);   // MFMA path: combine + scalars
 void launch_normalize_rows(const void* raw, int raw_bf16, int64_t ld_raw, int64_t b, int64_t d, void* unit, int unit_bf16,
                            int64_t ld_unit, float* norm, hipStream_t s);
 void launch_record_rmw(const int64_t* idx, int64_t n, float* rec, int64_t stride, hipStream_t s);    // measurement only
+bool launch_strips_measure(const StepCtx& c, int ablation, uint64_t* cycles);   // measurement only; false: not applicable
 void launch_mfma_ceiling(int workgroups, int iters, uint64_t* out, float* sink, hipStream_t s);   // measurement only
 
 void launch_state_flat(const int64_t* idx, int64_t n, int64_t stride, float gamma, float M,

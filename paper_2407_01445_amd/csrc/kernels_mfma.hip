@@ -312,11 +312,33 @@ __global__ void __launch_bounds__(256) k_strips_edge_bf16(StripArgs a) {
   }
 }
 
+static void make_strip_args(const StepCtx& c, StripArgs* out, bool* any_interior, bool* any_edge);
+
 void launch_strips_bf16(const StepCtx& c) {
+  StripArgs a;
+  bool any_interior, any_edge;
+  make_strip_args(c, &a, &any_interior, &any_edge);
+  if (any_interior) launch_strips_interior_bf16(a, c.s);
+  if (any_edge) hipLaunchKernelGGL(k_strips_edge_bf16, dim3((unsigned)a.ntiles), dim3(256), 0, c.s, a);
+}
+
+// Measurement: the whole-tile strip kernel of the plain mode with parts compiled out and cycle counters (kAbl* in
+// kernels_strips.hip).  Only for layouts in which every tile is whole and the mode is the plain one.
+bool launch_strips_measure(const StepCtx& c, int ablation, uint64_t* cycles) {
+  StripArgs a;
+  bool any_interior, any_edge;
+  make_strip_args(c, &a, &any_interior, &any_edge);
+  if (!any_interior || any_edge || a.square || a.colp) return false;
+  a.cycles = cycles;
+  return launch_strips_measure_bf16(a, ablation, c.s);
+}
+
+static void make_strip_args(const StepCtx& c, StripArgs* out, bool* any_interior_out, bool* any_edge_out) {
   const Layout& L = c.L;
   const bf16_t* img = (const bf16_t*)c.buf.img_glob;
   const bf16_t* txt = (const bf16_t*)c.buf.txt_glob;
-  StripArgs a;
+  StripArgs& a = *out;
+  a.cycles = nullptr;
   a.anchors[0] = img + L.off * c.cfg.ld_img;  a.ld_anchor[0] = c.cfg.ld_img;
   a.anchors[1] = txt + L.off * c.cfg.ld_txt;  a.ld_anchor[1] = c.cfg.ld_txt;
   a.contrasts[0] = txt;                       a.ld_contrast[0] = c.cfg.ld_txt;
@@ -345,8 +367,8 @@ void launch_strips_bf16(const StepCtx& c) {
     any_interior |= in && L.B >= 256;
     any_edge |= !in;
   }
-  if (any_interior) launch_strips_interior_bf16(a, c.s);
-  if (any_edge) hipLaunchKernelGGL(k_strips_edge_bf16, dim3((unsigned)a.ntiles), dim3(256), 0, c.s, a);
+  *any_interior_out = any_interior;
+  *any_edge_out = any_edge;
 }
 
 // ----------------------------------------------------------------------------------------------------------------

@@ -69,6 +69,15 @@ __device__ __forceinline__ void zero_acc24(f32x16 (&acc)[2][4]) {
 #define FC_HMM(ti, tj, A_, B_) \
   acc[ti][tj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A_[ti], B_[tj], acc[ti][tj], 0, 0, 0)
 #define FC_LDS16(p) (*(const bf16x8*)(p))
+// An operand read of the main loop; the measurement variants without operand reads keep what the register holds.
+#define FC_RD(p, keep) (((ABL) & kAblNoOperandReads) ? (keep) : FC_LDS16(p))
+
+// Measurement variants of k_strips_bf16 (template parameter ABL, 0 in the step): parts of the kernel compiled out, to
+// learn what each costs, and per-wave cycle counters.  Their results are meaningless; they write where the step writes.
+constexpr int kAblNoRequests = 1;       // no global -> LDS requests (operands are whatever the LDS holds)
+constexpr int kAblNoOperandReads = 2;   // no LDS operand reads in the main loop (register operands never change)
+constexpr int kAblNoEpilogue = 4;       // no exponentials, sums or stores
+constexpr int kAblTimed = 8;            // cycle counters of waves 0 and 4 of every workgroup go to StripArgs::cycles
 
 // Epilogue of one wave (64 contrasts x 128 anchors).  Accumulator (ti, tj, v) of lane (lr, hk): contrast
 // c_first + 32 ti + 8 (v >> 2) + 4 hk + (v & 3), anchor anchor0 + 32 tj + lr.  t = (s - s_pp) log2(e)/tau, l = 2^t.
@@ -282,12 +291,12 @@ __device__ __forceinline__ void half_epilogue_cols(f32x16 (&acc)[2][4], const fl
 // D0 .. D7 are statements (requests or nothing) placed one per MFMA.
 #define FC_NONE (void)0
 #define FC_STEP(XP, AP, XQ, AQ, px, pa, D0, D1, D2, D3, D4, D5, D6, D7)                               \
-  FC_HMM(0, 0, XP, AP); FC_PIN(); XQ[0] = FC_LDS16(px);         FC_PIN(); D0; FC_PIN();              \
-  FC_HMM(0, 1, XP, AP); FC_PIN(); AQ[0] = FC_LDS16(pa);         FC_PIN(); D1; FC_PIN();              \
-  FC_HMM(0, 2, XP, AP); FC_PIN(); XQ[1] = FC_LDS16(px + 4096);  FC_PIN(); D2; FC_PIN();              \
-  FC_HMM(0, 3, XP, AP); FC_PIN(); AQ[1] = FC_LDS16(pa + 4096);  FC_PIN(); D3; FC_PIN();              \
-  FC_HMM(1, 0, XP, AP); FC_PIN(); AQ[2] = FC_LDS16(pa + 8192);  FC_PIN(); D4; FC_PIN();              \
-  FC_HMM(1, 1, XP, AP); FC_PIN(); AQ[3] = FC_LDS16(pa + 12288); FC_PIN(); D5; FC_PIN();              \
+  FC_HMM(0, 0, XP, AP); FC_PIN(); XQ[0] = FC_RD(px, XQ[0]);         FC_PIN(); D0; FC_PIN();          \
+  FC_HMM(0, 1, XP, AP); FC_PIN(); AQ[0] = FC_RD(pa, AQ[0]);         FC_PIN(); D1; FC_PIN();          \
+  FC_HMM(0, 2, XP, AP); FC_PIN(); XQ[1] = FC_RD(px + 4096, XQ[1]);  FC_PIN(); D2; FC_PIN();          \
+  FC_HMM(0, 3, XP, AP); FC_PIN(); AQ[1] = FC_RD(pa + 4096, AQ[1]);  FC_PIN(); D3; FC_PIN();          \
+  FC_HMM(1, 0, XP, AP); FC_PIN(); AQ[2] = FC_RD(pa + 8192, AQ[2]);  FC_PIN(); D4; FC_PIN();          \
+  FC_HMM(1, 1, XP, AP); FC_PIN(); AQ[3] = FC_RD(pa + 12288, AQ[3]); FC_PIN(); D5; FC_PIN();          \
   FC_HMM(1, 2, XP, AP); FC_PIN(); D6; FC_PIN();                                                      \
   FC_HMM(1, 3, XP, AP); FC_PIN(); D7; FC_PIN()
 #define FC_STEP_PLAIN(XP, AP, XQ, AQ, px, pa) \
@@ -303,9 +312,11 @@ constexpr uint32_t kScolOff = 2048u, kSredOff = 6144u, kSredcOff = 14336u;
 #define FC_WAIT_VMCNT41() __builtin_amdgcn_s_waitcnt(0x8f79)   // 41 = 0b101001
 #define FC_WAIT_VMCNT42() __builtin_amdgcn_s_waitcnt(0x8f7a)   // 42 = 0b101010
 
-template <int MODE>
+template <int MODE, int ABL>
 __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   constexpr bool REMOTE = MODE == 1, SQUARE = MODE == 2;
+  uint64_t t_begin = 0, t_wall = 0, t_epilogue = 0;
+  if constexpr ((ABL & kAblTimed) != 0) { t_begin = __builtin_readcyclecounter(); t_wall = wall_clock64(); }
   __shared__ __attribute__((aligned(1024))) char ring[kRing5];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -378,7 +389,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   if (t >= a.ntiles) return;
   // ring positions (byte offsets) of X_g A_g X_g+1 A_g+1 X_g+2; every stage moves on by two
   uint32_t P0 = 0u, P1 = (uint32_t)kPart, P2 = 2u * kPart, P3 = 3u * kPart, P4 = 4u * kPart;
-  const bool requester = wave < 4;
+  const bool requester = (ABL & kAblNoRequests) ? false : wave < 4;
   open_x(t);
   open_a(t);
   if (requester) {
@@ -399,6 +410,11 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   x0[0] = FC_LDS16(ring + P0 + bx); x0[1] = FC_LDS16(ring + P0 + bx + 4096);
 #pragma unroll
   for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + P1 + ba + j * 4096);
+  if constexpr ((ABL & kAblNoOperandReads) != 0) {   // both operand sets start from the same (arbitrary) LDS contents
+    x1[0] = x0[1]; x1[1] = x0[0];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) a1[j] = a0[3 - j];
+  }
 
   bool pend_x = false;   // X_g+2 is still to be requested (always during the first step after a barrier's last step)
   bool after_epilogue = false;
@@ -443,7 +459,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
       after_epilogue = false;
       __syncthreads();
       FC_PIN();
-      if (last) {   // the tile's per-anchor scalars go into the panel A_g has just left (free until X_g+3 is requested)
+      if (last && !(ABL & kAblNoRequests)) {   // the tile's per-anchor scalars go into the panel A_g has just left (free until X_g+3 is requested)
         if (wave < 4) dma4(a.kscale[strip] + a_first + wave * 64, lane * 4, ring_addr + P1 + (uint32_t)wave * 256u);
         else dma4(a.diag + a_first + (wave - 4) * 64, lane * 4, ring_addr + P1 + 1024u + (uint32_t)(wave - 4) * 256u);
         if constexpr (REMOTE) {   // the tile's column parameters [4][256], two 256-byte pieces per wave
@@ -474,58 +490,71 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
     // called P4
     if (requester) FC_WAIT_VMCNT8(); else FC_WAIT_VMCNT0();
     __syncthreads();
-    const float* sk = (const float*)(ring + P4);
-    const float* sdiag = sk + 256;
-    const float* scol = (const float*)(ring + P4 + kScolOff);                    // MODE 1: [4][256]; MODE 2: [2][256]
-    float (*sred)[2][256] = (float (*)[2][256])(ring + P4 + kSredOff);           // [4 contrast quarters][2][256]
-    float (*sredc)[2][256] = (float (*)[2][256])(ring + P4 + kSredcOff);         // MODE 2: [2 anchor halves][2][256]
-    float sg[4] = {0.f, 0.f, 0.f, 0.f}, st[4] = {0.f, 0.f, 0.f, 0.f};
-    const int c_first = c_tile + wr * 64;
-    char* frag0 = (char*)a.E[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCB + (c_first >> 4)) * 1024;
-    const int64_t row_bytes = a.nCB * 1024;
-    const int own0 = (int)a.off + a_first + wc * 128;
-    const bool diagonal = (c_first < own0 + 128) && (c_first + 64 > own0);
-    if constexpr (REMOTE) {
-      char* fragF0 = (char*)a.F[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
-      const int64_t row_bytesF = a.nCBF * 1024;
-      const int cl0 = wr * 64 + 4 * (lane >> 5);
-      if (diagonal)
-        half_epilogue_remote<true>(acc, sk, sdiag, scol, sg, st, frag0, row_bytes, fragF0, row_bytesF, c_first, own0,
-                                   wc * 128, cl0, lane);
-      else
-        half_epilogue_remote<false>(acc, sk, sdiag, scol, sg, st, frag0, row_bytes, fragF0, row_bytesF, c_first, own0,
-                                    wc * 128, cl0, lane);
-    } else {
-      if (diagonal) half_epilogue<true>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
-      else half_epilogue<false>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
-    }
-    if constexpr (SQUARE) {
-      char* fragF0 = (char*)a.F[0] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
-      const int64_t row_bytesF = a.nCBF * 1024;
-      const int cl0 = wr * 64 + 4 * (lane >> 5);
-      if (diagonal) half_epilogue_cols<true>(acc, scol, scol + 256, sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
-      else half_epilogue_cols<false>(acc, scol, scol + 256, sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
-    }
-#pragma unroll
-    for (int tj = 0; tj < 4; ++tj) {
-      const int al = wc * 128 + tj * 32 + lr;
-      const float kk = sk[al];
-      const float g2 = sg[tj] + __shfl_xor(sg[tj], 32);
-      const float t2 = st[tj] + __shfl_xor(st[tj], 32);
-      if (hk == 0) {
-        sred[wr][0][al] = g2;
-        sred[wr][1][al] = kk > 0.f ? t2 * __builtin_amdgcn_rcpf(kk) : 0.f;   // sum of (s - s_pp) l
+    uint64_t t_e0 = 0;
+    if constexpr ((ABL & kAblTimed) != 0) t_e0 = __builtin_readcyclecounter();
+    if constexpr ((ABL & kAblNoEpilogue) == 0) {
+      const float* sk = (const float*)(ring + P4);
+      const float* sdiag = sk + 256;
+      const float* scol = (const float*)(ring + P4 + kScolOff);                    // MODE 1: [4][256]; MODE 2: [2][256]
+      float (*sred)[2][256] = (float (*)[2][256])(ring + P4 + kSredOff);           // [4 contrast quarters][2][256]
+      float (*sredc)[2][256] = (float (*)[2][256])(ring + P4 + kSredcOff);         // MODE 2: [2 anchor halves][2][256]
+      float sg[4] = {0.f, 0.f, 0.f, 0.f}, st[4] = {0.f, 0.f, 0.f, 0.f};
+      const int c_first = c_tile + wr * 64;
+      char* frag0 = (char*)a.E[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCB + (c_first >> 4)) * 1024;
+      const int64_t row_bytes = a.nCB * 1024;
+      const int own0 = (int)a.off + a_first + wc * 128;
+      const bool diagonal = (c_first < own0 + 128) && (c_first + 64 > own0);
+      if constexpr (REMOTE) {
+        char* fragF0 = (char*)a.F[strip] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
+        const int64_t row_bytesF = a.nCBF * 1024;
+        const int cl0 = wr * 64 + 4 * (lane >> 5);
+        if (diagonal)
+          half_epilogue_remote<true>(acc, sk, sdiag, scol, sg, st, frag0, row_bytes, fragF0, row_bytesF, c_first, own0,
+                                     wc * 128, cl0, lane);
+        else
+          half_epilogue_remote<false>(acc, sk, sdiag, scol, sg, st, frag0, row_bytes, fragF0, row_bytesF, c_first, own0,
+                                      wc * 128, cl0, lane);
+      } else {
+        if (diagonal) half_epilogue<true>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+        else half_epilogue<false>(acc, sk, sdiag, sg, st, frag0, row_bytes, c_first, own0, wc * 128, lane);
+      }
+      if constexpr (SQUARE) {
+        char* fragF0 = (char*)a.F[0] + (((int64_t)(a_first + wc * 128) >> 5) * a.nCBF + (c_first >> 4)) * 1024;
+        const int64_t row_bytesF = a.nCBF * 1024;
+        const int cl0 = wr * 64 + 4 * (lane >> 5);
+        if (diagonal) half_epilogue_cols<true>(acc, scol, scol + 256, sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
+        else half_epilogue_cols<false>(acc, scol, scol + 256, sredc[wc], fragF0, row_bytesF, c_first, own0, cl0, lane);
+      }
+  #pragma unroll
+      for (int tj = 0; tj < 4; ++tj) {
+        const int al = wc * 128 + tj * 32 + lr;
+        const float kk = sk[al];
+        const float g2 = sg[tj] + __shfl_xor(sg[tj], 32);
+        const float t2 = st[tj] + __shfl_xor(st[tj], 32);
+        if (hk == 0) {
+          sred[wr][0][al] = g2;
+          sred[wr][1][al] = kk > 0.f ? t2 * __builtin_amdgcn_rcpf(kk) : 0.f;   // sum of (s - s_pp) l
+        }
+      }
+      __syncthreads();
+      {
+        const int q = tid >> 8, m = tid & 255;
+        a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a_first + m] =
+            (sred[0][q][m] + sred[1][q][m]) + (sred[2][q][m] + sred[3][q][m]);
+        // the text anchors' sums (quantities 2, 3): partial number = the anchor tile, position = the column
+        if constexpr (SQUARE) a.sums[((size_t)(2 + q) * a.nparts + at) * a.bstride + c_tile + m] = sredc[0][q][m] + sredc[1][q][m];
       }
     }
-    __syncthreads();
-    {
-      const int q = tid >> 8, m = tid & 255;
-      a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + a_first + m] =
-          (sred[0][q][m] + sred[1][q][m]) + (sred[2][q][m] + sred[3][q][m]);
-      // the text anchors' sums (quantities 2, 3): partial number = the anchor tile, position = the column
-      if constexpr (SQUARE) a.sums[((size_t)(2 + q) * a.nparts + at) * a.bstride + c_tile + m] = sredc[0][q][m] + sredc[1][q][m];
+    if constexpr ((ABL & kAblNoEpilogue) != 0) {      // nothing reads the accumulators: keep the MFMAs that wrote them
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) asm volatile("" : : "a"(acc[i][j][v]));
     }
     __syncthreads();     // the panel is given back: X_g+3 is requested into it during the next step
+    if constexpr ((ABL & kAblTimed) != 0) t_epilogue += __builtin_readcyclecounter() - t_e0;
     if constexpr (MODE != 0) {
       // the first operands of the next tile (read during the last step above) are read again here, so that their
       // registers are free during these modes' larger epilogues; their panels are retired only by the next barrier
@@ -533,17 +562,40 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) a0[j] = FC_LDS16(ring + P1 + ba + j * 4096);
     }
-    after_epilogue = true;
+    after_epilogue = (ABL & kAblNoEpilogue) == 0;    // the epilogue's stores are what the longer wait counts
     t = next_interior(t + G);
   }
   FC_WAIT_VMCNT0();   // the trailing re-requests write LDS: they must land before the workgroup gives it back
+  if constexpr ((ABL & kAblTimed) != 0) {
+    if (a.cycles && lane == 0 && (wave & 3) == 0) {      // waves 0 and 4: the older and the younger wave of SIMD 0
+      uint64_t* o = a.cycles + ((size_t)blockIdx.x * 2 + (wave >> 2)) * 4;
+      o[0] = __builtin_readcyclecounter() - t_begin;
+      o[1] = t_epilogue;
+      o[2] = wall_clock64() - t_wall;
+      o[3] = 0;
+    }
+  }
 }
 
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s) {
   const int grid = a.ntiles < 256 ? a.ntiles : 256;
-  if (a.square) hipLaunchKernelGGL(k_strips_bf16<2>, dim3((unsigned)grid), dim3(512), 0, s, a);
-  else if (a.colp) hipLaunchKernelGGL(k_strips_bf16<1>, dim3((unsigned)grid), dim3(512), 0, s, a);
-  else hipLaunchKernelGGL(k_strips_bf16<0>, dim3((unsigned)grid), dim3(512), 0, s, a);
+  if (a.square) hipLaunchKernelGGL((k_strips_bf16<2, 0>), dim3((unsigned)grid), dim3(512), 0, s, a);
+  else if (a.colp) hipLaunchKernelGGL((k_strips_bf16<1, 0>), dim3((unsigned)grid), dim3(512), 0, s, a);
+  else hipLaunchKernelGGL((k_strips_bf16<0, 0>), dim3((unsigned)grid), dim3(512), 0, s, a);
+}
+
+// Measurement variants of the plain mode (see kAbl*); false if `ablation` is none of those built.
+bool launch_strips_measure_bf16(const StripArgs& a, int ablation, hipStream_t s) {
+  const dim3 grid((unsigned)(a.ntiles < 256 ? a.ntiles : 256)), block(512);
+  switch (ablation) {
+    case 0: hipLaunchKernelGGL((k_strips_bf16<0, kAblTimed>), grid, block, 0, s, a); return true;
+    case 1: hipLaunchKernelGGL((k_strips_bf16<0, kAblTimed | 1>), grid, block, 0, s, a); return true;
+    case 2: hipLaunchKernelGGL((k_strips_bf16<0, kAblTimed | 2>), grid, block, 0, s, a); return true;
+    case 3: hipLaunchKernelGGL((k_strips_bf16<0, kAblTimed | 3>), grid, block, 0, s, a); return true;
+    case 4: hipLaunchKernelGGL((k_strips_bf16<0, kAblTimed | 4>), grid, block, 0, s, a); return true;
+    case 7: hipLaunchKernelGGL((k_strips_bf16<0, kAblTimed | 7>), grid, block, 0, s, a); return true;
+    default: return false;
+  }
 }
 
 }  // namespace fc

@@ -111,6 +111,7 @@ struct StripArgs {
   // the whole batch is local and every tile is whole: only strip 0 is formed, l2(j, p) of the text anchors goes to
   // F[0] and their sums are taken down the columns
   int square;
+  uint64_t* cycles;             // measurement variants only: [workgroup][wave 0 | wave 4][4] counters, else nullptr
 };
 
 // Which tiles go to the persistent kernel (unguarded direct-to-LDS loads), which to the guarded one.  The persistent
@@ -228,5 +229,6 @@ __device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)
 }
 
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s);   // kernels_strips.hip
+bool launch_strips_measure_bf16(const StripArgs& a, int ablation, hipStream_t s);   // kernels_strips.hip
 
 }  // namespace fc

@@ -306,3 +306,18 @@ def test_normalize_rows_argument_errors():
     assert lib.fastclip_measure_record_rmw(0x1000, 4, 10, 0x2000, 12, None) == fc.ERR_SHAPE
     assert lib.fastclip_measure_record_rmw(0x1000, 4, 10, 0x2010, 8, None) == fc.ERR_UNSUPPORTED
     assert lib.fastclip_measure_record_rmw(0x1000, 0, 10, 0x2000, 8, None) == fc.OK
+
+
+def test_measure_strips_argument_errors():
+    lib = fc.load()
+    cfg = good_cfg(B=2048, b=512, off=512, d=128)
+    bufs = fake_bufs(cfg)
+    ms, stats = C.c_float(), (C.c_double * 6)()
+    need = fc.fastclip_workspace_bytes(cfg) + fc.MEASURE_STRIPS_EXTRA_BYTES
+    call = lambda c=cfg, ws=0x1000, nbytes=need, abl=0, reps=2: lib.fastclip_measure_strips(
+        C.byref(c), C.byref(bufs), ws, nbytes, None, abl, reps, C.byref(ms), stats)
+    assert call(nbytes=need - 1) == fc.ERR_WORKSPACE and call(ws=None) == fc.ERR_NULL and call(reps=0) == fc.ERR_SHAPE
+    assert call(c=good_cfg(emb_dtype=fc.F32, B=64, b=64, off=0, d=32), nbytes=1 << 30) == fc.ERR_UNSUPPORTED
+    assert call(c=good_cfg(B=2048, b=512, off=512, d=128, flags=fc.GATHERED_STATE), nbytes=1 << 30) == fc.ERR_UNSUPPORTED
+    assert lib.fastclip_measure_mfma_ceiling(0, 16, 0x1000, 1 << 20, None, C.byref(ms), stats) == fc.ERR_SHAPE
+    assert lib.fastclip_measure_mfma_ceiling(16, 16, 0x1000, 64, None, C.byref(ms), stats) == fc.ERR_WORKSPACE

@@ -1064,3 +1064,33 @@ def test_step_timed_reports_phases_and_same_result():
     assert all(v > 0 for k, v in ms.items() if k != "state") and ms["state"] >= 0     # few anchors: state runs inside "local"
     for x, y in zip(*outs):
         assert torch.equal(x, y)
+
+
+def test_measurement_entries_run_and_leave_the_step_intact():
+    """The measurement aids (MFMA ceiling, bare record read-modify-write, strip kernel variants) run, report sane figures,
+    and a step after them still agrees with the step before them bit for bit."""
+    B, b, off, d, N = 2048, 512, 512, 128, 20000
+    img, txt = make_embeddings(5, B, d, 0.5, "bf16")
+    idx = draw_indices(6, b, N)
+    runs = []
+    for measure in (False, True):
+        g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=V3, eps=1e-6, rho=6.5)
+        g.set_inputs(img, txt, idx)
+        if measure:
+            cfg = g.config(0.7)
+            ws = torch.empty(fc.fastclip_workspace_bytes(cfg) + fc.MEASURE_STRIPS_EXTRA_BYTES, dtype=torch.uint8, device=DEV)
+            for abl in (0, 1, 2, 3, 4, 7):
+                r = fc.fastclip_measure_strips(cfg, g.buffers(), ws, abl, reps=2)
+                assert r["ms"] > 0 and r["workgroups"] == 2 * 2 * 8 and 0.5 < r["ghz"] < 3.0
+                assert r["cycles_older_wave"] > 64 * 32 * r["stages_per_workgroup"] * 0.4       # the MFMAs were not optimised away
+            mc = fc.fastclip_measure_mfma_ceiling(64, 256, torch.empty(64 * 128 + 2048, dtype=torch.uint8, device=DEV))
+            assert 100 < mc["tflops"] < 2600 and 30 < mc["cycles_per_mfma"] < 80
+            rec = torch.zeros(N, 8, dtype=torch.float32, device=DEV)
+            fc.fastclip_measure_record_rmw(g.idx, b, N, rec, 8)
+            torch.cuda.synchronize()
+            touched = (rec != 0).any(dim=1)
+            assert int(touched.sum()) == b and bool(touched[g.idx].all()) and bool((rec[g.idx] == 0.25).all())
+        g.step(0.7)
+        runs.append((g.d_img.cpu(), g.d_txt.cpu(), g.u_img.cpu(), g.loss.cpu(), g.d_tau.cpu()))
+    for x, y in zip(*runs):
+        assert torch.equal(x, y)
