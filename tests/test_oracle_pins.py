@@ -519,7 +519,9 @@ def test_adamw_matches_the_library_optimizer_on_a_scalar():
         theta, m, v = parameter_update(theta, g, m, v, optimizer=ADAMW, lr=2e-4, step=t + 1, beta1=0.9, beta2=0.98,
                                        eps=1e-6)
         assert float(theta) == pytest.approx(th.item(), rel=1e-12)
-    # LAMB with the layer factor 1 (what the paper prescribes for tau) is the same update
+    # LAMB: this pins the READING, not LAMB itself.  Proc. parameter_update scales LAMB's step by a layer factor alpha
+    # and the paper sets alpha = 1 for the temperature, so for tau LAMB is the AdamW step above (which the library
+    # optimizer pins); a general LAMB, whose factor is |theta| / |r| per layer, is not part of the path.
     a = parameter_update(0.05, 0.3, 0.01, 0.02, optimizer=LAMB, lr=1e-3, step=4, beta1=0.9, beta2=0.99, eps=1e-8)
     b = parameter_update(0.05, 0.3, 0.01, 0.02, optimizer=ADAMW, lr=1e-3, step=4, beta1=0.9, beta2=0.99, eps=1e-8)
     assert all(float(x) == float(y) for x, y in zip(a, b))
