@@ -73,12 +73,18 @@ typedef enum { FASTCLIP_F32 = 0, FASTCLIP_BF16 = 1 } fastclip_dtype;
  * default path up to summation order.  NOT enabled by default: see the design notes (one of thirteen runs on hardware
  * ended in a memory fault whose cause has not been found). */
 #define FASTCLIP_FINE_TILES 2
+/* FASTCLIP_SINGLE_PASS (bf16 path, b == B): form the similarity matrix ONCE whatever the batch size: with the whole batch
+ * local the text strip is the transpose of the image strip, so every dot product yields both exponentials (Proc. 1 with
+ * k = K = 1).  Without the flag the library does so when it pays (more 256 x 256 tiles than compute units) and forms the
+ * two strips separately below that, where twice the workgroups finish sooner.  Same results up to summation order.
+ * Ignored when b < B or on the fp32 path. */
+#define FASTCLIP_SINGLE_PASS 4
 
 typedef struct {
   uint32_t struct_size;      /* sizeof(fastclip_config) */
   int32_t  version;          /* fastclip_version_t */
   int32_t  emb_dtype;        /* fastclip_dtype */
-  int32_t  flags;            /* 0 or an OR of FASTCLIP_GATHERED_STATE, FASTCLIP_FINE_TILES; any other bit is an error */
+  int32_t  flags;            /* 0 or an OR of the FASTCLIP_* flags above; any other bit is an error */
   int64_t  B, b, off, d;     /* global rows, local anchors, first local row, embedding width */
   int64_t  ld_img, ld_txt;   /* row strides of img_glob / txt_glob in elements, >= d */
   int64_t  N;                /* samples in the state arrays */

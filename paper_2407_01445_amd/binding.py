@@ -16,6 +16,7 @@ OK, ERR_NULL, ERR_SHAPE, ERR_VALUE, ERR_WORKSPACE, ERR_UNSUPPORTED, ERR_LAUNCH, 
 V0, V1, V2, V3 = 0, 1, 2, 3
 GATHERED_STATE = 1
 FINE_TILES = 2
+SINGLE_PASS = 4
 F32, BF16 = 0, 1
 N_PHASES = 8
 

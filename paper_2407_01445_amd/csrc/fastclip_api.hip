@@ -28,7 +28,7 @@ static fastclip_status hip_failed(hipError_t e) {
 
 fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
   if (!cfg) return FASTCLIP_ERR_NULL;
-  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~(FASTCLIP_GATHERED_STATE | FASTCLIP_FINE_TILES)))
+  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~(FASTCLIP_GATHERED_STATE | FASTCLIP_FINE_TILES | FASTCLIP_SINGLE_PASS)))
     return FASTCLIP_ERR_SHAPE;
   if (cfg->B < 2 || cfg->b < 1 || cfg->off < 0 || cfg->off + cfg->b > cfg->B || cfg->d < 1 ||
       cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1 || cfg->b > cfg->N || cfg->state_stride < 1 ||
@@ -116,9 +116,8 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   L->ncol = (int64_t)round_up((size_t)cfg.B, kTileContrasts);
   // forming the similarity matrix once halves the MFMA work of the strip phase but doubles the epilogue of every
   // tile: it pays once the tiles outnumber the compute units (below that one tile's latency is the phase's time)
-  const int64_t bt = cfg.B / kTileContrasts;
-  L->square = L->bf16 && cfg.b == cfg.B && cfg.B % kTileContrasts == 0 && cfg.d % 64 == 0 && cfg.d >= 128 &&
-              2 * bt * bt > 256;
+  const int64_t bt = (cfg.B + kTileContrasts - 1) / kTileContrasts;
+  L->square = L->bf16 && cfg.b == cfg.B && (2 * bt * bt > 256 || (cfg.flags & FASTCLIP_SINGLE_PASS));
   // Fine tiles (opt-in) where 256 x 256 tiles would leave most of the chip idle: fewer large strip tiles than three
   // quarters of the compute units (one per compute unit is what the large-tile kernels are built for).
   const int64_t big_tiles = 2 * ((cfg.b + 255) / 256) * ((cfg.B + 255) / 256);
@@ -201,7 +200,7 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   } else {
     for (int s = 0; s < 2; ++s) L->E[s] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
   }
-  if (L->square) L->F[0] = take(esz * (size_t)cfg.b * (size_t)L->ldE);
+  if (L->square) L->F[0] = take(esz * round_up((size_t)cfg.b, 256) * (size_t)L->ldE);
   if (L->gathered) {
     L->colp = take(sizeof(float) * 2 * 4 * (size_t)L->ncol);
     if (L->bf16) {

@@ -51,7 +51,7 @@ struct Layout {
   int fine;          // 1: MFMA path on fine tiles (kernels_fine.hip): 128 x 128 strip tiles, 64 x 64 output tiles of the
                      //    contraction; nparts counts 128-column tiles, nsplit / kslice count 64-deep stages, and with one
                      //    split there are no partial results
-  int square;        // 1: MFMA path, b == B and only whole tiles: the similarity matrix is formed once (F[0] holds
+  int square;        // 1: MFMA path, b == B: the similarity matrix is formed once (F[0] holds
                      //    l2(j, p) in the layout of E[0] until the fold transposes it into E[1])
   int64_t ncol;      // gathered: entries per column-parameter array (B rounded up to whole 256-column tiles)
   size_t diag, tau1, tau2, k1, k2;   // float[bstride]

@@ -277,25 +277,103 @@ __device__ __forceinline__ void guarded_mainloop(f32x16 (&acc)[4][4], const Tile
   __syncthreads();
 }
 
+// Second pass over the accumulators of one wave of an edge tile when the whole batch is local (b == B, off == 0; the
+// first pass is strip_epilogue with the image anchors' row parameters).  Every element s_pj also yields
+// f = l2(j, p) = 2^((s - s_jj) log2(e)/tau2_j) of the TEXT anchor j = its contrast column; f goes to the second strip
+// F[0] in the form of E[0] and is summed over the wave's anchors.  scol_k / scol_d: log2(e)/tau2_j and s_jj of the
+// tile's 256 columns (0 beyond the batch); sredc_w[quantity][column inside the tile] receives the wave's column sums
+// of f and of (s - s_jj) f.  Zero outside the batch and on the diagonal j == p (B_{j-} excludes j).  Accumulator
+// (ti, tj, v) of lane (lr, hk): contrast c0 + cw + 32 ti + 8 (v >> 2) + 4 hk + (v & 3), anchor a0 + aw + 32 tj + lr.
+__device__ __forceinline__ void edge_epilogue_cols(const StripArgs& a, f32x16 (&acc)[4][4], const float* scol_k,
+                                                   const float* scol_d, float (*sredc_w)[256], int64_t a0, int64_t c0,
+                                                   int cw, int aw, int lane) {
+  const int lr = lane & 31, hk = lane >> 5;
+  const int B = (int)a.B, b = (int)a.b;
+  bf16_t* __restrict__ F = a.F[0];
+  const int64_t ab0 = (a0 + aw) >> 5, cb0 = (c0 + cw) >> 4;
+#pragma unroll
+  for (int ti = 0; ti < 4; ++ti) {
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {            // the 16-byte fragment store j holds the groups g = 2 j, 2 j + 1
+      const int cl = cw + ti * 32 + 16 * j + 4 * hk;     // column inside the tile of (g = 2 j, q = 0)
+      const float4 k0 = *(const float4*)(scol_k + cl), k1 = *(const float4*)(scol_k + cl + 8);
+      const float4 d0 = *(const float4*)(scol_d + cl), d1 = *(const float4*)(scol_d + cl + 8);
+      const float ck[8] = {k0.x, k0.y, k0.z, k0.w, k1.x, k1.y, k1.z, k1.w};
+      const float cdk[8] = {d0.x * k0.x, d0.y * k0.y, d0.z * k0.z, d0.w * k0.w,
+                            d1.x * k1.x, d1.y * k1.y, d1.z * k1.z, d1.w * k1.w};
+      float cs[16];                          // column sums of this lane: f of 8 columns, then t f of 8 columns
+#pragma unroll
+      for (int i = 0; i < 16; ++i) cs[i] = 0.f;
+      const int64_t cb = cb0 + 2 * ti + j;
+#pragma unroll
+      for (int tj = 0; tj < 4; ++tj) {
+        const int anchor = (int)a0 + aw + tj * 32 + lr;
+        uint32_t pf[4];
+#pragma unroll
+        for (int gi = 0; gi < 2; ++gi) {
+          const int g = 2 * j + gi;
+          float t2[4], f[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) t2[q] = fmaf(acc_read(acc[ti][tj][4 * g + q]), ck[4 * gi + q], -cdk[4 * gi + q]);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int c = (int)c0 + cl + 8 * gi + q;
+            const bool ok = (c < B) && (anchor < b) && (c != anchor);
+            f[q] = ok ? __builtin_amdgcn_exp2f(t2[q]) : 0.f;
+          }
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            cs[4 * gi + q] += f[q];
+            cs[8 + 4 * gi + q] = fmaf(t2[q], f[q], cs[8 + 4 * gi + q]);
+          }
+          pf[2 * gi] = pack_bf16x2(f[0], f[1]);
+          pf[2 * gi + 1] = pack_bf16x2(f[2], f[3]);
+          FC_PIN();
+        }
+        const u32x4 wf = {pf[0], pf[1], pf[2], pf[3]};
+        if (16 * cb < a.ldE) *(u32x4*)(F + (((ab0 + tj) * a.nCBF + cb) * 64 + lane) * 8) = wf;
+        FC_PIN();
+      }
+      // divide the second quantity by log2(e)/tau_j while each lane still knows its columns, then sum over the lanes
+#pragma unroll
+      for (int i = 0; i < 8; ++i) cs[8 + i] = ck[i] > 0.f ? cs[8 + i] * __builtin_amdgcn_rcpf(ck[i]) : 0.f;
+      lanes32_sum(cs, lane);
+      if ((lr & 1) == 0) {
+        const int v = lr >> 1, gi = (v >> 2) & 1, q = v & 3;     // value v = 8 quantity + 4 gi + q
+        sredc_w[v >> 3][cl + 8 * gi + q] = cs[0];
+      }
+      FC_PIN();
+    }
+  }
+}
+
 // Tiles with a ragged edge (anchors, contrasts or width not a multiple of the tile): one workgroup per tile,
-// guarded loads, guarded epilogue.
+// guarded loads, guarded epilogue.  When the whole batch is local and the similarity matrix is formed once
+// (StripArgs::square) the tile also yields the text anchors' exponentials and their sums down the columns.
 __global__ void __launch_bounds__(256) k_strips_edge_bf16(StripArgs a) {
   __shared__ __attribute__((aligned(1024))) char ring[kStageBytes];
   __shared__ float sk[256];
   __shared__ float sdiag[256];
   __shared__ float sred[2][2][256];
+  __shared__ __attribute__((aligned(16))) float scol[2][256];   // square: log2(e)/tau2_j and s_jj of the tile's columns
+  __shared__ float sredc[2][2][256];                            // square: [anchor half][quantity][column]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   const int t = blockIdx.x;
   const int per_strip = a.nAT * a.nCT;
   const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
-  const int64_t a0 = strip_anchor_first(a, at), c0 = (int64_t)ct * 256;
+  const int64_t a0 = strip_anchor_first(a, at, a.square), c0 = (int64_t)ct * 256;
   if (strip_tile_is_interior(a, a0, c0)) return;
   const int S = (int)((a.d + BK - 1) / BK);
   {
     const int64_t m = a0 + tid;
     sk[tid] = m < a.b ? a.kscale[strip][m] : 0.f;
     sdiag[tid] = m < a.b ? a.diag[m] : 0.f;
+    if (a.square) {                    // off == 0: text anchor j is global row j
+      const int64_t j = c0 + tid;
+      scol[0][tid] = j < a.b ? a.kscale[1][j] : 0.f;
+      scol[1][tid] = j < a.b ? a.diag[j] : 0.f;
+    }
   }
   StripTile T;
   T.setup(a.contrasts[strip], a.ld_contrast[strip], c0, a.B, a.anchors[strip], a.ld_anchor[strip], a0, a.b, a.d, tid);
@@ -303,12 +381,20 @@ __global__ void __launch_bounds__(256) k_strips_edge_bf16(StripArgs a) {
   zero_acc(acc);
   guarded_mainloop(acc, T, ring, 0, S, tid);
   strip_epilogue<true, 4, 4>(a, acc, sk, sdiag, sred[wr], strip, a0, c0, wr * 128, wc * 128, lane);
+  if (a.square) edge_epilogue_cols(a, acc, scol[0], scol[1], sredc[wc], a0, c0, wr * 128, wc * 128, lane);
   __syncthreads();
   const int64_t m = a0 + tid;
   if (m < a.b) {
 #pragma unroll
     for (int q = 0; q < 2; ++q)
       a.sums[((size_t)(2 * strip + q) * a.nparts + ct) * a.bstride + m] = sred[0][q][tid] + sred[1][q][tid];
+  }
+  // the text anchors' sums (quantities 2, 3): partial number = the anchor tile, position = the column
+  const int64_t j = c0 + tid;
+  if (a.square && j < a.b) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+      a.sums[((size_t)(2 + q) * a.nparts + at) * a.bstride + j] = sredc[0][q][tid] + sredc[1][q][tid];
   }
 }
 
@@ -363,7 +449,7 @@ static void make_strip_args(const StepCtx& c, StripArgs* out, bool* any_interior
   const bool d_ok = L.d % 64 == 0 && L.d >= 128;
   bool any_interior = false, any_edge = !d_ok || (L.B % 256);
   for (int at = 0; at < a.nAT; ++at) {
-    const bool in = strip_tile_is_interior(a, strip_anchor_first(a, at), 0);
+    const bool in = strip_tile_is_interior(a, strip_anchor_first(a, at, a.square), 0);
     any_interior |= in && L.B >= 256;
     any_edge |= !in;
   }
@@ -524,7 +610,8 @@ __global__ void __launch_bounds__(256) k_fold_bf16(bf16_t* __restrict__ E0, bf16
 
 // The same when the whole batch is local and the similarity matrix was formed once: F0[r][q] holds l2(q, p_r) in the
 // layout of E0 (off == 0), so w = c1_r E0[r][q] + c2_q F0[r][q]; w / c1_r goes back to E0[r][q] and w / c2_q, transposed,
-// to E1[q][r], which nothing has written before.  b is a multiple of 256 here.
+// to E1[q][r], which nothing has written before: a block writes all 64 columns of its rows of E1, zeros beyond the
+// batch, so that every column of E1 up to its padded width holds a number for the contraction.
 __global__ void __launch_bounds__(256) k_fold_square_bf16(bf16_t* __restrict__ E0, const bf16_t* __restrict__ F0,
                                                           bf16_t* __restrict__ E1, int64_t nCB, StateArgs a) {
   __shared__ float t0[64][65];   // [r][q]: l1(r, q), then w / c1_r
@@ -538,6 +625,7 @@ __global__ void __launch_bounds__(256) k_fold_square_bf16(bf16_t* __restrict__ E
   fold_load(F0, nCB, r0, q0, b, t1);
   if (a.fused) fold_coefficients(a, r0, q0, sc, fs);
   __syncthreads();
+  const int nr = (int)(b - r0 < 64 ? b - r0 : 64), nq = (int)(b - q0 < 64 ? b - q0 : 64);
   float keep[16];
   {
     const int ql = threadIdx.x & 63;
@@ -545,7 +633,7 @@ __global__ void __launch_bounds__(256) k_fold_square_bf16(bf16_t* __restrict__ E
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int rl = (threadIdx.x >> 6) + 4 * i;
-      const float w = fmaf(sc[0][rl], t0[rl][ql], cq * t1[rl][ql]);
+      const float w = (rl < nr && ql < nq) ? fmaf(sc[0][rl], t0[rl][ql], cq * t1[rl][ql]) : 0.f;
       t0[rl][ql] = w * sc[2][rl];
       keep[i] = w * icq;
     }
@@ -620,7 +708,6 @@ struct ContractJob {
   size_t split_stride;
   int64_t nCB;        // column blocks (of 16) per anchor block of E
   int stages, slice;  // 32-deep stages in all; stages per split
-  int all_rows_valid; // no zero rows inside the column range (B == ldE)
 };
 struct ContractArgs {
   ContractJob job[2];   // the two strips
@@ -648,12 +735,20 @@ __global__ void __launch_bounds__(256) k_contract_bf16(ContractArgs g) {
   if (S > 0) {
     ContractTile T;
     T.setup(J.E, J.nCB, m0 >> 5, J.X, J.ldx, n0, g.N, g.B, tid);
-    if (J.all_rows_valid && n0 + 256 <= g.N) {
-      ring_prologue(T, ring_addr, s0, S);
-      ring_mainloop(acc, T, ring, ring_addr, s0, S);
-    } else {
-      guarded_mainloop(acc, T, ring, s0, S, tid);
+    // The unguarded loads of a stage take 32 whole rows of X and 256 columns from n0 on.  They stay inside the matrix
+    // (B rows of ldx elements, the last one of N) for the stages below `safe`: rows beyond B never, and where the tile
+    // is wider than what is left of a row (n0 + 256 > N) the words past the row's end are the next rows' - they exist
+    // except behind the last rows, and what they put into the columns from N on reaches no output.  Those stages run
+    // through the ring; the few that are left at the ragged end go one at a time with guards.
+    int64_t rows_ok = g.B;
+    if (n0 + 256 > g.N) rows_ok -= (n0 + 256 - g.N + J.ldx - 1) / J.ldx;
+    const int safe = rows_ok > 0 ? (int)(rows_ok / BK) : 0;
+    const int S_ring = s0 + S <= safe ? S : (safe > s0 ? safe - s0 : 0);
+    if (S_ring > 0) {
+      ring_prologue(T, ring_addr, s0, S_ring);
+      ring_mainloop(acc, T, ring, ring_addr, s0, S_ring);
     }
+    if (S_ring < S) guarded_mainloop(acc, T, ring, s0 + S_ring, S - S_ring, tid);
   }
   // The partial result leaves as whole tiles of [64 groups of 4 rows][256 columns][4 rows]: a lane holds C[m][n] for
   // n = n0 + wn 128 + tj 32 + lr and the rows m = m0 + wm 128 + ti 32 + 8 q + 4 hk + t, t = 0..3, so its four values of one
@@ -688,7 +783,6 @@ void launch_contract_bf16(const StepCtx& c) {
     J.nCB = L.ldE / 16;
     J.stages = (int)(L.ldE / BK);
     J.slice = (int)L.kslice;
-    J.all_rows_valid = L.B == L.ldE;
   }
   g.M = L.b; g.N = L.d; g.B = L.B;
   g.nsplit = L.nsplit;

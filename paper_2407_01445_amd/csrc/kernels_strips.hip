@@ -199,27 +199,6 @@ __device__ __forceinline__ void half_epilogue_remote(f32x16 (&acc)[2][4], const 
   }
 }
 
-// Sum of v[i] over the 32 lanes that share (lane >> 5), for 16 values at once: each step halves the number of values
-// a lane carries (the lower half of a lane pair keeps the first half of the values, the upper half the second), so
-// 16 values cost 16 exchanges instead of 80.  On return v[0] of lane l is the total of value number (l & 31) >> 1.
-template <int HALF, int MASK>
-__device__ __forceinline__ void lanes32_halve(float (&v)[16], int lane) {
-  const bool upper = (lane & MASK) != 0;
-#pragma unroll
-  for (int i = 0; i < HALF; ++i) {
-    const float send = upper ? v[i] : v[i + HALF];
-    const float keep = upper ? v[i + HALF] : v[i];
-    v[i] = keep + __shfl_xor(send, MASK);
-  }
-}
-__device__ __forceinline__ void lanes32_sum(float (&v)[16], int lane) {
-  lanes32_halve<8, 16>(v, lane);
-  lanes32_halve<4, 8>(v, lane);
-  lanes32_halve<2, 4>(v, lane);
-  lanes32_halve<1, 2>(v, lane);
-  v[0] += __shfl_xor(v[0], 1);
-}
-
 // Second pass over the accumulators of one wave when the whole batch is local (the first pass is half_epilogue, with
 // the image anchors' row parameters).  Every element s_pj also yields f = l2(j, p) = 2^((s - s_jj) log2(e)/tau2_j) of
 // the TEXT anchor j = its contrast column; f is stored in a second strip of the same form (fragF0) and summed over the
@@ -330,7 +309,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   const int per_strip = a.nAT * a.nCT;
   auto next_interior = [&](int tt) {
     while (tt < a.ntiles &&
-           !strip_tile_is_interior(a, strip_anchor_first(a, tt % a.nAT), (int64_t)((tt / a.nAT) % a.nCT) * 256))
+           !strip_tile_is_interior(a, strip_anchor_first(a, tt % a.nAT, SQUARE), (int64_t)((tt / a.nAT) % a.nCT) * 256))
       tt += G;
     return tt;
   };
@@ -357,7 +336,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   auto open_a = [&](int tt) {
     const int strip = tt / per_strip, at = tt % a.nAT;
     const int64_t ld = a.ld_anchor[strip];
-    qa = a.anchors[strip] + strip_anchor_first(a, at) * ld;
+    qa = a.anchors[strip] + strip_anchor_first(a, at, SQUARE) * ld;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int row = 8 * (4 * wave + i) + (lane >> 3);
@@ -420,7 +399,7 @@ __global__ void __launch_bounds__(512, 2) k_strips_bf16(StripArgs a) {
   bool after_epilogue = false;
   while (t < a.ntiles) {
     const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
-    const int a_first = (int)strip_anchor_first(a, at), c_tile = ct * 256;
+    const int a_first = (int)strip_anchor_first(a, at, SQUARE), c_tile = ct * 256;
     f32x16 acc[2][4];
     zero_acc24(acc);
 #pragma unroll 1

@@ -123,9 +123,11 @@ struct StripArgs {
 // anchors left is moved back to end exactly at b when the 32-anchor blocks of the stored strips allow it (b >= 256,
 // b % 32 == 0): it then recomputes some anchors of the tile before it - to the same bits, every anchor's values and
 // sums depend on its row and on the contrast tile only - and is a whole tile on every worker, also the last one.
-__host__ __device__ __forceinline__ int64_t strip_anchor_first(const StripArgs& a, int at) {
+// Not when the similarity matrix is formed once (square): there the tiles also sum down their columns over the anchors,
+// and an anchor computed twice would be counted twice.
+__host__ __device__ __forceinline__ int64_t strip_anchor_first(const StripArgs& a, int at, bool square) {
   const int64_t a0 = (int64_t)at * 256;
-  return (a0 + 256 > a.b && a.b >= 256 && a.b % 32 == 0) ? a.b - 256 : a0;
+  return (!square && a0 + 256 > a.b && a.b >= 256 && a.b % 32 == 0) ? a.b - 256 : a0;
 }
 __host__ __device__ __forceinline__ bool strip_tile_is_interior(const StripArgs& a, int64_t a0, int64_t c0) {
   return (a.off + a0 + 256 <= a.B) && (c0 + 256 <= a.B) && (a.d % 64 == 0) && (a.d >= 128);
@@ -226,6 +228,27 @@ __device__ __forceinline__ void strip_epilogue(const StripArgs& a, f32x16 (&acc)
       sred_w[1][al] = kk > 0.f ? st * __builtin_amdgcn_rcpf(kk) : 0.f;   // sum of (s - s_pp) l
     }
   }
+}
+
+// Sum of v[i] over the 32 lanes that share (lane >> 5), for 16 values at once: each step halves the number of values
+// a lane carries (the lower half of a lane pair keeps the first half of the values, the upper half the second), so
+// 16 values cost 16 exchanges instead of 80.  On return v[0] of lane l is the total of value number (l & 31) >> 1.
+template <int HALF, int MASK>
+__device__ __forceinline__ void lanes32_halve(float (&v)[16], int lane) {
+  const bool upper = (lane & MASK) != 0;
+#pragma unroll
+  for (int i = 0; i < HALF; ++i) {
+    const float send = upper ? v[i] : v[i + HALF];
+    const float keep = upper ? v[i + HALF] : v[i];
+    v[i] = keep + __shfl_xor(send, MASK);
+  }
+}
+__device__ __forceinline__ void lanes32_sum(float (&v)[16], int lane) {
+  lanes32_halve<8, 16>(v, lane);
+  lanes32_halve<4, 8>(v, lane);
+  lanes32_halve<2, 4>(v, lane);
+  lanes32_halve<1, 2>(v, lane);
+  v[0] += __shfl_xor(v[0], 1);
 }
 
 void launch_strips_interior_bf16(const StripArgs& a, hipStream_t s);   // kernels_strips.hip

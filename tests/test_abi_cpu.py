@@ -84,11 +84,27 @@ def test_struct_size_and_flags_are_checked():
     cfg.struct_size = 8
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
     cfg = good_cfg()
-    cfg.flags = 4
+    cfg.flags = 8
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
-    cfg.flags = fc.GATHERED_STATE | fc.FINE_TILES
+    cfg.flags = fc.GATHERED_STATE | fc.FINE_TILES | fc.SINGLE_PASS
     assert fc.fastclip_validate(cfg, None) == fc.OK
     assert fc.fastclip_validate(None, None) == fc.ERR_NULL
+
+
+def test_single_pass_flag_adds_the_second_strip_only_when_the_whole_batch_is_local():
+    """FASTCLIP_SINGLE_PASS keeps l2(j, p) in a strip of its own until the fold transposes it: one more strip of workspace
+    when b == B on the bf16 path, nothing otherwise; a batch with more 256 x 256 tiles than compute units takes that form
+    without the flag, ragged or not."""
+    full = dict(B=520, b=520, off=0, d=64, ld_img=64, ld_txt=64)
+    plain, single = good_cfg(**full), good_cfg(flags=fc.SINGLE_PASS, **full)
+    strip = 2 * 768 * 576                      # bf16, anchors padded to 256, columns to 64
+    assert fc.fastclip_workspace_bytes(single) - fc.fastclip_workspace_bytes(plain) == strip
+    share = dict(B=520, b=260, off=0, d=64, ld_img=64, ld_txt=64)
+    assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.SINGLE_PASS, **share)) == fc.fastclip_workspace_bytes(good_cfg(**share))
+    f32 = dict(emb_dtype=fc.F32, **full)
+    assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.SINGLE_PASS, **f32)) == fc.fastclip_workspace_bytes(good_cfg(**f32))
+    big = dict(B=3000, b=3000, off=0, d=128, ld_img=128, ld_txt=128)
+    assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.SINGLE_PASS, **big)) == fc.fastclip_workspace_bytes(good_cfg(**big))
 
 
 def test_fine_tiles_flag_changes_the_workspace_only_for_small_batches():

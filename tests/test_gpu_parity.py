@@ -248,6 +248,70 @@ def test_bf16_small_shapes(B, b, off, d, version):
     check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
 
 
+SINGLE_PASS_SHAPES = [
+    # b == B, off == 0, ragged in anchors / contrasts / width: every tile is guarded
+    (520, 520, 64), (1000, 1000, 136), (257, 257, 8), (300, 300, 72), (40, 40, 16),
+    # whole tiles only (the persistent kernel alone), forced below the size at which the library chooses the mode
+    (768, 768, 192), (512, 512, 128),
+    # whole tiles of the persistent kernel next to guarded ones (ragged last row and column of tiles)
+    (900, 900, 128), (1100, 1100, 256),
+]
+
+
+@pytest.mark.parametrize("B,b,d", SINGLE_PASS_SHAPES)
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_bf16_single_similarity_pass_on_any_shape(B, b, d, version):
+    """FASTCLIP_SINGLE_PASS: with the whole batch local the similarity matrix is formed once (the text strip is the
+    transpose of the image strip), also where tiles are ragged: against the oracle, and close to the two-strip form."""
+    N = 5000
+    rng = np.random.default_rng(B + 7 * version)
+    img, txt = make_embeddings(B + d + 1, B, d, 0.5, "bf16")
+    idx = draw_indices(B + 2, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    outs = []
+    for single in (True, False):
+        g = GpuStep(B=B, b=b, off=0, d=d, N=N, dtype="bf16", version=version, eps=1e-6, rho=6.5, tau=0.07,
+                    tau_grad_scale=1.0 / N, ld_img=d, ld_txt=d + 8, u_img0=u0i, u_txt0=u0t, tau_img0=t_img,
+                    tau_txt0=t_txt, single_pass=single)
+        g.set_inputs(img, txt, idx)
+        g.step(0.6)
+        u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+        want = oracle_step(g, img, txt, idx, u_img, u_txt, 0.6, tau=float(np.float32(0.07)),
+                           tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64))
+        compare(g.outputs(), want, version, TOL_BF16, "bf16 single pass %s %s v%d" % (single, (B, b, d), version))
+        check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
+        outs.append(g.outputs())
+    # the two forms round the same dot products: sums differ in their order only
+    for k in ("g_img", "g_txt", "u_new_img", "u_new_txt"):
+        assert rel_each(outs[0][k], outs[1][k]) < 1e-4, k
+
+
+def test_bf16_single_similarity_pass_chosen_by_the_library_on_a_ragged_batch():
+    """3000 x 3000 pairs: more 256 x 256 tiles than compute units, so the library forms the similarity matrix once without
+    being asked; 11 x 11 whole tiles go to the persistent kernel, the ragged last row and column to the guarded one."""
+    B = b = 3000
+    d, N = 128, 20_000
+    rng = np.random.default_rng(77)
+    img, txt = make_embeddings(78, B, d, 0.5, "bf16")
+    idx = draw_indices(79, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    g = GpuStep(B=B, b=b, off=0, d=d, N=N, dtype="bf16", version=V2, eps=1e-6, rho=6.5, tau=0.07,
+                tau_grad_scale=1.0 / N, u_img0=u0i, u_txt0=u0t, tau_img0=t_img, tau_txt0=t_txt)
+    g.set_inputs(img, txt, idx)
+    g.step(0.6)
+    u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+    want = oracle_step(g, img, txt, idx, u_img, u_txt, 0.6, tau=0.07, tau_img=t_img.astype(np.float64),
+                       tau_txt=t_txt.astype(np.float64))
+    compare(g.outputs(), want, V2, TOL_BF16, "bf16 single pass 3000", tol_measured=TOL_BF16_MEASURED)
+    check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
+
+
 FINE_TILES_OFF = ("FASTCLIP_FINE_TILES is switched off on the GPU: after twelve steps on this path that agreed with the oracle "
                   "(four on this very shape), a thirteenth ended in a GPU memory fault; a CPU emulation of every index the two "
                   "kernels form finds all of them in bounds, no cause has been shown, so the path is not run on the GPU")
