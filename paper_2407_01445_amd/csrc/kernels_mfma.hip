@@ -51,13 +51,16 @@ struct StripTile {
     X = Xc + c0 * ldx_; ldx = ldx_; x_rows = B - c0;
     A = An + a0 * lda_; lda = lda_; a_rows = b - a0;
     d = d_;
+    // The unguarded wave loads fetch, for a row of the tile that does not exist, the tile's last existing row instead
+    // (x_rows, a_rows >= 1): whatever such a row contributes lands in elements that the guarded epilogue discards.
+    const int x_last = (int)(x_rows < 256 ? x_rows : 256) - 1, a_last = (int)(a_rows < 256 ? a_rows : 256) - 1;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int j = wave * 4 + i;                      // wave load j covers rows 16 j .. 16 j + 15 of the tile
       const int row = 16 * j + (lane >> 2);
       const int chunk = (lane & 3) ^ rt_swz(row);      // logical chunk fetched into position (lane & 3)
-      oa[i] = (uint32_t)(row * (int)ldx_ + chunk * 8) * 2u;
-      ob[i] = (uint32_t)(row * (int)lda_ + chunk * 8) * 2u;
+      oa[i] = (uint32_t)((row < x_last ? row : x_last) * (int)ldx_ + chunk * 8) * 2u;
+      ob[i] = (uint32_t)((row < a_last ? row : a_last) * (int)lda_ + chunk * 8) * 2u;
       la[i] = (uint32_t)(j * 1024);
       lb[i] = (uint32_t)(kOpBytes + j * 1024);
     }
@@ -84,6 +87,9 @@ struct StripTile {
   }
   __device__ __forceinline__ bf16x8 read_b(const char* slot, int t, int kk) const {
     return *(const bf16x8*)(slot + kOpBytes + rt_off(wc_ * 128 + t * 32 + lr, kk * 2 + hk));
+  }
+  __device__ __forceinline__ u32x2 read_b_half(const char* slot, int t, int kk, int half) const {   // for the ring loop
+    return *(const u32x2*)(slot + kOpBytes + rt_off(wc_ * 128 + t * 32 + lr, kk * 2 + hk) + 8 * half);
   }
 };
 
@@ -347,16 +353,19 @@ __device__ __forceinline__ void edge_epilogue_cols(const StripArgs& a, f32x16 (&
   }
 }
 
-// Tiles with a ragged edge (anchors, contrasts or width not a multiple of the tile): one workgroup per tile,
-// guarded loads, guarded epilogue.  When the whole batch is local and the similarity matrix is formed once
-// (StripArgs::square) the tile also yields the text anchors' exponentials and their sums down the columns.
+// Tiles with a ragged edge (anchors, contrasts or width not a multiple of the tile): one workgroup per tile, guarded
+// epilogue.  The stages that lie wholly inside the width run through the ring of the contraction kernel with unguarded
+// direct-to-LDS loads (rows that do not exist are replaced by the tile's last existing row, see StripTile::setup); a
+// ragged last stage goes through registers with zero fill.  When the whole batch is local and the similarity matrix is
+// formed once (StripArgs::square) the tile also yields the text anchors' exponentials and their sums down the columns.
+// After the main loop the ring is free and holds the epilogue's scalars and cross-wave sums.
 __global__ void __launch_bounds__(256) k_strips_edge_bf16(StripArgs a) {
-  __shared__ __attribute__((aligned(1024))) char ring[kStageBytes];
-  __shared__ float sk[256];
-  __shared__ float sdiag[256];
-  __shared__ float sred[2][2][256];
-  __shared__ __attribute__((aligned(16))) float scol[2][256];   // square: log2(e)/tau2_j and s_jj of the tile's columns
-  __shared__ float sredc[2][2][256];                            // square: [anchor half][quantity][column]
+  __shared__ __attribute__((aligned(1024))) char ring[kRingBytes];
+  float* sk = (float*)ring;                                          // [256] log2(e)/tau of the tile's anchors
+  float* sdiag = sk + 256;                                           // [256] s_pp
+  float (*sred)[2][256] = (float (*)[2][256])(ring + 2048);          // [contrast half][quantity][anchor]
+  float* scol = (float*)(ring + 6144);                               // square: [2][256] log2(e)/tau2_j, s_jj of the columns
+  float (*sredc)[2][256] = (float (*)[2][256])(ring + 8192);         // square: [anchor half][quantity][column]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wr = wave >> 1, wc = wave & 1;
   const int t = blockIdx.x;
@@ -364,24 +373,29 @@ __global__ void __launch_bounds__(256) k_strips_edge_bf16(StripArgs a) {
   const int strip = t / per_strip, at = t % a.nAT, ct = (t / a.nAT) % a.nCT;
   const int64_t a0 = strip_anchor_first(a, at, a.square), c0 = (int64_t)ct * 256;
   if (strip_tile_is_interior(a, a0, c0)) return;
-  const int S = (int)((a.d + BK - 1) / BK);
+  const int S = (int)((a.d + BK - 1) / BK), S_ring = (int)(a.d / BK);
+  StripTile T;
+  T.setup(a.contrasts[strip], a.ld_contrast[strip], c0, a.B, a.anchors[strip], a.ld_anchor[strip], a0, a.b, a.d, tid);
+  f32x16 acc[4][4];
+  zero_acc(acc);
+  if (S_ring > 0) {
+    ring_prologue(T, lds_addr(ring), 0, S_ring);
+    ring_mainloop(acc, T, ring, lds_addr(ring), 0, S_ring);
+  }
+  if (S_ring < S) guarded_mainloop(acc, T, ring, S_ring, S - S_ring, tid);
   {
     const int64_t m = a0 + tid;
     sk[tid] = m < a.b ? a.kscale[strip][m] : 0.f;
     sdiag[tid] = m < a.b ? a.diag[m] : 0.f;
     if (a.square) {                    // off == 0: text anchor j is global row j
       const int64_t j = c0 + tid;
-      scol[0][tid] = j < a.b ? a.kscale[1][j] : 0.f;
-      scol[1][tid] = j < a.b ? a.diag[j] : 0.f;
+      scol[tid] = j < a.b ? a.kscale[1][j] : 0.f;
+      scol[256 + tid] = j < a.b ? a.diag[j] : 0.f;
     }
   }
-  StripTile T;
-  T.setup(a.contrasts[strip], a.ld_contrast[strip], c0, a.B, a.anchors[strip], a.ld_anchor[strip], a0, a.b, a.d, tid);
-  f32x16 acc[4][4];
-  zero_acc(acc);
-  guarded_mainloop(acc, T, ring, 0, S, tid);
+  __syncthreads();
   strip_epilogue<true, 4, 4>(a, acc, sk, sdiag, sred[wr], strip, a0, c0, wr * 128, wc * 128, lane);
-  if (a.square) edge_epilogue_cols(a, acc, scol[0], scol[1], sredc[wc], a0, c0, wr * 128, wc * 128, lane);
+  if (a.square) edge_epilogue_cols(a, acc, scol, scol + 256, sredc[wc], a0, c0, wr * 128, wc * 128, lane);
   __syncthreads();
   const int64_t m = a0 + tid;
   if (m < a.b) {
