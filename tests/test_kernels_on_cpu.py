@@ -1,0 +1,158 @@
+"""The kernels' own sources, compiled for the host against a stand-in for the HIP runtime and the gfx950 builtins
+(tests/emu), run one small step per code path under AddressSanitizer and are compared with the oracle.
+
+What this can show: an access outside a buffer (every buffer is an exact-size allocation, the matrices end with the
+last row's d elements), a barrier that not every thread reaches (the run would hang: bounded by a time-out), wrong
+indexing (the outputs would disagree with the oracle).  What it cannot: timing, the asynchrony of direct-to-LDS loads
+(they copy at once here), anything the GPU compiler does.  It is also the only place where the opt-in fine-tile path
+runs as long as it is kept off the GPU."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, os.path.join(ROOT, "tests", "emu"))
+import build_emu  # noqa: E402
+
+from oracle import V0, V1, V2, V3, fcco_step  # noqa: E402
+from paper_2407_01445_amd import binding as fc  # noqa: E402
+from paper_2407_01445_amd.workloads import draw_indices, make_embeddings  # noqa: E402
+
+pytestmark = pytest.mark.skipif(build_emu.host_compiler() is None, reason="no host clang++ to build the emulation with")
+
+
+# FASTCLIP_EMU_SANITIZER=thread (missing barriers show as data races on the LDS arrays) or =memory (with the workspace
+# and the outputs left uninitialised: a value nobody wrote that reaches a branch, an address or an output) instead of
+# the default AddressSanitizer; all three are clean on every case below.
+SANITIZER = os.environ.get("FASTCLIP_EMU_SANITIZER", "address")
+
+
+@pytest.fixture(scope="module")
+def emu_step():
+    return build_emu.build("-fsanitize=" + SANITIZER)
+
+
+def bf16_bits(x32):
+    return (np.ascontiguousarray(x32, np.float32).view(np.uint32) >> 16).astype(np.uint16)
+
+
+def run_case(exe, tmp_path, *, B, b, off, d, version, dtype="bf16", flags=0, ld_img=None, ld_txt=None, N=900, tau=0.07,
+             eps=1e-6, rho=6.5, gamma=0.6, seed=1, gathered=False):
+    ld_img, ld_txt = ld_img or d, ld_txt or d
+    rng = np.random.default_rng(seed)
+    img, txt = make_embeddings(seed + 41, B, d, 0.5, dtype)
+    idx = draw_indices(seed + 42, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    glob = None
+    if gathered:       # u^{t+1} and temperatures of every global row as other workers would have sent them
+        glob = dict(u_img=rng.uniform(0.05, 2.0, B).astype(np.float32), u_txt=rng.uniform(0.05, 2.0, B).astype(np.float32),
+                    tau_img=rng.uniform(0.05, 0.1, B).astype(np.float32), tau_txt=rng.uniform(0.05, 0.1, B).astype(np.float32))
+        flags |= fc.GATHERED_STATE
+
+    def matrix(x, ld):            # row stride ld, NaN in the padding, no padding behind the last row
+        full = np.full((B, ld), np.nan, np.float32)
+        full[:, :d] = x
+        flat = full.reshape(-1)[: (B - 1) * ld + d]
+        return bf16_bits(flat) if dtype == "bf16" else flat
+
+    fin, fout = str(tmp_path / "case.in"), str(tmp_path / "case.out")
+    with open(fin, "wb") as f:
+        np.array([version, fc.BF16 if dtype == "bf16" else fc.F32, flags, B, b, off, d, ld_img, ld_txt, N, 1,
+                  1 if gathered else 0], np.int64).tofile(f)
+        np.array([gamma, eps, rho, tau, 1.0 / N], np.float32).tofile(f)
+        matrix(img, ld_img).tofile(f)
+        matrix(txt, ld_txt).tofile(f)
+        idx.astype(np.int64).tofile(f)
+        u0i.tofile(f)
+        u0t.tofile(f)
+        if version == V2:
+            t_img.tofile(f)
+            t_txt.tofile(f)
+        if gathered:
+            glob["u_img"].tofile(f)
+            glob["u_txt"].tofile(f)
+            if version == V2:
+                glob["tau_img"].tofile(f)
+                glob["tau_txt"].tofile(f)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", TSAN_OPTIONS="report_thread_leaks=0")
+    if SANITIZER == "memory":
+        env["EMU_UNINIT"] = "1"
+    r = subprocess.run([exe, fin, fout], capture_output=True, text=True, timeout=600, env=env)
+    assert r.returncode == 0 and "Sanitizer" not in r.stderr, \
+        "the CPU build of the kernels failed (sanitizer report below)\n" + r.stderr[:6000]
+    out = np.fromfile(fout, np.float32)
+    fields = [("d_img", b * d), ("d_txt", b * d), ("loss", 1)]
+    if version in (V0, V3):
+        fields.append(("d_tau", 1))
+    if version == V2:
+        fields += [("d_tau_img", b), ("d_tau_txt", b)]
+    fields += [("g_img", b), ("g_txt", b), ("u_new_img", b), ("u_new_txt", b), ("u_img", N), ("u_txt", N)]
+    got, p = {}, 0
+    for k, n in fields:
+        got[k] = out[p:p + n].astype(np.float64)
+        p += n
+    assert p == out.size
+    ui, ut = u0i.astype(np.float64), u0t.astype(np.float64)
+    kw = {}
+    if gathered:
+        kw = dict(u_glob_img=glob["u_img"].astype(np.float64), u_glob_txt=glob["u_txt"].astype(np.float64))
+        if version == V2:
+            kw.update(tau_glob_img=glob["tau_img"].astype(np.float64), tau_glob_txt=glob["tau_txt"].astype(np.float64))
+    want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, ui, ut, version=version, gamma=gamma,
+                     eps=eps, rho=rho, tau=float(np.float32(tau)), tau_img=t_img.astype(np.float64),
+                     tau_txt=t_txt.astype(np.float64), tau_grad_scale=1.0 / N, **kw)
+    tol = 2e-2 if dtype == "bf16" else 1e-5
+    errs = {}
+    for k in ("d_img", "d_txt"):
+        errs[k] = np.max(np.abs(got[k].reshape(b, d) - want[k])) / np.max(np.abs(want[k]))
+    for k in ("g_img", "g_txt", "u_new_img", "u_new_txt"):
+        errs[k] = np.max(np.abs(got[k] - want[k]) / np.abs(want[k]))
+    errs["loss"] = abs(got["loss"][0] - want["loss"]) / want["loss_abs"]
+    if version in (V0, V3):
+        errs["d_tau"] = abs(got["d_tau"][0] - want["d_tau"]) / want["d_tau_abs"]
+    if version == V2:
+        for k in ("d_tau_img", "d_tau_txt"):
+            errs[k] = np.max(np.abs(got[k] - want[k])) / np.max(np.abs(want[k]))
+    # the state: the oracle's arrays after the step, everywhere (untouched entries bit for bit)
+    mask = np.ones(N, bool)
+    mask[idx] = False
+    assert np.array_equal(got["u_img"][mask], u0i[mask].astype(np.float64))
+    assert np.array_equal(got["u_txt"][mask], u0t[mask].astype(np.float64))
+    errs["u_img"] = np.max(np.abs(got["u_img"][idx] - ui[idx]) / ui[idx])
+    errs["u_txt"] = np.max(np.abs(got["u_txt"][idx] - ut[idx]) / ut[idx])
+    bad = {k: v for k, v in errs.items() if not v <= tol}
+    assert not bad, bad
+
+
+CASES = [
+    # fp32 accuracy path
+    dict(B=37, b=11, off=13, d=19, version=V2, dtype="f32", ld_img=23),
+    # MFMA path, every tile ragged: guarded strip tiles on the ring (rows replaced by the last one), ragged last stage,
+    # contraction with a guarded tail, fused state phase in the fold; padding between the rows of one side
+    dict(B=300, b=140, off=100, d=72, version=V3, ld_img=80),
+    dict(B=40, b=40, off=0, d=16, version=V0),
+    # whole tiles: the persistent eight-wave strip kernel and the contraction's ring, next to a ragged anchor tile
+    dict(B=512, b=300, off=212, d=128, version=V2),
+    # the whole batch local, similarity matrix formed once on ragged tiles (column pass of the guarded kernel)
+    dict(B=300, b=300, off=0, d=72, version=V2, flags=fc.SINGLE_PASS),
+    # ... and on whole tiles (column pass of the persistent kernel)
+    dict(B=512, b=512, off=0, d=128, version=V3, flags=fc.SINGLE_PASS),
+    # contrast side over every global anchor (second strip, remote fold)
+    dict(B=300, b=100, off=50, d=72, version=V2, gathered=True),
+    # fine tiles (opt-in): one split with the output tiles finished in place, and several splits with the finalize kernel
+    dict(B=300, b=140, off=100, d=72, version=V3, flags=fc.FINE_TILES, ld_txt=80),
+    dict(B=5120, b=64, off=640, d=64, version=V1, flags=fc.FINE_TILES),
+]
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "-".join("%s%s" % (k, v) for k, v in c.items()))
+def test_step_of_the_host_built_kernels_matches_the_oracle_under_asan(emu_step, tmp_path, case):
+    run_case(emu_step, tmp_path, **case)
