@@ -17,6 +17,7 @@ V0, V1, V2, V3 = 0, 1, 2, 3
 GATHERED_STATE = 1
 FINE_TILES = 2
 SINGLE_PASS = 4
+TILES_128 = 8
 F32, BF16 = 0, 1
 N_PHASES = 8
 

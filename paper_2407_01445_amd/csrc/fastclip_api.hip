@@ -28,7 +28,7 @@ static fastclip_status hip_failed(hipError_t e) {
 
 fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
   if (!cfg) return FASTCLIP_ERR_NULL;
-  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~(FASTCLIP_GATHERED_STATE | FASTCLIP_FINE_TILES | FASTCLIP_SINGLE_PASS)))
+  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~(FASTCLIP_GATHERED_STATE | FASTCLIP_FINE_TILES | FASTCLIP_SINGLE_PASS | FASTCLIP_TILES_128)))
     return FASTCLIP_ERR_SHAPE;
   if (cfg->B < 2 || cfg->b < 1 || cfg->off < 0 || cfg->off + cfg->b > cfg->B || cfg->d < 1 ||
       cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1 || cfg->b > cfg->N || cfg->state_stride < 1 ||
@@ -122,10 +122,31 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   // quarters of the compute units (one per compute unit is what the large-tile kernels are built for).
   const int64_t big_tiles = 2 * ((cfg.b + 255) / 256) * ((cfg.B + 255) / 256);
   L->fine = (cfg.flags & FASTCLIP_FINE_TILES) && L->bf16 && !L->gathered && !L->square && big_tiles < 192;
+  L->t128 = (cfg.flags & FASTCLIP_TILES_128) && L->bf16 && !L->gathered && !L->square && !L->fine && big_tiles < 192;
   size_t at = 0;
   auto take = [&](size_t bytes) { size_t o = at; at += round_up(bytes, 256); return o; };
   const size_t fb = sizeof(float) * (size_t)L->bstride;
-  if (L->fine) {
+  if (L->t128) {
+    L->nparts = (int)((cfg.B + 127) / 128);
+    L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
+    // Split of the contraction over its column range, in 32-deep stages.  Cost model in units of one stage time: rounds
+    // of 512 workgroups (two per compute unit) x (slice + 12 for the tile's start and end), and with more than one split
+    // the finalize kernel: 54 for its launch + 0.04 per split and output tile.  One split needs no finalize kernel.
+    const int64_t stages = L->ldE / 32;
+    const int64_t tiles = ((cfg.b + 127) / 128) * ((cfg.d + 127) / 128) * 2;
+    int64_t best = 1;
+    double best_cost = 0.0;
+    for (int64_t ns = 1; ns <= kMaxSplit && ns <= stages; ++ns) {
+      const int64_t slice = (stages + ns - 1) / ns;
+      const int64_t used = (stages + slice - 1) / slice;
+      if (used != ns) continue;                                     // every split must get at least one stage
+      const int64_t rounds = (tiles * ns + 511) / 512;
+      const double cost = (double)rounds * (double)(slice + 12) + (ns > 1 ? 54.0 + 0.04 * (double)tiles * (double)ns : 0.0);
+      if (ns == 1 || cost < best_cost) { best = ns; best_cost = cost; }
+    }
+    L->nsplit = (int)best;
+    L->kslice = (stages + best - 1) / best;
+  } else if (L->fine) {
     L->nparts = (int)((cfg.B + 127) / 128);
     L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
     // Split of the contraction over its column range, in 64-deep stages.  Cost model in units of one stage time: rounds
@@ -190,7 +211,10 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
     // fragment-ordered strips: anchors padded to whole 256-row tiles
     const size_t rows = round_up((size_t)cfg.b, 256);
     for (int s = 0; s < 2; ++s) L->E[s] = take(esz * rows * (size_t)L->ldE);
-    if (L->fine) {     // [nsplit][2 sides][b to 64][d to 64] floats, only with more than one split
+    if (L->t128) {     // [nsplit][2 sides][b to 128][d to 128] floats, only with more than one split
+      if (L->nsplit > 1)
+        L->Opart[0] = take(sizeof(float) * (size_t)L->nsplit * 2 * round_up((size_t)cfg.b, 128) * round_up((size_t)cfg.d, 128));
+    } else if (L->fine) {     // [nsplit][2 sides][b to 64][d to 64] floats, only with more than one split
       if (L->nsplit > 1)
         L->Opart[0] = take(sizeof(float) * (size_t)L->nsplit * 2 * round_up((size_t)cfg.b, 64) * round_up((size_t)cfg.d, 64));
     } else {
@@ -255,7 +279,13 @@ static fastclip_status run_step(const fastclip_config* cfg, const fastclip_buffe
   launch_prep(c);
   if (c.L.gathered) launch_prep_cols(c);
   mark(FASTCLIP_PHASE_PREP);
-  if (c.L.fine) {
+  if (c.L.t128) {
+    launch_strips_t128_bf16(c);           mark(FASTCLIP_PHASE_STRIPS);
+    if (!c.L.fused_state) { launch_state(c); mark(FASTCLIP_PHASE_STATE); }
+    launch_fold_bf16(c);                  mark(FASTCLIP_PHASE_LOCAL);   // with fused_state: the state phase as well
+    launch_contract_t128_bf16(c);         mark(FASTCLIP_PHASE_CONTRACT);  // outputs and scalars included
+    launch_norm_backward_bf16(c);
+  } else if (c.L.fine) {
     launch_strips_fine_bf16(c);           mark(FASTCLIP_PHASE_STRIPS);
     if (!c.L.fused_state) { launch_state(c); mark(FASTCLIP_PHASE_STATE); }
     launch_fold_bf16(c);                  mark(FASTCLIP_PHASE_LOCAL);   // with fused_state: the state phase as well
@@ -502,7 +532,7 @@ fastclip_status fastclip_measure_strips(const fastclip_config* cfg, const fastcl
   fc::make_layout(*cfg, &c.L);
   const size_t ncyc = (size_t)256 * 2 * 4;
   if (workspace_bytes < c.L.total + ncyc * sizeof(uint64_t) || ((uintptr_t)workspace & 255)) return FASTCLIP_ERR_WORKSPACE;
-  if (!c.L.bf16 || c.L.fine || c.L.square || c.L.gathered) return FASTCLIP_ERR_UNSUPPORTED;
+  if (!c.L.bf16 || c.L.fine || c.L.t128 || c.L.square || c.L.gathered) return FASTCLIP_ERR_UNSUPPORTED;
   c.ws = (char*)workspace;
   c.s = (hipStream_t)stream;
   uint64_t* cycles = (uint64_t*)(c.ws + c.L.total);

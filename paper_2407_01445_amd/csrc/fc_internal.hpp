@@ -51,6 +51,8 @@ struct Layout {
   int fine;          // 1: MFMA path on fine tiles (kernels_fine.hip): 128 x 128 strip tiles, 64 x 64 output tiles of the
                      //    contraction; nparts counts 128-column tiles, nsplit / kslice count 64-deep stages, and with one
                      //    split there are no partial results
+  int t128;          // 1: MFMA path on 128 x 128 tiles (kernels_tiles128.hip); nparts counts 128-column tiles, nsplit /
+                     //    kslice count 32-deep stages, and with one split there are no partial results
   int square;        // 1: MFMA path, b == B: the similarity matrix is formed once (F[0] holds
                      //    l2(j, p) in the layout of E[0] until the fold transposes it into E[1])
   int64_t ncol;      // gathered: entries per column-parameter array (B rounded up to whole 256-column tiles)
@@ -108,6 +110,8 @@ void launch_fold_bf16(const StepCtx& c);       // MFMA path: local contrast-side
 void launch_contract_bf16(const StepCtx& c);   // MFMA path: strips x X contractions
 void launch_strips_fine_bf16(const StepCtx& c);    // MFMA path, fine tiles: exp strips + row sums
 void launch_contract_fine_bf16(const StepCtx& c);  // MFMA path, fine tiles: contractions, outputs and scalars
+void launch_strips_t128_bf16(const StepCtx& c);    // MFMA path, 128 x 128 tiles: exp strips + row sums
+void launch_contract_t128_bf16(const StepCtx& c);  // MFMA path, 128 x 128 tiles: contractions, outputs and scalars
 void launch_norm_backward_bf16(const StepCtx& c);  // MFMA path: gradients through the L2 normalisation, if asked for
 void launch_finalize_bf16(const StepCtx& c);   // MFMA path: combine + scalars
 

@@ -74,6 +74,10 @@ __device__ inline double wave_sum_f64(double v) {
 
 // Scalars (called by one whole wavefront): loss of the local batch with g replaced by u^{t+1}; Eq. 8 (V0), Eq. 10 (V3).
 // red: the state phase's per-block sums of the anchors' loss terms and h terms.
+// Written as values chosen per version and then ONE store per output through the pointer it was given: with a return
+// per version, each ending in its own stores, the compiler merged the versions' last stores into one whose address
+// register the V3 path never set (it held the flag output of a v_div_scale_f64), so that V3 stored d_tau to a stray
+// address wherever this function was inlined behind other code.
 __device__ inline void write_scalars(const double* red, int nblocks, int64_t b, int version, const float* tau, float rho,
                                      float* loss, float* d_tau) {
   const int lane = threadIdx.x & 63;
@@ -81,13 +85,18 @@ __device__ inline void write_scalars(const double* red, int nblocks, int64_t b, 
   for (int i = lane; i < nblocks; i += 64) { A += red[2 * i]; H += red[2 * i + 1]; }
   A = wave_sum_f64(A) / (double)b;
   H = wave_sum_f64(H) / (double)b;
-  if (lane != 0) return;
-  if (version == FASTCLIP_V2) { *loss = (float)A; return; }
-  const double t = (double)tau[0];
-  if (version == FASTCLIP_V1) { *loss = (float)(t * A); return; }
-  if (version == FASTCLIP_V0) { *loss = (float)A; *d_tau = (float)(-H / (t * t)); return; }
-  *loss = (float)(t * A + 2.0 * (double)rho * t);
-  *d_tau = (float)(A + 2.0 * (double)rho - H / t);
+  const bool has_tau = version != FASTCLIP_V2;                         // V2 has no global temperature (tau may be NULL)
+  const bool has_dtau = version == FASTCLIP_V0 || version == FASTCLIP_V3;
+  const double t = has_tau ? (double)tau[0] : 1.0;
+  const double r2 = 2.0 * (double)rho;
+  double L = A, D = 0.0;                                               // V2: the temperatures are inside the anchors' terms
+  if (version == FASTCLIP_V1) L = t * A;
+  if (version == FASTCLIP_V0) D = -H / (t * t);
+  if (version == FASTCLIP_V3) { L = t * A + r2 * t; D = A + r2 - H / t; }
+  if (lane == 0) {
+    loss[0] = (float)L;
+    if (has_dtau) d_tau[0] = (float)D;
+  }
 }
 
 __device__ inline float ema_update(float u_old, float g, float gamma) {

@@ -84,9 +84,9 @@ def test_struct_size_and_flags_are_checked():
     cfg.struct_size = 8
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
     cfg = good_cfg()
-    cfg.flags = 8
+    cfg.flags = 16
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
-    cfg.flags = fc.GATHERED_STATE | fc.FINE_TILES | fc.SINGLE_PASS
+    cfg.flags = fc.GATHERED_STATE | fc.FINE_TILES | fc.SINGLE_PASS | fc.TILES_128
     assert fc.fastclip_validate(cfg, None) == fc.OK
     assert fc.fastclip_validate(None, None) == fc.ERR_NULL
 

@@ -312,12 +312,52 @@ def test_bf16_single_similarity_pass_chosen_by_the_library_on_a_ragged_batch():
     check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
 
 
-FINE_TILES_OFF = ("FASTCLIP_FINE_TILES is switched off on the GPU: after twelve steps on this path that agreed with the oracle "
-                  "(four on this very shape), a thirteenth ended in a GPU memory fault; a CPU emulation of every index the two "
-                  "kernels form finds all of them in bounds, no cause has been shown, so the path is not run on the GPU")
+TILES_128_SHAPES = [
+    # ragged in anchors, contrasts and width; a width below one stage; the whole batch local
+    (700, 300, 133, 72), (520, 520, 0, 64), (1000, 64, 936, 136), (257, 257, 0, 8),
+    # whole stages and tiles next to ragged ones; anchors at the very end of the global batch
+    (768, 512, 256, 128), (1024, 300, 724, 256), (1024, 320, 704, 128), (1100, 203, 50, 136),
+    # wide rows: many stages per tile, one width with a ragged last stage
+    (700, 300, 133, 2048), (300, 300, 0, 4104),
+    # the paper's own per-GPU shapes (128 - 640 anchors of 1024 - 5120, width 512) and the two small workloads' shapes
+    (1024, 128, 128, 512), (2560, 320, 320, 512), (5120, 640, 640, 512), (1024, 1024, 0, 512), (8192, 256, 1280, 512),
+]
 
 
-@pytest.mark.skip(reason=FINE_TILES_OFF)
+@pytest.mark.parametrize("B,b,off,d", TILES_128_SHAPES)
+@pytest.mark.parametrize("version", [V0, V1, V2, V3])
+def test_bf16_tiles_128(B, b, off, d, version):
+    """FASTCLIP_TILES_128: strips and contraction on 128 x 128 tiles (four times the workgroups, output tiles finished in
+    place when the column range needs no split), against the oracle and close to the default path."""
+    N = 5000
+    rng = np.random.default_rng(B + 3 * version)
+    img, txt = make_embeddings(B + d + 5, B, d, 0.5, "bf16")
+    idx = draw_indices(B + 6, b, N)
+    u0i = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    u0t = np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32)
+    t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
+    u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
+    want = None
+    outs = []
+    for small in (True, False):
+        print("[tiles 128 = %s] %s v%d" % (small, (B, b, off, d), version), flush=True)
+        g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=version, eps=1e-6, rho=6.5, tau=0.07,
+                    tau_grad_scale=1.0 / N, ld_img=d + 8, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img, tau_txt0=t_txt)
+        if small:
+            g.flags |= fc.TILES_128
+        g.set_inputs(img, txt, idx)
+        g.step(0.6)
+        if want is None:
+            want = oracle_step(g, img, txt, idx, u_img, u_txt, 0.6, tau=float(np.float32(0.07)),
+                               tau_img=t_img.astype(np.float64), tau_txt=t_txt.astype(np.float64))
+        compare(g.outputs(), want, version, TOL_BF16, "bf16 tiles 128 %s %s v%d" % (small, (B, b, off, d), version))
+        check_state(g, u0i, u0t, idx, u_img, u_txt, TOL_BF16)
+        outs.append(g.outputs())
+    for k in ("g_img", "g_txt", "u_new_img", "u_new_txt"):      # the same exponentials, summed in another order
+        assert rel_each(outs[0][k], outs[1][k]) < 1e-4, k
+
+
 @pytest.mark.parametrize("B,b,off,d", BF16_SMALL[:-1] + [(1024, 128, 128, 512), (2560, 320, 320, 512), (5120, 640, 640, 512)])
 @pytest.mark.parametrize("version", [V0, V1, V2, V3])
 def test_bf16_fine_tiles(B, b, off, d, version):

@@ -147,6 +147,12 @@ CASES = [
     dict(B=512, b=512, off=0, d=128, version=V3, flags=fc.SINGLE_PASS),
     # contrast side over every global anchor (second strip, remote fold)
     dict(B=300, b=100, off=50, d=72, version=V2, gathered=True),
+    # 128 x 128 tiles (opt-in): ragged everywhere with a guarded last stage; whole stages on the ring with rows replaced;
+    # the whole batch local with a width below one stage; several splits with the finalize kernel
+    dict(B=300, b=140, off=100, d=72, version=V3, flags=fc.TILES_128, ld_txt=80),
+    dict(B=512, b=300, off=212, d=128, version=V2, flags=fc.TILES_128),
+    dict(B=257, b=257, off=0, d=8, version=V0, flags=fc.TILES_128),
+    dict(B=5120, b=64, off=640, d=64, version=V1, flags=fc.TILES_128),
     # fine tiles (opt-in): one split with the output tiles finished in place, and several splits with the finalize kernel
     dict(B=300, b=140, off=100, d=72, version=V3, flags=fc.FINE_TILES, ld_txt=80),
     dict(B=5120, b=64, off=640, d=64, version=V1, flags=fc.FINE_TILES),
