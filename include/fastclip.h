@@ -79,11 +79,15 @@ typedef enum { FASTCLIP_F32 = 0, FASTCLIP_BF16 = 1 } fastclip_dtype;
  * two strips separately below that, where twice the workgroups finish sooner.  Same results up to summation order.
  * Ignored when b < B or on the fp32 path. */
 #define FASTCLIP_SINGLE_PASS 4
-/* FASTCLIP_TILES_128 (bf16 path without gathered state, batches whose 256 x 256 tiles would occupy fewer than 192 compute
- * units; ignored otherwise): the strip phase runs on 128 x 128 tiles and the contraction on 128 x 128 output tiles, four
- * times as many workgroups, two per compute unit; an output tile whose column range needs no split is finished in place
- * (no partial results, no finalize kernel).  Same results up to summation order. */
+/* Tile size of the bf16 path.  By default the library chooses: batches whose 256 x 256 strip tiles would occupy at most
+ * half of the compute units (2 ceil(b/256) ceil(B/256) <= 128; not with gathered state, not in the single-pass form) run
+ * the strip phase on 128 x 128 tiles and the contraction on 128 x 128 output tiles - four times as many workgroups, two
+ * per compute unit, and an output tile whose column range needs no split is finished in place (no partial results, no
+ * finalize kernel); everything else runs on 256 x 256 tiles.  FASTCLIP_TILES_128 asks for the small tiles wherever they
+ * apply (up to 191 large tiles), FASTCLIP_TILES_256 for the large ones always; both together are an error.  Same results
+ * up to summation order. */
 #define FASTCLIP_TILES_128 8
+#define FASTCLIP_TILES_256 16
 
 typedef struct {
   uint32_t struct_size;      /* sizeof(fastclip_config) */

@@ -18,6 +18,7 @@ GATHERED_STATE = 1
 FINE_TILES = 2
 SINGLE_PASS = 4
 TILES_128 = 8
+TILES_256 = 16
 F32, BF16 = 0, 1
 N_PHASES = 8
 

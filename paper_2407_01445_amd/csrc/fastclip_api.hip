@@ -28,12 +28,13 @@ static fastclip_status hip_failed(hipError_t e) {
 
 fastclip_status validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
   if (!cfg) return FASTCLIP_ERR_NULL;
-  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~(FASTCLIP_GATHERED_STATE | FASTCLIP_FINE_TILES | FASTCLIP_SINGLE_PASS | FASTCLIP_TILES_128)))
+  if (cfg->struct_size != sizeof(fastclip_config) || (cfg->flags & ~(FASTCLIP_GATHERED_STATE | FASTCLIP_FINE_TILES | FASTCLIP_SINGLE_PASS | FASTCLIP_TILES_128 | FASTCLIP_TILES_256)))
     return FASTCLIP_ERR_SHAPE;
   if (cfg->B < 2 || cfg->b < 1 || cfg->off < 0 || cfg->off + cfg->b > cfg->B || cfg->d < 1 ||
       cfg->ld_img < cfg->d || cfg->ld_txt < cfg->d || cfg->N < 1 || cfg->b > cfg->N || cfg->state_stride < 1 ||
       cfg->state_stride > 64)
     return FASTCLIP_ERR_SHAPE;
+  if ((cfg->flags & FASTCLIP_TILES_128) && (cfg->flags & FASTCLIP_TILES_256)) return FASTCLIP_ERR_VALUE;
   if (cfg->version < FASTCLIP_V0 || cfg->version > FASTCLIP_V3) return FASTCLIP_ERR_VALUE;
   if (cfg->emb_dtype != FASTCLIP_F32 && cfg->emb_dtype != FASTCLIP_BF16) return FASTCLIP_ERR_VALUE;
   if (bad_float(cfg->gamma) || bad_float(cfg->eps) || bad_float(cfg->rho) || bad_float(cfg->tau_grad_scale))
@@ -122,26 +123,36 @@ void make_layout(const fastclip_config& cfg, Layout* L) {
   // quarters of the compute units (one per compute unit is what the large-tile kernels are built for).
   const int64_t big_tiles = 2 * ((cfg.b + 255) / 256) * ((cfg.B + 255) / 256);
   L->fine = (cfg.flags & FASTCLIP_FINE_TILES) && L->bf16 && !L->gathered && !L->square && big_tiles < 192;
-  L->t128 = (cfg.flags & FASTCLIP_TILES_128) && L->bf16 && !L->gathered && !L->square && !L->fine && big_tiles < 192;
+  // 128 x 128 tiles: asked for (wherever a quarter of the large tiles' workgroups would still not fill the chip), or
+  // chosen when the large tiles would occupy at most half of the compute units (measured: b = 128 .. 1024 of
+  // B = 1024 .. 8192 at width 512 are 4 - 22 % faster, b = 640 of 5120, 120 large tiles, breaks even)
+  const bool small_ok = L->bf16 && !L->gathered && !L->square && !L->fine && !(cfg.flags & FASTCLIP_TILES_256);
+  L->t128 = small_ok && ((cfg.flags & FASTCLIP_TILES_128) ? big_tiles < 192 : big_tiles <= 128);
   size_t at = 0;
   auto take = [&](size_t bytes) { size_t o = at; at += round_up(bytes, 256); return o; };
   const size_t fb = sizeof(float) * (size_t)L->bstride;
   if (L->t128) {
     L->nparts = (int)((cfg.B + 127) / 128);
     L->ldE = (int64_t)round_up((size_t)cfg.B, 64);
-    // Split of the contraction over its column range, in 32-deep stages.  Cost model in units of one stage time: rounds
-    // of 512 workgroups (two per compute unit) x (slice + 12 for the tile's start and end), and with more than one split
-    // the finalize kernel: 54 for its launch + 0.04 per split and output tile.  One split needs no finalize kernel.
+    // Split of the contraction over its column range, in 32-deep stages.  Cost model in units of one stage time of a
+    // workgroup that has its compute unit to itself (0.65 us: a stage is the latency of its instructions, not its MFMA
+    // time); measured on b = 128 .. 1024 of B = 1024 .. 8192 at width 512.  Up to 256 workgroups run one per compute
+    // unit; a second one on a compute unit stretches both by 1.45; beyond 512 they run in rounds.  A tile's start and end
+    // cost 4; with more than one split the finalize kernel costs 5 + 0.42 per MiB of partial results it reads.  One split
+    // needs no finalize kernel (the tile is finished in place).
     const int64_t stages = L->ldE / 32;
     const int64_t tiles = ((cfg.b + 127) / 128) * ((cfg.d + 127) / 128) * 2;
+    const double tile_mib = 128.0 * 128.0 * 4.0 / (1024.0 * 1024.0);
     int64_t best = 1;
     double best_cost = 0.0;
     for (int64_t ns = 1; ns <= kMaxSplit && ns <= stages; ++ns) {
       const int64_t slice = (stages + ns - 1) / ns;
       const int64_t used = (stages + slice - 1) / slice;
       if (used != ns) continue;                                     // every split must get at least one stage
-      const int64_t rounds = (tiles * ns + 511) / 512;
-      const double cost = (double)rounds * (double)(slice + 12) + (ns > 1 ? 54.0 + 0.04 * (double)tiles * (double)ns : 0.0);
+      const int64_t wgs = tiles * ns;
+      const double stretch = wgs <= 256 ? 1.0 : (wgs <= 512 ? 1.0 + 0.45 * (double)(wgs - 256) / 256.0
+                                                            : 1.45 * (double)((wgs + 511) / 512));
+      const double cost = stretch * (double)slice + 4.0 + (ns > 1 ? 5.0 + 0.42 * tile_mib * (double)wgs : 0.0);
       if (ns == 1 || cost < best_cost) { best = ns; best_cost = cost; }
     }
     L->nsplit = (int)best;

@@ -9,7 +9,7 @@
 //                        splits the partial tiles go to the workspace and k_finalize_t128_bf16 adds them up.
 //
 // Both run the pipeline of the large-tile contraction in small: a ring of five LDS slots, each one 32-deep stage of
-// both operands (16 KiB), filled by direct-to-LDS loads three stages ahead, one barrier per stage; four wavefronts with
+// both operands (16 KiB), filled by direct-to-LDS loads four stages ahead, one barrier per stage; four wavefronts with
 // 2 x 2 accumulator blocks each.  Two workgroups share a compute unit (80 KiB of LDS each), which hides what the plain
 // instruction order of the loop leaves open.  Layouts (stored strips, accumulator blocks, LDS images) are those of the
 // large-tile kernels: see kernels_mfma.hip.
@@ -23,38 +23,48 @@ namespace fc {
 constexpr int kT = 128;                         // rows of either operand of a strip tile; rows and columns of an output tile
 constexpr int kHalf = kT * BK * 2;              // one operand of a stage: 8 KiB
 constexpr int kSlot = 2 * kHalf;                // 16 KiB
-constexpr int kSlots = 5;
-constexpr int kSmallRing = kSlots * kSlot;      // 80 KiB
+constexpr int kSlots = 5;                       // stages are requested four ahead (eight ahead in a ring of nine measured no faster)
+constexpr int kSmallRing = kSlots * kSlot;      // 80 KiB: two workgroups per compute unit
 
-#define FC_WAIT_VMCNT4() __builtin_amdgcn_s_waitcnt(0x0f74)
-#define FC_WAIT_VMCNT12() __builtin_amdgcn_s_waitcnt(0x0f7c)
+// "at most 4 n loads of this wave in flight", n = 0 .. 7 (s_waitcnt takes an immediate)
+__device__ __forceinline__ void wait_younger_stages(int n) {
+  switch (n) {
+    case 0: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+    case 1: __builtin_amdgcn_s_waitcnt(0x0f74); break;
+    case 2: __builtin_amdgcn_s_waitcnt(0x0f78); break;
+    case 3: __builtin_amdgcn_s_waitcnt(0x0f7c); break;
+    case 4: __builtin_amdgcn_s_waitcnt(0x4f70); break;
+    case 5: __builtin_amdgcn_s_waitcnt(0x4f74); break;
+    case 6: __builtin_amdgcn_s_waitcnt(0x4f78); break;
+    default: __builtin_amdgcn_s_waitcnt(0x4f7c); break;
+  }
+}
 // nothing may move across: the compiler does not see the direct-to-LDS loads write the ring
 #define FC_FENCE() do { FC_PIN(); asm volatile("" ::: "memory"); FC_PIN(); } while (0)
 
 // acc += (A operand tile) x (B operand tile)^T over the stages [s0, s0 + S), S >= 1.  Tile::dma(i, stage, slot address),
-// i = 0 .. 3, issues this wave's four wave loads of a stage.  Stage s lives in slot s mod 5; its loads are issued three
+// i = 0 .. 3, issues this wave's four wave loads of a stage.  Stage s lives in slot s mod 5; its loads are issued four
 // stages before it is read, right after the barrier of stage s - 4 ... which every wave passes only after its last read
 // of stage s - 5, the slot's previous tenant.  Vector memory operations complete in order, so "stage s has landed" is
 // "at most 4 x (stages requested after it) loads in flight".  On return no wave reads the ring any more.
 template <typename Tile>
 __device__ __forceinline__ void small_ring(f32x16 (&acc)[2][2], const Tile& T, char* ring, uint32_t ring_addr, int s0,
                                            int S) {
+  constexpr int kAhead = kSlots - 1;
 #pragma unroll
-  for (int p = 0; p < 4; ++p)
+  for (int p = 0; p < kAhead; ++p)
     if (p < S) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) T.dma(i, s0 + p, ring_addr + (uint32_t)(p * kSlot));
     }
-  int slot = 0, fill = 4;                       // slot of stage s; slot that stage s + 4 goes to
+  int slot = 0, fill = kAhead;                  // slot of stage s; slot that the stage kAhead on goes to
   for (int s = 0; s < S; ++s) {
-    const int younger = S - 1 - s < 3 ? S - 1 - s : 3;
-    if (younger == 3) FC_WAIT_VMCNT12(); else if (younger == 2) FC_WAIT_VMCNT8(); else if (younger == 1) FC_WAIT_VMCNT4();
-    else FC_WAIT_VMCNT0();
+    wait_younger_stages(S - 1 - s < kAhead - 1 ? S - 1 - s : kAhead - 1);
     __builtin_amdgcn_s_barrier();
     FC_FENCE();
-    if (s + 4 < S) {
+    if (s + kAhead < S) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) T.dma(i, s0 + s + 4, ring_addr + (uint32_t)(fill * kSlot));
+      for (int i = 0; i < 4; ++i) T.dma(i, s0 + s + kAhead, ring_addr + (uint32_t)(fill * kSlot));
     }
     const char* sl = ring + slot * kSlot;
 #pragma unroll

@@ -31,8 +31,10 @@ class GpuStep:
 
     def __init__(self, *, B, b, off, d, N, dtype, version, eps, rho=0.0, tau=0.07, tau_grad_scale=1.0,
                  ld_img=None, ld_txt=None, u_img0=None, u_txt0=None, tau_img0=None, tau_txt0=None, gathered=None,
-                 norms=None, state_stride=1, canonical_records=False, fine_tiles=False, single_pass=False):
-        """gathered: None, or dict(u_img=[B], u_txt=[B], tau_img=[B] or None, tau_txt=[B] or None) = the state
+                 norms=None, state_stride=1, canonical_records=False, fine_tiles=False, single_pass=False, tiles=256):
+        """tiles: 256 / 128 ask for that tile size on the bf16 path (FASTCLIP_TILES_256 / FASTCLIP_TILES_128), None leaves
+        the choice to the library; the default keeps the tests of the large-tile kernels on them whatever the batch size.
+        gathered: None, or dict(u_img=[B], u_txt=[B], tau_img=[B] or None, tau_txt=[B] or None) = the state
         gathered from all workers (the step then runs with FASTCLIP_GATHERED_STATE)."""
         self.B, self.b, self.off, self.d, self.N = B, b, off, d, N
         self.dtype, self.version = dtype, version
@@ -73,6 +75,8 @@ class GpuStep:
         self.cfg = None
         self.ws = None
         self.flags = (fc.FINE_TILES if fine_tiles else 0) | (fc.SINGLE_PASS if single_pass else 0)
+        if dtype == "bf16" and not fine_tiles:
+            self.flags |= {256: fc.TILES_256, 128: fc.TILES_128, None: 0}[tiles]
         self.u_glob_img = self.u_glob_txt = self.tau_glob_img = self.tau_glob_txt = None
         self.norm_img = self.norm_txt = None
         if norms is not None:       # (norm_img [b], norm_txt [b]): gradients through the L2 normalisation

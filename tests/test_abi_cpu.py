@@ -84,10 +84,12 @@ def test_struct_size_and_flags_are_checked():
     cfg.struct_size = 8
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
     cfg = good_cfg()
-    cfg.flags = 16
+    cfg.flags = 32
     assert fc.fastclip_validate(cfg, None) == fc.ERR_SHAPE
     cfg.flags = fc.GATHERED_STATE | fc.FINE_TILES | fc.SINGLE_PASS | fc.TILES_128
     assert fc.fastclip_validate(cfg, None) == fc.OK
+    cfg.flags = fc.TILES_128 | fc.TILES_256            # one tile size or the other
+    assert fc.fastclip_validate(cfg, None) == fc.ERR_VALUE
     assert fc.fastclip_validate(None, None) == fc.ERR_NULL
 
 
@@ -96,15 +98,31 @@ def test_single_pass_flag_adds_the_second_strip_only_when_the_whole_batch_is_loc
     when b == B on the bf16 path, nothing otherwise; a batch with more 256 x 256 tiles than compute units takes that form
     without the flag, ragged or not."""
     full = dict(B=520, b=520, off=0, d=64, ld_img=64, ld_txt=64)
-    plain, single = good_cfg(**full), good_cfg(flags=fc.SINGLE_PASS, **full)
+    plain, single = good_cfg(flags=fc.TILES_256, **full), good_cfg(flags=fc.SINGLE_PASS | fc.TILES_256, **full)
     strip = 2 * 768 * 576                      # bf16, anchors padded to 256, columns to 64
     assert fc.fastclip_workspace_bytes(single) - fc.fastclip_workspace_bytes(plain) == strip
     share = dict(B=520, b=260, off=0, d=64, ld_img=64, ld_txt=64)
-    assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.SINGLE_PASS, **share)) == fc.fastclip_workspace_bytes(good_cfg(**share))
+    assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.SINGLE_PASS | fc.TILES_256, **share)) == fc.fastclip_workspace_bytes(good_cfg(flags=fc.TILES_256, **share))
     f32 = dict(emb_dtype=fc.F32, **full)
     assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.SINGLE_PASS, **f32)) == fc.fastclip_workspace_bytes(good_cfg(**f32))
     big = dict(B=3000, b=3000, off=0, d=128, ld_img=128, ld_txt=128)
     assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.SINGLE_PASS, **big)) == fc.fastclip_workspace_bytes(good_cfg(**big))
+
+
+def test_tile_size_is_chosen_by_the_batch_size_unless_asked_for():
+    """At most 128 large strip tiles: the library takes 128 x 128 tiles by itself (the layout FASTCLIP_TILES_128 asks for);
+    FASTCLIP_TILES_128 reaches up to 191 large tiles; beyond that, with gathered state and in the single-pass form the tiles
+    are large whatever is asked."""
+    ws = fc.fastclip_workspace_bytes
+    small = dict(B=1024, b=256, off=512, d=512)                      # 8 large tiles
+    assert ws(good_cfg(**small)) == ws(good_cfg(flags=fc.TILES_128, **small)) != ws(good_cfg(flags=fc.TILES_256, **small))
+    mid = dict(B=8192, b=640, off=0, d=512)                          # 192 large tiles... one too many for either
+    assert ws(good_cfg(**mid)) == ws(good_cfg(flags=fc.TILES_128, **mid)) == ws(good_cfg(flags=fc.TILES_256, **mid))
+    asked = dict(B=5120, b=1024, off=0, d=512)                       # 160 large tiles: only when asked for
+    assert ws(good_cfg(**asked)) == ws(good_cfg(flags=fc.TILES_256, **asked)) != ws(good_cfg(flags=fc.TILES_128, **asked))
+    assert ws(good_cfg(flags=fc.GATHERED_STATE, **small)) == ws(good_cfg(flags=fc.GATHERED_STATE | fc.TILES_128, **small))
+    full = dict(B=512, b=512, off=0, d=128)
+    assert ws(good_cfg(flags=fc.SINGLE_PASS, **full)) == ws(good_cfg(flags=fc.SINGLE_PASS | fc.TILES_128, **full))
 
 
 def test_fine_tiles_flag_changes_the_workspace_only_for_small_batches():

@@ -343,9 +343,8 @@ def test_bf16_tiles_128(B, b, off, d, version):
     for small in (True, False):
         print("[tiles 128 = %s] %s v%d" % (small, (B, b, off, d), version), flush=True)
         g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=version, eps=1e-6, rho=6.5, tau=0.07,
-                    tau_grad_scale=1.0 / N, ld_img=d + 8, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img, tau_txt0=t_txt)
-        if small:
-            g.flags |= fc.TILES_128
+                    tau_grad_scale=1.0 / N, ld_img=d + 8, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img, tau_txt0=t_txt,
+                    tiles=128 if small else 256)
         g.set_inputs(img, txt, idx)
         g.step(0.6)
         if want is None:
@@ -847,8 +846,10 @@ def test_record_state_layout_is_the_dense_step(dtype, shape, version):
 TOL_BF16_MEASURED = 2e-3
 
 
-def run_workload(name, steps_checked, n_steps, gathered=False, own_trajectory=False, needs_contrast_side=False):
-    """own_trajectory: the oracle carries its own state arrays through all steps (else it is handed the GPU's state of
+def run_workload(name, steps_checked, n_steps, gathered=False, own_trajectory=False, needs_contrast_side=False,
+                 tiles=None):
+    """tiles: None = the tile size the library chooses, which is what bench.py times; 256 = the large-tile kernels.
+    own_trajectory: the oracle carries its own state arrays through all steps (else it is handed the GPU's state of
     the batch's samples before each checked step).  needs_contrast_side: also check that the result could not pass
     without the local anchors' part of Eqs. 3 / 5 / 7."""
     w = WORKLOADS[name]
@@ -861,7 +862,7 @@ def run_workload(name, steps_checked, n_steps, gathered=False, own_trajectory=Fa
                       tau_glob_img=None if tg1 is None else tg1.astype(np.float64),
                       tau_glob_txt=None if tg2 is None else tg2.astype(np.float64))
     g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=w["dtype"], version=version, eps=w["eps"], rho=w["rho"],
-                tau=w["tau"], tau_grad_scale=1.0 / N, gathered=gath)
+                tau=w["tau"], tau_grad_scale=1.0 / N, gathered=gath, tiles=tiles)
     tau32 = float(np.float32(w["tau"]))
     own_u_img, own_u_txt = (np.zeros(N), np.zeros(N)) if own_trajectory else (None, None)
     for step in range(n_steps):
@@ -925,15 +926,17 @@ def run_workload(name, steps_checked, n_steps, gathered=False, own_trajectory=Fa
     return g
 
 
-def test_cfg1_full_size():
+@pytest.mark.parametrize("tiles", [None, 256])
+def test_cfg1_full_size(tiles):
     """100 steps with the cosine gamma schedule, a fresh batch every step, the state carried on the GPU and, on its
     own, by the oracle (which never sees a value of the GPU's); every output compared at the first, second, middle and
     last step, the whole state after the last."""
-    run_workload("cfg1", {0, 1, 50, 99}, 100, own_trajectory=True)
+    run_workload("cfg1", {0, 1, 50, 99}, 100, own_trajectory=True, tiles=tiles)
 
 
-def test_cfg2_full_size():
-    run_workload("cfg2", {0, 2}, 3, needs_contrast_side=True)
+@pytest.mark.parametrize("tiles", [None, 256])
+def test_cfg2_full_size(tiles):
+    run_workload("cfg2", {0, 2}, 3, needs_contrast_side=True, tiles=tiles)
 
 
 def test_cfg3_full_size():

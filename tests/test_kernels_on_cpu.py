@@ -137,19 +137,20 @@ CASES = [
     dict(B=37, b=11, off=13, d=19, version=V2, dtype="f32", ld_img=23),
     # MFMA path, every tile ragged: guarded strip tiles on the ring (rows replaced by the last one), ragged last stage,
     # contraction with a guarded tail, fused state phase in the fold; padding between the rows of one side
-    dict(B=300, b=140, off=100, d=72, version=V3, ld_img=80),
-    dict(B=40, b=40, off=0, d=16, version=V0),
+    dict(B=300, b=140, off=100, d=72, version=V3, ld_img=80, flags=fc.TILES_256),
+    dict(B=40, b=40, off=0, d=16, version=V0, flags=fc.TILES_256),
     # whole tiles: the persistent eight-wave strip kernel and the contraction's ring, next to a ragged anchor tile
-    dict(B=512, b=300, off=212, d=128, version=V2),
+    dict(B=512, b=300, off=212, d=128, version=V2, flags=fc.TILES_256),
     # the whole batch local, similarity matrix formed once on ragged tiles (column pass of the guarded kernel)
     dict(B=300, b=300, off=0, d=72, version=V2, flags=fc.SINGLE_PASS),
     # ... and on whole tiles (column pass of the persistent kernel)
     dict(B=512, b=512, off=0, d=128, version=V3, flags=fc.SINGLE_PASS),
     # contrast side over every global anchor (second strip, remote fold)
     dict(B=300, b=100, off=50, d=72, version=V2, gathered=True),
+    # the library's own choice for a small batch: 128 x 128 tiles
     # 128 x 128 tiles (opt-in): ragged everywhere with a guarded last stage; whole stages on the ring with rows replaced;
     # the whole batch local with a width below one stage; several splits with the finalize kernel
-    dict(B=300, b=140, off=100, d=72, version=V3, flags=fc.TILES_128, ld_txt=80),
+    dict(B=300, b=140, off=100, d=72, version=V3, ld_txt=80),
     dict(B=512, b=300, off=212, d=128, version=V2, flags=fc.TILES_128),
     dict(B=257, b=257, off=0, d=8, version=V0, flags=fc.TILES_128),
     dict(B=5120, b=64, off=640, d=64, version=V1, flags=fc.TILES_128),
