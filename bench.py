@@ -345,7 +345,9 @@ def main():
     alg = algorithmic_flops(B, b, d, args.gathered)
     dom = max(("strips", "contract"), key=lambda k: phase_ms.get(k, 0.0))
     achieved = alg[dom] / (phase_ms[dom] * 1e-3) / 1e12
-    kernel_of = {"strips": "k_strips_bf16", "contract": "k_contract_bf16"}
+    plan = fc.fastclip_describe(cfgs[0])           # which tiles the library runs this workload on
+    kernel_of = {"strips": "k_strips_t128_bf16", "contract": "k_contract_t128_bf16"} if plan["tile"] == 128 else \
+                {"strips": "k_strips_bf16", "contract": "k_contract_bf16"}
     roofline = {"kernel": kernel_of[dom], "bound": "mfma",
                 "achieved": round(achieved, 2), "peak": PEAK_BF16_FLOPS / 1e12, "unit": "TFLOP/s",
                 "frac": round(achieved * 1e12 / PEAK_BF16_FLOPS, 4),
@@ -369,9 +371,9 @@ def main():
     # what the two MFMA kernels execute: whole 256-row tiles, two strips unless the whole batch is local in whole
     # tiles on more tiles than compute units (one similarity pass), two contractions over the padded column range
     up = lambda x, m: (x + m - 1) // m * m
-    one_pass = b == B and B % 256 == 0 and d % 64 == 0 and d >= 128 and 2 * (B // 256) ** 2 > 256
-    executed = {"strips": (1 if one_pass else 2) * 2.0 * up(b, 256) * up(B, 256) * d,
-                "contract": 2 * 2.0 * up(b, 256) * up(B, 64) * up(d, 256)}
+    tile = plan["tile"]
+    executed = {"strips": (1 if plan["single_pass"] else 2) * 2.0 * up(b, tile) * up(B, tile) * d,
+                "contract": 2 * 2.0 * up(b, tile) * up(B, 64) * up(d, tile)}
     gemm_ms = phase_ms["strips"] + phase_ms["contract"]
     gemm_phases = {"algorithmic_tflops": round((alg["strips"] + alg["contract"]) / (gemm_ms * 1e-3) / 1e12, 2),
                    "frac_of_bf16_peak": round((alg["strips"] + alg["contract"]) / (gemm_ms * 1e-3) / PEAK_BF16_FLOPS, 4),
@@ -389,7 +391,8 @@ def main():
                                                       (", temperature update fused in" if args.update_tau else "")),
                       "B": B, "b": b, "off": off, "d": d, "N": N, "version": version,
                       "state_layout": "one 32-byte record {u_1, tau_1, m_1, v_1, u_2, tau_2, m_2, v_2} per sample"
-                                      if records is not None else "dense arrays"},
+                                      if records is not None else "dense arrays",
+                      "plan": plan},
            "sources": digest,
            "step_ms_hip_events": step_ms, "step_ms_hip_graph_replay": round(graph_ms, 5), "roofline": roofline, "gemm_phases": gemm_phases,
            "phase_ms": {k: round(v, 5) for k, v in phase_ms.items()},

@@ -67,11 +67,10 @@ typedef enum { FASTCLIP_F32 = 0, FASTCLIP_BF16 = 1 } fastclip_dtype;
  * (u_new_img / u_new_txt) and gathering; on a single GPU holding the whole batch (b == B) the
  * flag changes nothing and the arrays are not read. */
 #define FASTCLIP_GATHERED_STATE 1
-/* FASTCLIP_FINE_TILES (opt-in, bf16 path without gathered state): batches whose 256 x 256 tiles would occupy fewer than
- * 192 compute units run the strip phase on 128 x 128 tiles and the contraction on 64 x 64 output tiles that are finished
- * in place (no partial results and no finalize kernel when the column range needs no split).  Results are those of the
- * default path up to summation order.  NOT enabled by default: see the design notes (one of thirteen runs on hardware
- * ended in a memory fault whose cause has not been found). */
+/* FASTCLIP_FINE_TILES (opt-in, bf16 path without gathered state, fewer than 192 large strip tiles): an older form of the
+ * small-tile path: strips on 128 x 128 tiles staged through registers, contraction on 64 x 64 output tiles finished in
+ * place when the column range needs no split.  Kept because its contraction is the faster one where the whole batch is
+ * local and small (b = B = 1024); the library never chooses it by itself.  Same results up to summation order. */
 #define FASTCLIP_FINE_TILES 2
 /* FASTCLIP_SINGLE_PASS (bf16 path, b == B): form the similarity matrix ONCE whatever the batch size: with the whole batch
  * local the text strip is the transpose of the image strip, so every dot product yields both exponentials (Proc. 1 with
@@ -147,6 +146,20 @@ typedef struct {
 /* Bytes of device workspace fastclip_step needs for this configuration; 0 if the
  * configuration is invalid.  Pure host function. */
 size_t fastclip_workspace_bytes(const fastclip_config* cfg);
+
+/* How the library will run this configuration (pure host function; FASTCLIP_OK or the status fastclip_validate(cfg, NULL)
+ * gives, then *plan is untouched).  For callers that want to know which kernels a profile will show and for the
+ * benchmark's labels; nothing in it has to be passed back. */
+typedef struct {
+  int32_t tile;          /* rows of a strip tile on the bf16 path: 256, 128, or 64 for FASTCLIP_FINE_TILES (whose strip tiles
+                            are 128 x 128 and output tiles 64 x 64); 0 on the fp32 path */
+  int32_t single_pass;   /* 1: b == B and the similarity matrix is formed once */
+  int32_t gathered;      /* 1: the contrast side runs over every global anchor (flag set and b < B) */
+  int32_t fused_state;   /* 1: the state phase runs inside the fold kernel (few anchors, few partial sums) */
+  int32_t nsplit;        /* splits of the contraction's column range; 1 on the small-tile paths: tiles finished in place */
+  int32_t nparts;        /* partial sums per anchor and quantity that the strip phase leaves to the state phase */
+} fastclip_plan;
+fastclip_status fastclip_describe(const fastclip_config* cfg, fastclip_plan* plan);
 
 /* Validate a configuration (and, if bufs != NULL, the pointers it requires) exactly as
  * fastclip_step does, without launching anything.  Pure host function. */

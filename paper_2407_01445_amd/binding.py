@@ -23,6 +23,11 @@ F32, BF16 = 0, 1
 N_PHASES = 8
 
 
+class fastclip_plan(C.Structure):
+    _fields_ = [("tile", C.c_int32), ("single_pass", C.c_int32), ("gathered", C.c_int32), ("fused_state", C.c_int32),
+                ("nsplit", C.c_int32), ("nparts", C.c_int32)]
+
+
 class fastclip_config(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("version", C.c_int32), ("emb_dtype", C.c_int32),
                 ("flags", C.c_int32),
@@ -77,6 +82,8 @@ def load(build_if_missing: bool = True):
     cfgp, bufp = C.POINTER(fastclip_config), C.POINTER(fastclip_buffers)
     lib.fastclip_workspace_bytes.restype = C.c_size_t
     lib.fastclip_workspace_bytes.argtypes = [cfgp]
+    lib.fastclip_describe.restype = C.c_int
+    lib.fastclip_describe.argtypes = [cfgp, C.POINTER(fastclip_plan)]
     lib.fastclip_validate.restype = C.c_int
     lib.fastclip_validate.argtypes = [cfgp, bufp]
     lib.fastclip_step.restype = C.c_int
@@ -190,6 +197,15 @@ def _stream(stream):
 
 def fastclip_workspace_bytes(cfg: fastclip_config) -> int:
     return int(load().fastclip_workspace_bytes(C.byref(cfg)))
+
+
+def fastclip_describe(cfg: fastclip_config) -> dict:
+    """The header's fastclip_plan as a dict; raises on an invalid configuration."""
+    plan = fastclip_plan()
+    st = int(load().fastclip_describe(C.byref(cfg), C.byref(plan)))
+    if st != OK:
+        raise RuntimeError("fastclip_describe: status %d" % st)
+    return {n: int(getattr(plan, n)) for n, _ in fastclip_plan._fields_}
 
 
 def fastclip_validate(cfg, bufs=None) -> int:

@@ -380,6 +380,21 @@ size_t fastclip_workspace_bytes(const fastclip_config* cfg) {
   return L.total;
 }
 
+fastclip_status fastclip_describe(const fastclip_config* cfg, fastclip_plan* plan) {
+  if (!plan) return FASTCLIP_ERR_NULL;
+  const fastclip_status st = fc::validate(cfg, nullptr);
+  if (st != FASTCLIP_OK) return st;
+  fc::Layout L;
+  fc::make_layout(*cfg, &L);
+  plan->tile = !L.bf16 ? 0 : (L.t128 ? 128 : (L.fine ? 64 : 256));
+  plan->single_pass = L.square;
+  plan->gathered = L.gathered;
+  plan->fused_state = L.fused_state;
+  plan->nsplit = L.nsplit;
+  plan->nparts = L.nparts;
+  return FASTCLIP_OK;
+}
+
 fastclip_status fastclip_validate(const fastclip_config* cfg, const fastclip_buffers* bufs) {
   return fc::validate(cfg, bufs);
 }

@@ -109,6 +109,21 @@ def test_single_pass_flag_adds_the_second_strip_only_when_the_whole_batch_is_loc
     assert fc.fastclip_workspace_bytes(good_cfg(flags=fc.SINGLE_PASS, **big)) == fc.fastclip_workspace_bytes(good_cfg(**big))
 
 
+def test_describe_reports_the_plan():
+    assert fc.fastclip_describe(good_cfg(B=1024, b=256, off=512, d=512))["tile"] == 128
+    assert fc.fastclip_describe(good_cfg(B=1024, b=256, off=512, d=512, flags=fc.TILES_256))["tile"] == 256
+    assert fc.fastclip_describe(good_cfg(B=1024, b=256, off=512, d=512, flags=fc.FINE_TILES))["tile"] == 64
+    big = fc.fastclip_describe(good_cfg(B=32768, b=1024, off=0, d=1024))
+    assert big["tile"] == 256 and big["nsplit"] == 8 and big["nparts"] == 128 and not big["fused_state"]
+    sq = fc.fastclip_describe(good_cfg(B=4096, b=4096, off=0, d=768))
+    assert sq["single_pass"] == 1 and sq["tile"] == 256
+    assert fc.fastclip_describe(good_cfg(emb_dtype=fc.F32))["tile"] == 0
+    g = fc.fastclip_describe(good_cfg(flags=fc.GATHERED_STATE))
+    assert g["gathered"] == 1 and g["tile"] == 256
+    with pytest.raises(RuntimeError):
+        fc.fastclip_describe(good_cfg(B=1))
+
+
 def test_tile_size_is_chosen_by_the_batch_size_unless_asked_for():
     """At most 128 large strip tiles: the library takes 128 x 128 tiles by itself (the layout FASTCLIP_TILES_128 asks for);
     FASTCLIP_TILES_128 reaches up to 191 large tiles; beyond that, with gathered state and in the single-pass form the tiles
