@@ -157,6 +157,9 @@ def main():
     ap.add_argument("--update-tau", action="store_true",
                     help="time fastclip_step_update_tau (the step with the temperature update fused in, AdamW) instead of "
                          "fastclip_step; not the headline workload")
+    ap.add_argument("--tiles", type=int, choices=(128, 256), default=None,
+                    help="ask for this tile size (FASTCLIP_TILES_128 / FASTCLIP_TILES_256) instead of the library's choice; "
+                         "not the headline configuration")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-state-bench", action="store_true")
     ap.add_argument("--no-stock-ops", action="store_true", help="skip timing the step written with stock PyTorch ops")
@@ -237,7 +240,8 @@ def main():
     def cfg_at(t):
         return fc.make_config(version=version, emb_dtype=fc.BF16 if w["dtype"] == "bf16" else fc.F32, B=B, b=b,
                               off=off, d=d, N=N, gamma=gamma_at(t), eps=w["eps"], rho=w["rho"], tau_grad_scale=1.0 / N,
-                              flags=fc.GATHERED_STATE if args.gathered else 0, state_stride=stride)
+                              flags=(fc.GATHERED_STATE if args.gathered else 0) |
+                                    {None: 0, 128: fc.TILES_128, 256: fc.TILES_256}[args.tiles], state_stride=stride)
 
     def bufs_at(t):
         return fc.make_buffers(img_glob=img, txt_glob=txt, idx=idx_sets[t % n_sets], u_img=u_img, u_txt=u_txt, tau=tau,
