@@ -525,6 +525,11 @@ def test_adamw_matches_the_library_optimizer_on_a_scalar():
     a = parameter_update(0.05, 0.3, 0.01, 0.02, optimizer=LAMB, lr=1e-3, step=4, beta1=0.9, beta2=0.99, eps=1e-8)
     b = parameter_update(0.05, 0.3, 0.01, 0.02, optimizer=ADAMW, lr=1e-3, step=4, beta1=0.9, beta2=0.99, eps=1e-8)
     assert all(float(x) == float(y) for x, y in zip(a, b))
+    # ... and one such step expanded by hand in exact decimal arithmetic (Proc. parameter_update with alpha = 1):
+    # m = 0.9 * 0.01 + 0.1 * 0.3 = 0.039, v = 0.99 * 0.02 + 0.01 * 0.09 = 0.0207, m^ = m / (1 - 0.9^4) = 0.039 / 0.3439,
+    # v^ = v / (1 - 0.99^4) = 0.0207 / 0.03940399, theta = 0.05 - 1e-3 * m^ / (sqrt(v^) + 1e-8)
+    assert float(a[1]) == pytest.approx(0.039, rel=1e-14) and float(a[2]) == pytest.approx(0.0207, rel=1e-14)
+    assert float(a[0]) == pytest.approx(0.04984353494663746525, rel=1e-14)
 
 
 def test_adamw_first_step_closed_form_and_weight_decay():
