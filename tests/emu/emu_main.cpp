@@ -87,7 +87,11 @@ template <typename T> static T* nan_buf(size_t n) {
 
 // case file: 12 int64 {version, emb_dtype, flags, B, b, off, d, ld_img, ld_txt, N, state_stride, has_glob},
 // 5 float {gamma, eps, rho, tau, tau_grad_scale}, img, txt (each (B - 1) ld + d elements), idx [b], u_img, u_txt [N],
-// V2: tau_img, tau_txt [N], has_glob: u_glob_img, u_glob_txt [B] and for V2 tau_glob_img, tau_glob_txt [B]
+// V2: tau_img, tau_txt [N], has_glob: u_glob_img, u_glob_txt [B] and for V2 tau_glob_img, tau_glob_txt [B].
+// With a third argument "tau" the file goes on with 2 int64 {optimizer, step}, 7 float {lr, beta1, beta2, eps, tau_min,
+// lr_drop_below, lr_drop_factor}, then V2: m_img, v_img, m_txt, v_txt [N], else m, v [1], and fastclip_step_update_tau
+// runs instead of fastclip_step; with state_stride 8 the eight per-sample arrays of V2 are packed into records
+// {u_1, tau_1, m_1, v_1, u_2, tau_2, m_2, v_2} first (the layout the library moves as 16-byte words).
 int main(int argc, char** argv) {
   emu::g_lds_hi = (uintptr_t)&emu::g_marker & ~(uintptr_t)0xffffffffull;
   if (argc < 3) return 2;
@@ -117,6 +121,40 @@ int main(int argc, char** argv) {
     b.u_glob_img = rd<float>(f, cfg.B); b.u_glob_txt = rd<float>(f, cfg.B);
     if (cfg.version == FASTCLIP_V2) { b.tau_glob_img = rd<float>(f, cfg.B); b.tau_glob_txt = rd<float>(f, cfg.B); }
   }
+  const bool with_tau = argc > 3 && !strcmp(argv[3], "tau");
+  const bool v2_ = cfg.version == FASTCLIP_V2;
+  fastclip_tau_update upd;
+  fastclip_tau_state tst;
+  memset(&upd, 0, sizeof(upd));
+  memset(&tst, 0, sizeof(tst));
+  float* rec = nullptr;
+  const int64_t S = cfg.state_stride;
+  if (with_tau) {
+    int64_t ih[2];
+    float fp[7];
+    if (fread(ih, 8, 2, f) != 2 || fread(fp, 4, 7, f) != 7) return 2;
+    upd.struct_size = sizeof(upd); upd.optimizer = (int32_t)ih[0]; upd.step = ih[1];
+    upd.lr = fp[0]; upd.beta1 = fp[1]; upd.beta2 = fp[2]; upd.eps = fp[3]; upd.tau_min = fp[4];
+    upd.lr_drop_below = fp[5]; upd.lr_drop_factor = fp[6]; upd.state_stride = (int32_t)S;
+    if (v2_) {
+      tst.m_img = rd<float>(f, cfg.N); tst.v_img = rd<float>(f, cfg.N);
+      tst.m_txt = rd<float>(f, cfg.N); tst.v_txt = rd<float>(f, cfg.N);
+      tst.tau_img = (float*)b.tau_img; tst.tau_txt = (float*)b.tau_txt;
+    } else {
+      tst.tau = tau; tst.m = rd<float>(f, 1); tst.v = rd<float>(f, 1);
+    }
+  }
+  if (S > 1) {          // pack the per-sample arrays into records (canonical field order), exact-size allocation
+    if (S < 8 || !v2_ || !with_tau) { fprintf(stderr, "records: V2 with the temperature update and stride >= 8 only\n"); return 3; }
+    rec = (float*)malloc(sizeof(float) * cfg.N * S);
+    float* src[8] = {b.u_img, tst.tau_img, tst.m_img, tst.v_img, b.u_txt, tst.tau_txt, tst.m_txt, tst.v_txt};
+    for (int64_t n = 0; n < cfg.N; ++n)
+      for (int64_t k = 0; k < S; ++k) rec[n * S + k] = k < 8 ? src[k][n] : 7.5f;
+    for (int k = 0; k < 8; ++k) free(src[k]);
+    b.u_img = rec + 0; tst.tau_img = rec + 1; tst.m_img = rec + 2; tst.v_img = rec + 3;
+    b.u_txt = rec + 4; tst.tau_txt = rec + 5; tst.m_txt = rec + 6; tst.v_txt = rec + 7;
+    b.tau_img = tst.tau_img; b.tau_txt = tst.tau_txt;
+  }
   fclose(f);
   b.d_img = nan_buf<float>(cfg.b * cfg.d); b.d_txt = nan_buf<float>(cfg.b * cfg.d);
   b.loss = nan_buf<float>(1); b.d_tau = nan_buf<float>(1);
@@ -128,7 +166,8 @@ int main(int argc, char** argv) {
   void* ws = nullptr;
   if (posix_memalign(&ws, 256, need)) return 2;
   if (!getenv("EMU_UNINIT")) memset(ws, 0xff, need);
-  const fastclip_status st = fastclip_step(&cfg, &b, ws, need, nullptr);
+  const fastclip_status st = with_tau ? fastclip_step_update_tau(&cfg, &b, &upd, &tst, ws, need, nullptr)
+                                      : fastclip_step(&cfg, &b, ws, need, nullptr);
   if (st != FASTCLIP_OK) { fprintf(stderr, "fastclip_step: %d\n", (int)st); return 4; }
   FILE* o = fopen(argv[2], "wb");
   if (!o) return 2;
@@ -139,7 +178,19 @@ int main(int argc, char** argv) {
   if (v2) { fwrite(b.d_tau_img, 4, cfg.b, o); fwrite(b.d_tau_txt, 4, cfg.b, o); }
   fwrite(b.g_img, 4, cfg.b, o); fwrite(b.g_txt, 4, cfg.b, o);
   fwrite(b.u_new_img, 4, cfg.b, o); fwrite(b.u_new_txt, 4, cfg.b, o);
-  fwrite(b.u_img, 4, cfg.N, o); fwrite(b.u_txt, 4, cfg.N, o);
+  auto field = [&](const float* p) {      // a per-sample array, dense or a field of the records
+    for (int64_t n = 0; n < cfg.N; ++n) fwrite(p + n * S, 4, 1, o);
+  };
+  field(b.u_img); field(b.u_txt);
+  if (with_tau) {
+    if (v2) { field(tst.tau_img); field(tst.tau_txt); field(tst.m_img); field(tst.v_img); field(tst.m_txt); field(tst.v_txt); }
+    else if (has_tau) { fwrite(tst.tau, 4, 1, o); fwrite(tst.m, 4, 1, o); fwrite(tst.v, 4, 1, o); }
+  }
+  if (rec) {                               // bytes of the records that belong to no field stay as they were
+    for (int64_t n = 0; n < cfg.N; ++n)
+      for (int64_t k = 8; k < S; ++k)
+        if (rec[n * S + k] != 7.5f) { fprintf(stderr, "record padding touched\n"); return 5; }
+  }
   fclose(o);
   return 0;
 }

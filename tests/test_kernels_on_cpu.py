@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, os.path.join(ROOT, "tests", "emu"))
 import build_emu  # noqa: E402
 
-from oracle import V0, V1, V2, V3, fcco_step  # noqa: E402
+from oracle import ADAMW, LION, V0, V1, V2, V3, fcco_step, temperature_update  # noqa: E402
 from paper_2407_01445_amd import binding as fc  # noqa: E402
 from paper_2407_01445_amd.workloads import draw_indices, make_embeddings  # noqa: E402
 
@@ -163,3 +163,98 @@ CASES = [
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "-".join("%s%s" % (k, v) for k, v in c.items()))
 def test_step_of_the_host_built_kernels_matches_the_oracle_under_asan(emu_step, tmp_path, case):
     run_case(emu_step, tmp_path, **case)
+
+
+# ------------------------------------------------------------------ the step with the temperature update fused in
+UPD = dict(lr=2e-3, step=3, beta1=0.9, beta2=0.98, eps=1e-8, tau_min=0.02, lr_drop_below=0.06, lr_drop_factor=1.0 / 3.0)
+
+
+@pytest.mark.parametrize("case", [
+    # V2 on records {u_1, tau_1, m_1, v_1, u_2, tau_2, m_2, v_2} that the state kernel moves as 16-byte words per side
+    dict(B=300, b=140, off=100, d=72, version=V2, optimizer=ADAMW, stride=8, flags=fc.TILES_256),
+    # ... records with four floats of padding that must stay untouched; the state phase inside the fold (small tiles)
+    dict(B=300, b=140, off=100, d=72, version=V2, optimizer=ADAMW, stride=12),
+    # dense arrays, field by field
+    dict(B=40, b=40, off=0, d=16, version=V2, optimizer=LION, stride=1),
+    # the global temperature stepped by a kernel of its own once its gradient is complete
+    dict(B=300, b=140, off=100, d=72, version=V3, optimizer=ADAMW, stride=1),
+], ids=lambda c: "-".join("%s%s" % (k, v) for k, v in c.items()))
+def test_step_with_temperature_update_of_the_host_built_kernels(emu_step, tmp_path, case):
+    """fastclip_step_update_tau: every output of the step, the state, and the temperatures with their moments after
+    Proc. temperature_update, against the oracle's step followed by its temperature update."""
+    B, b, off, d, version, S = case["B"], case["b"], case["off"], case["d"], case["version"], case["stride"]
+    N, gamma, eps, rho, tau = 700, 0.6, 1e-6, 6.5, 0.07
+    rng = np.random.default_rng(5)
+    img, txt = make_embeddings(51, B, d, 0.5, "bf16")
+    idx = draw_indices(52, b, N)
+    f32 = lambda a: np.asarray(a, np.float32)
+    st = dict(u_img=f32(np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N))),
+              u_txt=f32(np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N))),
+              tau_img=f32(rng.uniform(0.04, 0.1, N)), tau_txt=f32(rng.uniform(0.04, 0.1, N)),
+              m_img=f32(rng.normal(0, 0.1, N)), v_img=f32(rng.uniform(0.0, 0.05, N)),
+              m_txt=f32(rng.normal(0, 0.1, N)), v_txt=f32(rng.uniform(0.0, 0.05, N)))
+    m0, v0 = np.float32(0.03), np.float32(0.002)
+    fin, fout = str(tmp_path / "case.in"), str(tmp_path / "case.out")
+    with open(fin, "wb") as f:
+        np.array([version, fc.BF16, case.get("flags", 0), B, b, off, d, d, d, N, S, 0], np.int64).tofile(f)
+        np.array([gamma, eps, rho, tau, 1.0 / N], np.float32).tofile(f)
+        bf16_bits(img).tofile(f)
+        bf16_bits(txt).tofile(f)
+        idx.astype(np.int64).tofile(f)
+        st["u_img"].tofile(f)
+        st["u_txt"].tofile(f)
+        if version == V2:
+            st["tau_img"].tofile(f)
+            st["tau_txt"].tofile(f)
+        np.array([case["optimizer"], UPD["step"]], np.int64).tofile(f)
+        np.array([UPD["lr"], UPD["beta1"], UPD["beta2"], UPD["eps"], UPD["tau_min"], UPD["lr_drop_below"],
+                  UPD["lr_drop_factor"]], np.float32).tofile(f)
+        if version == V2:
+            for k in ("m_img", "v_img", "m_txt", "v_txt"):
+                st[k].tofile(f)
+        else:
+            np.array([m0], np.float32).tofile(f)
+            np.array([v0], np.float32).tofile(f)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", TSAN_OPTIONS="report_thread_leaks=0")
+    r = subprocess.run([emu_step, fin, fout, "tau"], capture_output=True, text=True, timeout=600, env=env)
+    assert r.returncode == 0 and "Sanitizer" not in r.stderr, r.stderr[:6000]
+    out = np.fromfile(fout, np.float32).astype(np.float64)
+    fields = [("d_img", b * d), ("d_txt", b * d), ("loss", 1)]
+    fields += [("d_tau", 1)] if version != V2 else [("d_tau_img", b), ("d_tau_txt", b)]
+    fields += [("g_img", b), ("g_txt", b), ("u_new_img", b), ("u_new_txt", b), ("u_img", N), ("u_txt", N)]
+    fields += [(k, N) for k in ("tau_img", "tau_txt", "m_img", "v_img", "m_txt", "v_txt")] if version == V2 else \
+              [("tau", 1), ("m", 1), ("v", 1)]
+    got, p = {}, 0
+    for k, n in fields:
+        got[k] = out[p:p + n]
+        p += n
+    assert p == out.size
+    # the oracle: the step with the temperatures of before the call, then the temperature update from its gradients
+    w = {k: v.astype(np.float64) for k, v in st.items()}
+    want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, w["u_img"], w["u_txt"], version=version,
+                     gamma=gamma, eps=eps, rho=rho, tau=float(np.float32(tau)), tau_img=w["tau_img"].copy(),
+                     tau_txt=w["tau_txt"].copy(), tau_grad_scale=1.0 / N)
+    kw = {k: (float(np.float32(v)) if isinstance(v, float) else v) for k, v in UPD.items()}
+    if version == V2:
+        temperature_update(V2, want, optimizer=case["optimizer"], tau_img=w["tau_img"], tau_txt=w["tau_txt"], idx=idx,
+                           m_img=w["m_img"], v_img=w["v_img"], m_txt=w["m_txt"], v_txt=w["v_txt"], **kw)
+        for k in ("tau_img", "tau_txt", "m_img", "v_img", "m_txt", "v_txt"):
+            if case["optimizer"] == LION and k.startswith("v_"):
+                assert np.array_equal(got[k], st[k].astype(np.float64))          # Lion keeps no second moment
+                continue
+            scale = np.max(np.abs(w[k]))
+            assert np.max(np.abs(got[k] - w[k])) <= 2e-2 * scale, k
+            mask = np.ones(N, bool)
+            mask[idx] = False
+            assert np.array_equal(got[k][mask], st[k][mask].astype(np.float64)), k    # other samples untouched
+    else:
+        t_new, m_new, v_new = temperature_update(version, want, optimizer=case["optimizer"], tau=float(np.float32(tau)),
+                                                 m=float(m0), v=float(v0), **kw)
+        assert got["tau"][0] == pytest.approx(t_new, rel=1e-4)
+        assert got["m"][0] == pytest.approx(m_new, rel=2e-2) and got["v"][0] == pytest.approx(v_new, rel=4e-2)
+    for k in ("d_img", "d_txt"):
+        assert np.max(np.abs(got[k].reshape(b, d) - want[k])) <= 2e-2 * np.max(np.abs(want[k])), k
+    for k in ("g_img", "g_txt", "u_new_img", "u_new_txt"):
+        assert np.max(np.abs(got[k] - want[k]) / np.abs(want[k])) <= 2e-2, k
+    assert np.max(np.abs(got["u_img"] - w["u_img"])) <= 2e-2 * np.max(w["u_img"])
+    assert np.max(np.abs(got["u_txt"] - w["u_txt"])) <= 2e-2 * np.max(w["u_txt"])
