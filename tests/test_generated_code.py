@@ -4,7 +4,8 @@ Why: one fault of this library was in no source line.  write_scalars, inlined at
 had a return per version, each after its own stores; the compiler merged the versions' last store into one whose
 address register one path never set (it held the flag output of a v_div_scale_f64), and that path stored to a stray
 address.  The function now stores once per output; this test reads the generated code of every kernel that computes
-the scalars and demands that each scalar store goes through a register pair loaded straight from the kernel arguments.
+the scalars - of every kernel, and every memory instruction whose address is an SGPR pair - and demands that no
+definition by a flag, carry or mask output can reach such an address along the kernel's branches.
 It also holds the kernels to their budgets: no private (scratch) memory, LDS within a compute unit's 160 KiB."""
 from __future__ import annotations
 
@@ -43,17 +44,19 @@ def sgprs_written(line: str):
     return out
 
 
-def scalar_stores_with_stray_address(asm: str):
-    """For every kernel of `asm` that divides in fp64 and stores single dwords through an SGPR address pair after its
-    first fp64 reciprocal (the tail that computes the step's scalars): every definition of that pair that can REACH the
-    store along the kernel's branches, followed through plain copies (s_mov_b64).  An address must come from the kernel
-    arguments (s_load) or from scalar arithmetic on them; a definition by a vector instruction (a flag or mask output)
-    or by a mask operation is a stray address.  Returns (kernel, store, definition) triples of stray ones."""
-    bad = []
+MASK_OPS = ("s_cselect_b64", "s_and_b64", "s_or_b64", "s_andn2_b64", "s_xor_b64", "s_orn2_b64", "s_and_saveexec_b64",
+            "s_or_saveexec_b64")
+
+
+def memory_instructions_with_stray_base(asm: str):
+    """Every global_* / s_load_* instruction of every kernel of `asm` whose address is an SGPR pair: every definition of
+    that pair that can REACH the instruction along the kernel's branches, followed through plain copies (s_mov_b64).  An
+    address must come from the kernel arguments (s_load) or from scalar arithmetic on them; a definition by a vector
+    instruction other than a lane read (a flag or carry output) or by a mask operation is a stray address.
+    Returns (number of instructions checked, [(kernel, instruction, definition)] of stray ones)."""
+    bad, checked = [], 0
     for m in re.finditer(r"^(_ZN2fc\w+):.*?(?=^\s*\.section)", asm, re.S | re.M):
         name, body = m.group(1), m.group(0)
-        if "v_div_fixup_f64" not in body:
-            continue
         lines = [ln for ln in body.split("\n") if ln.strip() and not ln.lstrip().startswith(";")]
         label_at = {ln.strip()[:-1]: i for i, ln in enumerate(lines) if ln.strip().endswith(":")}
         preds = {i: [] for i in range(len(lines))}
@@ -84,25 +87,29 @@ def scalar_stores_with_stray_address(asm: str):
                 work += preds[j]
             return found
 
-        first = next(i for i, ln in enumerate(lines) if "v_rcp_f64" in ln)
-        for i in range(first, len(lines)):
-            st = re.match(r"\s*global_store_dword\s+\S+,\s*\S+,\s*s\[(\d+):(\d+)\]", lines[i])
-            if not st:
+        for i, ln in enumerate(lines):
+            ins = ln.strip().split(None, 1)
+            if len(ins) < 2 or not ins[0].startswith(("global_", "s_load_")):
                 continue
-            for d in reaching(i, int(st.group(1)), int(st.group(2))):
+            ops = [o.strip().split()[0] for o in ins[1].split(",") if o.strip()]
+            cand = [ops[1]] if ins[0].startswith("s_load_") and len(ops) > 1 else ops[::-1]
+            pair = next((SREG.match(o) for o in cand if SREG.match(o) and SREG.match(o).group(1)), None)
+            if pair is None:
+                continue
+            checked += 1
+            for d in reaching(i, int(pair.group(1)), int(pair.group(2))):
                 op = d.split()[0]
-                stray = op.startswith("v_") or op in ("s_cselect_b64", "s_and_b64", "s_or_b64", "s_andn2_b64", "s_xor_b64",
-                                                      "s_orn2_b64", "s_and_saveexec_b64", "s_or_saveexec_b64")
-                if stray:
-                    bad.append((name, lines[i].strip(), d))
-    return bad
+                if (op.startswith("v_") and not op.startswith(("v_readlane", "v_readfirstlane"))) or op in MASK_OPS:
+                    bad.append((name, ln.strip(), d))
+    return checked, bad
 
 
 def test_the_checker_sees_the_store_that_faulted():
     """The generated code that faulted, kept as a fixture: the merged last store can be reached with its address pair
     last written by a v_div_scale_f64 (the V3 path), besides the two good definitions (the loss and the d_tau pointer)."""
     asm = open(os.path.join(ROOT, "tests", "golden", "faulty_scalar_tail_gfx950.s")).read()
-    bad = scalar_stores_with_stray_address(asm)
+    checked, bad = memory_instructions_with_stray_base(asm)
+    assert checked >= 4
     assert bad and all(b[1] == "global_store_dword v1, v0, s[4:5]" and b[2].startswith("v_div_scale_f64") for b in bad)
 
 
@@ -120,14 +127,15 @@ def assembly(tmp_path_factory):
     return out
 
 
-def test_scalar_stores_go_through_the_pointers_the_kernel_was_given(assembly):
-    seen = 0
+def test_every_scalar_address_comes_from_the_kernel_arguments(assembly):
+    """All kernels, every memory instruction whose address is an SGPR pair (1600 of them): none can be reached with
+    that pair last written by a flag, carry or mask output."""
+    total = 0
     for src, asm in assembly.items():
-        bad = scalar_stores_with_stray_address(asm)
-        assert not bad, "%s: %s" % (src, bad)
-        seen += sum(1 for m in re.finditer(r"^(_ZN2fc\w+):.*?(?=^\s*\.section)", asm, re.S | re.M)
-                    if "v_div_fixup_f64" in m.group(0))
-    assert seen >= 6        # the finishing kernels of every path and the scalars' own kernel
+        checked, bad = memory_instructions_with_stray_base(asm)
+        assert not bad, "%s: %s" % (src, bad[:5])
+        total += checked
+    assert total >= 1000
 
 
 def test_no_kernel_uses_scratch_memory_and_lds_fits_a_compute_unit(assembly):
