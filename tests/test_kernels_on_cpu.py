@@ -165,6 +165,27 @@ def test_step_of_the_host_built_kernels_matches_the_oracle_under_asan(emu_step, 
     run_case(emu_step, tmp_path, **case)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_random_small_shapes_on_the_host_built_kernels(emu_step, tmp_path, seed):
+    """Shapes, strides, version and path drawn at random (seeded): B up to 300, any b and off, widths of 8 .. 320 that are
+    no whole stages, padded rows; tile size asked for or left to the library, fine tiles, single pass, gathered state."""
+    import random
+    rng = random.Random(1000 + seed)
+    B = rng.choice([rng.randint(2, 40), rng.randint(41, 300), 256])
+    full = rng.random() < 0.3
+    b = B if full else rng.randint(1, B)
+    off = 0 if full else rng.randint(0, B - b)
+    d = 8 * rng.choice([1, 2, 3, 4, 8, 9, 16, 17, 24, 32, 33, 40])
+    path = ["256", "128", "auto", "fine", "single", "gathered", "128", "256"][seed]
+    flags = {"256": fc.TILES_256, "128": fc.TILES_128, "auto": 0, "fine": fc.FINE_TILES, "single": fc.SINGLE_PASS,
+             "gathered": 0}[path]
+    if path == "single":
+        b, off = B, 0
+    run_case(emu_step, tmp_path, B=B, b=b, off=off, d=d, version=rng.randint(0, 3), flags=flags,
+             N=max(b, 50) + rng.randint(0, 500), ld_img=d + 8 * rng.randint(0, 2), ld_txt=d + 8 * rng.randint(0, 2),
+             seed=77 + seed, gathered=(path == "gathered"))
+
+
 # ------------------------------------------------------------------ the step with the temperature update fused in
 UPD = dict(lr=2e-3, step=3, beta1=0.9, beta2=0.98, eps=1e-8, tau_min=0.02, lr_drop_below=0.06, lr_drop_factor=1.0 / 3.0)
 
