@@ -610,14 +610,17 @@ def test_temperature_update_alone(opt, hp, stride):
             assert v.item() == pytest.approx(wv, rel=1e-5)
 
 
+@pytest.mark.parametrize("tiles", [256, None])   # the large-tile kernels; the library's choice (small tiles here)
 @pytest.mark.parametrize("stride", [1, 8, "canonical 8", "canonical 16"])
 @pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (64, 64, 0, 32)), ("bf16", TOL_BF16, (700, 300, 133, 72)),
                                              # enough anchors that the state phase is a kernel of its own on the MFMA path
                                              ("bf16", TOL_BF16, (2048, 1536, 256, 64))])
 @pytest.mark.parametrize("version", [V2, V3, V0])
-def test_step_with_temperature_update_three_iterations(dtype, tol, shape, version, stride):
+def test_step_with_temperature_update_three_iterations(dtype, tol, shape, version, stride, tiles):
     """fastclip_step_update_tau: step + temperature update per iteration, temperatures and moments carried on the
     device, against the oracle's step followed by Proc. temperature_update."""
+    if dtype == "f32" and tiles is None:
+        pytest.skip("the tile size concerns the bf16 path only")
     B, b, off, d = shape
     canonical = isinstance(stride, str)       # records {u_1, tau_1, m_1, v_1, u_2, tau_2, m_2, v_2}: 16-byte words per side
     stride = int(stride.split()[1]) if canonical else stride
@@ -628,7 +631,7 @@ def test_step_with_temperature_update_three_iterations(dtype, tol, shape, versio
     t_img0 = rng.uniform(0.05, 0.1, N).astype(np.float32)
     t_txt0 = rng.uniform(0.05, 0.1, N).astype(np.float32)
     g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
-                tau_grad_scale=1.0, tau_img0=t_img0, tau_txt0=t_txt0, state_stride=stride, canonical_records=canonical)
+                tau_grad_scale=1.0, tau_img0=t_img0, tau_txt0=t_txt0, state_stride=stride, canonical_records=canonical, tiles=tiles)
     z = lambda n: torch.zeros(n, dtype=torch.float32, device=DEV)
     if version == V2 and canonical:
         for k in ("m_img", "v_img", "m_txt", "v_txt"):
@@ -680,11 +683,14 @@ def test_step_with_temperature_update_three_iterations(dtype, tol, shape, versio
         assert (g.records[:, 8:] == RECORD_FILL).all()       # what lies behind the eight fields is never touched
 
 
+@pytest.mark.parametrize("tiles", [256, None])   # the large-tile kernels; the library's choice (small tiles here)
 # ------------------------------------------------------------------------------- cosine similarity, MBCL
 @pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (37, 11, 13, 19)), ("bf16", TOL_BF16, (700, 300, 133, 72)),
                                              ("bf16", TOL_BF16, (768, 512, 256, 128))])
 @pytest.mark.parametrize("version", [V2, V3])
-def test_gradients_through_normalisation(dtype, tol, shape, version):
+def test_gradients_through_normalisation(dtype, tol, shape, version, tiles):
+    if dtype == "f32" and tiles is None:
+        pytest.skip("the tile size concerns the bf16 path only")
     B, b, off, d = shape
     N = 3000
     rng = np.random.default_rng(B + version)
@@ -695,7 +701,7 @@ def test_gradients_through_normalisation(dtype, tol, shape, version):
     t_img = rng.uniform(0.05, 0.1, N).astype(np.float32)
     t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
     g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
-                tau_grad_scale=1.0 / N, tau_img0=t_img, tau_txt0=t_txt, norms=(n_img, n_txt))
+                tau_grad_scale=1.0 / N, tau_img0=t_img, tau_txt0=t_txt, norms=(n_img, n_txt), tiles=tiles)
     g.set_inputs(img, txt, idx)
     g.step(0.6)
     want = fcco_step(img.astype(np.float64), txt.astype(np.float64), off, b, idx, np.zeros(N), np.zeros(N),
@@ -742,14 +748,17 @@ def test_normalize_rows(raw_dtype, unit_dtype, b, d, pad):
         assert (t_unit[:, d:].float() == 7.5).all()                     # nothing written beyond the row
 
 
+@pytest.mark.parametrize("tiles", [256, None])   # the large-tile kernels; the library's choice (small tiles here)
 @pytest.mark.parametrize("dtype,tol,shape", [("f32", TOL_F32, (37, 11, 13, 19)), ("bf16", TOL_BF16, (700, 300, 133, 72)),
                                              ("bf16", TOL_BF16, (1024, 320, 704, 128))])
 @pytest.mark.parametrize("version", [V2, V3])
-def test_from_raw_encoder_rows_to_gradients_of_raw_rows(dtype, tol, shape, version):
+def test_from_raw_encoder_rows_to_gradients_of_raw_rows(dtype, tol, shape, version, tiles):
     """The worker's whole boundary: its b raw image and text rows are normalised by the library into its slice of the
     global batch (cosine similarity, Sec. 3), the step runs on the unit rows with the norms it was handed, and d_img / d_txt
     are gradients with respect to the RAW rows.  The oracle normalises the same raw rows itself, rounds them to the
     storage type, and differentiates through the normalisation."""
+    if dtype == "f32" and tiles is None:
+        pytest.skip("the tile size concerns the bf16 path only")
     B, b, off, d = shape
     N = 3000
     rng = np.random.default_rng(B + 3 * version)
@@ -763,7 +772,7 @@ def test_from_raw_encoder_rows_to_gradients_of_raw_rows(dtype, tol, shape, versi
     t_txt = rng.uniform(0.05, 0.1, N).astype(np.float32)
     g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
                 tau_grad_scale=1.0 / N, tau_img0=t_img, tau_txt0=t_txt,
-                norms=(np.full(b, np.nan, np.float32), np.full(b, np.nan, np.float32)))
+                norms=(np.full(b, np.nan, np.float32), np.full(b, np.nan, np.float32)), tiles=tiles)
     g.set_inputs(img, txt, idx)
     tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
     code = fc.BF16 if dtype == "bf16" else fc.F32
@@ -1122,15 +1131,16 @@ def test_state_update_alone(n):
     assert np.array_equal(got_t[mask].view(np.uint32), u0t[mask].view(np.uint32))
 
 
+@pytest.mark.parametrize("tiles", [256, None])   # the large-tile kernels; the library's choice (small tiles here)
 @pytest.mark.parametrize("shape,version", [((768, 512, 256, 128), V2), ((700, 300, 133, 72), V3)])
-def test_step_replayed_from_a_hip_graph_equals_the_eager_step(shape, version):
+def test_step_replayed_from_a_hip_graph_equals_the_eager_step(shape, version, tiles):
     """The step allocates nothing and records no memset, so a caller may capture it in a HIP graph: every replay, on
     new inputs copied into the captured buffers and with eager work in between, equals the eager step bit for bit
     (state carried from replay to replay on both sides)."""
     B, b, off, d = shape
     N = 4000
     mk = lambda: GpuStep(B=B, b=b, off=off, d=d, N=N, dtype="bf16", version=version, eps=1e-6, rho=6.5, tau=0.07,
-                         tau_grad_scale=1.0 / N)
+                         tau_grad_scale=1.0 / N, tiles=tiles)
     eager, cap = mk(), mk()
     inputs = [(make_embeddings(70 + i, B, d, 0.5, "bf16"), draw_indices(80 + i, b, N)) for i in range(4)]
     (img, txt), idx = inputs[0]

@@ -204,7 +204,7 @@ def test_step_with_temperature_update_of_the_host_built_kernels(emu_step, tmp_pa
     """fastclip_step_update_tau: every output of the step, the state, and the temperatures with their moments after
     Proc. temperature_update, against the oracle's step followed by its temperature update."""
     B, b, off, d, version, S = case["B"], case["b"], case["off"], case["d"], case["version"], case["stride"]
-    N, gamma, eps, rho, tau = 700, 0.6, 1e-6, 6.5, 0.07
+    N, gamma, eps, rho, tau = max(700, b + 100), 0.6, 1e-6, 6.5, 0.07
     rng = np.random.default_rng(5)
     img, txt = make_embeddings(51, B, d, 0.5, "bf16")
     idx = draw_indices(52, b, N)
