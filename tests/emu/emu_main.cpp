@@ -92,8 +92,50 @@ template <typename T> static T* nan_buf(size_t n) {
 // lr_drop_below, lr_drop_factor}, then V2: m_img, v_img, m_txt, v_txt [N], else m, v [1], and fastclip_step_update_tau
 // runs instead of fastclip_step; with state_stride 8 the eight per-sample arrays of V2 are packed into records
 // {u_1, tau_1, m_1, v_1, u_2, tau_2, m_2, v_2} first (the layout the library moves as 16-byte words).
+// The small entry points on one file: "misc" <in> <out>.  In: 6 int64 {b, d, ld_raw, ld_unit, N, n}, 2 float {gamma, M},
+// raw fp32 rows ((b - 1) ld_raw + d), idx [n], sum_img, sum_txt [n], u_img, u_txt [N].  Runs fastclip_normalize_rows
+// (fp32 -> bf16), fastclip_check_indices on idx and on idx with its last entry repeated, fastclip_state_update.
+// Out: norm [b], unit rows as raw bf16 bits ((b - 1) ld_unit + d, 2 bytes each), 2 int32 statuses, u_img, u_txt [N],
+// u_new_img, u_new_txt [n].
+static int run_misc(const char* fin, const char* fout) {
+  FILE* f = fopen(fin, "rb");
+  if (!f) return 2;
+  int64_t h[6];
+  float p[2];
+  if (fread(h, 8, 6, f) != 6 || fread(p, 4, 2, f) != 2) return 2;
+  const int64_t b = h[0], d = h[1], ld_raw = h[2], ld_unit = h[3], N = h[4], n = h[5];
+  float* raw = rd<float>(f, (size_t)(b - 1) * ld_raw + d);
+  int64_t* idx = rd<int64_t>(f, n);
+  float *sum_img = rd<float>(f, n), *sum_txt = rd<float>(f, n), *u_img = rd<float>(f, N), *u_txt = rd<float>(f, N);
+  fclose(f);
+  const size_t n_unit = (size_t)(b - 1) * ld_unit + d;
+  uint16_t* unit = nan_buf<uint16_t>(n_unit);
+  float* norm = nan_buf<float>(b);
+  if (fastclip_normalize_rows(raw, FASTCLIP_F32, ld_raw, b, d, unit, FASTCLIP_BF16, ld_unit, norm, nullptr) != FASTCLIP_OK)
+    return 4;
+  const size_t wsb = fastclip_check_indices_workspace_bytes(n);
+  void* ws = nullptr;
+  if (posix_memalign(&ws, 256, wsb)) return 2;
+  int32_t st[2];
+  st[0] = (int32_t)fastclip_check_indices(idx, n, N, ws, wsb, nullptr);
+  int64_t* dup = (int64_t*)malloc(sizeof(int64_t) * n);
+  memcpy(dup, idx, sizeof(int64_t) * n);
+  if (n > 1) dup[n - 1] = dup[0];
+  st[1] = (int32_t)fastclip_check_indices(dup, n, N, ws, wsb, nullptr);
+  float *u_new_img = nan_buf<float>(n), *u_new_txt = nan_buf<float>(n);
+  if (fastclip_state_update(idx, n, N, p[0], p[1], sum_img, sum_txt, u_img, u_txt, u_new_img, u_new_txt, nullptr) != FASTCLIP_OK)
+    return 4;
+  FILE* o = fopen(fout, "wb");
+  if (!o) return 2;
+  fwrite(norm, 4, b, o); fwrite(unit, 2, n_unit, o); fwrite(st, 4, 2, o);
+  fwrite(u_img, 4, N, o); fwrite(u_txt, 4, N, o); fwrite(u_new_img, 4, n, o); fwrite(u_new_txt, 4, n, o);
+  fclose(o);
+  return 0;
+}
+
 int main(int argc, char** argv) {
   emu::g_lds_hi = (uintptr_t)&emu::g_marker & ~(uintptr_t)0xffffffffull;
+  if (argc == 4 && !strcmp(argv[1], "misc")) return run_misc(argv[2], argv[3]);
   if (argc < 3) return 2;
   FILE* f = fopen(argv[1], "rb");
   if (!f) return 2;

@@ -19,7 +19,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 sys.path.insert(0, os.path.join(ROOT, "tests", "emu"))
 import build_emu  # noqa: E402
 
-from oracle import ADAMW, LION, V0, V1, V2, V3, fcco_step, temperature_update  # noqa: E402
+from oracle import ADAMW, LION, V0, V1, V2, V3, ema_update, fcco_step, normalize_rows, temperature_update  # noqa: E402
 from paper_2407_01445_amd import binding as fc  # noqa: E402
 from paper_2407_01445_amd.workloads import draw_indices, make_embeddings  # noqa: E402
 
@@ -279,3 +279,48 @@ def test_step_with_temperature_update_of_the_host_built_kernels(emu_step, tmp_pa
         assert np.max(np.abs(got[k] - want[k]) / np.abs(want[k])) <= 2e-2, k
     assert np.max(np.abs(got["u_img"] - w["u_img"])) <= 2e-2 * np.max(w["u_img"])
     assert np.max(np.abs(got["u_txt"] - w["u_txt"])) <= 2e-2 * np.max(w["u_txt"])
+
+
+# ------------------------------------------------------------------ the small entry points
+@pytest.mark.parametrize("b,d,n", [(37, 19, 300), (5, 4104, 2), (130, 72, 1), (1, 1, 1000)])
+def test_small_entry_points_of_the_host_built_kernels(emu_step, tmp_path, b, d, n):
+    """fastclip_normalize_rows (a wavefront per row, padded rows on both sides), fastclip_check_indices (hash table on
+    the device; distinct indices pass, a repeated one is reported), fastclip_state_update (Eq. 1 alone)."""
+    rng = np.random.default_rng(b + d)
+    ld_raw, ld_unit, N = d + 3, d + 5, 4 * n + 7
+    raw = np.full((b, ld_raw), np.nan, np.float32)
+    raw[:, :d] = rng.normal(0, 1, (b, d)) * rng.uniform(0.1, 30.0, (b, 1))
+    idx = draw_indices(9, n, N)
+    sums = [rng.uniform(1.0, 50.0, n).astype(np.float32) for _ in range(2)]
+    u0 = [np.where(rng.random(N) < 0.5, 0.0, rng.uniform(0.05, 2.0, N)).astype(np.float32) for _ in range(2)]
+    gamma, M = np.float32(0.3), np.float32(77.0)
+    fin, fout = str(tmp_path / "misc.in"), str(tmp_path / "misc.out")
+    with open(fin, "wb") as f:
+        np.array([b, d, ld_raw, ld_unit, N, n], np.int64).tofile(f)
+        np.array([gamma, M], np.float32).tofile(f)
+        raw.reshape(-1)[: (b - 1) * ld_raw + d].tofile(f)
+        idx.astype(np.int64).tofile(f)
+        for a in sums + u0:
+            a.tofile(f)
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", TSAN_OPTIONS="report_thread_leaks=0")
+    r = subprocess.run([emu_step, "misc", fin, fout], capture_output=True, text=True, timeout=600, env=env)
+    assert r.returncode == 0 and "Sanitizer" not in r.stderr, r.stderr[:6000]
+    blob = open(fout, "rb").read()
+    n_unit = (b - 1) * ld_unit + d
+    norm = np.frombuffer(blob, np.float32, b, 0).astype(np.float64)
+    bits = np.frombuffer(blob, np.uint16, n_unit, 4 * b)
+    st = np.frombuffer(blob, np.int32, 2, 4 * b + 2 * n_unit)
+    rest = np.frombuffer(blob, np.float32, 2 * N + 2 * n, 4 * b + 2 * n_unit + 8).astype(np.float64)
+    want_unit, want_norm = normalize_rows(raw[:, :d])
+    assert np.max(np.abs(norm - want_norm) / want_norm) <= 1e-6
+    full = np.zeros(b * ld_unit, np.uint16)
+    full[:n_unit] = bits
+    unit = (full.reshape(b, ld_unit)[:, :d].astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert np.max(np.abs(unit - want_unit)) <= 2.0 ** -8                       # one rounding to bf16 of values <= 1
+    assert st[0] == fc.OK and st[1] == (fc.ERR_INDEX if n > 1 else fc.OK)
+    u_img, u_txt, new_img, new_txt = rest[:N], rest[N:2 * N], rest[2 * N:2 * N + n], rest[2 * N + n:]
+    for got, got_new, u_before, s_ in ((u_img, new_img, u0[0], sums[0]), (u_txt, new_txt, u0[1], sums[1])):
+        want = u_before.astype(np.float64)
+        new = ema_update(want, idx, s_.astype(np.float64) / float(M), float(gamma))
+        assert np.max(np.abs(got - want) / np.maximum(want, 1e-30)) <= 1e-6
+        assert np.max(np.abs(got_new - new) / new) <= 1e-6
