@@ -520,8 +520,9 @@ def test_random_shapes(dtype, tol, cases):
         N = int(rs.integers(b, 4 * b + 100))
         pad = int(rs.choice([0, 8, 24]))
         normed = bool(rs.integers(0, 3) == 0)       # gradients with respect to rows that were normalised outside
-        print("[random %s %d] B=%d b=%d off=%d d=%d v%d gathered=%d stride=%d gamma=%.2f N=%d pad=%d normed=%d"
-              % (dtype, case, B, b, off, d, version, gathered, stride, gamma, N, pad, normed), flush=True)
+        tiles = (256, None, 128)[case % 3]          # bf16: large tiles, the library's choice, small tiles where they apply
+        print("[random %s %d] B=%d b=%d off=%d d=%d v%d gathered=%d stride=%d gamma=%.2f N=%d pad=%d normed=%d tiles=%s"
+              % (dtype, case, B, b, off, d, version, gathered, stride, gamma, N, pad, normed, tiles), flush=True)
         rng = np.random.default_rng(case)
         img, txt = make_embeddings(case + 7, B, d, 0.5, dtype)
         idx = draw_indices(case + 3, b, N)
@@ -541,7 +542,7 @@ def test_random_shapes(dtype, tol, cases):
             extra.update(norm_img=f64(norms[0]), norm_txt=f64(norms[1]))
         g = GpuStep(B=B, b=b, off=off, d=d, N=N, dtype=dtype, version=version, eps=1e-6, rho=6.5, tau=0.07,
                     tau_grad_scale=1.0 / N, ld_img=d + pad, ld_txt=d, u_img0=u0i, u_txt0=u0t, tau_img0=t_img,
-                    tau_txt0=t_txt, gathered=gath, state_stride=stride, norms=norms)
+                    tau_txt0=t_txt, gathered=gath, state_stride=stride, norms=norms, tiles=tiles)
         g.set_inputs(img, txt, idx)
         g.step(gamma)
         u_img, u_txt = u0i.astype(np.float64), u0t.astype(np.float64)
