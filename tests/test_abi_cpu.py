@@ -124,6 +124,29 @@ def test_describe_reports_the_plan():
         fc.fastclip_describe(good_cfg(B=1))
 
 
+def test_plans_are_sane_over_a_sweep_of_shapes():
+    """Every valid bf16 shape of a sweep: the plan's splits fit the column range, the partial sums count the contrast
+    tiles of the chosen size, the workspace is large enough for the two stored strips, and the tile flags behave."""
+    import itertools
+    for B, frac, d, flags in itertools.product([2, 40, 257, 1000, 1024, 4000, 8192, 40003], [0.01, 0.3, 1.0],
+                                                [8, 72, 512, 1024], [0, fc.TILES_128, fc.TILES_256, fc.SINGLE_PASS]):
+        b = max(1, int(B * frac))
+        cfg = good_cfg(B=B, b=b, off=B - b, d=d, N=max(b, 10), flags=flags)
+        assert fc.fastclip_validate(cfg, None) == fc.OK, (B, b, d, flags)
+        plan = fc.fastclip_describe(cfg)
+        assert plan["tile"] in (128, 256)
+        if flags == fc.TILES_256:
+            assert plan["tile"] == 256
+        if plan["single_pass"]:
+            assert b == B and plan["tile"] == 256
+        stage_cols = 32
+        stages = -(-(-(-B // 64) * 64) // stage_cols)
+        assert 1 <= plan["nsplit"] <= min(64, stages), (B, b, d, flags, plan)
+        assert plan["nparts"] == -(-B // plan["tile"])
+        rows = -(-b // 256) * 256
+        assert fc.fastclip_workspace_bytes(cfg) >= 2 * 2 * rows * (-(-B // 64) * 64)
+
+
 def test_tile_size_is_chosen_by_the_batch_size_unless_asked_for():
     """At most 128 large strip tiles: the library takes 128 x 128 tiles by itself (the layout FASTCLIP_TILES_128 asks for);
     FASTCLIP_TILES_128 reaches up to 191 large tiles; beyond that, with gathered state and in the single-pass form the tiles
